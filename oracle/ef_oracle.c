@@ -1,0 +1,322 @@
+/*
+ * CPU oracle for the cache-aware MoE-layer hot path (TEST INFRASTRUCTURE ONLY).
+ *
+ * Plain, slow, fp64, obviously-correct evaluation of what the path computes.
+ * It shares no code with the HIP library: own bf16 decoding, own loops, no
+ * blocking or fusion.  Only tests, the smoke check and the benchmark's
+ * cpu_baseline leg may call it; the product path never does.
+ *
+ * What each function follows:
+ *   - pre-gating (hidden state through a later layer's router gives a
+ *     distribution over experts): paper Sec. 2.3.2 and Sec. 3.2.1;
+ *   - the deviation Delta added to the pre-gate result: Sec. 3.2.2 (read in the
+ *     logit domain, so Delta = 0 falls back exactly to top-k of router logits,
+ *     the fallback that section names);
+ *   - residency preference of cache-aware routing: Sec. 3.4 (read as an
+ *     additive bias beta on the selection score of resident experts);
+ *   - expected activation count by cumulative probability and the step size
+ *     S = N_e * E_s / (C_s * T_l): Sec. 3.2.1 and its equation;
+ *   - the layer math itself (softmax over all experts, top-k, SwiGLU expert,
+ *     weighted combine) is not written out in the paper; it is the standard
+ *     definition for the model families the paper evaluates (Sec. 4.1).
+ *
+ * Pinned by tests against closed forms, brute force and library fp64 routines.
+ * "parity unpinned": the Delta path and the combine-weight renormalisation are
+ * definitions by fiat (no paper value fixes them); they are pinned only
+ * against their own stated definition through special cases.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+static double bf16_to_f64(uint16_t v)
+{
+    uint32_t bits = ((uint32_t)v) << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+/* round a double to the nearest bf16 value (ties to even), returned as double */
+static double round_to_bf16(double x)
+{
+    float f = (float)x;
+    uint32_t bits;
+    memcpy(&bits, &f, sizeof bits);
+    uint32_t lsb = (bits >> 16) & 1u;
+    bits += 0x7FFFu + lsb;
+    bits &= 0xFFFF0000u;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+/* z[t,e] = sum_i h[t,i] * Wg[e,i] + b[e]        (router logits) */
+void oracle_gate_logits(const uint16_t *h, const uint16_t *Wg, const float *b,
+                        int T, int d, int E, double *z)
+{
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        for (int e = 0; e < E; ++e) {
+            double acc = 0.0;
+            for (int i = 0; i < d; ++i)
+                acc += bf16_to_f64(h[(size_t)t * d + i]) * bf16_to_f64(Wg[(size_t)e * d + i]);
+            z[(size_t)t * E + e] = acc + (b ? (double)b[e] : 0.0);
+        }
+    }
+}
+
+/* p[t,:] = softmax over ALL experts of z[t,:] */
+void oracle_softmax(const double *z, int T, int E, double *p)
+{
+    for (int t = 0; t < T; ++t) {
+        const double *zr = z + (size_t)t * E;
+        double m = zr[0];
+        for (int e = 1; e < E; ++e)
+            if (zr[e] > m) m = zr[e];
+        double s = 0.0;
+        for (int e = 0; e < E; ++e) {
+            p[(size_t)t * E + e] = exp(zr[e] - m);
+            s += p[(size_t)t * E + e];
+        }
+        for (int e = 0; e < E; ++e)
+            p[(size_t)t * E + e] /= s;
+    }
+}
+
+/* selection score s[t,e] = z[t,e] + beta * r[e] + Delta[req(t), e] */
+void oracle_scores(const double *z, int T, int E, double beta, const uint8_t *resident,
+                   const float *delta /* [R,E] or NULL */, const int32_t *tok2req /* [T] or NULL */,
+                   double *s)
+{
+    for (int t = 0; t < T; ++t) {
+        int r = tok2req ? tok2req[t] : 0;
+        for (int e = 0; e < E; ++e) {
+            double v = z[(size_t)t * E + e];
+            if (resident && resident[e]) v += beta;
+            if (delta) v += (double)delta[(size_t)r * E + e];
+            s[(size_t)t * E + e] = v;
+        }
+    }
+}
+
+/*
+ * ids[t,:] = the k experts with the largest score; equal scores: lower expert
+ * id wins; emitted in ascending expert id.  gap[t] = k-th largest score minus
+ * the (k+1)-th largest (infinity when k == E).
+ */
+void oracle_topk(const double *s, int T, int E, int k, int32_t *ids, double *gap)
+{
+    uint8_t *taken = (uint8_t *)malloc((size_t)E);
+    for (int t = 0; t < T; ++t) {
+        const double *sr = s + (size_t)t * E;
+        memset(taken, 0, (size_t)E);
+        double kth = 0.0;
+        for (int j = 0; j < k; ++j) {
+            int best = -1;
+            for (int e = 0; e < E; ++e) {
+                if (taken[e]) continue;
+                if (best < 0 || sr[e] > sr[best]) best = e; /* strict: lower id keeps ties */
+            }
+            taken[best] = 1;
+            kth = sr[best];
+        }
+        int n = 0;
+        for (int e = 0; e < E; ++e)
+            if (taken[e]) ids[(size_t)t * k + n++] = e;
+        if (gap) {
+            if (k >= E) {
+                gap[t] = INFINITY;
+            } else {
+                int nxt = -1;
+                for (int e = 0; e < E; ++e) {
+                    if (taken[e]) continue;
+                    if (nxt < 0 || sr[e] > sr[nxt]) nxt = e;
+                }
+                gap[t] = kth - sr[nxt];
+            }
+        }
+    }
+    free(taken);
+}
+
+/* w[t,j] = p[t, ids[t,j]] (the unbiased probability), optionally / sum_j, times routed_scale */
+void oracle_weights(const double *p, const int32_t *ids, int T, int E, int k,
+                    int renorm, double routed_scale, double *w)
+{
+    for (int t = 0; t < T; ++t) {
+        double s = 0.0;
+        for (int j = 0; j < k; ++j) {
+            w[(size_t)t * k + j] = p[(size_t)t * E + ids[(size_t)t * k + j]];
+            s += w[(size_t)t * k + j];
+        }
+        for (int j = 0; j < k; ++j) {
+            if (renorm) w[(size_t)t * k + j] /= s;
+            w[(size_t)t * k + j] *= routed_scale;
+        }
+    }
+}
+
+/* hist[e] = number of assignments to expert e */
+void oracle_histogram(const int32_t *ids, int n_assign, int E, int32_t *hist)
+{
+    for (int e = 0; e < E; ++e) hist[e] = 0;
+    for (int a = 0; a < n_assign; ++a) hist[ids[a]] += 1;
+}
+
+/*
+ * Stable grouping of the assignments a = t*k + j by expert id:
+ * counts[e], offsets = exclusive prefix (offsets[E] = T*k),
+ * perm[pos] = a, inv_perm[a] = pos, positions ordered by (expert, a).
+ */
+void oracle_permute(const int32_t *ids, int T, int k, int E,
+                    int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm)
+{
+    int n = T * k;
+    for (int e = 0; e < E; ++e) counts[e] = 0;
+    for (int a = 0; a < n; ++a) counts[ids[a]] += 1;
+    offsets[0] = 0;
+    for (int e = 0; e < E; ++e) offsets[e + 1] = offsets[e] + counts[e];
+    int32_t *cursor = (int32_t *)malloc((size_t)E * sizeof(int32_t));
+    for (int e = 0; e < E; ++e) cursor[e] = offsets[e];
+    for (int a = 0; a < n; ++a) {
+        int pos = cursor[ids[a]]++;
+        perm[pos] = a;
+        inv_perm[a] = pos;
+    }
+    free(cursor);
+}
+
+/* y = W2 * (silu(W1 x) .* (W3 x)) for one token row x [d]; W1,W3 [F,d], W2 [d,F] */
+static void swiglu_row(const uint16_t *x, int d, int F,
+                       const uint16_t *W1, const uint16_t *W3, const uint16_t *W2,
+                       int round_act, double *act /* [F] scratch */, double *y /* [d] */)
+{
+    for (int f = 0; f < F; ++f) {
+        double g = 0.0, u = 0.0;
+        for (int i = 0; i < d; ++i) {
+            double xi = bf16_to_f64(x[i]);
+            g += bf16_to_f64(W1[(size_t)f * d + i]) * xi;
+            u += bf16_to_f64(W3[(size_t)f * d + i]) * xi;
+        }
+        double a = g / (1.0 + exp(-g)) * u;
+        act[f] = round_act ? round_to_bf16(a) : a;
+    }
+    for (int c = 0; c < d; ++c) {
+        double acc = 0.0;
+        for (int f = 0; f < F; ++f)
+            acc += bf16_to_f64(W2[(size_t)c * F + f]) * act[f];
+        y[c] = acc;
+    }
+}
+
+/*
+ * Expert FFN over the grouped positions: for each pos, token = perm[pos] / k,
+ * expert = ids[perm[pos]], y[pos,:] = FFN_expert(h[token,:]).
+ * W1/W3/W2 are arrays of E pointers (NULL allowed for experts no position uses).
+ * Only positions in [pos_begin, pos_end) are evaluated (for sampled checks).
+ */
+void oracle_expert_ffn(const uint16_t *h, int d, int F, int k,
+                       const uint16_t *const *W1, const uint16_t *const *W3, const uint16_t *const *W2,
+                       const int32_t *ids, const int32_t *perm, int pos_begin, int pos_end,
+                       int round_act, double *y /* [(pos_end-pos_begin), d] */)
+{
+#pragma omp parallel
+    {
+        double *act = (double *)malloc((size_t)F * sizeof(double));
+#pragma omp for schedule(dynamic, 1)
+        for (int pos = pos_begin; pos < pos_end; ++pos) {
+            int a = perm[pos];
+            int e = ids[a];
+            swiglu_row(h + (size_t)(a / k) * d, d, F, W1[e], W3[e], W2[e], round_act, act,
+                       y + (size_t)(pos - pos_begin) * d);
+        }
+        free(act);
+    }
+}
+
+/* dense SwiGLU on every token: out[t,:] = FFN(h[t,:])  (always-resident shared experts) */
+void oracle_dense_ffn(const uint16_t *h, int T, int d, int F,
+                      const uint16_t *W1, const uint16_t *W3, const uint16_t *W2,
+                      int round_act, double *out /* [T,d] */)
+{
+#pragma omp parallel
+    {
+        double *act = (double *)malloc((size_t)F * sizeof(double));
+#pragma omp for schedule(dynamic, 1)
+        for (int t = 0; t < T; ++t)
+            swiglu_row(h + (size_t)t * d, d, F, W1, W3, W2, round_act, act, out + (size_t)t * d);
+        free(act);
+    }
+}
+
+/* out[t,:] = sum_j w[t,j] * y[inv_perm[t*k+j], :] + shared[t,:] */
+void oracle_combine(const double *y, const double *w, const int32_t *inv_perm,
+                    int T, int k, int d, const double *shared /* [T,d] or NULL */, double *out)
+{
+    for (int t = 0; t < T; ++t) {
+        for (int c = 0; c < d; ++c) {
+            double acc = 0.0;
+            for (int j = 0; j < k; ++j)
+                acc += w[(size_t)t * k + j] * y[(size_t)inv_perm[(size_t)t * k + j] * d + c];
+            if (shared) acc += shared[(size_t)t * d + c];
+            out[(size_t)t * d + c] = acc;
+        }
+    }
+}
+
+/*
+ * Expected activation count: q[e] = hist[e] / sum(hist); take experts in
+ * descending q (equal q: lower id first) until the cumulative share reaches
+ * tau.  Returns N_e; *n_miss = how many of those are not resident;
+ * order_out (optional, [E]) receives the descending order.
+ */
+int oracle_expected_activations(const int32_t *hist, int E, double tau,
+                                const uint8_t *resident, int *n_miss, int32_t *order_out)
+{
+    int64_t total = 0;
+    for (int e = 0; e < E; ++e) total += hist[e];
+    int32_t *order = (int32_t *)malloc((size_t)E * sizeof(int32_t));
+    uint8_t *used = (uint8_t *)calloc((size_t)E, 1);
+    for (int j = 0; j < E; ++j) {
+        int best = -1;
+        for (int e = 0; e < E; ++e) {
+            if (used[e]) continue;
+            if (best < 0 || hist[e] > hist[best]) best = e;
+        }
+        used[best] = 1;
+        order[j] = best;
+    }
+    int n = 0, miss = 0;
+    if (total > 0) {
+        int64_t cum = 0;
+        while (n < E) {
+            int e = order[n];
+            if (hist[e] == 0) break;
+            cum += hist[e];
+            n += 1;
+            if (!(resident && resident[e])) miss += 1;
+            if ((double)cum / (double)total >= tau) break;
+        }
+    }
+    if (n_miss) *n_miss = miss;
+    if (order_out) memcpy(order_out, order, (size_t)E * sizeof(int32_t));
+    free(order);
+    free(used);
+    return n;
+}
+
+/* S = N_e * E_s / (C_s * T_l); returned raw (no rounding) */
+double oracle_step_size_raw(double n_e, double expert_bytes, double bandwidth_Bps, double layer_seconds)
+{
+    return n_e * expert_bytes / (bandwidth_Bps * layer_seconds);
+}
+
+/* horizon = clamp(ceil(S), 1, h_max) */
+int oracle_horizon(double n_e, double expert_bytes, double bandwidth_Bps, double layer_seconds, int h_max)
+{
+    double s = ceil(oracle_step_size_raw(n_e, expert_bytes, bandwidth_Bps, layer_seconds));
+    if (s < 1.0) s = 1.0;
+    if (s > (double)h_max) s = (double)h_max;
+    return (int)s;
+}
