@@ -1,0 +1,216 @@
+/*
+ * expertflow.h -- C ABI of the MI355X (gfx950) MoE-layer hot path with adaptive
+ * expert prefetching and cache-aware routing.
+ *
+ * One GPU, one context per model replica.  Plain C: opaque context, plain
+ * pointers and sizes.  Every pointer is tagged [dev] (device memory on the
+ * current HIP device), [host] (ordinary host memory) or [pinned] (page-locked
+ * host memory).  `stream` arguments are a hipStream_t passed as void*
+ * (NULL = the default stream).  The caller owns every buffer it passes; the
+ * library owns the context, its HBM expert-slot pool, its copy stream, its
+ * events and its scratch buffers.
+ *
+ * Asynchrony: ef_predict / ef_route / ef_moe_ffn only enqueue work on `stream`;
+ * outputs are valid once the caller has synchronised that stream.
+ * ef_cache_swap_in enqueues a host-to-device copy on the library's own copy
+ * stream and returns at once.
+ *
+ * Errors: every call returns 0 (EF_OK) or a negative code; on error nothing
+ * has been enqueued.  ef_last_error() gives the text of the last failure.
+ *
+ * Limits: n_experts <= 64, top_k <= 8 and <= n_experts, look-ahead H <= 7,
+ * d_model a multiple of 64, d_ff and d_ff_shared multiples of 32.
+ *
+ * Expert weight layout ("packed blob").  An expert (SwiGLU: W1 [F,d] gate,
+ * W3 [F,d] up, W2 [d,F] down, bf16) is stored as ef_expert_bytes(d,F) =
+ * 3*d*F*2 bytes of 1 KiB "fragments".  A fragment holds a 32-row x 16-column
+ * block of a row-major matrix M in matrix-core operand order: 64 lanes x 8
+ * bf16, lane l = 32*g + i (g in {0,1}, i in 0..31) holds
+ *   natural order : M[r0 + i][c0 + 8*g + t],              t = 0..7
+ *   paired order  : M[r0 + i][c0 + 8*(t/4) + 4*g + t%4],   t = 0..7
+ * Section A, for rb in 0..F/32-1: d/16 natural-order fragments of W1 rows
+ * [32rb, 32rb+32) (c0 = 0, 16, ...), then the same for W3.  Section B, at byte
+ * 2*d*F*2, for cb in 0..d/32-1: F/16 paired-order fragments of W2 rows
+ * [32cb, 32cb+32).  ef_pack_expert() builds a blob from row-major matrices.
+ * The layout is a pure permutation of the weights: it makes every wavefront
+ * load of weights one contiguous 1 KiB read that lands directly in matrix-core
+ * operand registers.
+ */
+#ifndef EXPERTFLOW_H
+#define EXPERTFLOW_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EF_MAX_EXPERTS 64
+#define EF_MAX_TOPK 8
+#define EF_MAX_HORIZON 7
+
+enum {
+    EF_OK = 0,
+    EF_EINVAL = -1,       /* null pointer, bad shape, bad range, bad alignment */
+    EF_ENOMEM = -2,       /* host or device allocation failed */
+    EF_EHIP = -3,         /* a HIP runtime call failed */
+    EF_EBUSY = -4,        /* no evictable cache slot */
+    EF_ENOTRESIDENT = -5, /* strict mode: FFN needs an expert that is not in the cache */
+    EF_ENOSYS = -6        /* not available (e.g. device call on a fake-copy context) */
+};
+
+/* ef_config.flags */
+#define EF_FLAG_FAKE_COPY 1u   /* no device at all: the cache runtime runs against a fake copy
+                                  engine and a fake clock (host-logic tests); kernels return EF_ENOSYS */
+#define EF_FLAG_STRICT_RESIDENT 2u /* ef_moe_ffn fails with EF_ENOTRESIDENT instead of swapping in misses itself */
+
+typedef struct ef_ctx ef_ctx;
+
+typedef struct ef_config {
+    int32_t n_layers;
+    int32_t d_model;             /* d */
+    int32_t n_experts;           /* E routed experts per layer */
+    int32_t top_k;               /* k */
+    int32_t d_ff;                /* F, hidden dim of a routed expert */
+    int32_t d_ff_shared;         /* hidden dim of the always-resident dense SwiGLU (0 = none) */
+    int32_t slots_total;         /* HBM expert cache: number of expert-sized slots in the pool */
+    int32_t slots_per_layer_max; /* cap of resident experts per layer, 0 = no cap */
+    int32_t max_tokens;          /* largest T any call will pass (sizes the scratch) */
+    int32_t h_max;               /* clamp of the look-ahead horizon, 1..EF_MAX_HORIZON */
+    int32_t renorm_topk;         /* 1: combine weights are renormalised over the selected k */
+    float routed_scale;          /* factor on the combine weights */
+    float cum_threshold;         /* tau of the expected-activation rule (paper Sec. 3.2.1) */
+    int32_t stall_thresh;        /* feedback loop: stalls before S += 1 (paper Sec. 3.2.2) */
+    int32_t overfetch_thresh;    /* feedback loop: overfetches before S -= 1 */
+    uint32_t flags;
+    float init_bandwidth_gbps;   /* starting value of the C_s estimate, GB/s */
+    float init_layer_us;         /* starting value of the T_l estimate, microseconds */
+} ef_config;
+
+typedef struct ef_stats {
+    int64_t hits;               /* experts needed by a layer and found resident (ready or in flight) */
+    int64_t misses;             /* experts needed by a layer and not resident: priority swap-ins */
+    int64_t prefetch_issued;    /* prefetch swap-ins that started a copy */
+    int64_t prefetch_redundant; /* prefetch requests for experts already resident ("overfetch") */
+    int64_t evictions;
+    int64_t bytes_copied;       /* host-to-device expert bytes */
+    int64_t layers_run;         /* ef_moe_ffn calls */
+    int64_t tokens_run;         /* sum of T over ef_moe_ffn calls */
+    double copy_seconds;        /* summed duration of completed copies (copy-stream events) */
+    double stall_seconds;       /* time the compute stream spent waiting for swap-ins */
+    double layer_seconds;       /* summed ef_route..ef_moe_ffn layer time (compute-stream events) */
+    double bandwidth_Bps;       /* current C_s estimate */
+    double layer_seconds_est;   /* current T_l estimate */
+    double miss_rate;           /* R_miss = 1 - hits / (hits + misses)  (paper Sec. 2.2) */
+    int32_t horizon;            /* current look-ahead S */
+    int32_t stall_counter, overfetch_counter;
+} ef_stats;
+
+/* ---- utilities (host only, no device needed) -------------------------------------------- */
+
+const char *ef_strerror(int code);
+
+/* bytes of one packed expert blob: 3*d*F*2; 0 if d % 64 or F % 32 is non-zero */
+size_t ef_expert_bytes(int d_model, int d_ff);
+
+/* Pack row-major W1 [F,d], W3 [F,d], W2 [d,F] (bf16 bit patterns) [host] into blob [host],
+ * ef_expert_bytes(d,F) bytes, in the layout described at the top.  Model-load-time helper. */
+int ef_pack_expert(const uint16_t *W1, const uint16_t *W3, const uint16_t *W2,
+                   int d_model, int d_ff, void *blob);
+
+/* ---- context ---------------------------------------------------------------------------- */
+
+/* Allocates the slot pool (slots_total * ef_expert_bytes), scratch for max_tokens tokens, one copy
+ * stream and the events.  With EF_FLAG_FAKE_COPY nothing touches the GPU. */
+int ef_create(const ef_config *cfg, ef_ctx **out);
+int ef_destroy(ef_ctx *ctx);
+const char *ef_last_error(ef_ctx *ctx);
+
+/* Register one layer.  gate_w [dev] [E,d] bf16 row-major; gate_b [dev] [E] f32 or NULL;
+ * experts [pinned] E consecutive packed blobs (the authoritative copy; must outlive the context;
+ * with EF_FLAG_FAKE_COPY any non-NULL value); shared_blob [dev] packed blob of the dense SwiGLU
+ * with hidden d_ff_shared, or NULL.  The library keeps the pointers, it copies nothing. */
+int ef_register_layer(ef_ctx *ctx, int layer, const void *gate_w, const float *gate_b,
+                      const void *experts, const void *shared_blob);
+
+/* ---- hot path ---------------------------------------------------------------------------- */
+
+/*
+ * Cross-layer prediction (pre-gating, paper Sec. 2.3.2 / 3.2.1, with the deviation Delta of
+ * Sec. 3.2.2): the hidden states of `layer` go through the gates of layers layer+1..layer+H.
+ * For j = 1..H: z = hidden * Wg_{layer+j}^T + b;  score = z + beta*resident_{layer+j} + Delta_j;
+ * topk_ids[j-1][t][:] = the k best experts of token t in ascending id (ties: lower id);
+ * hist[j-1][e] = number of (token, slot) assignments to e.  Residency is the cache state at call
+ * time.  Layers past the last one are not predicted: H is clamped to n_layers-1-layer and the
+ * effective H is returned in *H_eff (may be 0: nothing enqueued).
+ *   hidden   [dev]  [T,d] bf16 row-major
+ *   delta    [dev]  [R,H,E] f32 or NULL;  tok2req [dev] [T] i32 request of each token or NULL (=0)
+ *   topk_ids [dev]  [H,T,k] i32;  hist [dev] [H,E] i32 (overwritten)
+ */
+int ef_predict(ef_ctx *ctx, int layer, const void *hidden, int T, int H,
+               const float *delta, const int32_t *tok2req, float beta,
+               int32_t *topk_ids, int32_t *hist, int *H_eff, void *stream);
+
+/*
+ * Cache-aware routing of one layer (paper Sec. 3.4; fallback "top-k of the router logits",
+ * Sec. 3.2.2): z = hidden * Wg^T + b; p = softmax(z) over all E; selection score z + beta*resident;
+ * top-k as in ef_predict; topk_w[t][j] = p[t][ids[t][j]] (unbiased), renormalised over the k if
+ * renorm_topk, times routed_scale.  Then the stable grouping of the assignments a = t*k + j by
+ * expert: counts[e], offsets (exclusive prefix, offsets[E] = T*k), perm[pos] = a, inv_perm[a] = pos.
+ * All outputs [dev]: topk_ids [T,k] i32, topk_w [T,k] f32, counts [E] i32, offsets [E+1] i32,
+ * perm [T*k] i32, inv_perm [T*k] i32.  T = 0 is allowed (counts/offsets are zeroed).
+ */
+int ef_route(ef_ctx *ctx, int layer, const void *hidden, int T, float beta,
+             int32_t *topk_ids, float *topk_w, int32_t *counts, int32_t *offsets,
+             int32_t *perm, int32_t *inv_perm, void *stream);
+
+/*
+ * Grouped SwiGLU expert FFN over the cache slots and weighted un-permute:
+ * out[t] = sum_j topk_w[t][j] * FFN_{ids[t][j]}(hidden[t]) (+ dense shared FFN(hidden[t])).
+ * Groups whose expert is ready run first; groups whose expert is still being copied run after
+ * their copy event; experts not resident at all are swapped in here at miss priority (unless
+ * EF_FLAG_STRICT_RESIDENT) while the resident groups compute.  counts_host [host] [E] is the
+ * caller's host copy of `counts` (launch planning and cache decisions).  out [dev] [T,d] f32.
+ * Advances the cache clock by one layer.
+ */
+int ef_moe_ffn(ef_ctx *ctx, int layer, const void *hidden, int T,
+               const int32_t *topk_ids, const float *topk_w, const int32_t *counts_host,
+               const int32_t *offsets, const int32_t *perm, const int32_t *inv_perm,
+               float *out, void *stream);
+
+/*
+ * Make (layer, expert) resident in the HBM cache: pick a slot (free, else the two-level LRU's
+ * victim: low tier first, paper Sec. 3.3.1), copy the blob from the pinned store on the copy
+ * stream and record its ready event.  priority 0 = prefetch, due_in = layers until it is needed;
+ * priority 1 = miss of the layer being run (due_in ignored).  An expert already resident is only
+ * promoted.  *slot_out (may be NULL) receives the slot.  Returns EF_EBUSY if no slot can be evicted.
+ */
+int ef_cache_swap_in(ef_ctx *ctx, int layer, int expert, int priority, int due_in, int *slot_out);
+
+/* resident_host [host] [E]: 1 if the expert is in the cache (ready or copy in flight) */
+int ef_cache_query(ef_ctx *ctx, int layer, uint8_t *resident_host);
+
+/*
+ * Horizon controller (paper Sec. 3.2.1): from the predicted histograms hist_host [host] [H,E] of
+ * layers layer+1..layer+H, take experts in descending demand until their cumulative share reaches
+ * cum_threshold (N_e); N_miss = those not resident; S = clamp(ceil(N_miss*E_s/(C_s*T_l)), 1, h_max)
+ * with the current C_s and T_l estimates, further moved by the stall / overfetch feedback counters
+ * (Sec. 3.2.2).  *H_next receives S; prefetch_list [host] [H*E] receives (j << 16 | expert) for the
+ * non-resident experts of the first min(H,S) look-ahead layers, nearest layer first, in descending
+ * demand; *n_prefetch their number.  Also re-tiers the cache for the new S.
+ */
+int ef_choose_horizon(ef_ctx *ctx, int layer, const int32_t *hist_host, int H, int T,
+                      int *H_next, int32_t *prefetch_list, int *n_prefetch);
+
+/* Statistics; synchronises outstanding timing events first (not for the hot loop). */
+int ef_get_stats(ef_ctx *ctx, ef_stats *out);
+int ef_reset_stats(ef_ctx *ctx);
+
+/* Fake-copy contexts only: advance the fake clock; copies complete after bytes/bandwidth seconds. */
+int ef_fake_advance_time(ef_ctx *ctx, double seconds);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EXPERTFLOW_H */

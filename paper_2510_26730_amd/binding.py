@@ -1,0 +1,233 @@
+"""ctypes binding of ``libexpertflow.so``: the same entry points as ``include/expertflow.h``.
+
+Argument marshalling only.  Device buffers are passed as torch tensors (their
+``data_ptr()``) or raw integer addresses, host buffers as numpy arrays.  Every
+step of the hot path runs inside the library's kernels; nothing here computes.
+The library must have been built (``python -m paper_2510_26730_amd.build``);
+a missing library is an error, there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libexpertflow.so")
+
+EF_OK, EF_EINVAL, EF_ENOMEM, EF_EHIP, EF_EBUSY, EF_ENOTRESIDENT, EF_ENOSYS = 0, -1, -2, -3, -4, -5, -6
+EF_FLAG_FAKE_COPY = 1
+EF_FLAG_STRICT_RESIDENT = 2
+EF_MAX_EXPERTS, EF_MAX_TOPK, EF_MAX_HORIZON = 64, 8, 7
+
+EXPORTS = [
+    "ef_strerror", "ef_expert_bytes", "ef_pack_expert", "ef_create", "ef_destroy", "ef_last_error",
+    "ef_register_layer", "ef_predict", "ef_route", "ef_moe_ffn", "ef_cache_swap_in", "ef_cache_query",
+    "ef_choose_horizon", "ef_get_stats", "ef_reset_stats", "ef_fake_advance_time",
+]
+
+
+class ef_config(C.Structure):
+    _fields_ = [
+        ("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_experts", C.c_int32), ("top_k", C.c_int32),
+        ("d_ff", C.c_int32), ("d_ff_shared", C.c_int32), ("slots_total", C.c_int32),
+        ("slots_per_layer_max", C.c_int32), ("max_tokens", C.c_int32), ("h_max", C.c_int32),
+        ("renorm_topk", C.c_int32), ("routed_scale", C.c_float), ("cum_threshold", C.c_float),
+        ("stall_thresh", C.c_int32), ("overfetch_thresh", C.c_int32), ("flags", C.c_uint32),
+        ("init_bandwidth_gbps", C.c_float), ("init_layer_us", C.c_float),
+    ]
+
+
+class ef_stats(C.Structure):
+    _fields_ = [
+        ("hits", C.c_int64), ("misses", C.c_int64), ("prefetch_issued", C.c_int64),
+        ("prefetch_redundant", C.c_int64), ("evictions", C.c_int64), ("bytes_copied", C.c_int64),
+        ("layers_run", C.c_int64), ("tokens_run", C.c_int64), ("copy_seconds", C.c_double),
+        ("stall_seconds", C.c_double), ("layer_seconds", C.c_double), ("bandwidth_Bps", C.c_double),
+        ("layer_seconds_est", C.c_double), ("miss_rate", C.c_double), ("horizon", C.c_int32),
+        ("stall_counter", C.c_int32), ("overfetch_counter", C.c_int32),
+    ]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class EfError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"expertflow error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Load the built library; fails loudly if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is not built; run python -m paper_2510_26730_amd.build")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, f32 = C.c_void_p, C.c_int, C.c_float
+        L.ef_strerror.restype = C.c_char_p
+        L.ef_strerror.argtypes = [i32]
+        L.ef_expert_bytes.restype = C.c_size_t
+        L.ef_expert_bytes.argtypes = [i32, i32]
+        L.ef_pack_expert.argtypes = [vp, vp, vp, i32, i32, vp]
+        L.ef_create.argtypes = [C.POINTER(ef_config), C.POINTER(vp)]
+        L.ef_destroy.argtypes = [vp]
+        L.ef_last_error.restype = C.c_char_p
+        L.ef_last_error.argtypes = [vp]
+        L.ef_register_layer.argtypes = [vp, i32, vp, vp, vp, vp]
+        L.ef_predict.argtypes = [vp, i32, vp, i32, i32, vp, vp, f32, vp, vp, C.POINTER(i32), vp]
+        L.ef_route.argtypes = [vp, i32, vp, i32, f32, vp, vp, vp, vp, vp, vp, vp]
+        L.ef_moe_ffn.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.ef_cache_swap_in.argtypes = [vp, i32, i32, i32, i32, C.POINTER(i32)]
+        L.ef_cache_query.argtypes = [vp, i32, vp]
+        L.ef_choose_horizon.argtypes = [vp, i32, vp, i32, i32, C.POINTER(i32), vp, C.POINTER(i32)]
+        L.ef_get_stats.argtypes = [vp, C.POINTER(ef_stats)]
+        L.ef_reset_stats.argtypes = [vp]
+        L.ef_fake_advance_time.argtypes = [vp, C.c_double]
+        _lib = L
+    return _lib
+
+
+def _ptr(x):
+    """Address of a torch tensor / numpy array / raw int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if isinstance(x, np.ndarray):
+        assert x.flags["C_CONTIGUOUS"]
+        return x.ctypes.data
+    assert x.is_contiguous()
+    return x.data_ptr()
+
+
+def _check(ctx, rc):
+    if rc != 0:
+        text = lib().ef_last_error(ctx)
+        raise EfError(rc, (text or b"").decode())
+    return rc
+
+
+def _stream(stream):
+    if stream is None:
+        return None
+    return stream if isinstance(stream, int) else stream.cuda_stream
+
+
+# ---- utilities ------------------------------------------------------------------------------
+
+def ef_strerror(code):
+    return lib().ef_strerror(code).decode()
+
+
+def ef_expert_bytes(d_model, d_ff):
+    return int(lib().ef_expert_bytes(d_model, d_ff))
+
+
+def ef_pack_expert(W1, W3, W2, blob=None):
+    """W1, W3 [F,d], W2 [d,F] uint16 numpy arrays -> packed blob (numpy uint8, or written into `blob`)."""
+    F, d = W1.shape
+    assert W3.shape == (F, d) and W2.shape == (d, F)
+    n = ef_expert_bytes(d, F)
+    if n == 0:
+        raise EfError(EF_EINVAL, "d_model must be a multiple of 64 and d_ff of 32")
+    out = np.empty(n, dtype=np.uint8) if blob is None else blob
+    W1, W3, W2 = (np.ascontiguousarray(w, dtype=np.uint16) for w in (W1, W3, W2))
+    _check(None, lib().ef_pack_expert(_ptr(W1), _ptr(W3), _ptr(W2), d, F, _ptr(out)))
+    return out
+
+
+# ---- context ----------------------------------------------------------------------------------
+
+def ef_create(**kw):
+    """Keyword arguments are the fields of ef_config; returns the opaque context handle."""
+    cfg = ef_config()
+    defaults = dict(d_ff_shared=0, slots_per_layer_max=0, h_max=4, renorm_topk=1, routed_scale=1.0,
+                    cum_threshold=0.9, stall_thresh=4, overfetch_thresh=4, flags=0,
+                    init_bandwidth_gbps=50.0, init_layer_us=200.0)
+    defaults.update(kw)
+    for k, v in defaults.items():
+        setattr(cfg, k, v)
+    h = C.c_void_p()
+    _check(None, lib().ef_create(C.byref(cfg), C.byref(h)))
+    return h
+
+
+def ef_destroy(ctx):
+    return lib().ef_destroy(ctx)
+
+
+def ef_last_error(ctx):
+    return (lib().ef_last_error(ctx) or b"").decode()
+
+
+def ef_register_layer(ctx, layer, gate_w, gate_b, experts, shared_blob=None):
+    return _check(ctx, lib().ef_register_layer(ctx, layer, _ptr(gate_w), _ptr(gate_b), _ptr(experts),
+                                               _ptr(shared_blob)))
+
+
+# ---- hot path ---------------------------------------------------------------------------------
+
+def ef_predict(ctx, layer, hidden, T, H, delta, tok2req, beta, topk_ids, hist, stream=None):
+    """Returns the effective H (clamped at the last layer)."""
+    he = C.c_int(0)
+    _check(ctx, lib().ef_predict(ctx, layer, _ptr(hidden), T, H, _ptr(delta), _ptr(tok2req), beta,
+                                 _ptr(topk_ids), _ptr(hist), C.byref(he), _stream(stream)))
+    return he.value
+
+
+def ef_route(ctx, layer, hidden, T, beta, topk_ids, topk_w, counts, offsets, perm, inv_perm, stream=None):
+    return _check(ctx, lib().ef_route(ctx, layer, _ptr(hidden), T, beta, _ptr(topk_ids), _ptr(topk_w),
+                                      _ptr(counts), _ptr(offsets), _ptr(perm), _ptr(inv_perm),
+                                      _stream(stream)))
+
+
+def ef_moe_ffn(ctx, layer, hidden, T, topk_ids, topk_w, counts_host, offsets, perm, inv_perm, out,
+               stream=None):
+    counts_host = np.ascontiguousarray(counts_host, dtype=np.int32)
+    return _check(ctx, lib().ef_moe_ffn(ctx, layer, _ptr(hidden), T, _ptr(topk_ids), _ptr(topk_w),
+                                        _ptr(counts_host), _ptr(offsets), _ptr(perm), _ptr(inv_perm),
+                                        _ptr(out), _stream(stream)))
+
+
+def ef_cache_swap_in(ctx, layer, expert, priority=0, due_in=0):
+    """Returns the slot."""
+    slot = C.c_int(-1)
+    _check(ctx, lib().ef_cache_swap_in(ctx, layer, expert, priority, due_in, C.byref(slot)))
+    return slot.value
+
+
+def ef_cache_query(ctx, layer, n_experts):
+    r = np.zeros(n_experts, dtype=np.uint8)
+    _check(ctx, lib().ef_cache_query(ctx, layer, _ptr(r)))
+    return r
+
+
+def ef_choose_horizon(ctx, layer, hist_host, T):
+    """hist_host [H,E] int32 numpy.  Returns (H_next, [(j, expert), ...])."""
+    hist_host = np.ascontiguousarray(hist_host, dtype=np.int32)
+    H, E = hist_host.shape if hist_host.ndim == 2 else (0, 0)
+    lst = np.zeros(max(1, H * E), dtype=np.int32)
+    hn, n = C.c_int(0), C.c_int(0)
+    _check(ctx, lib().ef_choose_horizon(ctx, layer, _ptr(hist_host) if H else None, H, T, C.byref(hn),
+                                        _ptr(lst), C.byref(n)))
+    return hn.value, [(int(v) >> 16, int(v) & 0xFFFF) for v in lst[:n.value]]
+
+
+def ef_get_stats(ctx):
+    st = ef_stats()
+    _check(ctx, lib().ef_get_stats(ctx, C.byref(st)))
+    return st.as_dict()
+
+
+def ef_reset_stats(ctx):
+    return _check(ctx, lib().ef_reset_stats(ctx))
+
+
+def ef_fake_advance_time(ctx, seconds):
+    return _check(ctx, lib().ef_fake_advance_time(ctx, seconds))

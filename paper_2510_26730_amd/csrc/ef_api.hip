@@ -1,0 +1,894 @@
+// C-ABI layer: context, expert cache runtime (slots, copy streams, events, estimators, horizon
+// controller) and the launch plans of the hot-path kernels.  Declarations and argument contracts
+// are in include/expertflow.h.
+#include "../../include/expertflow.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <new>
+#include <string>
+#include <thread>
+#include <vector>
+
+#include "ef_cache.h"
+#include "ef_kernels.h"
+
+namespace {
+
+struct LayerReg {
+    const uint16_t *gate_w = nullptr;
+    const float *gate_b = nullptr;
+    const char *experts = nullptr;
+    const void *shared_blob = nullptr;
+    bool set = false;
+};
+
+struct SlotDev {
+    hipEvent_t copy_start = nullptr, ready = nullptr;
+    hipEvent_t last_read = nullptr;   // borrowed from the read-event ring (may be null)
+    bool copy_pending = false;        // a copy was enqueued and not yet seen complete
+    double fake_ready_at = 0.0;       // fake-copy contexts: completion time of the copy
+    size_t copy_bytes = 0;
+};
+
+struct EventPair {
+    hipEvent_t a, b;
+};
+
+}  // namespace
+
+struct ef_ctx {
+    ef_config cfg{};
+    size_t expert_bytes = 0;
+    bool fake = false;
+    std::vector<LayerReg> layers;
+    ef::ExpertCache *cache = nullptr;
+    char *pool = nullptr;
+    std::vector<SlotDev> slots;
+    hipStream_t copy_stream[2] = {nullptr, nullptr};  // [0] prefetch, [1] miss
+    // scratch
+    int32_t *blockcounts = nullptr, *blockbase = nullptr;
+    void *xp = nullptr, *act = nullptr;
+    float *y = nullptr;
+    int max_tiles = 0;
+    // event rings
+    std::vector<hipEvent_t> read_ring;
+    size_t read_next = 0;
+    std::vector<EventPair> stall_ring, layer_ring;
+    size_t stall_next = 0, layer_next = 0;
+    std::deque<EventPair> stall_pending, layer_pending;
+    bool layer_open = false;
+    EventPair layer_cur{nullptr, nullptr};
+    // estimators and feedback
+    double bw_Bps = 50e9, layer_s = 200e-6;
+    int horizon = 1, fb_adjust = 0;
+    int stall_counter = 0, overfetch_counter = 0;
+    ef_stats st{};
+    // fake clock
+    double fake_now = 0.0, fake_engine_free[2] = {0.0, 0.0};
+    std::string err;
+};
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(ef_ctx *ctx, int code, const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (ctx) ctx->err = buf;
+    g_err = buf;
+    return code;
+}
+
+#define EF_HIP(ctx, call)                                                                       \
+    do {                                                                                        \
+        hipError_t _e = (call);                                                                 \
+        if (_e != hipSuccess)                                                                   \
+            return fail(ctx, EF_EHIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(_e),    \
+                        __FILE__, __LINE__);                                                    \
+    } while (0)
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+void ema(double &est, double sample, double alpha = 0.25) { est = (1.0 - alpha) * est + alpha * sample; }
+
+// ---- completion polling ---------------------------------------------------------------------
+
+void poll_copy(ef_ctx *c, int slot) {
+    SlotDev &s = c->slots[(size_t)slot];
+    if (!s.copy_pending) return;
+    if (c->fake) {
+        if (c->fake_now >= s.fake_ready_at) s.copy_pending = false;
+        return;
+    }
+    if (hipEventQuery(s.ready) == hipSuccess) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, s.copy_start, s.ready) == hipSuccess && ms > 0.f) {
+            double sec = ms * 1e-3;
+            c->st.copy_seconds += sec;
+            ema(c->bw_Bps, (double)s.copy_bytes / sec);
+        }
+        s.copy_pending = false;
+    } else {
+        (void)hipGetLastError();  // hipErrorNotReady is not an error
+    }
+}
+
+void poll_all_copies(ef_ctx *c) {
+    for (int s = 0; s < (int)c->slots.size(); ++s) poll_copy(c, s);
+}
+
+void poll_pairs(ef_ctx *c, bool wait) {
+    if (c->fake) return;
+    while (!c->stall_pending.empty()) {
+        EventPair p = c->stall_pending.front();
+        hipError_t q = wait ? hipEventSynchronize(p.b) : hipEventQuery(p.b);
+        if (q != hipSuccess) { (void)hipGetLastError(); break; }
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess) c->st.stall_seconds += ms * 1e-3;
+        c->stall_pending.pop_front();
+    }
+    while (!c->layer_pending.empty()) {
+        EventPair p = c->layer_pending.front();
+        hipError_t q = wait ? hipEventSynchronize(p.b) : hipEventQuery(p.b);
+        if (q != hipSuccess) { (void)hipGetLastError(); break; }
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess && ms > 0.f) {
+            c->st.layer_seconds += ms * 1e-3;
+            ema(c->layer_s, ms * 1e-3);
+        }
+        c->layer_pending.pop_front();
+    }
+}
+
+EventPair next_pair(std::vector<EventPair> &ring, size_t &next, std::deque<EventPair> &pending) {
+    // never hand out a pair that is still waiting to be read
+    if (pending.size() >= ring.size()) {
+        EventPair p = pending.front();
+        (void)hipEventSynchronize(p.b);
+        pending.pop_front();
+    }
+    EventPair p = ring[next];
+    next = (next + 1) % ring.size();
+    return p;
+}
+
+uint64_t resident_mask(ef_ctx *c, int layer) {
+    uint64_t m = 0;
+    for (int e = 0; e < c->cfg.n_experts; ++e)
+        if (c->cache->lookup(layer, e) >= 0) m |= (1ull << e);
+    return m;
+}
+
+// ---- swap-in ---------------------------------------------------------------------------------
+
+int swap_in_impl(ef_ctx *c, int layer, int expert, int priority, int due_in, int *slot_out, bool *loaded) {
+    int slot = -1, evl = -1, eve = -1;
+    if (loaded) *loaded = false;
+    ef::SwapResult r = c->cache->swap_in(layer, expert, priority ? 0 : due_in, &slot, &evl, &eve);
+    if (r == ef::SwapResult::Busy)
+        return fail(c, EF_EBUSY, "no evictable cache slot for layer %d expert %d", layer, expert);
+    if (slot_out) *slot_out = slot;
+    if (r == ef::SwapResult::Hit) {
+        if (!priority) c->st.prefetch_redundant += 1;
+        return EF_OK;
+    }
+    if (evl >= 0) c->st.evictions += 1;
+    SlotDev &s = c->slots[(size_t)slot];
+    const size_t bytes = c->expert_bytes;
+    const int q = priority ? 1 : 0;
+    if (c->fake) {
+        double start = std::max(c->fake_now, c->fake_engine_free[q]);
+        s.fake_ready_at = start + (double)bytes / c->bw_Bps;
+        c->fake_engine_free[q] = s.fake_ready_at;
+        c->st.copy_seconds += (double)bytes / c->bw_Bps;
+    } else {
+        hipStream_t cs = c->copy_stream[q];
+        hipError_t e = hipSuccess;
+        // the slot may still be read by an enqueued FFN, or written by an earlier copy on the other stream
+        if (s.last_read) e = hipStreamWaitEvent(cs, s.last_read, 0);
+        if (e == hipSuccess && s.copy_pending) e = hipStreamWaitEvent(cs, s.ready, 0);
+        if (e == hipSuccess) e = hipEventRecord(s.copy_start, cs);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(c->pool + (size_t)slot * bytes,
+                               c->layers[(size_t)layer].experts + (size_t)expert * bytes, bytes,
+                               hipMemcpyHostToDevice, cs);
+        if (e == hipSuccess) e = hipEventRecord(s.ready, cs);
+        if (e != hipSuccess) {
+            c->cache->drop(slot);
+            return fail(c, EF_EHIP, "swap-in of layer %d expert %d failed: %s", layer, expert,
+                        hipGetErrorString(e));
+        }
+    }
+    s.copy_pending = true;
+    s.copy_bytes = bytes;
+    s.last_read = nullptr;
+    c->st.bytes_copied += (int64_t)bytes;
+    if (!priority) c->st.prefetch_issued += 1;
+    if (loaded) *loaded = true;
+    return EF_OK;
+}
+
+int check_ctx_layer(ef_ctx *c, int layer) {
+    if (!c) return fail(nullptr, EF_EINVAL, "null context");
+    if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, EF_EINVAL, "layer %d out of range", layer);
+    if (!c->layers[(size_t)layer].set) return fail(c, EF_EINVAL, "layer %d is not registered", layer);
+    return EF_OK;
+}
+
+}  // namespace
+
+// =================================================================================================
+// utilities
+// =================================================================================================
+
+extern "C" const char *ef_strerror(int code) {
+    switch (code) {
+        case EF_OK: return "ok";
+        case EF_EINVAL: return "invalid argument";
+        case EF_ENOMEM: return "out of memory";
+        case EF_EHIP: return "HIP runtime error";
+        case EF_EBUSY: return "no evictable cache slot";
+        case EF_ENOTRESIDENT: return "expert not resident";
+        case EF_ENOSYS: return "not available in this context";
+        default: return "unknown error";
+    }
+}
+
+extern "C" size_t ef_expert_bytes(int d, int F) {
+    if (d <= 0 || F <= 0 || d % 64 != 0 || F % 32 != 0) return 0;
+    return (size_t)3 * (size_t)d * (size_t)F * 2;
+}
+
+extern "C" int ef_pack_expert(const uint16_t *W1, const uint16_t *W3, const uint16_t *W2, int d, int F,
+                              void *blob) {
+    if (!W1 || !W3 || !W2 || !blob) return fail(nullptr, EF_EINVAL, "ef_pack_expert: null pointer");
+    if (ef_expert_bytes(d, F) == 0) return fail(nullptr, EF_EINVAL, "ef_pack_expert: d %% 64 or F %% 32 != 0");
+    uint16_t *out = static_cast<uint16_t *>(blob);
+    const int nkb = d / 16, nrb = F / 32, ncb = d / 32, nkb2 = F / 16;
+    auto section_a = [&](int rb0, int rb1) {
+        for (int rb = rb0; rb < rb1; ++rb)
+            for (int which = 0; which < 2; ++which) {
+                const uint16_t *W = which ? W3 : W1;
+                uint16_t *dst = out + ((size_t)rb * 2 + which) * nkb * 512;
+                for (int kb = 0; kb < nkb; ++kb)
+                    for (int lane = 0; lane < 64; ++lane) {
+                        int g = lane >> 5, i = lane & 31;
+                        memcpy(dst + ((size_t)kb * 64 + lane) * 8,
+                               W + (size_t)(rb * 32 + i) * d + kb * 16 + 8 * g, 16);
+                    }
+            }
+    };
+    auto section_b = [&](int cb0, int cb1) {
+        uint16_t *base = out + (size_t)2 * d * F;
+        for (int cb = cb0; cb < cb1; ++cb)
+            for (int kb = 0; kb < nkb2; ++kb)
+                for (int lane = 0; lane < 64; ++lane) {
+                    int g = lane >> 5, i = lane & 31;
+                    const uint16_t *src = W2 + (size_t)(cb * 32 + i) * F + kb * 16 + 4 * g;
+                    uint16_t *dst = base + (((size_t)cb * nkb2 + kb) * 64 + lane) * 8;
+                    memcpy(dst, src, 8);          // t = 0..3 -> columns 4g + t
+                    memcpy(dst + 4, src + 8, 8);  // t = 4..7 -> columns 8 + 4g + (t-4)
+                }
+    };
+    unsigned hw = std::thread::hardware_concurrency();
+    int nth = (int)std::min<unsigned>(hw ? hw : 1, 16);
+    if ((size_t)d * F < (1u << 20)) nth = 1;
+    std::vector<std::thread> th;
+    for (int t = 0; t < nth; ++t)
+        th.emplace_back([&, t] {
+            section_a((int)((long long)nrb * t / nth), (int)((long long)nrb * (t + 1) / nth));
+            section_b((int)((long long)ncb * t / nth), (int)((long long)ncb * (t + 1) / nth));
+        });
+    for (auto &t : th) t.join();
+    return EF_OK;
+}
+
+// =================================================================================================
+// context
+// =================================================================================================
+
+extern "C" int ef_destroy(ef_ctx *c) {
+    if (!c) return EF_OK;
+    if (!c->fake) {
+        (void)hipDeviceSynchronize();
+        for (auto &s : c->slots) {
+            if (s.copy_start) (void)hipEventDestroy(s.copy_start);
+            if (s.ready) (void)hipEventDestroy(s.ready);
+        }
+        for (auto e : c->read_ring) (void)hipEventDestroy(e);
+        for (auto &p : c->stall_ring) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+        for (auto &p : c->layer_ring) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+        for (int q = 0; q < 2; ++q)
+            if (c->copy_stream[q]) (void)hipStreamDestroy(c->copy_stream[q]);
+        if (c->pool) (void)hipFree(c->pool);
+        if (c->blockcounts) (void)hipFree(c->blockcounts);
+        if (c->blockbase) (void)hipFree(c->blockbase);
+        if (c->xp) (void)hipFree(c->xp);
+        if (c->act) (void)hipFree(c->act);
+        if (c->y) (void)hipFree(c->y);
+    }
+    delete c->cache;
+    delete c;
+    return EF_OK;
+}
+
+extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
+    if (!cfg || !out) return fail(nullptr, EF_EINVAL, "ef_create: null argument");
+    *out = nullptr;
+    const ef_config &g = *cfg;
+    if (g.n_layers <= 0 || g.n_experts <= 0 || g.n_experts > EF_MAX_EXPERTS || g.top_k <= 0 ||
+        g.top_k > EF_MAX_TOPK || g.top_k > g.n_experts)
+        return fail(nullptr, EF_EINVAL, "ef_create: need 1 <= top_k <= min(n_experts, %d), n_experts <= %d",
+                    EF_MAX_TOPK, EF_MAX_EXPERTS);
+    if (ef_expert_bytes(g.d_model, g.d_ff) == 0)
+        return fail(nullptr, EF_EINVAL, "ef_create: d_model must be a multiple of 64 and d_ff of 32");
+    if (g.d_ff_shared < 0 || g.d_ff_shared % 32 != 0)
+        return fail(nullptr, EF_EINVAL, "ef_create: d_ff_shared must be a non-negative multiple of 32");
+    if (g.slots_total <= 0 || g.slots_per_layer_max < 0 || g.max_tokens <= 0)
+        return fail(nullptr, EF_EINVAL, "ef_create: slots_total and max_tokens must be positive");
+    if (g.h_max < 1 || g.h_max > EF_MAX_HORIZON)
+        return fail(nullptr, EF_EINVAL, "ef_create: h_max must be in 1..%d", EF_MAX_HORIZON);
+    if (!(g.cum_threshold > 0.f && g.cum_threshold <= 1.f))
+        return fail(nullptr, EF_EINVAL, "ef_create: cum_threshold must be in (0, 1]");
+    if ((long long)g.max_tokens * g.top_k > (1ll << 30))
+        return fail(nullptr, EF_EINVAL, "ef_create: max_tokens * top_k too large");
+
+    ef_ctx *c = new (std::nothrow) ef_ctx();
+    if (!c) return fail(nullptr, EF_ENOMEM, "ef_create: host allocation failed");
+    c->cfg = g;
+    c->expert_bytes = ef_expert_bytes(g.d_model, g.d_ff);
+    c->fake = (g.flags & EF_FLAG_FAKE_COPY) != 0;
+    c->layers.resize((size_t)g.n_layers);
+    c->cache = new ef::ExpertCache(g.slots_total, g.slots_per_layer_max, g.n_layers, g.n_experts);
+    c->slots.resize((size_t)g.slots_total);
+    if (g.init_bandwidth_gbps > 0.f) c->bw_Bps = (double)g.init_bandwidth_gbps * 1e9;
+    if (g.init_layer_us > 0.f) c->layer_s = (double)g.init_layer_us * 1e-6;
+    c->horizon = 1;
+    c->cache->set_S(1);
+    if (c->fake) {
+        *out = c;
+        return EF_OK;
+    }
+
+    const int E = g.n_experts, k = g.top_k, d = g.d_model;
+    const long long Tm = g.max_tokens;
+    const int ntile_tok = (int)((Tm + ef::kTile - 1) / ef::kTile);
+    const int routed_tiles = (int)((Tm * k + ef::kTile - 1) / ef::kTile) + E;
+    const int shared_tiles = g.d_ff_shared > 0 ? ntile_tok : 0;
+    c->max_tiles = routed_tiles + shared_tiles;
+    const size_t xp_bytes = (size_t)c->max_tiles * ef::kTile * d * 2;
+    const size_t act_bytes = (size_t)routed_tiles * ef::kTile * g.d_ff * 2 +
+                             (size_t)shared_tiles * ef::kTile * g.d_ff_shared * 2;
+    const size_t y_bytes = (size_t)(Tm * k + (g.d_ff_shared > 0 ? Tm : 0)) * d * 4;
+
+    auto bail = [&](hipError_t e, const char *what) {
+        int rc = fail(nullptr, e == hipErrorOutOfMemory ? EF_ENOMEM : EF_EHIP, "ef_create: %s: %s", what,
+                      hipGetErrorString(e));
+        std::string keep = g_err;
+        ef_destroy(c);
+        g_err = keep;
+        return rc;
+    };
+    hipError_t e;
+    if ((e = hipMalloc(&c->pool, (size_t)g.slots_total * c->expert_bytes)) != hipSuccess) return bail(e, "slot pool");
+    if ((e = hipMalloc(&c->blockcounts, (size_t)ntile_tok * E * 4)) != hipSuccess) return bail(e, "blockcounts");
+    if ((e = hipMalloc(&c->blockbase, (size_t)ntile_tok * E * 4)) != hipSuccess) return bail(e, "blockbase");
+    if ((e = hipMalloc(&c->xp, xp_bytes)) != hipSuccess) return bail(e, "packed-token scratch");
+    if ((e = hipMalloc(&c->act, act_bytes)) != hipSuccess) return bail(e, "activation scratch");
+    if ((e = hipMalloc(&c->y, y_bytes)) != hipSuccess) return bail(e, "expert-output scratch");
+    for (int q = 0; q < 2; ++q)
+        if ((e = hipStreamCreateWithFlags(&c->copy_stream[q], hipStreamNonBlocking)) != hipSuccess)
+            return bail(e, "copy stream");
+    for (auto &s : c->slots) {
+        if ((e = hipEventCreate(&s.copy_start)) != hipSuccess) return bail(e, "event");
+        if ((e = hipEventCreate(&s.ready)) != hipSuccess) return bail(e, "event");
+    }
+    c->read_ring.resize(128);
+    for (auto &ev : c->read_ring)
+        if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
+    c->stall_ring.resize(128);
+    c->layer_ring.resize(128);
+    for (auto *ring : {&c->stall_ring, &c->layer_ring})
+        for (auto &p : *ring) {
+            if ((e = hipEventCreate(&p.a)) != hipSuccess) return bail(e, "event");
+            if ((e = hipEventCreate(&p.b)) != hipSuccess) return bail(e, "event");
+        }
+    *out = c;
+    return EF_OK;
+}
+
+extern "C" const char *ef_last_error(ef_ctx *c) { return c ? c->err.c_str() : g_err.c_str(); }
+
+extern "C" int ef_register_layer(ef_ctx *c, int layer, const void *gate_w, const float *gate_b,
+                                 const void *experts, const void *shared_blob) {
+    if (!c) return fail(nullptr, EF_EINVAL, "null context");
+    if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, EF_EINVAL, "layer %d out of range", layer);
+    if (!experts) return fail(c, EF_EINVAL, "ef_register_layer: experts is null");
+    if (!c->fake) {
+        if (!gate_w) return fail(c, EF_EINVAL, "ef_register_layer: gate_w is null");
+        if (!aligned16(gate_w) || !aligned16(experts) || !aligned16(shared_blob))
+            return fail(c, EF_EINVAL, "ef_register_layer: pointers must be 16-byte aligned");
+        if (c->cfg.d_ff_shared > 0 && !shared_blob)
+            return fail(c, EF_EINVAL, "ef_register_layer: shared_blob required when d_ff_shared > 0");
+    }
+    LayerReg &L = c->layers[(size_t)layer];
+    L.gate_w = static_cast<const uint16_t *>(gate_w);
+    L.gate_b = gate_b;
+    L.experts = static_cast<const char *>(experts);
+    L.shared_blob = shared_blob;
+    L.set = true;
+    return EF_OK;
+}
+
+// =================================================================================================
+// hot path
+// =================================================================================================
+
+extern "C" int ef_predict(ef_ctx *c, int layer, const void *hidden, int T, int H, const float *delta,
+                          const int32_t *tok2req, float beta, int32_t *topk_ids, int32_t *hist, int *H_eff,
+                          void *stream) {
+    int rc = check_ctx_layer(c, layer);
+    if (rc) return rc;
+    if (c->fake) return fail(c, EF_ENOSYS, "ef_predict: fake-copy context has no device");
+    if (H < 0 || H > EF_MAX_HORIZON) return fail(c, EF_EINVAL, "ef_predict: H must be in 0..%d", EF_MAX_HORIZON);
+    if (T < 0 || T > c->cfg.max_tokens) return fail(c, EF_EINVAL, "ef_predict: T=%d outside 0..max_tokens", T);
+    int He = std::min(H, c->cfg.n_layers - 1 - layer);
+    if (H_eff) *H_eff = He;
+    if (He <= 0) {
+        if (H_eff) *H_eff = 0;
+        return EF_OK;
+    }
+    if (T == 0) {
+        if (!hist) return fail(c, EF_EINVAL, "ef_predict: null pointer");
+        EF_HIP(c, ef::launch_fill_i32(hist, He * c->cfg.n_experts, 0, static_cast<hipStream_t>(stream)));
+        return EF_OK;
+    }
+    if (!hidden || !topk_ids || !hist) return fail(c, EF_EINVAL, "ef_predict: null pointer");
+    if (!aligned16(hidden)) return fail(c, EF_EINVAL, "ef_predict: hidden must be 16-byte aligned");
+    for (int j = 1; j <= He; ++j)
+        if (!c->layers[(size_t)(layer + j)].set)
+            return fail(c, EF_EINVAL, "ef_predict: layer %d is not registered", layer + j);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int E = c->cfg.n_experts, k = c->cfg.top_k;
+    EF_HIP(c, ef::launch_fill_i32(hist, He * E, 0, s));
+    const int per_launch = std::max(1, std::min(ef::kMaxGates, ef::kGateMaxCols / E));
+    for (int j0 = 0; j0 < He; j0 += per_launch) {
+        ef::GateArgs a{};
+        a.h = static_cast<const uint16_t *>(hidden);
+        a.T = T; a.d = c->cfg.d_model; a.E = E; a.k = k;
+        a.G = std::min(per_launch, He - j0);
+        for (int gidx = 0; gidx < a.G; ++gidx) {
+            const LayerReg &L = c->layers[(size_t)(layer + 1 + j0 + gidx)];
+            a.Wg[gidx] = L.gate_w;
+            a.bias[gidx] = L.gate_b;
+            a.resident[gidx] = resident_mask(c, layer + 1 + j0 + gidx);
+        }
+        a.beta = beta;
+        a.delta = delta ? delta + (size_t)j0 * E : nullptr;
+        a.delta_req_stride = H * E;
+        a.tok2req = tok2req;
+        a.ids = topk_ids + (size_t)j0 * T * k;
+        a.w = nullptr;
+        a.renorm = 0; a.routed_scale = 1.f;
+        a.hist = hist + (size_t)j0 * E;
+        a.blockcounts = nullptr;
+        EF_HIP(c, ef::launch_gate(a, s));
+    }
+    return EF_OK;
+}
+
+extern "C" int ef_route(ef_ctx *c, int layer, const void *hidden, int T, float beta, int32_t *topk_ids,
+                        float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
+                        void *stream) {
+    int rc = check_ctx_layer(c, layer);
+    if (rc) return rc;
+    if (c->fake) return fail(c, EF_ENOSYS, "ef_route: fake-copy context has no device");
+    if (T < 0 || T > c->cfg.max_tokens) return fail(c, EF_EINVAL, "ef_route: T=%d outside 0..max_tokens", T);
+    if (!counts || !offsets) return fail(c, EF_EINVAL, "ef_route: null pointer");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int E = c->cfg.n_experts, k = c->cfg.top_k;
+    if (T == 0) {
+        EF_HIP(c, ef::launch_fill_i32(counts, E, 0, s));
+        EF_HIP(c, ef::launch_fill_i32(offsets, E + 1, 0, s));
+        return EF_OK;
+    }
+    if (!hidden || !topk_ids || !topk_w || !perm || !inv_perm) return fail(c, EF_EINVAL, "ef_route: null pointer");
+    if (!aligned16(hidden)) return fail(c, EF_EINVAL, "ef_route: hidden must be 16-byte aligned");
+
+    poll_pairs(c, false);
+    c->layer_cur = next_pair(c->layer_ring, c->layer_next, c->layer_pending);
+    EF_HIP(c, hipEventRecord(c->layer_cur.a, s));
+    c->layer_open = true;
+
+    const LayerReg &L = c->layers[(size_t)layer];
+    ef::GateArgs a{};
+    a.h = static_cast<const uint16_t *>(hidden);
+    a.T = T; a.d = c->cfg.d_model; a.E = E; a.k = k; a.G = 1;
+    a.Wg[0] = L.gate_w;
+    a.bias[0] = L.gate_b;
+    a.resident[0] = resident_mask(c, layer);
+    a.beta = beta;
+    a.delta = nullptr; a.delta_req_stride = 0; a.tok2req = nullptr;
+    a.ids = topk_ids;
+    a.w = topk_w;
+    a.renorm = c->cfg.renorm_topk;
+    a.routed_scale = c->cfg.routed_scale;
+    a.hist = nullptr;
+    a.blockcounts = c->blockcounts;
+    const int ntiles = (T + ef::kTile - 1) / ef::kTile;
+    EF_HIP(c, ef::launch_gate(a, s));
+    EF_HIP(c, ef::launch_group_scan(c->blockcounts, ntiles, E, c->blockbase, counts, offsets, s));
+    EF_HIP(c, ef::launch_group_scatter(topk_ids, T, k, E, c->blockbase, offsets, perm, inv_perm, s));
+    return EF_OK;
+}
+
+extern "C" int ef_cache_swap_in(ef_ctx *c, int layer, int expert, int priority, int due_in, int *slot_out) {
+    int rc = check_ctx_layer(c, layer);
+    if (rc) return rc;
+    if (expert < 0 || expert >= c->cfg.n_experts) return fail(c, EF_EINVAL, "expert %d out of range", expert);
+    if (priority != 0 && priority != 1) return fail(c, EF_EINVAL, "priority must be 0 or 1");
+    if (due_in < 0) return fail(c, EF_EINVAL, "due_in must be >= 0");
+    poll_all_copies(c);
+    return swap_in_impl(c, layer, expert, priority, due_in, slot_out, nullptr);
+}
+
+extern "C" int ef_cache_query(ef_ctx *c, int layer, uint8_t *resident_host) {
+    if (!c) return fail(nullptr, EF_EINVAL, "null context");
+    if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, EF_EINVAL, "layer %d out of range", layer);
+    if (!resident_host) return fail(c, EF_EINVAL, "ef_cache_query: null pointer");
+    for (int e = 0; e < c->cfg.n_experts; ++e) resident_host[e] = c->cache->lookup(layer, e) >= 0 ? 1 : 0;
+    return EF_OK;
+}
+
+namespace {
+
+struct PhaseGroup {
+    int expert;  // -1: dense shared FFN
+    int slot;
+};
+
+// Build the launch tables of one phase and enqueue both FFN halves.
+int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, const int32_t *counts_host,
+                 const std::vector<int> &offs_host, const std::vector<int> &tile_start,
+                 const std::vector<long long> &act_off, int shared_tile_start, long long shared_act_off, int T,
+                 hipStream_t s) {
+    if (groups.empty()) return EF_OK;
+    const int d = c->cfg.d_model, k = c->cfg.top_k;
+    ef::GroupTable gu{}, dn{};
+    int n = 0, max_tiles = 1;
+    for (const PhaseGroup &pg : groups) {
+        int cnt, ts, F, ro;
+        long long ao;
+        const void *blob;
+        if (pg.expert < 0) {
+            cnt = T; ts = shared_tile_start; F = c->cfg.d_ff_shared; ro = T * k; ao = shared_act_off;
+            blob = c->layers[(size_t)layer].shared_blob;
+        } else {
+            cnt = counts_host[pg.expert]; ts = tile_start[(size_t)pg.expert]; F = c->cfg.d_ff;
+            ro = offs_host[(size_t)pg.expert]; ao = act_off[(size_t)pg.expert];
+            blob = c->pool + (size_t)pg.slot * c->expert_bytes;
+        }
+        gu.tile_start[n] = ts; gu.n_tiles[n] = (cnt + ef::kTile - 1) / ef::kTile; gu.row_offset[n] = ro;
+        gu.count[n] = cnt; gu.F[n] = F; gu.act_off[n] = ao; gu.blob[n] = blob;
+        max_tiles = std::max(max_tiles, gu.n_tiles[n]);
+        ++n;
+    }
+    gu.n_groups = n;
+    dn = gu;
+    const int tpp = max_tiles >= 2 ? 2 : 1;
+    int wg_gu = 0, wg_dn = 0;
+    for (int i = 0; i < n; ++i) {
+        gu.wg_start[i] = wg_gu;
+        dn.wg_start[i] = wg_dn;
+        wg_gu += ef::ffn_gate_up_wgs(gu.F[i], gu.n_tiles[i], tpp);
+        wg_dn += ef::ffn_down_wgs(d, gu.n_tiles[i], tpp);
+    }
+    gu.wg_start[n] = wg_gu;
+    dn.wg_start[n] = wg_dn;
+    EF_HIP(c, ef::launch_ffn_gate_up(gu, wg_gu, tpp, c->xp, c->act, d, s));
+    EF_HIP(c, ef::launch_ffn_down(dn, wg_dn, tpp, c->act, c->y, d, s));
+    return EF_OK;
+}
+
+}  // namespace
+
+extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const int32_t *topk_ids,
+                          const float *topk_w, const int32_t *counts_host, const int32_t *offsets,
+                          const int32_t *perm, const int32_t *inv_perm, float *out, void *stream) {
+    int rc = check_ctx_layer(c, layer);
+    if (rc) return rc;
+    if (T < 0 || T > c->cfg.max_tokens) return fail(c, EF_EINVAL, "ef_moe_ffn: T=%d outside 0..max_tokens", T);
+    if (!counts_host) return fail(c, EF_EINVAL, "ef_moe_ffn: counts_host is null");
+    const int E = c->cfg.n_experts, k = c->cfg.top_k, d = c->cfg.d_model;
+    long long tot = 0;
+    for (int e = 0; e < E; ++e) {
+        if (counts_host[e] < 0 || counts_host[e] > T)
+            return fail(c, EF_EINVAL, "ef_moe_ffn: counts_host[%d]=%d outside 0..T", e, counts_host[e]);
+        tot += counts_host[e];
+    }
+    if (tot != (long long)T * k) return fail(c, EF_EINVAL, "ef_moe_ffn: counts_host sums to %lld, not T*k", tot);
+    if (!c->fake && T > 0) {
+        if (!hidden || !topk_ids || !topk_w || !offsets || !perm || !inv_perm || !out)
+            return fail(c, EF_EINVAL, "ef_moe_ffn: null pointer");
+        if (!aligned16(hidden) || !aligned16(out)) return fail(c, EF_EINVAL, "ef_moe_ffn: hidden/out must be 16-byte aligned");
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool strict = (c->cfg.flags & EF_FLAG_STRICT_RESIDENT) != 0;
+    poll_all_copies(c);
+
+    // host copies of the group geometry
+    std::vector<int> offs_host((size_t)E + 1, 0), tile_start((size_t)E, 0);
+    std::vector<long long> act_off((size_t)E, 0);
+    int tiles = 0;
+    for (int e = 0; e < E; ++e) {
+        offs_host[(size_t)e + 1] = offs_host[(size_t)e] + counts_host[e];
+        tile_start[(size_t)e] = tiles;
+        act_off[(size_t)e] = (long long)tiles * ef::kTile * c->cfg.d_ff / 8;   // 16-byte units
+        tiles += (counts_host[e] + ef::kTile - 1) / ef::kTile;
+    }
+    const bool has_shared = c->cfg.d_ff_shared > 0 && T > 0;
+    const int shared_tile_start = tiles;
+    const long long shared_act_off = (long long)tiles * ef::kTile * c->cfg.d_ff / 8;
+    if (has_shared) tiles += (T + ef::kTile - 1) / ef::kTile;
+    if (!c->fake && tiles > c->max_tiles) return fail(c, EF_EINVAL, "ef_moe_ffn: scratch too small (internal)");
+
+    // classify the needed experts
+    std::vector<PhaseGroup> ready, loading;
+    std::vector<int> missing;
+    bool any_not_ready = false;
+    for (int e = 0; e < E; ++e) {
+        if (counts_host[e] == 0) continue;
+        int slot = c->cache->lookup(layer, e);
+        if (slot < 0) {
+            if (strict) {
+                for (const auto &g : ready) c->cache->pin(g.slot, false);
+                for (const auto &g : loading) c->cache->pin(g.slot, false);
+                return fail(c, EF_ENOTRESIDENT, "ef_moe_ffn: layer %d expert %d is not resident", layer, e);
+            }
+            missing.push_back(e);
+            any_not_ready = true;
+            c->st.misses += 1;
+            continue;
+        }
+        c->st.hits += 1;
+        c->cache->touch(slot);
+        c->cache->pin(slot, true);
+        if (c->slots[(size_t)slot].copy_pending) { loading.push_back({e, slot}); any_not_ready = true; }
+        else ready.push_back({e, slot});
+    }
+    // feedback counters (paper Sec. 3.2.2): a layer that had to wait counts as a stall, a layer
+    // whose experts were all loaded in time counts as an overfetch
+    if (T > 0) {
+        if (any_not_ready) {
+            if (++c->stall_counter >= std::max(1, c->cfg.stall_thresh)) { c->stall_counter = 0; c->fb_adjust += 1; }
+        } else {
+            if (++c->overfetch_counter >= std::max(1, c->cfg.overfetch_thresh)) { c->overfetch_counter = 0; c->fb_adjust -= 1; }
+        }
+        c->fb_adjust = std::max(-(c->cfg.h_max - 1), std::min(c->cfg.h_max - 1, c->fb_adjust));
+    }
+
+    auto unpin_all = [&](const std::vector<PhaseGroup> &v) {
+        for (const auto &g : v)
+            if (g.expert >= 0) c->cache->pin(g.slot, false);
+    };
+    // start what misses can start right now (slots not needed by this layer)
+    std::vector<int> deferred;
+    for (int e : missing) {
+        int slot = -1;
+        int r = swap_in_impl(c, layer, e, 1, 0, &slot, nullptr);
+        if (r == EF_EBUSY) { deferred.push_back(e); continue; }
+        if (r != EF_OK) { unpin_all(ready); unpin_all(loading); return r; }
+        c->cache->touch(slot);
+        c->cache->pin(slot, true);
+        loading.push_back({e, slot});
+    }
+
+    auto mark_read = [&](const std::vector<PhaseGroup> &v) -> int {
+        if (c->fake) { unpin_all(v); return EF_OK; }
+        hipEvent_t ev = c->read_ring[c->read_next];
+        c->read_next = (c->read_next + 1) % c->read_ring.size();
+        EF_HIP(c, hipEventRecord(ev, s));
+        for (const auto &g : v)
+            if (g.expert >= 0) c->slots[(size_t)g.slot].last_read = ev;
+        unpin_all(v);
+        return EF_OK;
+    };
+    auto wait_loaded = [&](const std::vector<PhaseGroup> &v) -> int {
+        if (v.empty()) return EF_OK;
+        if (c->fake) {
+            double need = c->fake_now;
+            for (const auto &g : v) need = std::max(need, c->slots[(size_t)g.slot].fake_ready_at);
+            c->st.stall_seconds += need - c->fake_now;
+            c->fake_now = need;
+            for (const auto &g : v) poll_copy(c, g.slot);
+            return EF_OK;
+        }
+        EventPair p = next_pair(c->stall_ring, c->stall_next, c->stall_pending);
+        EF_HIP(c, hipEventRecord(p.a, s));
+        for (const auto &g : v) EF_HIP(c, hipStreamWaitEvent(s, c->slots[(size_t)g.slot].ready, 0));
+        EF_HIP(c, hipEventRecord(p.b, s));
+        c->stall_pending.push_back(p);
+        return EF_OK;
+    };
+    auto run_phase = [&](std::vector<PhaseGroup> &v, bool with_shared) -> int {
+        std::vector<PhaseGroup> g = v;
+        if (with_shared && has_shared) g.push_back({-1, -1});
+        if (!c->fake) {
+            int r = launch_phase(c, layer, g, counts_host, offs_host, tile_start, act_off, shared_tile_start,
+                                 shared_act_off, T, s);
+            if (r) return r;
+        }
+        return mark_read(v);
+    };
+
+    if (T > 0) {
+        if (!c->fake) {
+            // token permutation into per-expert tiles (all groups of this layer in one launch)
+            ef::PackTable pt{};
+            int n = 0;
+            for (int e = 0; e < E; ++e) {
+                if (counts_host[e] == 0) continue;
+                pt.tile_start[n] = tile_start[(size_t)e];
+                pt.row_offset[n] = offs_host[(size_t)e];
+                pt.count[n] = counts_host[e];
+                ++n;
+            }
+            if (has_shared) {
+                pt.tile_start[n] = shared_tile_start;
+                pt.row_offset[n] = -1;
+                pt.count[n] = T;
+                ++n;
+            }
+            pt.tile_start[n] = tiles;
+            pt.n_groups = n;
+            int r = EF_OK;
+            hipError_t he = ef::launch_pack_x(pt, tiles, static_cast<const uint16_t *>(hidden), d, k, perm, c->xp, s);
+            if (he != hipSuccess) r = fail(c, EF_EHIP, "pack_x launch failed: %s", hipGetErrorString(he));
+            if (r) { unpin_all(ready); unpin_all(loading); return r; }
+        }
+        // phase A: experts that are ready (+ the dense shared FFN): tokens whose experts are resident go first
+        rc = run_phase(ready, true);
+        if (rc) { unpin_all(loading); return rc; }
+        // phase B: experts whose copy is in flight (earlier prefetches and the misses started above)
+        if (!loading.empty()) {
+            rc = wait_loaded(loading);
+            if (!rc) rc = run_phase(loading, false);
+            if (rc) { unpin_all(loading); return rc; }
+        }
+        // phase C: misses that had no slot until an earlier phase released one
+        size_t next = 0;
+        while (next < deferred.size()) {
+            std::vector<PhaseGroup> wave;
+            while (next < deferred.size()) {
+                int slot = -1;
+                int r = swap_in_impl(c, layer, deferred[next], 1, 0, &slot, nullptr);
+                if (r == EF_EBUSY) break;
+                if (r != EF_OK) { unpin_all(wave); return r; }
+                c->cache->touch(slot);
+                c->cache->pin(slot, true);
+                wave.push_back({deferred[next], slot});
+                ++next;
+            }
+            if (wave.empty()) return fail(c, EF_EBUSY, "ef_moe_ffn: no cache slot can be freed for layer %d", layer);
+            rc = wait_loaded(wave);
+            if (!rc) rc = run_phase(wave, false);
+            if (rc) { unpin_all(wave); return rc; }
+        }
+        if (!c->fake) {
+            const float *shared_y = has_shared ? c->y + (size_t)T * k * d : nullptr;
+            EF_HIP(c, ef::launch_combine(c->y, topk_w, inv_perm, T, k, d, shared_y, out, s));
+        }
+    }
+    if (!c->fake && c->layer_open) {
+        EF_HIP(c, hipEventRecord(c->layer_cur.b, s));
+        c->layer_pending.push_back(c->layer_cur);
+        c->layer_open = false;
+    }
+    c->st.layers_run += 1;
+    c->st.tokens_run += T;
+    c->cache->advance();
+    return EF_OK;
+}
+
+extern "C" int ef_choose_horizon(ef_ctx *c, int layer, const int32_t *hist_host, int H, int T, int *H_next,
+                                 int32_t *prefetch_list, int *n_prefetch) {
+    if (!c) return fail(nullptr, EF_EINVAL, "null context");
+    if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, EF_EINVAL, "layer %d out of range", layer);
+    if (H < 0 || H > EF_MAX_HORIZON) return fail(c, EF_EINVAL, "ef_choose_horizon: H out of range");
+    if (!H_next || !n_prefetch || (H > 0 && (!hist_host || !prefetch_list)))
+        return fail(c, EF_EINVAL, "ef_choose_horizon: null pointer");
+    (void)T;
+    poll_all_copies(c);
+    poll_pairs(c, false);
+    const int E = c->cfg.n_experts;
+    const double tau = (double)c->cfg.cum_threshold;
+    *n_prefetch = 0;
+    H = std::min(H, c->cfg.n_layers - 1 - layer);
+    if (H < 0) H = 0;
+
+    // descending-demand order and the cumulative-share cut of each look-ahead layer
+    std::vector<std::vector<int>> chosen((size_t)H);
+    int n_miss_first = 0;
+    for (int j = 0; j < H; ++j) {
+        const int32_t *hj = hist_host + (size_t)j * E;
+        long long total = 0;
+        for (int e = 0; e < E; ++e) {
+            if (hj[e] < 0) return fail(c, EF_EINVAL, "ef_choose_horizon: negative histogram entry");
+            total += hj[e];
+        }
+        std::vector<int> order((size_t)E);
+        for (int e = 0; e < E; ++e) order[(size_t)e] = e;
+        std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return hj[x] > hj[y]; });
+        long long cum = 0;
+        for (int r = 0; r < E && total > 0; ++r) {
+            int e = order[(size_t)r];
+            if (hj[e] == 0) break;
+            cum += hj[e];
+            chosen[(size_t)j].push_back(e);
+            if ((double)cum / (double)total >= tau) break;
+        }
+        if (j == 0) {
+            for (int e : chosen[0])
+                if (c->cache->lookup(layer + 1, e) < 0) ++n_miss_first;
+        }
+    }
+    double raw = (double)n_miss_first * (double)c->expert_bytes / (c->bw_Bps * c->layer_s);
+    int S = (int)std::ceil(raw);
+    S += c->fb_adjust;
+    S = std::max(1, std::min(c->cfg.h_max, S));
+    c->horizon = S;
+    c->cache->set_S(S);
+    *H_next = S;
+    int n = 0;
+    for (int j = 0; j < std::min(H, S); ++j)
+        for (int e : chosen[(size_t)j])
+            if (c->cache->lookup(layer + 1 + j, e) < 0) prefetch_list[n++] = ((j + 1) << 16) | e;
+    *n_prefetch = n;
+    return EF_OK;
+}
+
+extern "C" int ef_get_stats(ef_ctx *c, ef_stats *out) {
+    if (!c || !out) return fail(c, EF_EINVAL, "ef_get_stats: null pointer");
+    if (!c->fake) {
+        for (int q = 0; q < 2; ++q) (void)hipStreamSynchronize(c->copy_stream[q]);
+        poll_pairs(c, true);
+    }
+    poll_all_copies(c);
+    c->st.bandwidth_Bps = c->bw_Bps;
+    c->st.layer_seconds_est = c->layer_s;
+    c->st.horizon = c->horizon;
+    c->st.stall_counter = c->stall_counter;
+    c->st.overfetch_counter = c->overfetch_counter;
+    int64_t n = c->st.hits + c->st.misses;
+    c->st.miss_rate = n > 0 ? 1.0 - (double)c->st.hits / (double)n : 0.0;
+    *out = c->st;
+    return EF_OK;
+}
+
+extern "C" int ef_reset_stats(ef_ctx *c) {
+    if (!c) return fail(nullptr, EF_EINVAL, "null context");
+    if (!c->fake) poll_pairs(c, true);
+    c->st = ef_stats{};
+    return EF_OK;
+}
+
+extern "C" int ef_fake_advance_time(ef_ctx *c, double seconds) {
+    if (!c) return fail(nullptr, EF_EINVAL, "null context");
+    if (!c->fake) return fail(c, EF_ENOSYS, "ef_fake_advance_time: not a fake-copy context");
+    if (!(seconds >= 0.0)) return fail(c, EF_EINVAL, "seconds must be >= 0");
+    c->fake_now += seconds;
+    c->st.layer_seconds += seconds;
+    poll_all_copies(c);
+    return EF_OK;
+}

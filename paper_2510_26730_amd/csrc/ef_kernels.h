@@ -1,0 +1,79 @@
+// Internal launch interface between the C-ABI layer and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+namespace ef {
+
+constexpr int kMaxE = 64;      // experts per layer
+constexpr int kMaxK = 8;       // top-k
+constexpr int kMaxGates = 8;   // gate matrices per launch (look-ahead + 1)
+constexpr int kTile = 32;      // tokens per tile (rows of one matrix-core operand fragment)
+constexpr int kMaxGroups = kMaxE + 1;  // routed experts + the dense shared FFN
+constexpr int kGateMaxCols = 320;      // G*E columns one gate launch can hold
+
+// Gate / predict launch: G gate matrices applied to the same hidden states.
+struct GateArgs {
+    const uint16_t *h;             // [T,d] bf16
+    int T, d, E, k, G;
+    const uint16_t *Wg[kMaxGates]; // [E,d] bf16 each
+    const float *bias[kMaxGates];  // [E] or null
+    uint64_t resident[kMaxGates];  // bit e: expert e of that gate's layer is in the cache
+    float beta;
+    const float *delta;            // f32 or null: delta[req*delta_req_stride + gate*E + e]
+    int delta_req_stride;
+    const int32_t *tok2req;        // [T] or null
+    int32_t *ids;                  // [G,T,k]
+    float *w;                      // [T,k] combine weights of gate 0, or null
+    int renorm;
+    float routed_scale;
+    int32_t *hist;                 // [G,E] accumulated with integer atomics, or null
+    int32_t *blockcounts;          // [ntiles,E] per-tile counts of gate 0, or null
+};
+
+// Grouped FFN launch: one group per active expert (+ one for the dense shared FFN).
+struct GroupTable {
+    int n_groups;
+    int wg_start[kMaxGroups + 1];  // first workgroup of each group in this launch (cumulative)
+    int tile_start[kMaxGroups];    // first 32-row tile of the group in the packed X / activation space
+    int n_tiles[kMaxGroups];
+    int row_offset[kMaxGroups];    // first row of the group in Y (= offsets[e]; T*k for the shared FFN)
+    int count[kMaxGroups];         // rows in the group
+    int F[kMaxGroups];             // FFN hidden dim of the group
+    long long act_off[kMaxGroups]; // first 16-byte unit of the group's activation fragments
+    const void *blob[kMaxGroups];  // packed weights (cache slot or shared blob)
+};
+
+// Describes how rows are gathered into tiles for the X packing kernel.
+struct PackTable {
+    int n_groups;
+    int tile_start[kMaxGroups + 1]; // cumulative over groups
+    int row_offset[kMaxGroups];     // offsets[e] (index into perm); -1 = identity (shared FFN: row = token)
+    int count[kMaxGroups];
+};
+
+hipError_t launch_fill_i32(int32_t *p, int n, int32_t v, hipStream_t s);
+hipError_t launch_gate(const GateArgs &a, hipStream_t s);
+hipError_t launch_group_scan(const int32_t *blockcounts, int ntiles, int E, int32_t *blockbase,
+                             int32_t *counts, int32_t *offsets, hipStream_t s);
+hipError_t launch_group_scatter(const int32_t *ids, int T, int k, int E, const int32_t *blockbase,
+                                const int32_t *offsets, int32_t *perm, int32_t *inv_perm, hipStream_t s);
+hipError_t launch_pack_x(const PackTable &pt, int total_tiles, const uint16_t *h, int d, int k,
+                         const int32_t *perm, void *xp, hipStream_t s);
+hipError_t launch_ffn_gate_up(const GroupTable &gt, int total_wgs, int tiles_per_pass, const void *xp,
+                              void *act, int d, hipStream_t s);
+hipError_t launch_ffn_down(const GroupTable &gt, int total_wgs, int tiles_per_pass, const void *act,
+                           float *y, int d, hipStream_t s);
+hipError_t launch_combine(const float *y, const float *w, const int32_t *inv_perm, int T, int k, int d,
+                          const float *shared_y, float *out, hipStream_t s);
+
+// workgroups a group needs in the two FFN launches
+inline int ffn_gate_up_wgs(int F, int n_tiles, int tiles_per_pass) {
+    int nrb = F / 32;
+    return ((nrb + 3) / 4) * ((n_tiles + tiles_per_pass - 1) / tiles_per_pass);
+}
+inline int ffn_down_wgs(int d, int n_tiles, int tiles_per_pass) {
+    return (d / 32) * ((n_tiles + tiles_per_pass - 1) / tiles_per_pass);
+}
+
+}  // namespace ef

@@ -1,0 +1,245 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Integer results bit-exact outside near-ties (oracle gap < 1e-4); float results within
+max-abs 2e-2 and relative L2 1e-2 (bf16 inputs, fp32 accumulation)."""
+import dataclasses
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2510_26730_amd import binding as ef
+from paper_2510_26730_amd import synth
+
+import helpers
+from helpers import LayerStack, check_route, dev_u16, float_close, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def shape(base, **kw):
+    return dataclasses.replace(synth.CONFIGS[base], **kw)
+
+
+SMALL_QWEN = shape("qwen15_moe", name="small_qwen", d=256, F=96, F_shared=160, T=77)
+SMALL_DEEPSEEK = shape("deepseek_v2_lite", name="small_deepseek", d=192, F=64, F_shared=128, T=130)
+
+
+def oracle_layer(oracle_mod, st, layer, h, beta, resident, forced_ids=None):
+    c = st.cfg
+    return oracle_mod.moe_layer(h, st.gates[layer], st.biases[layer], st.experts[layer], c.k, beta=beta,
+                                resident=resident, renorm=c.renorm, shared=st.shared.get(layer),
+                                forced_ids=forced_ids)
+
+
+@pytest.mark.parametrize("beta", [0.0, 0.75])
+def test_tiny_route_and_layer(oracle_mod, beta):
+    cfg = synth.CONFIGS["tiny"]
+    say(f"tiny layer beta={beta}")
+    st = LayerStack(cfg, 3, slots_total=12, per_layer=4, max_tokens=64)
+    try:
+        for e in np.nonzero(synth.residency(cfg, 0))[0]:
+            ef.ef_cache_swap_in(st.ctx, 0, int(e), 0, 0)
+        res = ef.ef_cache_query(st.ctx, 0, cfg.E)
+        assert np.array_equal(res, synth.residency(cfg, 0))
+        h = synth.hidden(cfg, 0)
+        hd = dev_u16(h)
+        r = st.route(0, hd, cfg.T, beta)
+        got = to_np(r, cfg.T, cfg.k)
+        ora = oracle_mod.route(h, st.gates[0], st.biases[0], cfg.k, beta, res, renorm=cfg.renorm)
+        forced, nties = check_route(got, ora, cfg.E, cfg.k, cfg.renorm, oracle_mod=oracle_mod)
+        out = st.ffn(0, hd, cfg.T, r)
+        full = oracle_layer(oracle_mod, st, 0, h, beta, res, forced_ids=got["ids"])
+        e1, e2 = float_close(out, full["out"])
+        say(f"  near-ties {nties}, max abs {e1:.2e}, rel l2 {e2:.2e}")
+        stats = ef.ef_get_stats(st.ctx)
+        assert stats["layers_run"] == 1 and stats["tokens_run"] == cfg.T
+        assert stats["hits"] + stats["misses"] == int((got["counts"] > 0).sum())
+    finally:
+        st.close()
+
+
+def test_tiny_predict_with_delta_and_residency(oracle_mod):
+    cfg = synth.CONFIGS["tiny"]
+    say("tiny predict H=2")
+    st = LayerStack(cfg, 3, slots_total=12, per_layer=4, max_tokens=64, expert_layers=[0])
+    try:
+        ef.ef_cache_swap_in(st.ctx, 1, 3, 0, 1)
+        ef.ef_cache_swap_in(st.ctx, 2, 5, 0, 2)
+        ef.ef_cache_swap_in(st.ctx, 2, 0, 0, 2)
+        h = synth.hidden(cfg, 0)
+        R, H = 3, 2
+        delta = synth.delta(cfg, 0, R, H)
+        t2r = synth.tok2req(cfg, cfg.T, R)
+        residents = [ef.ef_cache_query(st.ctx, 1 + j, cfg.E) for j in range(H)]
+        assert [int(r.sum()) for r in residents] == [1, 2]
+        for beta, dl, tr in [(0.0, None, None), (0.5, delta, t2r), (0.5, delta, None)]:
+            he, ids, hist = st.predict(0, dev_u16(h), cfg.T, H, beta, dl, tr)
+            assert he == H
+            oids, ohist, ogap = oracle_mod.predict(h, st.gates[1:3], st.biases[1:3], cfg.k, beta, residents,
+                                                   dl, tr)
+            tie = ogap < helpers.TIE_GAP
+            assert np.array_equal(ids[~tie], oids[~tie])
+            for j in range(H):
+                assert np.array_equal(hist[j], oracle_mod.histogram(ids[j], cfg.E))
+                assert hist[j].sum() == cfg.T * cfg.k
+            if not tie.any():
+                assert np.array_equal(hist, ohist)
+        # look-ahead is clamped at the last layer
+        he, ids, hist = st.predict(1, dev_u16(h), cfg.T, 2, 0.0)
+        assert he == 1
+        assert np.array_equal(ids[0], oracle_mod.route(h, st.gates[2], st.biases[2], cfg.k)["ids"])
+        he, _, _ = st.predict(2, dev_u16(h), cfg.T, 2, 0.0)
+        assert he == 0
+    finally:
+        st.close()
+
+
+@pytest.mark.parametrize("cfg,T", [(synth.CONFIGS["tiny"], 1), (synth.CONFIGS["tiny"], 31),
+                                   (synth.CONFIGS["tiny"], 33), (synth.CONFIGS["tiny"], 100),
+                                   (SMALL_QWEN, 77), (SMALL_QWEN, 3), (SMALL_DEEPSEEK, 130),
+                                   (SMALL_DEEPSEEK, 32)])
+def test_ragged_shapes_full_layer(oracle_mod, cfg, T):
+    say(f"ragged {cfg.name} T={T} E={cfg.E} k={cfg.k} d={cfg.d} F={cfg.F} Fs={cfg.F_shared}")
+    st = LayerStack(cfg, 1, slots_total=cfg.E, max_tokens=max(T, 8))
+    try:
+        res = synth.residency(cfg, 0, n_resident=max(1, cfg.E // 4), most_popular=False)
+        for e in np.nonzero(res)[0]:
+            ef.ef_cache_swap_in(st.ctx, 0, int(e), 0, 0)
+        h = synth.hidden(cfg, 3, T)
+        hd = dev_u16(h)
+        beta = 0.5
+        r = st.route(0, hd, T, beta)
+        got = to_np(r, T, cfg.k)
+        ora = oracle_mod.route(h, st.gates[0], st.biases[0], cfg.k, beta, res, renorm=cfg.renorm)
+        check_route(got, ora, cfg.E, cfg.k, cfg.renorm, oracle_mod=oracle_mod)
+        out = st.ffn(0, hd, T, r)               # misses are swapped in by the call itself
+        full = oracle_layer(oracle_mod, st, 0, h, beta, res, forced_ids=got["ids"])
+        e1, e2 = float_close(out, full["out"])
+        say(f"  max abs {e1:.2e}, rel l2 {e2:.2e}")
+    finally:
+        st.close()
+
+
+def test_empty_batch(oracle_mod):
+    cfg = synth.CONFIGS["tiny"]
+    say("T=0")
+    st = LayerStack(cfg, 2, slots_total=4, max_tokens=8, expert_layers=[0])
+    try:
+        hd = dev_u16(synth.hidden(cfg, 0, 8))
+        r = st.route(0, hd, 0, 0.0)
+        torch.cuda.synchronize()
+        assert r["counts"].cpu().numpy().tolist() == [0] * cfg.E
+        assert r["offsets"].cpu().numpy().tolist() == [0] * (cfg.E + 1)
+        out = st.ffn(0, hd, 0, r)
+        assert out.shape[0] == 0
+        he, ids, hist = st.predict(0, hd, 0, 1, 0.0)
+        assert he == 1 and hist.sum() == 0
+    finally:
+        st.close()
+
+
+def test_outputs_do_not_depend_on_slots_or_phase_order(oracle_mod):
+    """Same routing, different cache histories: experts preloaded in different slots, or missing and
+    swapped in by the FFN call in several phases through a 2-slot layer: bitwise the same output."""
+    cfg = synth.CONFIGS["tiny"]
+    say("slot / phase invariance")
+    h = synth.hidden(cfg, 5)
+    outs = []
+    for variant in range(3):
+        st = LayerStack(cfg, 1, slots_total=8 if variant < 2 else 2, per_layer=0 if variant < 2 else 2,
+                        max_tokens=64)
+        try:
+            order = list(range(cfg.E)) if variant == 0 else list(reversed(range(cfg.E)))
+            if variant < 2:
+                for e in order:
+                    ef.ef_cache_swap_in(st.ctx, 0, e, 0, 0)
+            hd = dev_u16(h)
+            r = st.route(0, hd, cfg.T, 0.0)       # beta = 0: routing is independent of residency
+            outs.append((to_np(r, cfg.T, cfg.k), st.ffn(0, hd, cfg.T, r)))
+            if variant == 2:
+                s = ef.ef_get_stats(st.ctx)
+                assert s["misses"] == int((outs[-1][0]["counts"] > 0).sum()) and s["evictions"] >= 1
+        finally:
+            st.close()
+    for name in ("ids", "w", "perm"):
+        assert np.array_equal(outs[0][0][name], outs[1][0][name]) and np.array_equal(outs[0][0][name], outs[2][0][name])
+    assert np.array_equal(outs[0][1], outs[1][1]) and np.array_equal(outs[0][1], outs[2][1])
+
+
+def _sampled_layer_check(oracle_mod, st, layer, h, T, beta, res, n_sample, seed):
+    cfg = st.cfg
+    hd = dev_u16(h)
+    r = st.route(layer, hd, T, beta)
+    got = to_np(r, T, cfg.k)
+    ora = oracle_mod.route(h, st.gates[layer], st.biases[layer], cfg.k, beta, res, renorm=cfg.renorm)
+    forced, nties = check_route(got, ora, cfg.E, cfg.k, cfg.renorm, oracle_mod=oracle_mod)
+    out = st.ffn(layer, hd, T, r)
+    assert np.all(np.isfinite(out))
+    toks = np.sort(np.random.default_rng(seed).permutation(T)[:n_sample])
+    hs = np.ascontiguousarray(h[toks])
+    ids_s = np.ascontiguousarray(got["ids"][toks])
+    sub = oracle_mod.route_from_ids(ora["p"][toks], ids_s, cfg.E, cfg.renorm)
+    y = oracle_mod.expert_ffn(hs, st.experts[layer], ids_s, sub["perm"])
+    sh = None if not cfg.F_shared else oracle_mod.dense_ffn(hs, *st.shared[layer])
+    ref = oracle_mod.combine(y, sub["w"], sub["inv_perm"], sh)
+    e1, e2 = float_close(out[toks], ref)
+    say(f"  near-ties {nties}, sampled {len(toks)} tokens: max abs {e1:.2e}, rel l2 {e2:.2e}")
+
+
+def test_full_size_mixtral_decode_layer(oracle_mod):
+    cfg = synth.CONFIGS["mixtral_decode"]
+    say("full size: Mixtral-shaped decode layer, T=64 (the benchmark's launch configuration)")
+    st = LayerStack(cfg, 1, slots_total=8, per_layer=0, max_tokens=64)
+    try:
+        res = synth.residency(cfg, 0)
+        for e in np.nonzero(res)[0]:
+            ef.ef_cache_swap_in(st.ctx, 0, int(e), 0, 0)
+        _sampled_layer_check(oracle_mod, st, 0, synth.hidden(cfg, 0, 64), 64, 1.0, res, 6, 1)
+    finally:
+        st.close()
+
+
+def test_full_size_qwen_mixed_batch(oracle_mod):
+    cfg = synth.CONFIGS["qwen15_moe"]
+    say("full size: Qwen1.5-MoE-shaped layer, T=640, shared expert")
+    st = LayerStack(cfg, 1, slots_total=cfg.E, max_tokens=640)
+    try:
+        res = synth.residency(cfg, 0)
+        for e in np.nonzero(res)[0]:
+            ef.ef_cache_swap_in(st.ctx, 0, int(e), 0, 0)
+        _sampled_layer_check(oracle_mod, st, 0, synth.hidden(cfg, 0, 640), 640, 0.5, res, 24, 2)
+    finally:
+        st.close()
+
+
+def test_full_size_deepseek_prefill(oracle_mod):
+    cfg = synth.CONFIGS["deepseek_v2_lite"]
+    say("full size: DeepSeek-V2-Lite-shaped layer, T=1056 (32 decode + 1024 prefill), shared experts")
+    st = LayerStack(cfg, 1, slots_total=cfg.E, max_tokens=1056)
+    try:
+        res = synth.residency(cfg, 0)
+        for e in np.nonzero(res)[0]:
+            ef.ef_cache_swap_in(st.ctx, 0, int(e), 0, 0)
+        _sampled_layer_check(oracle_mod, st, 0, synth.hidden(cfg, 0, 1056), 1056, 0.5, res, 24, 3)
+    finally:
+        st.close()
+
+
+def test_full_size_mixtral_prefill_layer(oracle_mod):
+    cfg = synth.CONFIGS["mixtral_prefill"]
+    say("full size: Mixtral-shaped prefill layer, T=8192")
+    st = LayerStack(cfg, 1, slots_total=8, max_tokens=8192)
+    try:
+        res = synth.residency(cfg, 0)
+        for e in range(cfg.E):
+            ef.ef_cache_swap_in(st.ctx, 0, e, 0, 0)
+        res = ef.ef_cache_query(st.ctx, 0, cfg.E)
+        _sampled_layer_check(oracle_mod, st, 0, synth.hidden(cfg, 0, 8192), 8192, 0.0, res, 6, 4)
+    finally:
+        st.close()
