@@ -64,6 +64,21 @@ enum {
 #define EF_FLAG_FAKE_COPY 1u   /* no device at all: the cache runtime runs against a fake copy
                                   engine and a fake clock (host-logic tests); kernels return EF_ENOSYS */
 #define EF_FLAG_STRICT_RESIDENT 2u /* ef_moe_ffn fails with EF_ENOTRESIDENT instead of swapping in misses itself */
+#define EF_FLAG_PROFILE 4u         /* bracket every kernel launch with HIP events on its own stream and
+                                      accumulate per-kernel time, launches and algorithmic bytes in ef_stats */
+
+/* index of the per-kernel arrays in ef_stats */
+enum {
+    EF_K_PREDICT = 0,  /* gate + top-k + histogram of the look-ahead layers */
+    EF_K_ROUTE = 1,    /* gate + softmax + biased top-k + per-tile counts of the current layer */
+    EF_K_SCAN = 2,     /* per-expert prefix over the tiles */
+    EF_K_SCATTER = 3,  /* stable scatter: perm / inv_perm */
+    EF_K_PACK = 4,     /* token permutation into per-expert operand tiles */
+    EF_K_FFN_UP = 5,   /* grouped act = silu(X W1^T) * (X W3^T) */
+    EF_K_FFN_DOWN = 6, /* grouped Y = act W2^T */
+    EF_K_COMBINE = 7,  /* weighted un-permute */
+    EF_K_COUNT = 8
+};
 
 typedef struct ef_ctx ef_ctx;
 
@@ -105,6 +120,12 @@ typedef struct ef_stats {
     double miss_rate;           /* R_miss = 1 - hits / (hits + misses)  (paper Sec. 2.2) */
     int32_t horizon;            /* current look-ahead S */
     int32_t stall_counter, overfetch_counter;
+    int32_t reserved_;
+    /* EF_FLAG_PROFILE only: summed event time, launches and algorithmic bytes (minimal HBM traffic
+     * the operation needs: operands read once, results written once) per kernel kind */
+    double kernel_seconds[EF_K_COUNT];
+    double kernel_bytes[EF_K_COUNT];
+    int64_t kernel_launches[EF_K_COUNT];
 } ef_stats;
 
 /* ---- utilities (host only, no device needed) -------------------------------------------- */

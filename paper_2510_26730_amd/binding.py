@@ -19,6 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libexpertflow.so")
 EF_OK, EF_EINVAL, EF_ENOMEM, EF_EHIP, EF_EBUSY, EF_ENOTRESIDENT, EF_ENOSYS = 0, -1, -2, -3, -4, -5, -6
 EF_FLAG_FAKE_COPY = 1
 EF_FLAG_STRICT_RESIDENT = 2
+EF_FLAG_PROFILE = 4
+EF_KERNELS = ["predict", "route", "scan", "scatter", "pack", "ffn_up", "ffn_down", "combine"]
 EF_MAX_EXPERTS, EF_MAX_TOPK, EF_MAX_HORIZON = 64, 8, 7
 
 EXPORTS = [
@@ -46,11 +48,17 @@ class ef_stats(C.Structure):
         ("layers_run", C.c_int64), ("tokens_run", C.c_int64), ("copy_seconds", C.c_double),
         ("stall_seconds", C.c_double), ("layer_seconds", C.c_double), ("bandwidth_Bps", C.c_double),
         ("layer_seconds_est", C.c_double), ("miss_rate", C.c_double), ("horizon", C.c_int32),
-        ("stall_counter", C.c_int32), ("overfetch_counter", C.c_int32),
+        ("stall_counter", C.c_int32), ("overfetch_counter", C.c_int32), ("reserved_", C.c_int32),
+        ("kernel_seconds", C.c_double * 8), ("kernel_bytes", C.c_double * 8),
+        ("kernel_launches", C.c_int64 * 8),
     ]
 
     def as_dict(self):
-        return {n: getattr(self, n) for n, _ in self._fields_}
+        out = {}
+        for n, _ in self._fields_:
+            v = getattr(self, n)
+            out[n] = list(v) if hasattr(v, "__len__") else v
+        return out
 
 
 class EfError(RuntimeError):

@@ -63,6 +63,11 @@ struct ef_ctx {
     std::vector<EventPair> stall_ring, layer_ring;
     size_t stall_next = 0, layer_next = 0;
     std::deque<EventPair> stall_pending, layer_pending;
+    struct ProfItem { EventPair p; int kind; double bytes; };
+    std::vector<EventPair> prof_ring;
+    size_t prof_next = 0;
+    std::deque<ProfItem> prof_pending;
+    bool profile = false;
     bool layer_open = false;
     EventPair layer_cur{nullptr, nullptr};
     // estimators and feedback
@@ -150,6 +155,42 @@ void poll_pairs(ef_ctx *c, bool wait) {
         c->layer_pending.pop_front();
     }
 }
+
+void poll_prof(ef_ctx *c, bool wait) {
+    while (!c->prof_pending.empty()) {
+        ef_ctx::ProfItem it = c->prof_pending.front();
+        hipError_t q = wait ? hipEventSynchronize(it.p.b) : hipEventQuery(it.p.b);
+        if (q != hipSuccess) { (void)hipGetLastError(); break; }
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, it.p.a, it.p.b) == hipSuccess) {
+            c->st.kernel_seconds[it.kind] += ms * 1e-3;
+            c->st.kernel_bytes[it.kind] += it.bytes;
+            c->st.kernel_launches[it.kind] += 1;
+        }
+        c->prof_pending.pop_front();
+    }
+}
+
+// Brackets one kernel launch with events on the launch stream when profiling is on.
+struct KernelTimer {
+    ef_ctx *c;
+    hipStream_t s;
+    int kind;
+    double bytes;
+    EventPair p{nullptr, nullptr};
+    KernelTimer(ef_ctx *ctx, hipStream_t st, int k, double b) : c(ctx), s(st), kind(k), bytes(b) {
+        if (!c->profile) return;
+        if (c->prof_pending.size() >= c->prof_ring.size()) poll_prof(c, true);
+        p = c->prof_ring[c->prof_next];
+        c->prof_next = (c->prof_next + 1) % c->prof_ring.size();
+        (void)hipEventRecord(p.a, s);
+    }
+    ~KernelTimer() {
+        if (!c->profile) return;
+        (void)hipEventRecord(p.b, s);
+        c->prof_pending.push_back({p, kind, bytes});
+    }
+};
 
 EventPair next_pair(std::vector<EventPair> &ring, size_t &next, std::deque<EventPair> &pending) {
     // never hand out a pair that is still waiting to be read
@@ -309,6 +350,7 @@ extern "C" int ef_destroy(ef_ctx *c) {
         for (auto e : c->read_ring) (void)hipEventDestroy(e);
         for (auto &p : c->stall_ring) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
         for (auto &p : c->layer_ring) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+        for (auto &p : c->prof_ring) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
         for (int q = 0; q < 2; ++q)
             if (c->copy_stream[q]) (void)hipStreamDestroy(c->copy_stream[q]);
         if (c->pool) (void)hipFree(c->pool);
@@ -399,7 +441,9 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
         if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
     c->stall_ring.resize(128);
     c->layer_ring.resize(128);
-    for (auto *ring : {&c->stall_ring, &c->layer_ring})
+    c->profile = (g.flags & EF_FLAG_PROFILE) != 0;
+    if (c->profile) c->prof_ring.resize(1024);
+    for (auto *ring : {&c->stall_ring, &c->layer_ring, &c->prof_ring})
         for (auto &p : *ring) {
             if ((e = hipEventCreate(&p.a)) != hipSuccess) return bail(e, "event");
             if ((e = hipEventCreate(&p.b)) != hipSuccess) return bail(e, "event");
@@ -483,7 +527,11 @@ extern "C" int ef_predict(ef_ctx *c, int layer, const void *hidden, int T, int H
         a.renorm = 0; a.routed_scale = 1.f;
         a.hist = hist + (size_t)j0 * E;
         a.blockcounts = nullptr;
-        EF_HIP(c, ef::launch_gate(a, s));
+        {
+            KernelTimer kt(c, s, EF_K_PREDICT, (double)T * a.d * 2 + (double)a.G * E * a.d * 2 +
+                                                   (double)a.G * T * k * 4 + (double)a.G * E * 4);
+            EF_HIP(c, ef::launch_gate(a, s));
+        }
     }
     return EF_OK;
 }
@@ -527,9 +575,19 @@ extern "C" int ef_route(ef_ctx *c, int layer, const void *hidden, int T, float b
     a.hist = nullptr;
     a.blockcounts = c->blockcounts;
     const int ntiles = (T + ef::kTile - 1) / ef::kTile;
-    EF_HIP(c, ef::launch_gate(a, s));
-    EF_HIP(c, ef::launch_group_scan(c->blockcounts, ntiles, E, c->blockbase, counts, offsets, s));
-    EF_HIP(c, ef::launch_group_scatter(topk_ids, T, k, E, c->blockbase, offsets, perm, inv_perm, s));
+    {
+        KernelTimer kt(c, s, EF_K_ROUTE, (double)T * a.d * 2 + (double)E * a.d * 2 + (double)T * k * 8 +
+                                             (double)ntiles * E * 4);
+        EF_HIP(c, ef::launch_gate(a, s));
+    }
+    {
+        KernelTimer kt(c, s, EF_K_SCAN, (double)ntiles * E * 8 + (double)(2 * E + 1) * 4);
+        EF_HIP(c, ef::launch_group_scan(c->blockcounts, ntiles, E, c->blockbase, counts, offsets, s));
+    }
+    {
+        KernelTimer kt(c, s, EF_K_SCATTER, (double)T * k * 12 + (double)ntiles * E * 4);
+        EF_HIP(c, ef::launch_group_scatter(topk_ids, T, k, E, c->blockbase, offsets, perm, inv_perm, s));
+    }
     return EF_OK;
 }
 
@@ -596,8 +654,19 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
     }
     gu.wg_start[n] = wg_gu;
     dn.wg_start[n] = wg_dn;
-    EF_HIP(c, ef::launch_ffn_gate_up(gu, wg_gu, tpp, c->xp, c->act, d, s));
-    EF_HIP(c, ef::launch_ffn_down(dn, wg_dn, tpp, c->act, c->y, d, s));
+    double b_up = 0.0, b_dn = 0.0;
+    for (int i = 0; i < n; ++i) {
+        b_up += 4.0 * d * gu.F[i] + 2.0 * gu.count[i] * d + 2.0 * gu.count[i] * gu.F[i];
+        b_dn += 2.0 * d * gu.F[i] + 2.0 * gu.count[i] * gu.F[i] + 4.0 * gu.count[i] * d;
+    }
+    {
+        KernelTimer kt(c, s, EF_K_FFN_UP, b_up);
+        EF_HIP(c, ef::launch_ffn_gate_up(gu, wg_gu, tpp, c->xp, c->act, d, s));
+    }
+    {
+        KernelTimer kt(c, s, EF_K_FFN_DOWN, b_dn);
+        EF_HIP(c, ef::launch_ffn_down(dn, wg_dn, tpp, c->act, c->y, d, s));
+    }
     return EF_OK;
 }
 
@@ -753,6 +822,8 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
             pt.tile_start[n] = tiles;
             pt.n_groups = n;
             int r = EF_OK;
+            long long rows = (long long)T * k + (has_shared ? T : 0);
+            KernelTimer kt(c, s, EF_K_PACK, 4.0 * rows * d + 4.0 * T * k);
             hipError_t he = ef::launch_pack_x(pt, tiles, static_cast<const uint16_t *>(hidden), d, k, perm, c->xp, s);
             if (he != hipSuccess) r = fail(c, EF_EHIP, "pack_x launch failed: %s", hipGetErrorString(he));
             if (r) { unpin_all(ready); unpin_all(loading); return r; }
@@ -787,6 +858,8 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         }
         if (!c->fake) {
             const float *shared_y = has_shared ? c->y + (size_t)T * k * d : nullptr;
+            KernelTimer kt(c, s, EF_K_COMBINE, 4.0 * ((double)T * k + (has_shared ? T : 0)) * d + 4.0 * T * d +
+                                                   8.0 * T * k);
             EF_HIP(c, ef::launch_combine(c->y, topk_w, inv_perm, T, k, d, shared_y, out, s));
         }
     }
@@ -863,6 +936,7 @@ extern "C" int ef_get_stats(ef_ctx *c, ef_stats *out) {
     if (!c->fake) {
         for (int q = 0; q < 2; ++q) (void)hipStreamSynchronize(c->copy_stream[q]);
         poll_pairs(c, true);
+        poll_prof(c, true);
     }
     poll_all_copies(c);
     c->st.bandwidth_Bps = c->bw_Bps;
@@ -878,7 +952,7 @@ extern "C" int ef_get_stats(ef_ctx *c, ef_stats *out) {
 
 extern "C" int ef_reset_stats(ef_ctx *c) {
     if (!c) return fail(nullptr, EF_EINVAL, "null context");
-    if (!c->fake) poll_pairs(c, true);
+    if (!c->fake) { poll_pairs(c, true); poll_prof(c, true); }
     c->st = ef_stats{};
     return EF_OK;
 }
