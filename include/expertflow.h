@@ -67,12 +67,15 @@ enum {
 #define EF_FLAG_PROFILE 4u         /* bracket every kernel launch with HIP events on its own stream and
                                       accumulate per-kernel time, launches and algorithmic bytes in ef_stats */
 
+#define EF_FLAG_PROFILE_FFN_UP 16u  /* as EF_FLAG_PROFILE, but only the first FFN half (the dominant kernel) */
+#define EF_FLAG_FIXED_ESTIMATES 8u /* keep C_s and T_l at their initial values (reproducible horizon decisions) */
+
 /* index of the per-kernel arrays in ef_stats */
 enum {
     EF_K_PREDICT = 0,  /* gate + top-k + histogram of the look-ahead layers */
     EF_K_ROUTE = 1,    /* gate + softmax + biased top-k + per-tile counts of the current layer */
-    EF_K_SCAN = 2,     /* per-expert prefix over the tiles */
-    EF_K_SCATTER = 3,  /* stable scatter: perm / inv_perm */
+    EF_K_GROUP = 2,    /* per-expert prefix over the tiles + stable scatter: counts, offsets, perm, inv_perm */
+    EF_K_RESERVED = 3,
     EF_K_PACK = 4,     /* token permutation into per-expert operand tiles */
     EF_K_FFN_UP = 5,   /* grouped act = silu(X W1^T) * (X W3^T) */
     EF_K_FFN_DOWN = 6, /* grouped Y = act W2^T */
@@ -187,6 +190,19 @@ int ef_route(ef_ctx *ctx, int layer, const void *hidden, int T, float beta,
              int32_t *perm, int32_t *inv_perm, void *stream);
 
 /*
+ * ef_route and ef_predict of the same layer on ONE pass over `hidden` (the look-ahead gates see the
+ * same hidden states as the layer's own gate, paper Sec. 2.3.2, so the hidden states need to be read
+ * from HBM only once).  Results are identical to calling ef_route(layer, ..., beta) and
+ * ef_predict(layer, ..., H, delta, tok2req, beta) one after the other; arguments as there
+ * (pred_ids [dev] [H,T,k], pred_hist [dev] [H,E]).
+ */
+int ef_route_predict(ef_ctx *ctx, int layer, const void *hidden, int T, float beta, int H,
+                     const float *delta, const int32_t *tok2req,
+                     int32_t *topk_ids, float *topk_w, int32_t *counts, int32_t *offsets,
+                     int32_t *perm, int32_t *inv_perm,
+                     int32_t *pred_ids, int32_t *pred_hist, int *H_eff, void *stream);
+
+/*
  * Grouped SwiGLU expert FFN over the cache slots and weighted un-permute:
  * out[t] = sum_j topk_w[t][j] * FFN_{ids[t][j]}(hidden[t]) (+ dense shared FFN(hidden[t])).
  * Groups whose expert is ready run first; groups whose expert is still being copied run after
@@ -224,9 +240,28 @@ int ef_cache_query(ef_ctx *ctx, int layer, uint8_t *resident_host);
 int ef_choose_horizon(ef_ctx *ctx, int layer, const int32_t *hist_host, int H, int T,
                       int *H_next, int32_t *prefetch_list, int *n_prefetch);
 
+/*
+ * One whole layer of the method in one call, in the paper's order (Sec. 3.1 overview, 3.2, 3.3.2, 3.4):
+ * ef_route_predict with look-ahead H (H < 0: the controller's current horizon) into library-owned
+ * buffers; the grouping kernel hands counts and demand histograms to the host through host-mapped
+ * memory and the call polls a flag instead of synchronising the stream; ef_choose_horizon; one
+ * ef_cache_swap_in(prefetch) per entry of its list (EF_EBUSY skips that prefetch); ef_moe_ffn.
+ * Results are those of the separate calls.  *H_next (may be NULL) receives the horizon chosen for the
+ * next layer, counts_host_out [host] [E] (may be NULL) the per-expert token counts.  out [dev]
+ * [T,d] f32 is valid after the caller synchronises `stream`.  The call blocks the host until the
+ * routing kernels of this layer have finished (not until the FFN has).  T must be positive.
+ */
+int ef_layer_step(ef_ctx *ctx, int layer, const void *hidden, int T, float beta, int H,
+                  const float *delta, const int32_t *tok2req, float *out, int *H_next,
+                  int32_t *counts_host_out, void *stream);
+
 /* Statistics; synchronises outstanding timing events first (not for the hot loop). */
 int ef_get_stats(ef_ctx *ctx, ef_stats *out);
 int ef_reset_stats(ef_ctx *ctx);
+
+/* Choose at run time which kernel kinds are bracketed with events: bit (1 << EF_K_*) per kind,
+ * 0 = none (overrides the EF_FLAG_PROFILE* flags given at creation). */
+int ef_set_profile(ef_ctx *ctx, unsigned kinds_mask);
 
 /* Fake-copy contexts only: advance the fake clock; copies complete after bytes/bandwidth seconds. */
 int ef_fake_advance_time(ef_ctx *ctx, double seconds);

@@ -20,13 +20,15 @@ EF_OK, EF_EINVAL, EF_ENOMEM, EF_EHIP, EF_EBUSY, EF_ENOTRESIDENT, EF_ENOSYS = 0, 
 EF_FLAG_FAKE_COPY = 1
 EF_FLAG_STRICT_RESIDENT = 2
 EF_FLAG_PROFILE = 4
-EF_KERNELS = ["predict", "route", "scan", "scatter", "pack", "ffn_up", "ffn_down", "combine"]
+EF_FLAG_FIXED_ESTIMATES = 8
+EF_FLAG_PROFILE_FFN_UP = 16
+EF_KERNELS = ["predict", "route", "group", "reserved", "pack", "ffn_up", "ffn_down", "combine"]
 EF_MAX_EXPERTS, EF_MAX_TOPK, EF_MAX_HORIZON = 64, 8, 7
 
 EXPORTS = [
     "ef_strerror", "ef_expert_bytes", "ef_pack_expert", "ef_create", "ef_destroy", "ef_last_error",
-    "ef_register_layer", "ef_predict", "ef_route", "ef_moe_ffn", "ef_cache_swap_in", "ef_cache_query",
-    "ef_choose_horizon", "ef_get_stats", "ef_reset_stats", "ef_fake_advance_time",
+    "ef_register_layer", "ef_predict", "ef_route", "ef_route_predict", "ef_moe_ffn", "ef_layer_step", "ef_cache_swap_in", "ef_cache_query",
+    "ef_choose_horizon", "ef_get_stats", "ef_reset_stats", "ef_set_profile", "ef_fake_advance_time",
 ]
 
 
@@ -90,12 +92,16 @@ def lib():
         L.ef_register_layer.argtypes = [vp, i32, vp, vp, vp, vp]
         L.ef_predict.argtypes = [vp, i32, vp, i32, i32, vp, vp, f32, vp, vp, C.POINTER(i32), vp]
         L.ef_route.argtypes = [vp, i32, vp, i32, f32, vp, vp, vp, vp, vp, vp, vp]
+        L.ef_route_predict.argtypes = [vp, i32, vp, i32, f32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                       C.POINTER(i32), vp]
         L.ef_moe_ffn.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.ef_layer_step.argtypes = [vp, i32, vp, i32, f32, i32, vp, vp, vp, C.POINTER(i32), vp, vp]
         L.ef_cache_swap_in.argtypes = [vp, i32, i32, i32, i32, C.POINTER(i32)]
         L.ef_cache_query.argtypes = [vp, i32, vp]
         L.ef_choose_horizon.argtypes = [vp, i32, vp, i32, i32, C.POINTER(i32), vp, C.POINTER(i32)]
         L.ef_get_stats.argtypes = [vp, C.POINTER(ef_stats)]
         L.ef_reset_stats.argtypes = [vp]
+        L.ef_set_profile.argtypes = [vp, C.c_uint]
         L.ef_fake_advance_time.argtypes = [vp, C.c_double]
         _lib = L
     return _lib
@@ -195,12 +201,31 @@ def ef_route(ctx, layer, hidden, T, beta, topk_ids, topk_w, counts, offsets, per
                                       _stream(stream)))
 
 
+def ef_route_predict(ctx, layer, hidden, T, beta, H, delta, tok2req, topk_ids, topk_w, counts, offsets, perm,
+                     inv_perm, pred_ids, pred_hist, stream=None):
+    """Returns the effective H."""
+    he = C.c_int(0)
+    _check(ctx, lib().ef_route_predict(ctx, layer, _ptr(hidden), T, beta, H, _ptr(delta), _ptr(tok2req),
+                                       _ptr(topk_ids), _ptr(topk_w), _ptr(counts), _ptr(offsets), _ptr(perm),
+                                       _ptr(inv_perm), _ptr(pred_ids), _ptr(pred_hist), C.byref(he),
+                                       _stream(stream)))
+    return he.value
+
+
 def ef_moe_ffn(ctx, layer, hidden, T, topk_ids, topk_w, counts_host, offsets, perm, inv_perm, out,
                stream=None):
     counts_host = np.ascontiguousarray(counts_host, dtype=np.int32)
     return _check(ctx, lib().ef_moe_ffn(ctx, layer, _ptr(hidden), T, _ptr(topk_ids), _ptr(topk_w),
                                         _ptr(counts_host), _ptr(offsets), _ptr(perm), _ptr(inv_perm),
                                         _ptr(out), _stream(stream)))
+
+
+def ef_layer_step(ctx, layer, hidden, T, beta, H, delta, tok2req, out, counts_host=None, stream=None):
+    """Whole layer in one call; returns the horizon chosen for the next layer."""
+    hn = C.c_int(0)
+    _check(ctx, lib().ef_layer_step(ctx, layer, _ptr(hidden), T, beta, H, _ptr(delta), _ptr(tok2req), _ptr(out),
+                                    C.byref(hn), _ptr(counts_host), _stream(stream)))
+    return hn.value
 
 
 def ef_cache_swap_in(ctx, layer, expert, priority=0, due_in=0):
@@ -235,6 +260,10 @@ def ef_get_stats(ctx):
 
 def ef_reset_stats(ctx):
     return _check(ctx, lib().ef_reset_stats(ctx))
+
+
+def ef_set_profile(ctx, kinds_mask):
+    return _check(ctx, lib().ef_set_profile(ctx, kinds_mask))
 
 
 def ef_fake_advance_time(ctx, seconds):

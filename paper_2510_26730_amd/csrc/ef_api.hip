@@ -56,7 +56,14 @@ struct ef_ctx {
     int32_t *blockcounts = nullptr, *blockbase = nullptr;
     void *xp = nullptr, *act = nullptr;
     float *y = nullptr;
+    long long y_floats = 0;          // capacity of y: several K-slice planes when the batch is small
     int max_tiles = 0;
+    // buffers of ef_layer_step (library-owned routing state and the host-mapped hand-over area)
+    int32_t *st_ids = nullptr, *st_counts = nullptr, *st_offsets = nullptr, *st_perm = nullptr,
+            *st_inv = nullptr, *st_pred_ids = nullptr, *st_pred_hist = nullptr;
+    float *st_w = nullptr;
+    int32_t *meta_host = nullptr, *meta_dev = nullptr;
+    int meta_seq = 0;
     // event rings
     std::vector<hipEvent_t> read_ring;
     size_t read_next = 0;
@@ -67,7 +74,7 @@ struct ef_ctx {
     std::vector<EventPair> prof_ring;
     size_t prof_next = 0;
     std::deque<ProfItem> prof_pending;
-    bool profile = false;
+    unsigned profile_mask = 0;       // bit per kernel kind that is bracketed with events
     bool layer_open = false;
     EventPair layer_cur{nullptr, nullptr};
     // estimators and feedback
@@ -105,6 +112,13 @@ int fail(ef_ctx *ctx, int code, const char *fmt, ...) {
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Debug knob: an integer environment variable overrides a launch heuristic (read on every call,
+// so a tuning script can sweep it inside one process).
+int tune(const char *name, int dflt) {
+    const char *v = getenv(name);
+    return (v && *v) ? atoi(v) : dflt;
+}
+
 void ema(double &est, double sample, double alpha = 0.25) { est = (1.0 - alpha) * est + alpha * sample; }
 
 // ---- completion polling ---------------------------------------------------------------------
@@ -121,7 +135,7 @@ void poll_copy(ef_ctx *c, int slot) {
         if (hipEventElapsedTime(&ms, s.copy_start, s.ready) == hipSuccess && ms > 0.f) {
             double sec = ms * 1e-3;
             c->st.copy_seconds += sec;
-            ema(c->bw_Bps, (double)s.copy_bytes / sec);
+            if (!(c->cfg.flags & EF_FLAG_FIXED_ESTIMATES)) ema(c->bw_Bps, (double)s.copy_bytes / sec);
         }
         s.copy_pending = false;
     } else {
@@ -150,7 +164,7 @@ void poll_pairs(ef_ctx *c, bool wait) {
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess && ms > 0.f) {
             c->st.layer_seconds += ms * 1e-3;
-            ema(c->layer_s, ms * 1e-3);
+            if (!(c->cfg.flags & EF_FLAG_FIXED_ESTIMATES)) ema(c->layer_s, ms * 1e-3);
         }
         c->layer_pending.pop_front();
     }
@@ -178,15 +192,17 @@ struct KernelTimer {
     int kind;
     double bytes;
     EventPair p{nullptr, nullptr};
-    KernelTimer(ef_ctx *ctx, hipStream_t st, int k, double b) : c(ctx), s(st), kind(k), bytes(b) {
-        if (!c->profile) return;
+    bool on;
+    KernelTimer(ef_ctx *ctx, hipStream_t st, int k, double b)
+        : c(ctx), s(st), kind(k), bytes(b), on(((ctx->profile_mask >> k) & 1u) != 0) {
+        if (!on) return;
         if (c->prof_pending.size() >= c->prof_ring.size()) poll_prof(c, true);
         p = c->prof_ring[c->prof_next];
         c->prof_next = (c->prof_next + 1) % c->prof_ring.size();
         (void)hipEventRecord(p.a, s);
     }
     ~KernelTimer() {
-        if (!c->profile) return;
+        if (!on) return;
         (void)hipEventRecord(p.b, s);
         c->prof_pending.push_back({p, kind, bytes});
     }
@@ -359,6 +375,10 @@ extern "C" int ef_destroy(ef_ctx *c) {
         if (c->xp) (void)hipFree(c->xp);
         if (c->act) (void)hipFree(c->act);
         if (c->y) (void)hipFree(c->y);
+        for (void *p : {(void *)c->st_ids, (void *)c->st_counts, (void *)c->st_offsets, (void *)c->st_perm,
+                        (void *)c->st_inv, (void *)c->st_pred_ids, (void *)c->st_pred_hist, (void *)c->st_w})
+            if (p) (void)hipFree(p);
+        if (c->meta_host) (void)hipHostFree(c->meta_host);
     }
     delete c->cache;
     delete c;
@@ -412,7 +432,12 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
     const size_t xp_bytes = (size_t)c->max_tiles * ef::kTile * d * 2;
     const size_t act_bytes = (size_t)routed_tiles * ef::kTile * g.d_ff * 2 +
                              (size_t)shared_tiles * ef::kTile * g.d_ff_shared * 2;
-    const size_t y_bytes = (size_t)(Tm * k + (g.d_ff_shared > 0 ? Tm : 0)) * d * 4;
+    // expert outputs: one plane of (T*k [+T]) x d floats, times up to 8 K-slice planes while that stays
+    // under 64 MiB (small batches split K of the second FFN half across workgroups)
+    const long long y_plane_max = (Tm * k + (g.d_ff_shared > 0 ? Tm : 0)) * d;
+    long long planes = std::max(1ll, std::min(8ll, (16ll << 20) / y_plane_max));
+    c->y_floats = y_plane_max * planes;
+    const size_t y_bytes = (size_t)c->y_floats * 4;
 
     auto bail = [&](hipError_t e, const char *what) {
         int rc = fail(nullptr, e == hipErrorOutOfMemory ? EF_ENOMEM : EF_EHIP, "ef_create: %s: %s", what,
@@ -429,6 +454,27 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
     if ((e = hipMalloc(&c->xp, xp_bytes)) != hipSuccess) return bail(e, "packed-token scratch");
     if ((e = hipMalloc(&c->act, act_bytes)) != hipSuccess) return bail(e, "activation scratch");
     if ((e = hipMalloc(&c->y, y_bytes)) != hipSuccess) return bail(e, "expert-output scratch");
+
+    {
+        const size_t n = (size_t)Tm * k;
+        if ((e = hipMalloc(&c->st_ids, n * 4)) != hipSuccess) return bail(e, "step buffers");
+        if ((e = hipMalloc(&c->st_w, n * 4)) != hipSuccess) return bail(e, "step buffers");
+        if ((e = hipMalloc(&c->st_perm, n * 4)) != hipSuccess) return bail(e, "step buffers");
+        if ((e = hipMalloc(&c->st_inv, n * 4)) != hipSuccess) return bail(e, "step buffers");
+        if ((e = hipMalloc(&c->st_pred_ids, n * 4 * EF_MAX_HORIZON)) != hipSuccess) return bail(e, "step buffers");
+        if ((e = hipMalloc(&c->st_counts, (size_t)E * 4)) != hipSuccess) return bail(e, "step buffers");
+        if ((e = hipMalloc(&c->st_offsets, (size_t)(E + 1) * 4)) != hipSuccess) return bail(e, "step buffers");
+        if ((e = hipMalloc(&c->st_pred_hist, (size_t)EF_MAX_HORIZON * E * 4)) != hipSuccess)
+            return bail(e, "step buffers");
+        if ((e = hipMemset(c->st_pred_hist, 0, (size_t)EF_MAX_HORIZON * E * 4)) != hipSuccess)
+            return bail(e, "step buffers");
+        if ((e = hipHostMalloc(reinterpret_cast<void **>(&c->meta_host), (size_t)ef::kMetaInts * 4,
+                               hipHostMallocMapped)) != hipSuccess)
+            return bail(e, "host-mapped hand-over buffer");
+        memset(c->meta_host, 0, (size_t)ef::kMetaInts * 4);
+        if ((e = hipHostGetDevicePointer(reinterpret_cast<void **>(&c->meta_dev), c->meta_host, 0)) != hipSuccess)
+            return bail(e, "host-mapped hand-over buffer");
+    }
     for (int q = 0; q < 2; ++q)
         if ((e = hipStreamCreateWithFlags(&c->copy_stream[q], hipStreamNonBlocking)) != hipSuccess)
             return bail(e, "copy stream");
@@ -441,8 +487,9 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
         if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
     c->stall_ring.resize(128);
     c->layer_ring.resize(128);
-    c->profile = (g.flags & EF_FLAG_PROFILE) != 0;
-    if (c->profile) c->prof_ring.resize(1024);
+    if (g.flags & EF_FLAG_PROFILE) c->profile_mask = 0xFFu;
+    else if (g.flags & EF_FLAG_PROFILE_FFN_UP) c->profile_mask = 1u << EF_K_FFN_UP;
+    if (c->profile_mask) c->prof_ring.resize(1024);
     for (auto *ring : {&c->stall_ring, &c->layer_ring, &c->prof_ring})
         for (auto &p : *ring) {
             if ((e = hipEventCreate(&p.a)) != hipSuccess) return bail(e, "event");
@@ -479,61 +526,118 @@ extern "C" int ef_register_layer(ef_ctx *c, int layer, const void *gate_w, const
 // hot path
 // =================================================================================================
 
+namespace {
+
+const ef::GroupExport kNoExport{nullptr, nullptr, 0, 0, 0};
+
+// One pass over `hidden`: optionally the current layer's own gate (routing outputs and grouping)
+// and the gates of the next He layers (prediction outputs).  Wide launches are split over the gates.
+int run_gates(ef_ctx *c, int layer, const void *hidden, int T, float beta, bool do_route, int He, int H_stride,
+              const float *delta, const int32_t *tok2req, int32_t *topk_ids, float *topk_w, int32_t *counts,
+              int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *pred_ids, int32_t *pred_hist,
+              const ef::GroupExport &ex, hipStream_t s) {
+    const int E = c->cfg.n_experts, k = c->cfg.top_k, d = c->cfg.d_model;
+    const int ntiles = (T + ef::kTile - 1) / ef::kTile;
+    // the library's own histogram buffer is left zeroed by the hand-over step of the previous layer
+    if (He > 0 && !ex.host_meta) EF_HIP(c, ef::launch_fill_i32(pred_hist, He * E, 0, s));
+    const int per_launch = ef::kMaxGates;
+    const int total_gates = (do_route ? 1 : 0) + He;
+    for (int g0 = 0; g0 < total_gates; g0 += per_launch) {
+        ef::GateArgs a{};
+        a.h = static_cast<const uint16_t *>(hidden);
+        a.T = T; a.d = d; a.E = E; a.k = k;
+        a.G = std::min(per_launch, total_gates - g0);
+        a.beta = beta;
+        a.tok2req = tok2req;
+        a.delta = nullptr;
+        a.delta_req_stride = H_stride * E;
+        a.delta_gate_begin = 0;
+        bool first_pred = true;
+        for (int gi = 0; gi < a.G; ++gi) {
+            const int gg = g0 + gi;                       // index over [route?] + predictions
+            const bool is_route = do_route && gg == 0;
+            const int j = gg - (do_route ? 1 : 0);        // prediction index (0-based) when !is_route
+            const int ly = is_route ? layer : layer + 1 + j;
+            const LayerReg &L = c->layers[(size_t)ly];
+            a.Wg[gi] = L.gate_w;
+            a.bias[gi] = L.gate_b;
+            a.resident[gi] = resident_mask(c, ly);
+            if (is_route) {
+                a.ids[gi] = topk_ids;
+                a.hist[gi] = nullptr;
+                a.w = topk_w;
+                a.blockcounts = c->blockcounts;
+                a.renorm = c->cfg.renorm_topk;
+                a.routed_scale = c->cfg.routed_scale;
+            } else {
+                a.ids[gi] = pred_ids + (size_t)j * T * k;
+                a.hist[gi] = pred_hist + (size_t)j * E;
+                if (first_pred) {
+                    a.delta_gate_begin = gi;
+                    a.delta = delta ? delta + (size_t)j * E : nullptr;
+                    first_pred = false;
+                }
+            }
+        }
+        a.gpw = ef::gate_pick_gpw(T, a.G, E);
+        const bool has_route = do_route && g0 == 0;
+        {
+            KernelTimer kt(c, s, has_route ? EF_K_ROUTE : EF_K_PREDICT,
+                           (double)T * d * 2 + (double)a.G * E * d * 2 + (double)a.G * T * k * 4 +
+                               (has_route ? (double)T * k * 4 + (double)ntiles * E * 4 : 0.0) +
+                               (double)(a.G - (has_route ? 1 : 0)) * E * 4);
+            EF_HIP(c, ef::launch_gate(a, s));
+        }
+    }
+    if (do_route) {
+        KernelTimer kt(c, s, EF_K_GROUP, (double)ntiles * E * 8 + (double)(2 * E + 1) * 4 + (double)T * k * 12);
+        EF_HIP(c, ef::launch_group(c->blockcounts, topk_ids, T, k, E, c->blockbase, counts, offsets, perm,
+                                   inv_perm, ex, s));
+    }
+    return EF_OK;
+}
+
+int check_predict_args(ef_ctx *c, int layer, int T, int H, int *He_out, const char *who) {
+    if (c->fake) return fail(c, EF_ENOSYS, "%s: fake-copy context has no device", who);
+    if (H < 0 || H > EF_MAX_HORIZON) return fail(c, EF_EINVAL, "%s: H must be in 0..%d", who, EF_MAX_HORIZON);
+    if (T < 0 || T > c->cfg.max_tokens) return fail(c, EF_EINVAL, "%s: T=%d outside 0..max_tokens", who, T);
+    int He = std::max(0, std::min(H, c->cfg.n_layers - 1 - layer));
+    for (int j = 1; j <= He; ++j)
+        if (!c->layers[(size_t)(layer + j)].set)
+            return fail(c, EF_EINVAL, "%s: layer %d is not registered", who, layer + j);
+    *He_out = He;
+    return EF_OK;
+}
+
+int open_layer_timer(ef_ctx *c, hipStream_t s) {
+    poll_pairs(c, false);
+    c->layer_cur = next_pair(c->layer_ring, c->layer_next, c->layer_pending);
+    EF_HIP(c, hipEventRecord(c->layer_cur.a, s));
+    c->layer_open = true;
+    return EF_OK;
+}
+
+}  // namespace
+
 extern "C" int ef_predict(ef_ctx *c, int layer, const void *hidden, int T, int H, const float *delta,
                           const int32_t *tok2req, float beta, int32_t *topk_ids, int32_t *hist, int *H_eff,
                           void *stream) {
     int rc = check_ctx_layer(c, layer);
     if (rc) return rc;
-    if (c->fake) return fail(c, EF_ENOSYS, "ef_predict: fake-copy context has no device");
-    if (H < 0 || H > EF_MAX_HORIZON) return fail(c, EF_EINVAL, "ef_predict: H must be in 0..%d", EF_MAX_HORIZON);
-    if (T < 0 || T > c->cfg.max_tokens) return fail(c, EF_EINVAL, "ef_predict: T=%d outside 0..max_tokens", T);
-    int He = std::min(H, c->cfg.n_layers - 1 - layer);
+    int He = 0;
+    if ((rc = check_predict_args(c, layer, T, H, &He, "ef_predict"))) return rc;
     if (H_eff) *H_eff = He;
-    if (He <= 0) {
-        if (H_eff) *H_eff = 0;
-        return EF_OK;
-    }
-    if (T == 0) {
-        if (!hist) return fail(c, EF_EINVAL, "ef_predict: null pointer");
-        EF_HIP(c, ef::launch_fill_i32(hist, He * c->cfg.n_experts, 0, static_cast<hipStream_t>(stream)));
-        return EF_OK;
-    }
-    if (!hidden || !topk_ids || !hist) return fail(c, EF_EINVAL, "ef_predict: null pointer");
-    if (!aligned16(hidden)) return fail(c, EF_EINVAL, "ef_predict: hidden must be 16-byte aligned");
-    for (int j = 1; j <= He; ++j)
-        if (!c->layers[(size_t)(layer + j)].set)
-            return fail(c, EF_EINVAL, "ef_predict: layer %d is not registered", layer + j);
+    if (He == 0) return EF_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int E = c->cfg.n_experts, k = c->cfg.top_k;
-    EF_HIP(c, ef::launch_fill_i32(hist, He * E, 0, s));
-    const int per_launch = std::max(1, std::min(ef::kMaxGates, ef::kGateMaxCols / E));
-    for (int j0 = 0; j0 < He; j0 += per_launch) {
-        ef::GateArgs a{};
-        a.h = static_cast<const uint16_t *>(hidden);
-        a.T = T; a.d = c->cfg.d_model; a.E = E; a.k = k;
-        a.G = std::min(per_launch, He - j0);
-        for (int gidx = 0; gidx < a.G; ++gidx) {
-            const LayerReg &L = c->layers[(size_t)(layer + 1 + j0 + gidx)];
-            a.Wg[gidx] = L.gate_w;
-            a.bias[gidx] = L.gate_b;
-            a.resident[gidx] = resident_mask(c, layer + 1 + j0 + gidx);
-        }
-        a.beta = beta;
-        a.delta = delta ? delta + (size_t)j0 * E : nullptr;
-        a.delta_req_stride = H * E;
-        a.tok2req = tok2req;
-        a.ids = topk_ids + (size_t)j0 * T * k;
-        a.w = nullptr;
-        a.renorm = 0; a.routed_scale = 1.f;
-        a.hist = hist + (size_t)j0 * E;
-        a.blockcounts = nullptr;
-        {
-            KernelTimer kt(c, s, EF_K_PREDICT, (double)T * a.d * 2 + (double)a.G * E * a.d * 2 +
-                                                   (double)a.G * T * k * 4 + (double)a.G * E * 4);
-            EF_HIP(c, ef::launch_gate(a, s));
-        }
+    if (!hist) return fail(c, EF_EINVAL, "ef_predict: null pointer");
+    if (T == 0) {
+        EF_HIP(c, ef::launch_fill_i32(hist, He * c->cfg.n_experts, 0, s));
+        return EF_OK;
     }
-    return EF_OK;
+    if (!hidden || !topk_ids) return fail(c, EF_EINVAL, "ef_predict: null pointer");
+    if (!aligned16(hidden)) return fail(c, EF_EINVAL, "ef_predict: hidden must be 16-byte aligned");
+    return run_gates(c, layer, hidden, T, beta, false, He, H, delta, tok2req, nullptr, nullptr, nullptr, nullptr,
+                     nullptr, nullptr, topk_ids, hist, kNoExport, s);
 }
 
 extern "C" int ef_route(ef_ctx *c, int layer, const void *hidden, int T, float beta, int32_t *topk_ids,
@@ -545,7 +649,7 @@ extern "C" int ef_route(ef_ctx *c, int layer, const void *hidden, int T, float b
     if (T < 0 || T > c->cfg.max_tokens) return fail(c, EF_EINVAL, "ef_route: T=%d outside 0..max_tokens", T);
     if (!counts || !offsets) return fail(c, EF_EINVAL, "ef_route: null pointer");
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int E = c->cfg.n_experts, k = c->cfg.top_k;
+    const int E = c->cfg.n_experts;
     if (T == 0) {
         EF_HIP(c, ef::launch_fill_i32(counts, E, 0, s));
         EF_HIP(c, ef::launch_fill_i32(offsets, E + 1, 0, s));
@@ -553,42 +657,35 @@ extern "C" int ef_route(ef_ctx *c, int layer, const void *hidden, int T, float b
     }
     if (!hidden || !topk_ids || !topk_w || !perm || !inv_perm) return fail(c, EF_EINVAL, "ef_route: null pointer");
     if (!aligned16(hidden)) return fail(c, EF_EINVAL, "ef_route: hidden must be 16-byte aligned");
+    if ((rc = open_layer_timer(c, s))) return rc;
+    return run_gates(c, layer, hidden, T, beta, true, 0, 0, nullptr, nullptr, topk_ids, topk_w, counts, offsets,
+                     perm, inv_perm, nullptr, nullptr, kNoExport, s);
+}
 
-    poll_pairs(c, false);
-    c->layer_cur = next_pair(c->layer_ring, c->layer_next, c->layer_pending);
-    EF_HIP(c, hipEventRecord(c->layer_cur.a, s));
-    c->layer_open = true;
-
-    const LayerReg &L = c->layers[(size_t)layer];
-    ef::GateArgs a{};
-    a.h = static_cast<const uint16_t *>(hidden);
-    a.T = T; a.d = c->cfg.d_model; a.E = E; a.k = k; a.G = 1;
-    a.Wg[0] = L.gate_w;
-    a.bias[0] = L.gate_b;
-    a.resident[0] = resident_mask(c, layer);
-    a.beta = beta;
-    a.delta = nullptr; a.delta_req_stride = 0; a.tok2req = nullptr;
-    a.ids = topk_ids;
-    a.w = topk_w;
-    a.renorm = c->cfg.renorm_topk;
-    a.routed_scale = c->cfg.routed_scale;
-    a.hist = nullptr;
-    a.blockcounts = c->blockcounts;
-    const int ntiles = (T + ef::kTile - 1) / ef::kTile;
-    {
-        KernelTimer kt(c, s, EF_K_ROUTE, (double)T * a.d * 2 + (double)E * a.d * 2 + (double)T * k * 8 +
-                                             (double)ntiles * E * 4);
-        EF_HIP(c, ef::launch_gate(a, s));
+extern "C" int ef_route_predict(ef_ctx *c, int layer, const void *hidden, int T, float beta, int H,
+                                const float *delta, const int32_t *tok2req, int32_t *topk_ids, float *topk_w,
+                                int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
+                                int32_t *pred_ids, int32_t *pred_hist, int *H_eff, void *stream) {
+    int rc = check_ctx_layer(c, layer);
+    if (rc) return rc;
+    int He = 0;
+    if ((rc = check_predict_args(c, layer, T, H, &He, "ef_route_predict"))) return rc;
+    if (H_eff) *H_eff = He;
+    if (!counts || !offsets || (He > 0 && !pred_hist)) return fail(c, EF_EINVAL, "ef_route_predict: null pointer");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int E = c->cfg.n_experts;
+    if (T == 0) {
+        EF_HIP(c, ef::launch_fill_i32(counts, E, 0, s));
+        EF_HIP(c, ef::launch_fill_i32(offsets, E + 1, 0, s));
+        if (He > 0) EF_HIP(c, ef::launch_fill_i32(pred_hist, He * E, 0, s));
+        return EF_OK;
     }
-    {
-        KernelTimer kt(c, s, EF_K_SCAN, (double)ntiles * E * 8 + (double)(2 * E + 1) * 4);
-        EF_HIP(c, ef::launch_group_scan(c->blockcounts, ntiles, E, c->blockbase, counts, offsets, s));
-    }
-    {
-        KernelTimer kt(c, s, EF_K_SCATTER, (double)T * k * 12 + (double)ntiles * E * 4);
-        EF_HIP(c, ef::launch_group_scatter(topk_ids, T, k, E, c->blockbase, offsets, perm, inv_perm, s));
-    }
-    return EF_OK;
+    if (!hidden || !topk_ids || !topk_w || !perm || !inv_perm || (He > 0 && !pred_ids))
+        return fail(c, EF_EINVAL, "ef_route_predict: null pointer");
+    if (!aligned16(hidden)) return fail(c, EF_EINVAL, "ef_route_predict: hidden must be 16-byte aligned");
+    if ((rc = open_layer_timer(c, s))) return rc;
+    return run_gates(c, layer, hidden, T, beta, true, He, H, delta, tok2req, topk_ids, topk_w, counts, offsets,
+                     perm, inv_perm, pred_ids, pred_hist, kNoExport, s);
 }
 
 extern "C" int ef_cache_swap_in(ef_ctx *c, int layer, int expert, int priority, int due_in, int *slot_out) {
@@ -620,7 +717,7 @@ struct PhaseGroup {
 int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, const int32_t *counts_host,
                  const std::vector<int> &offs_host, const std::vector<int> &tile_start,
                  const std::vector<long long> &act_off, int shared_tile_start, long long shared_act_off, int T,
-                 hipStream_t s) {
+                 int ksg, long long y_plane, hipStream_t s) {
     if (groups.empty()) return EF_OK;
     const int d = c->cfg.d_model, k = c->cfg.top_k;
     ef::GroupTable gu{}, dn{};
@@ -645,12 +742,20 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
     gu.n_groups = n;
     dn = gu;
     const int tpp = max_tiles >= 2 ? 2 : 1;
+    // K slices inside a workgroup of the first half: split while the launch has too few waves to
+    // keep enough weight bytes in flight, as long as a slice keeps >= 16 fragments
+    long long units = 0;
+    for (int i = 0; i < n; ++i) units += (long long)(gu.F[i] / 32) * ((gu.n_tiles[i] + tpp - 1) / tpp);
+    int ks = 1;
+    const int want_waves = tune("EF_TUNE_UP_WAVES", 768), nkb = d / 16;
+    while (ks < 4 && units * ks < want_waves && nkb / (ks * 2) >= 16) ks *= 2;
+    ks = tune("EF_TUNE_UP_KS", ks);
     int wg_gu = 0, wg_dn = 0;
     for (int i = 0; i < n; ++i) {
         gu.wg_start[i] = wg_gu;
         dn.wg_start[i] = wg_dn;
-        wg_gu += ef::ffn_gate_up_wgs(gu.F[i], gu.n_tiles[i], tpp);
-        wg_dn += ef::ffn_down_wgs(d, gu.n_tiles[i], tpp);
+        wg_gu += ef::ffn_gate_up_wgs(gu.F[i], gu.n_tiles[i], tpp, ks);
+        wg_dn += ef::ffn_down_wgs(d, gu.n_tiles[i], tpp, ksg);
     }
     gu.wg_start[n] = wg_gu;
     dn.wg_start[n] = wg_dn;
@@ -661,11 +766,11 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
     }
     {
         KernelTimer kt(c, s, EF_K_FFN_UP, b_up);
-        EF_HIP(c, ef::launch_ffn_gate_up(gu, wg_gu, tpp, c->xp, c->act, d, s));
+        EF_HIP(c, ef::launch_ffn_gate_up(gu, wg_gu, tpp, ks, c->xp, c->act, d, s));
     }
     {
         KernelTimer kt(c, s, EF_K_FFN_DOWN, b_dn);
-        EF_HIP(c, ef::launch_ffn_down(dn, wg_dn, tpp, c->act, c->y, d, s));
+        EF_HIP(c, ef::launch_ffn_down(dn, wg_dn, tpp, ksg, c->act, c->y, y_plane, d, s));
     }
     return EF_OK;
 }
@@ -711,6 +816,30 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
     const long long shared_act_off = (long long)tiles * ef::kTile * c->cfg.d_ff / 8;
     if (has_shared) tiles += (T + ef::kTile - 1) / ef::kTile;
     if (!c->fake && tiles > c->max_tiles) return fail(c, EF_EINVAL, "ef_moe_ffn: scratch too small (internal)");
+
+    // K slices of the second FFN half across workgroups (one Y plane each, summed by the un-permute):
+    // split while the layer's launch would have too few workgroups, a slice keeps >= 32 fragments per
+    // wave and the planes fit the scratch.  One value per call: every phase shares the planes.
+    const long long y_plane = ((long long)T * k + (has_shared ? T : 0)) * d;
+    int ksg = 1;
+    if (T > 0) {
+        long long base_wgs = 0;
+        int tmax = 1;
+        for (int e = 0; e < E; ++e) tmax = std::max(tmax, (counts_host[e] + ef::kTile - 1) / ef::kTile);
+        if (has_shared) tmax = std::max(tmax, (T + ef::kTile - 1) / ef::kTile);
+        const int tpp = tmax >= 2 ? 2 : 1;
+        for (int e = 0; e < E; ++e)
+            if (counts_host[e] > 0)
+                base_wgs += ef::ffn_down_wgs(d, (counts_host[e] + ef::kTile - 1) / ef::kTile, tpp, 1);
+        if (has_shared) base_wgs += ef::ffn_down_wgs(d, (T + ef::kTile - 1) / ef::kTile, tpp, 1);
+        const int want = tune("EF_TUNE_DOWN_WGS", 256);
+        const int nkb_min = std::min(c->cfg.d_ff, has_shared ? c->cfg.d_ff_shared : c->cfg.d_ff) / 16;
+        while (ksg < 8 && base_wgs * ksg < want && nkb_min / (ksg * 2 * 4) >= 32 &&
+               y_plane * (ksg * 2) <= c->y_floats)
+            ksg *= 2;
+        int forced = tune("EF_TUNE_DOWN_KSG", ksg);
+        if (forced >= 1 && forced <= 8 && y_plane * forced <= c->y_floats) ksg = forced;
+    }
 
     // classify the needed experts
     std::vector<PhaseGroup> ready, loading;
@@ -795,7 +924,7 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         if (with_shared && has_shared) g.push_back({-1, -1});
         if (!c->fake) {
             int r = launch_phase(c, layer, g, counts_host, offs_host, tile_start, act_off, shared_tile_start,
-                                 shared_act_off, T, s);
+                                 shared_act_off, T, ksg, y_plane, s);
             if (r) return r;
         }
         return mark_read(v);
@@ -857,10 +986,10 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
             if (rc) { unpin_all(wave); return rc; }
         }
         if (!c->fake) {
-            const float *shared_y = has_shared ? c->y + (size_t)T * k * d : nullptr;
             KernelTimer kt(c, s, EF_K_COMBINE, 4.0 * ((double)T * k + (has_shared ? T : 0)) * d + 4.0 * T * d +
                                                    8.0 * T * k);
-            EF_HIP(c, ef::launch_combine(c->y, topk_w, inv_perm, T, k, d, shared_y, out, s));
+            EF_HIP(c, ef::launch_combine(c->y, ksg, y_plane, topk_w, inv_perm, T, k, d,
+                                         has_shared ? (long long)T * k : -1ll, out, s));
         }
     }
     if (!c->fake && c->layer_open) {
@@ -931,6 +1060,62 @@ extern "C" int ef_choose_horizon(ef_ctx *c, int layer, const int32_t *hist_host,
     return EF_OK;
 }
 
+extern "C" int ef_layer_step(ef_ctx *c, int layer, const void *hidden, int T, float beta, int H,
+                             const float *delta, const int32_t *tok2req, float *out, int *H_next,
+                             int32_t *counts_host_out, void *stream) {
+    int rc = check_ctx_layer(c, layer);
+    if (rc) return rc;
+    if (H < 0) H = c->horizon;
+    int He = 0;
+    if ((rc = check_predict_args(c, layer, T, H, &He, "ef_layer_step"))) return rc;
+    if (T <= 0) return fail(c, EF_EINVAL, "ef_layer_step: T must be positive");
+    if (!hidden || !out) return fail(c, EF_EINVAL, "ef_layer_step: null pointer");
+    if (!aligned16(hidden) || !aligned16(out)) return fail(c, EF_EINVAL, "ef_layer_step: hidden/out must be 16-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int E = c->cfg.n_experts;
+    if ((rc = open_layer_timer(c, s))) return rc;
+    // 1. one pass over the hidden states: routing of this layer + demand of the next He layers; the
+    //    grouping kernel hands counts and histograms to the host through mapped memory
+    const int seq = ++c->meta_seq;
+    ef::GroupExport ex{c->meta_dev, c->st_pred_hist, He * E, EF_MAX_HORIZON * E, seq};
+    rc = run_gates(c, layer, hidden, T, beta, true, He, H, delta, tok2req, c->st_ids, c->st_w, c->st_counts,
+                   c->st_offsets, c->st_perm, c->st_inv, c->st_pred_ids, c->st_pred_hist, ex, s);
+    if (rc) return rc;
+    // 2. wait for the flag (bounded: fall back to a stream synchronisation, then give up)
+    volatile int32_t *flag = c->meta_host + ef::kMetaFlag;
+    bool seen = false;
+    for (long long spin = 0; spin < (1ll << 34); ++spin) {
+        if (*flag == seq) { seen = true; break; }
+        __builtin_ia32_pause();
+        if ((spin & 0xFFFFF) == 0xFFFFF && hipStreamQuery(s) == hipSuccess) break;   // stream drained
+    }
+    if (!seen) {
+        EF_HIP(c, hipStreamSynchronize(s));
+        if (*flag != seq) return fail(c, EF_EHIP, "ef_layer_step: routing results never reached the host");
+    }
+    __atomic_thread_fence(__ATOMIC_ACQUIRE);
+    int32_t counts_host[EF_MAX_EXPERTS];
+    for (int e = 0; e < E; ++e) counts_host[e] = c->meta_host[e];
+    if (counts_host_out) memcpy(counts_host_out, counts_host, (size_t)E * 4);
+    // 3. horizon for the next layer and prefetches, issued before the FFN so the copies overlap it
+    int Hn = c->horizon;
+    if (He > 0) {
+        int32_t lst[EF_MAX_HORIZON * EF_MAX_EXPERTS];
+        int n = 0;
+        rc = ef_choose_horizon(c, layer, c->meta_host + ef::kMetaHist, He, T, &Hn, lst, &n);
+        if (rc) return rc;
+        for (int i = 0; i < n; ++i) {
+            const int j = lst[i] >> 16, e = lst[i] & 0xFFFF;
+            rc = swap_in_impl(c, layer + j, e, 0, j, nullptr, nullptr);
+            if (rc != EF_OK && rc != EF_EBUSY) return rc;   // a full, pinned cache only skips the prefetch
+        }
+    }
+    if (H_next) *H_next = Hn;
+    // 4. grouped FFN: resident groups first, misses swapped in meanwhile, weighted un-permute
+    return ef_moe_ffn(c, layer, hidden, T, c->st_ids, c->st_w, counts_host, c->st_offsets, c->st_perm, c->st_inv,
+                      out, stream);
+}
+
 extern "C" int ef_get_stats(ef_ctx *c, ef_stats *out) {
     if (!c || !out) return fail(c, EF_EINVAL, "ef_get_stats: null pointer");
     if (!c->fake) {
@@ -947,6 +1132,21 @@ extern "C" int ef_get_stats(ef_ctx *c, ef_stats *out) {
     int64_t n = c->st.hits + c->st.misses;
     c->st.miss_rate = n > 0 ? 1.0 - (double)c->st.hits / (double)n : 0.0;
     *out = c->st;
+    return EF_OK;
+}
+
+extern "C" int ef_set_profile(ef_ctx *c, unsigned kinds_mask) {
+    if (!c) return fail(nullptr, EF_EINVAL, "null context");
+    if (c->fake) return fail(c, EF_ENOSYS, "ef_set_profile: fake-copy context has no device");
+    poll_prof(c, true);
+    if (kinds_mask && c->prof_ring.empty()) {
+        c->prof_ring.resize(1024);
+        for (auto &p : c->prof_ring) {
+            EF_HIP(c, hipEventCreate(&p.a));
+            EF_HIP(c, hipEventCreate(&p.b));
+        }
+    }
+    c->profile_mask = kinds_mask & 0xFFu;
     return EF_OK;
 }
 

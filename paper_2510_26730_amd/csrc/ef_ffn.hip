@@ -1,0 +1,446 @@
+// Grouped SwiGLU expert FFN over the cache slots: token permutation into operand tiles, the two
+// weight-streaming matrix-core kernels, and the weighted un-permute.
+//
+// Both FFN halves are bound by streaming the active experts' weights from HBM whenever an expert
+// sees few tokens (decode); every weight fragment is then used exactly once.  The kernels are
+// therefore built around long, contiguous, software-pipelined 1 KiB fragment streams per wave and
+// enough waves in flight; the matrix cores only have to keep up.
+#include "ef_device.h"
+#include "ef_kernels.h"
+
+namespace ef {
+
+// ------------------------------------------------------------------------------------------
+// token permutation into per-expert groups, written directly in operand-fragment order:
+// xp[tile][kb][lane (g,i)] = 8 bf16 of row i of the tile, columns kb*16 + 8g .. +8.
+// grid = (tiles, column chunks); a workgroup copies a 32-row x (16*kb_per_wg)-column panel.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pack_x_kernel(PackTable pt, const uint16_t *__restrict__ h, int d, int k,
+                                                     const int32_t *__restrict__ perm, uint4 *__restrict__ xp,
+                                                     int kb_per_wg) {
+    const int tile = blockIdx.x;
+    int grp = 0;
+    while (grp + 1 < pt.n_groups && pt.tile_start[grp + 1] <= tile) ++grp;
+    const int local = tile - pt.tile_start[grp];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int g = lane >> 5, i = lane & 31;
+    const int r = local * kTile + i;
+    const bool valid = r < pt.count[grp];
+    int token = 0;
+    if (valid) token = pt.row_offset[grp] < 0 ? r : perm[pt.row_offset[grp] + r] / k;
+    const uint4 *src = reinterpret_cast<const uint4 *>(h + (size_t)token * d);
+    const int nkb = d >> 4;
+    uint4 *dst = xp + (size_t)tile * nkb * 64 + lane;
+    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    const int kb0 = blockIdx.y * kb_per_wg;
+    const int kb1 = min(nkb, kb0 + kb_per_wg);
+    for (int kb = kb0 + wave; kb < kb1; kb += 4) dst[(size_t)kb * 64] = valid ? src[kb * 2 + g] : zero4;
+}
+
+hipError_t launch_pack_x(const PackTable &pt, int total_tiles, const uint16_t *h, int d, int k,
+                         const int32_t *perm, void *xp, hipStream_t s) {
+    if (total_tiles <= 0) return hipSuccess;
+    const int nkb = d >> 4;
+    // enough workgroups to fill the chip at small tile counts, at least 8 fragments per workgroup
+    int chunks = 1;
+    while (total_tiles * chunks < 1024 && nkb / (chunks * 2) >= 8) chunks *= 2;
+    const int kb_per_wg = (nkb + chunks - 1) / chunks;
+    hipLaunchKernelGGL(pack_x_kernel, dim3(total_tiles, chunks), dim3(256), 0, s, pt, h, d, k, perm,
+                       reinterpret_cast<uint4 *>(xp), kb_per_wg);
+    return hipGetLastError();
+}
+
+// K loop of the first FFN half for NTL live token tiles: three register stages of UNR fragments per
+// operand; stages c+1 and c+2 are in flight while stage c feeds the matrix cores.  Every load is
+// unconditional (the last prefetch re-reads the final stage, in bounds).
+template <int TT, int NTL, int UNR>
+__device__ __forceinline__ void up_stream(const uint4 *__restrict__ w1, const uint4 *__restrict__ w3,
+                                          const uint4 *__restrict__ x0, int nkb, int k0, int k1,
+                                          floatx16 (&G)[TT], floatx16 (&U)[TT]) {
+    u32x4_t a1A[UNR], a3A[UNR], xA[NTL][UNR], a1B[UNR], a3B[UNR], xB[NTL][UNR], a1C[UNR], a3C[UNR], xC[NTL][UNR];
+#define EF_UP_LOAD(a1, a3, x, kb)                                                                        \
+    {                                                                                                    \
+        _Pragma("unroll") for (int u = 0; u < UNR; ++u) {                                                \
+            a1[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(w1 + (size_t)((kb) + u) * 64)); \
+            a3[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(w3 + (size_t)((kb) + u) * 64)); \
+        }                                                                                                \
+        _Pragma("unroll") for (int tt = 0; tt < NTL; ++tt)                                               \
+            _Pragma("unroll") for (int u = 0; u < UNR; ++u)                                              \
+                x[tt][u] = *reinterpret_cast<const u32x4_t *>(x0 + ((size_t)tt * nkb + (kb) + u) * 64);  \
+    }
+#define EF_UP_COMPUTE(a1, a3, x)                                                                         \
+    {                                                                                                    \
+        _Pragma("unroll") for (int u = 0; u < UNR; ++u)                                                  \
+            _Pragma("unroll") for (int tt = 0; tt < NTL; ++tt) {                                         \
+                G[tt] = mfma32v(a1[u], x[tt][u], G[tt]);                                                 \
+                U[tt] = mfma32v(a3[u], x[tt][u], U[tt]);                                                 \
+            }                                                                                            \
+    }
+    const int nfull = (k1 - k0) / UNR;
+    int kb = k0;
+    if (nfull > 0) {
+        const int last = k0 + (nfull - 1) * UNR;
+        EF_UP_LOAD(a1A, a3A, xA, kb)
+        EF_UP_LOAD(a1B, a3B, xB, min(kb + UNR, last))
+        int c = 0;
+        for (; c + 3 <= nfull; c += 3) {   // three register stages: two are always in flight
+            EF_UP_LOAD(a1C, a3C, xC, kb + 2 * UNR)
+            EF_UP_COMPUTE(a1A, a3A, xA)
+            EF_UP_LOAD(a1A, a3A, xA, min(kb + 3 * UNR, last))
+            EF_UP_COMPUTE(a1B, a3B, xB)
+            EF_UP_LOAD(a1B, a3B, xB, min(kb + 4 * UNR, last))
+            EF_UP_COMPUTE(a1C, a3C, xC)
+            kb += 3 * UNR;
+        }
+        if (c < nfull) {
+            EF_UP_COMPUTE(a1A, a3A, xA)
+            kb += UNR;
+        }
+        if (c + 1 < nfull) {
+            EF_UP_COMPUTE(a1B, a3B, xB)
+            kb += UNR;
+        }
+    }
+    for (; kb < k1; ++kb) {
+        const uint4 b1 = load_stream(w1 + (size_t)kb * 64), b3 = load_stream(w3 + (size_t)kb * 64);
+#pragma unroll
+        for (int tt = 0; tt < NTL; ++tt) {
+            const uint4 xv = x0[((size_t)tt * nkb + kb) * 64];
+            G[tt] = mfma32(b1, xv, G[tt]);
+            U[tt] = mfma32(b3, xv, U[tt]);
+        }
+    }
+#undef EF_UP_LOAD
+#undef EF_UP_COMPUTE
+}
+
+// ------------------------------------------------------------------------------------------
+// first half: act = silu(X W1^T) * (X W3^T).
+//
+// Work unit of a wave: (group, 32 F-rows "rb", pass of TT token tiles, K slice).  Weights are
+// operand A (rows = F index), packed tokens operand B (columns = tokens), so a lane ends with 16
+// F-values of one token: exactly the two paired-order fragments the second half consumes.
+// A workgroup is 4 waves = (4/KS row blocks) x (KS K-slices); K-slices are summed in a fixed
+// order through LDS before the non-linear epilogue.  Loads are double-buffered in registers:
+// the fragments of chunk c+1 are in flight while chunk c feeds the matrix cores.
+// ------------------------------------------------------------------------------------------
+template <int TT, int KS>
+__global__ __launch_bounds__(256) void ffn_gate_up_kernel(GroupTable gt, const uint4 *__restrict__ xp,
+                                                          uint4 *__restrict__ act, int d) {
+    constexpr int RBW = 4 / KS;
+    constexpr int UNR = (TT == 1) ? 4 : 2;    // fragments per operand per pipeline stage (register budget)
+    constexpr int REGION = TT * 2 * 16 * 64;  // floats of one wave's partial (G and U of TT tiles)
+    __shared__ float red[(KS > 1) ? 2 * REGION : 1];
+
+    const int wg = blockIdx.x;
+    int grp = 0;
+    while (grp + 1 < gt.n_groups && gt.wg_start[grp + 1] <= wg) ++grp;
+    const int local = wg - gt.wg_start[grp];
+    const int F = gt.F[grp];
+    const int nrb = F >> 5, rbw = (nrb + RBW - 1) / RBW;
+    const int pass = local / rbw;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int rbl = wave / KS, ks = wave % KS;
+    const int rb = (local % rbw) * RBW + rbl;
+    const bool active = rb < nrb;
+    int ntl = gt.n_tiles[grp] - pass * TT;
+    if (ntl > TT) ntl = TT;
+    const int nkb = d >> 4;
+    const int k0 = (int)((long long)ks * nkb / KS), k1 = (int)((long long)(ks + 1) * nkb / KS);
+
+    floatx16 G[TT], U[TT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) { zero16(G[tt]); zero16(U[tt]); }
+
+    if (active) {
+        const uint4 *w1 = reinterpret_cast<const uint4 *>(gt.blob[grp]) + (size_t)rb * 2 * nkb * 64 + lane;
+        const uint4 *w3 = w1 + (size_t)nkb * 64;
+        const uint4 *x0 = xp + (size_t)(gt.tile_start[grp] + pass * TT) * nkb * 64 + lane;
+        // the number of live token tiles is wave-uniform: pick a loop whose loads are unconditional,
+        // so the compiler knows how many are in flight and waits only for the oldest stage
+        if (TT == 1 || ntl == 1) up_stream<TT, 1, UNR>(w1, w3, x0, nkb, k0, k1, G, U);
+        else up_stream<TT, TT, UNR>(w1, w3, x0, nkb, k0, k1, G, U);
+    }
+
+    // fixed-order sum of the K-slices: (p0 + p2) + (p1 + p3) for KS = 4, p0 + p1 for KS = 2
+    if (KS > 1) {
+        auto put = [&](float *r) {
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    r[((tt * 2 + 0) * 16 + v) * 64 + lane] = G[tt][v];
+                    r[((tt * 2 + 1) * 16 + v) * 64 + lane] = U[tt][v];
+                }
+        };
+        auto add = [&](const float *r) {
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    G[tt][v] += r[((tt * 2 + 0) * 16 + v) * 64 + lane];
+                    U[tt][v] += r[((tt * 2 + 1) * 16 + v) * 64 + lane];
+                }
+        };
+        if (KS == 4) {
+            if (ks >= 2) put(red + (ks - 2) * REGION);
+            __syncthreads();
+            if (ks < 2) add(red + ks * REGION);
+            __syncthreads();
+            if (ks == 1) put(red);
+            __syncthreads();
+            if (ks == 0) add(red);
+        } else {
+            if (ks == 1) put(red + rbl * REGION);
+            __syncthreads();
+            if (ks == 0) add(red + rbl * REGION);
+        }
+    }
+
+    if (active && ks == 0) {
+        const int nkb2 = F >> 4;
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            if (tt >= ntl) break;
+            uint4 *dst = act + gt.act_off[grp] + ((size_t)(pass * TT + tt) * nkb2 + rb * 2) * 64 + lane;
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                uint32_t pk[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float g0 = G[tt][8 * s + 2 * q], g1 = G[tt][8 * s + 2 * q + 1];
+                    const float v0 = g0 / (1.f + __expf(-g0)) * U[tt][8 * s + 2 * q];
+                    const float v1 = g1 / (1.f + __expf(-g1)) * U[tt][8 * s + 2 * q + 1];
+                    pk[q] = f32_to_bf16_bits(v0) | (f32_to_bf16_bits(v1) << 16);
+                }
+                dst[(size_t)s * 64] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+            }
+        }
+    }
+}
+
+template <int TT>
+static hipError_t launch_up_tt(const GroupTable &gt, int total_wgs, int ks, const uint4 *x, uint4 *a, int d,
+                               hipStream_t s) {
+    if (ks == 1) hipLaunchKernelGGL((ffn_gate_up_kernel<TT, 1>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
+    else if (ks == 2) hipLaunchKernelGGL((ffn_gate_up_kernel<TT, 2>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
+    else if (ks == 4) hipLaunchKernelGGL((ffn_gate_up_kernel<TT, 4>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_ffn_gate_up(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ks, const void *xp,
+                              void *act, int d, hipStream_t s) {
+    if (total_wgs <= 0) return hipSuccess;
+    const uint4 *x = reinterpret_cast<const uint4 *>(xp);
+    uint4 *a = reinterpret_cast<uint4 *>(act);
+    if (tiles_per_pass == 1) return launch_up_tt<1>(gt, total_wgs, ks, x, a, d, s);
+    if (tiles_per_pass == 2) return launch_up_tt<2>(gt, total_wgs, ks, x, a, d, s);
+    return hipErrorInvalidValue;
+}
+
+// K loop of the second FFN half for NTL live token tiles and CBW column blocks per wave (same
+// three-stage pipeline as up_stream).  An activation fragment is loaded once and multiplied with
+// CBW weight fragments: activations come from L2 and are shared by every column block of the
+// group, so blocking over columns cuts that traffic and leaves the fetch paths to the weights.
+template <int TT, int NTL, int CBW, int UNR>
+__device__ __forceinline__ void down_stream(const uint4 *__restrict__ w2, size_t cb_stride,
+                                            const uint4 *__restrict__ a0, int nkb, int k0, int k1,
+                                            floatx16 (&acc)[CBW][TT]) {
+    u32x4_t bA[CBW][UNR], aA[NTL][UNR], bB[CBW][UNR], aB[NTL][UNR], bC[CBW][UNR], aC[NTL][UNR];
+#define EF_DN_LOAD(b, a, kb)                                                                             \
+    {                                                                                                    \
+        _Pragma("unroll") for (int cw = 0; cw < CBW; ++cw)                                               \
+            _Pragma("unroll") for (int u = 0; u < UNR; ++u)                                              \
+                b[cw][u] = __builtin_nontemporal_load(                                                   \
+                    reinterpret_cast<const u32x4_t *>(w2 + cw * cb_stride + (size_t)((kb) + u) * 64));   \
+        _Pragma("unroll") for (int tt = 0; tt < NTL; ++tt)                                               \
+            _Pragma("unroll") for (int u = 0; u < UNR; ++u)                                              \
+                a[tt][u] = *reinterpret_cast<const u32x4_t *>(a0 + ((size_t)tt * nkb + (kb) + u) * 64);  \
+    }
+#define EF_DN_COMPUTE(b, a)                                                                              \
+    {                                                                                                    \
+        _Pragma("unroll") for (int u = 0; u < UNR; ++u)                                                  \
+            _Pragma("unroll") for (int tt = 0; tt < NTL; ++tt)                                           \
+                _Pragma("unroll") for (int cw = 0; cw < CBW; ++cw)                                       \
+                    acc[cw][tt] = mfma32v(a[tt][u], b[cw][u], acc[cw][tt]);                              \
+    }
+    const int nfull = (k1 - k0) / UNR;
+    int kb = k0;
+    if (nfull > 0) {
+        const int last = k0 + (nfull - 1) * UNR;
+        EF_DN_LOAD(bA, aA, kb)
+        EF_DN_LOAD(bB, aB, min(kb + UNR, last))
+        int c = 0;
+        for (; c + 3 <= nfull; c += 3) {
+            EF_DN_LOAD(bC, aC, kb + 2 * UNR)
+            EF_DN_COMPUTE(bA, aA)
+            EF_DN_LOAD(bA, aA, min(kb + 3 * UNR, last))
+            EF_DN_COMPUTE(bB, aB)
+            EF_DN_LOAD(bB, aB, min(kb + 4 * UNR, last))
+            EF_DN_COMPUTE(bC, aC)
+            kb += 3 * UNR;
+        }
+        if (c < nfull) {
+            EF_DN_COMPUTE(bA, aA)
+            kb += UNR;
+        }
+        if (c + 1 < nfull) {
+            EF_DN_COMPUTE(bB, aB)
+            kb += UNR;
+        }
+    }
+    for (; kb < k1; ++kb) {
+#pragma unroll
+        for (int cw = 0; cw < CBW; ++cw) {
+            const uint4 b = load_stream(w2 + cw * cb_stride + (size_t)kb * 64);
+#pragma unroll
+            for (int tt = 0; tt < NTL; ++tt)
+                acc[cw][tt] = mfma32(a0[((size_t)tt * nkb + kb) * 64], b, acc[cw][tt]);
+        }
+    }
+#undef EF_DN_LOAD
+#undef EF_DN_COMPUTE
+}
+
+// ------------------------------------------------------------------------------------------
+// second half: Y = act W2^T.  A workgroup owns (group, pass of TT token tiles, CBW*32 output
+// columns, one of `ksg` K-slices); its four waves split that slice again and are summed in a fixed
+// order, (p0 + p2) + (p1 + p3), through LDS.  Each K-slice writes its own partial Y plane; the
+// un-permute sums the planes in order.  Activations are operand A (rows = tokens), W2 fragments
+// operand B (columns = outputs).
+// ------------------------------------------------------------------------------------------
+template <int TT>
+__global__ __launch_bounds__(256, 2) void ffn_down_kernel(GroupTable gt, const uint4 *__restrict__ act,
+                                                       float *__restrict__ Y, int d, int ksg,
+                                                       long long y_plane) {
+    constexpr int CBW = kDownColBlocks;
+    constexpr int UNR = 2;
+    constexpr int REGION = CBW * TT * 16 * 64;   // floats of one wave's partial
+    __shared__ float red[2 * REGION];
+    const int wg = blockIdx.x;
+    int grp = 0;
+    while (grp + 1 < gt.n_groups && gt.wg_start[grp + 1] <= wg) ++grp;
+    const int local = wg - gt.wg_start[grp];
+    const int ncbw = (d >> 5) / CBW;
+    const int kslice = local % ksg;
+    const int cb0 = ((local / ksg) % ncbw) * CBW, pass = (local / ksg) / ncbw;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int F = gt.F[grp];
+    const int nkb = F >> 4;
+    const int part = kslice * 4 + wave, nparts = ksg * 4;
+    const int k0 = (int)((long long)part * nkb / nparts), k1 = (int)((long long)(part + 1) * nkb / nparts);
+    int ntl = gt.n_tiles[grp] - pass * TT;
+    if (ntl > TT) ntl = TT;
+    const size_t cb_stride = (size_t)nkb * 64;
+    const uint4 *w2 = reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(gt.blob[grp]) +
+                                                      (size_t)4 * d * F) + (size_t)cb0 * cb_stride + lane;
+    const uint4 *a0 = act + gt.act_off[grp] + (size_t)(pass * TT) * nkb * 64 + lane;
+
+    floatx16 acc[CBW][TT];
+#pragma unroll
+    for (int cw = 0; cw < CBW; ++cw)
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) zero16(acc[cw][tt]);
+
+    if (TT == 1 || ntl == 1) down_stream<TT, 1, CBW, UNR>(w2, cb_stride, a0, nkb, k0, k1, acc);
+    else down_stream<TT, TT, CBW, UNR>(w2, cb_stride, a0, nkb, k0, k1, acc);
+
+    auto put = [&](float *r) {
+#pragma unroll
+        for (int cw = 0; cw < CBW; ++cw)
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) r[((cw * TT + tt) * 16 + v) * 64 + lane] = acc[cw][tt][v];
+    };
+    auto add = [&](const float *r) {
+#pragma unroll
+        for (int cw = 0; cw < CBW; ++cw)
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[cw][tt][v] += r[((cw * TT + tt) * 16 + v) * 64 + lane];
+    };
+    if (wave >= 2) put(red + (wave - 2) * REGION);
+    __syncthreads();
+    if (wave < 2) add(red + wave * REGION);
+    __syncthreads();
+    if (wave == 1) put(red);
+    __syncthreads();
+    if (wave != 0) return;
+    add(red);
+
+    const int g = lane >> 5;
+    float *Yp = Y + (size_t)kslice * y_plane;
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        if (tt >= ntl) break;
+#pragma unroll
+        for (int cw = 0; cw < CBW; ++cw) {
+            const int col = (cb0 + cw) * 32 + (lane & 31);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int tl = (pass * TT + tt) * kTile + 8 * (v >> 2) + 4 * g + (v & 3);
+                if (tl < gt.count[grp]) Yp[(size_t)(gt.row_offset[grp] + tl) * d + col] = acc[cw][tt][v];
+            }
+        }
+    }
+}
+
+hipError_t launch_ffn_down(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ksg, const void *act,
+                           float *y, long long y_plane, int d, hipStream_t s) {
+    if (total_wgs <= 0) return hipSuccess;
+    const uint4 *a = reinterpret_cast<const uint4 *>(act);
+    if (tiles_per_pass == 1)
+        hipLaunchKernelGGL((ffn_down_kernel<1>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
+    else if (tiles_per_pass == 2)
+        hipLaunchKernelGGL((ffn_down_kernel<2>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// weighted un-permute: out[t] = sum_j w[t,j] * (sum over K-slice planes of Y[inv_perm[t*k+j]])
+//                               (+ the dense shared FFN's row of token t)
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ Y, int ksg, long long y_plane,
+                                                      const float *__restrict__ w,
+                                                      const int32_t *__restrict__ inv_perm, int T, int k, int d,
+                                                      long long shared_row0, float *__restrict__ out) {
+    const int t = blockIdx.x;
+    const int c = (blockIdx.y * 256 + threadIdx.x) * 4;
+    if (c >= d) return;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int j = 0; j < k; ++j) {
+        const int a = t * k + j;
+        const float wj = w[a];
+        const float *row = Y + (size_t)inv_perm[a] * d + c;
+        float4 y = *reinterpret_cast<const float4 *>(row);
+        for (int p = 1; p < ksg; ++p) {
+            const float4 z = *reinterpret_cast<const float4 *>(row + (size_t)p * y_plane);
+            y.x += z.x; y.y += z.y; y.z += z.z; y.w += z.w;
+        }
+        acc.x += wj * y.x; acc.y += wj * y.y; acc.z += wj * y.z; acc.w += wj * y.w;
+    }
+    if (shared_row0 >= 0) {
+        const float *row = Y + (size_t)(shared_row0 + t) * d + c;
+        float4 y = *reinterpret_cast<const float4 *>(row);
+        for (int p = 1; p < ksg; ++p) {
+            const float4 z = *reinterpret_cast<const float4 *>(row + (size_t)p * y_plane);
+            y.x += z.x; y.y += z.y; y.z += z.z; y.w += z.w;
+        }
+        acc.x += y.x; acc.y += y.y; acc.z += y.z; acc.w += y.w;
+    }
+    *reinterpret_cast<float4 *>(out + (size_t)t * d + c) = acc;
+}
+
+hipError_t launch_combine(const float *y, int ksg, long long y_plane, const float *w, const int32_t *inv_perm,
+                          int T, int k, int d, long long shared_row0, float *out, hipStream_t s) {
+    if (T <= 0) return hipSuccess;
+    hipLaunchKernelGGL(combine_kernel, dim3(T, (d + 1023) / 1024), dim3(256), 0, s, y, ksg, y_plane, w, inv_perm,
+                       T, k, d, shared_row0, out);
+    return hipGetLastError();
+}
+
+}  // namespace ef

@@ -10,7 +10,8 @@ constexpr int kMaxK = 8;       // top-k
 constexpr int kMaxGates = 8;   // gate matrices per launch (look-ahead + 1)
 constexpr int kTile = 32;      // tokens per tile (rows of one matrix-core operand fragment)
 constexpr int kMaxGroups = kMaxE + 1;  // routed experts + the dense shared FFN
-constexpr int kGateMaxCols = 320;      // G*E columns one gate launch can hold
+constexpr int kDownColBlocks = 2;      // 32-column blocks per wave in the second FFN half
+constexpr int kGroupSmallTiles = 64;   // token tiles the single-workgroup grouping kernel handles
 
 // Gate / predict launch: G gate matrices applied to the same hidden states.
 struct GateArgs {
@@ -20,15 +21,17 @@ struct GateArgs {
     const float *bias[kMaxGates];  // [E] or null
     uint64_t resident[kMaxGates];  // bit e: expert e of that gate's layer is in the cache
     float beta;
-    const float *delta;            // f32 or null: delta[req*delta_req_stride + gate*E + e]
+    const float *delta;            // f32 or null: delta[req*delta_req_stride + (gate-delta_gate_begin)*E + e]
     int delta_req_stride;
+    int delta_gate_begin;          // gates below this index take no delta (the current layer's own gate)
     const int32_t *tok2req;        // [T] or null
-    int32_t *ids;                  // [G,T,k]
+    int32_t *ids[kMaxGates];       // per gate: [T,k]
     float *w;                      // [T,k] combine weights of gate 0, or null
     int renorm;
     float routed_scale;
-    int32_t *hist;                 // [G,E] accumulated with integer atomics, or null
+    int32_t *hist[kMaxGates];      // per gate: [E] accumulated with integer atomics, or null
     int32_t *blockcounts;          // [ntiles,E] per-tile counts of gate 0, or null
+    int gpw;                       // gates per workgroup (gpw * E <= 128 logit columns)
 };
 
 // Grouped FFN launch: one group per active expert (+ one for the dense shared FFN).
@@ -44,6 +47,18 @@ struct GroupTable {
     const void *blob[kMaxGroups];  // packed weights (cache slot or shared blob)
 };
 
+// Optional hand-over of counts and predicted histograms to the host (host-mapped memory + flag).
+constexpr int kMetaHist = kMaxE;                          // hist starts after the E counts
+constexpr int kMetaFlag = kMaxE + (kMaxGates - 1) * kMaxE; // sequence flag
+constexpr int kMetaInts = kMetaFlag + 1;
+struct GroupExport {
+    int32_t *host_meta;   // device view of the host-mapped buffer, or null
+    int32_t *hist;        // [n_hist] device histograms to copy out; [n_clear] is zeroed afterwards
+    int n_hist;
+    int n_clear;
+    int seq;
+};
+
 // Describes how rows are gathered into tiles for the X packing kernel.
 struct PackTable {
     int n_groups;
@@ -53,27 +68,27 @@ struct PackTable {
 };
 
 hipError_t launch_fill_i32(int32_t *p, int n, int32_t v, hipStream_t s);
+int gate_pick_gpw(int T, int G, int E);
 hipError_t launch_gate(const GateArgs &a, hipStream_t s);
-hipError_t launch_group_scan(const int32_t *blockcounts, int ntiles, int E, int32_t *blockbase,
-                             int32_t *counts, int32_t *offsets, hipStream_t s);
-hipError_t launch_group_scatter(const int32_t *ids, int T, int k, int E, const int32_t *blockbase,
-                                const int32_t *offsets, int32_t *perm, int32_t *inv_perm, hipStream_t s);
+hipError_t launch_group(const int32_t *blockcounts, const int32_t *ids, int T, int k, int E, int32_t *blockbase,
+                        int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
+                        const GroupExport &ex, hipStream_t s);
 hipError_t launch_pack_x(const PackTable &pt, int total_tiles, const uint16_t *h, int d, int k,
                          const int32_t *perm, void *xp, hipStream_t s);
-hipError_t launch_ffn_gate_up(const GroupTable &gt, int total_wgs, int tiles_per_pass, const void *xp,
+hipError_t launch_ffn_gate_up(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ks, const void *xp,
                               void *act, int d, hipStream_t s);
-hipError_t launch_ffn_down(const GroupTable &gt, int total_wgs, int tiles_per_pass, const void *act,
-                           float *y, int d, hipStream_t s);
-hipError_t launch_combine(const float *y, const float *w, const int32_t *inv_perm, int T, int k, int d,
-                          const float *shared_y, float *out, hipStream_t s);
+hipError_t launch_ffn_down(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ksg, const void *act,
+                           float *y, long long y_plane, int d, hipStream_t s);
+hipError_t launch_combine(const float *y, int ksg, long long y_plane, const float *w, const int32_t *inv_perm,
+                          int T, int k, int d, long long shared_row0, float *out, hipStream_t s);
 
 // workgroups a group needs in the two FFN launches
-inline int ffn_gate_up_wgs(int F, int n_tiles, int tiles_per_pass) {
-    int nrb = F / 32;
-    return ((nrb + 3) / 4) * ((n_tiles + tiles_per_pass - 1) / tiles_per_pass);
+inline int ffn_gate_up_wgs(int F, int n_tiles, int tiles_per_pass, int ks) {
+    int nrb = F / 32, rbw = 4 / ks;
+    return ((nrb + rbw - 1) / rbw) * ((n_tiles + tiles_per_pass - 1) / tiles_per_pass);
 }
-inline int ffn_down_wgs(int d, int n_tiles, int tiles_per_pass) {
-    return (d / 32) * ((n_tiles + tiles_per_pass - 1) / tiles_per_pass);
+inline int ffn_down_wgs(int d, int n_tiles, int tiles_per_pass, int ksg) {
+    return (d / 32 / kDownColBlocks) * ((n_tiles + tiles_per_pass - 1) / tiles_per_pass) * ksg;
 }
 
 }  // namespace ef

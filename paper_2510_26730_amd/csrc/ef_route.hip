@@ -1,0 +1,456 @@
+// Gate / predict kernel (matrix-core logits, wave-level softmax and biased top-k, per-tile expert
+// counts, demand histograms) and the stable grouping of assignments by expert.
+#include "ef_device.h"
+#include "ef_kernels.h"
+
+#include <algorithm>
+
+namespace ef {
+
+// ------------------------------------------------------------------------------------------
+// small fill (used instead of memset so that callers may capture the stream in a graph)
+// ------------------------------------------------------------------------------------------
+__global__ void fill_i32_kernel(int32_t *p, int n, int32_t v) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+hipError_t launch_fill_i32(int32_t *p, int n, int32_t v, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p, n, v);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// gate: logits of a group of gate matrices on one 32-token tile, then per-token softmax, biased
+// top-k, combine weights, per-tile expert counts and demand histograms.
+//
+// grid = (token tiles, gate groups): the G gates of a launch are cut into groups of `gpw` gates
+// (at most 128 logit columns); groups are independent, so no workgroup ever waits for or reduces
+// with another one.  Hidden states and gate rows are row-major in memory, so a K panel of both is
+// first brought into LDS with fully coalesced loads (a wave reads 512 or 256 contiguous bytes of a
+// row; reading operand fragments straight from 32 strided rows costs eight times the L1 tag
+// look-ups and makes small batches latency-bound); the next panel is prefetched into registers
+// while the eight waves run their share of the MFMA steps of the current one from LDS.
+// ------------------------------------------------------------------------------------------
+constexpr int kGateWaves = 8;
+
+// arr[idx] of a by-value kernel-argument array without forcing the struct into scratch memory
+template <class T>
+__device__ __forceinline__ T pick(const T (&arr)[kMaxGates], int idx) {
+    T v = arr[0];
+#pragma unroll
+    for (int q = 1; q < kMaxGates; ++q)
+        if (idx == q) v = arr[q];
+    return v;
+}
+
+template <int NB>
+__global__ __launch_bounds__(64 * kGateWaves) void gate_kernel(GateArgs a) {
+    constexpr int NW = kGateWaves, NT = 64 * NW;
+    constexpr int KC = NB == 1 ? 256 : 128;            // K panel (elements)
+    constexpr int LDK = KC + 8;                        // padded LDS row: 16-byte reads of 16 rows hit 64 banks
+    constexpr int C4 = KC / 8;                         // 16-byte units per panel row
+    constexpr int A_PER = 32 * C4 / NT;                // 16-byte loads per thread per panel
+    constexpr int B_PER = NB * 32 * C4 / NT;
+    constexpr int KSW = KC / 16 / NW;                  // MFMA k-steps per wave per panel
+    __shared__ __attribute__((aligned(16))) uint16_t As[32 * LDK];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[NB * 32 * LDK];
+    __shared__ float logits[kTile][NB * 32 + 1];
+    __shared__ int cnt[4 * 32];
+    __shared__ float sbias[4 * 32];
+    __shared__ __attribute__((aligned(16))) float s_sc[NW][64];
+    __shared__ __attribute__((aligned(16))) float s_z[NW][64];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int g = lane >> 5, i = lane & 31;
+    const int tile = blockIdx.x;
+    const int g0 = blockIdx.y * a.gpw;                 // first gate of this workgroup's group
+    const int Gl = min(a.gpw, a.G - g0);               // gates in the group
+    const int t0 = tile * kTile;
+    const int N = Gl * a.E;                            // logit columns of the group (<= NB*32)
+
+    for (int x = tid; x < NB * 32; x += NT) cnt[x] = 0;
+    // gate biases go to LDS now, so their latency hides behind the matrix-core phase
+    for (int x = tid; x < N; x += NT) {
+        const float *bp = pick(a.bias, g0 + x / a.E);
+        sbias[x] = bp ? bp[x % a.E] : 0.f;
+    }
+
+    // per-thread source rows of the panel loads (fixed over the K loop)
+    const uint16_t *asrc[A_PER];
+    const uint16_t *bsrc[B_PER];
+    bool aok[A_PER], bok[B_PER];
+#pragma unroll
+    for (int r = 0; r < A_PER; ++r) {
+        const int row = (tid + r * NT) / C4;
+        aok[r] = t0 + row < a.T;
+        asrc[r] = a.h + (size_t)(aok[r] ? t0 + row : 0) * a.d;
+    }
+#pragma unroll
+    for (int r = 0; r < B_PER; ++r) {
+        const int n = (tid + r * NT) / C4;
+        bok[r] = n < N;
+        bsrc[r] = pick(a.Wg, g0 + (bok[r] ? n / a.E : 0)) + (size_t)(bok[r] ? n % a.E : 0) * a.d;
+    }
+
+    floatx16 acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) zero16(acc[nb]);
+
+    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    const u32x4_t zero4v = {0u, 0u, 0u, 0u};
+    // PF panels are kept in flight in registers: with few token tiles the kernel is bound by memory
+    // latency, and one panel per round trip would cost d/KC round trips
+    constexpr int PF = 4;
+    u32x4_t ra[PF][A_PER], rb[PF][B_PER];
+#pragma unroll
+    for (int p = 0; p < PF; ++p) {
+#pragma unroll
+        for (int r = 0; r < A_PER; ++r) ra[p][r] = zero4v;
+#pragma unroll
+        for (int r = 0; r < B_PER; ++r) rb[p][r] = zero4v;
+    }
+#define EF_GATE_GLOAD(p, st)                                                                           \
+    {                                                                                                  \
+        _Pragma("unroll") for (int r = 0; r < A_PER; ++r) {                                            \
+            const int col = (st) * KC + ((tid + r * NT) % C4) * 8;                                     \
+            ra[p][r] = *reinterpret_cast<const u32x4_t *>(asrc[r] + min(col, a.d - 8));                \
+        }                                                                                              \
+        _Pragma("unroll") for (int r = 0; r < B_PER; ++r) {                                            \
+            const int col = (st) * KC + ((tid + r * NT) % C4) * 8;                                     \
+            rb[p][r] = *reinterpret_cast<const u32x4_t *>(bsrc[r] + min(col, a.d - 8));                \
+        }                                                                                              \
+    }
+    const int sbeg = 0, nstage = (a.d + KC - 1) / KC;
+    // prefetches are unconditional (past the end they re-read the last panel, in bounds) so that the
+    // number of loads in flight is known at compile time and only the oldest panel is waited for
+#pragma unroll
+    for (int p = 0; p < PF; ++p) EF_GATE_GLOAD(p, min(sbeg + p, nstage - 1))
+    for (int st0 = sbeg; st0 < nstage; st0 += PF) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            const int st = st0 + p;
+            {   // stages past the end (when nstage is not a multiple of PF) multiply zero panels
+#pragma unroll
+                for (int r = 0; r < A_PER; ++r) {
+                    const int idx = tid + r * NT;   // rows past T and columns past d contribute zeros
+                    const bool ok = aok[r] && st < nstage && st * KC + (idx % C4) * 8 < a.d;
+                    *reinterpret_cast<u32x4_t *>(&As[(idx / C4) * LDK + (idx % C4) * 8]) = ok ? ra[p][r] : zero4v;
+                }
+#pragma unroll
+                for (int r = 0; r < B_PER; ++r) {
+                    const int idx = tid + r * NT;
+                    const bool ok = bok[r] && st < nstage && st * KC + (idx % C4) * 8 < a.d;
+                    *reinterpret_cast<u32x4_t *>(&Bs[(idx / C4) * LDK + (idx % C4) * 8]) = ok ? rb[p][r] : zero4v;
+                }
+                __syncthreads();
+                EF_GATE_GLOAD(p, min(st + PF, nstage - 1))
+#pragma unroll
+                for (int q = 0; q < KSW; ++q) {
+                    const int kcol = (wave * KSW + q) * 16 + 8 * g;
+                    const uint4 af = *reinterpret_cast<const uint4 *>(&As[i * LDK + kcol]);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        const uint4 bf = *reinterpret_cast<const uint4 *>(&Bs[(nb * 32 + i) * LDK + kcol]);
+                        acc[nb] = mfma32(af, bf, acc[nb]);
+                    }
+                }
+                __syncthreads();
+            }
+        }
+    }
+
+#undef EF_GATE_GLOAD
+
+    // fixed-order reduction of the waves' partials (wave 0, 1, 2, ...) through LDS
+    for (int w = 0; w < NW; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    int row = 8 * (v >> 2) + 4 * g + (v & 3);
+                    if (w == 0) logits[row][nb * 32 + i] = acc[nb][v];
+                    else logits[row][nb * 32 + i] += acc[nb][v];
+                }
+        }
+        __syncthreads();
+    }
+
+    // per-token epilogue.  A sub-group of W lanes (W = power of two >= E) owns one token; a wave
+    // handles 64/W tokens of ONE gate per round (the gate index is wave-uniform, so per-gate
+    // arguments are scalar loads).  Selection is by rank: lane e counts, from an LDS copy of the
+    // token's scores, how many experts beat it (greater score, or equal score and lower id); the k
+    // best are those with rank < k.  No dependent shuffle chains: the loops are LDS broadcast reads.
+    int W = 8;
+    while (W < a.E) W <<= 1;
+    const int per_wave = 64 / W;
+    const int sub = lane / W, e = lane % W;
+    const int chunks_per_gate = kTile / per_wave;
+    const int total_chunks = Gl * chunks_per_gate;
+    const bool evalid = e < a.E;
+    const float NEG_INF = -__builtin_inff();
+
+    for (int it = 0; it * NW < total_chunks; ++it) {   // same trip count for all waves (barriers inside)
+        const int chunk = it * NW + wave;
+        const bool cact = chunk < total_chunks;
+        const int gl = cact ? chunk / chunks_per_gate : 0;   // gate inside the group
+        const int gi = g0 + gl;                              // gate of the launch
+        const int ti = (chunk % chunks_per_gate) * per_wave + sub;
+        const int t = t0 + ti;
+        const bool live = cact && t < a.T;
+        const bool want_w = cact && (a.w != nullptr) && gi == 0;  // wave-uniform
+        float z = NEG_INF;
+        if (live && evalid) z = logits[ti][gl * a.E + e] + sbias[gl * a.E + e];
+        float sc = z;
+        if (live && evalid) {
+            if ((pick(a.resident, gi) >> e) & 1ull) sc += a.beta;
+            if (a.delta && gi >= a.delta_gate_begin) {
+                int req = a.tok2req ? a.tok2req[t] : 0;
+                sc += a.delta[(size_t)req * a.delta_req_stride + (gi - a.delta_gate_begin) * a.E + e];
+            }
+        }
+        s_sc[wave][lane] = sc;
+        s_z[wave][lane] = z;
+        __syncthreads();
+        const float4 *srow = reinterpret_cast<const float4 *>(&s_sc[wave][sub * W]);
+        int rank = 0;
+        for (int j = 0; j < W; j += 4) {
+            const float4 v = srow[j >> 2];
+            rank += (v.x > sc || (v.x == sc && j + 0 < e)) ? 1 : 0;
+            rank += (v.y > sc || (v.y == sc && j + 1 < e)) ? 1 : 0;
+            rank += (v.z > sc || (v.z == sc && j + 2 < e)) ? 1 : 0;
+            rank += (v.w > sc || (v.w == sc && j + 3 < e)) ? 1 : 0;
+        }
+        const bool sel = live && evalid && rank < a.k;
+        float ex = 0.f;
+        if (want_w) {   // softmax over all experts, fp32: max, exp, sum (sum taken below)
+            const float4 *zrow = reinterpret_cast<const float4 *>(&s_z[wave][sub * W]);
+            float m = NEG_INF;
+            for (int j = 0; j < W; j += 4) {
+                const float4 v = zrow[j >> 2];
+                m = fmaxf(fmaxf(m, v.x), fmaxf(v.y, fmaxf(v.z, v.w)));
+            }
+            ex = (live && evalid) ? __expf(z - m) : 0.f;
+        }
+        __syncthreads();
+        if (want_w) s_z[wave][lane] = ex;
+        __syncthreads();
+        const unsigned long long ball = __ballot(sel);
+        const unsigned long long submask = (W == 64) ? ball : ((ball >> (sub * W)) & ((1ull << W) - 1ull));
+        const int slot = __popcll(submask & ((1ull << e) - 1ull));   // ascending expert id
+        if (sel) {
+            pick(a.ids, gi)[(size_t)t * a.k + slot] = e;
+            if (want_w) {
+                const float *erow = &s_z[wave][sub * W];
+                float den = 0.f;
+                if (a.renorm) {   // p_e / sum of selected p = ex_e / sum of selected ex, ascending id
+                    unsigned long long mm = submask;
+                    while (mm) {
+                        const int j = __ffsll((long long)mm) - 1;
+                        den += erow[j];
+                        mm &= mm - 1;
+                    }
+                } else {
+                    for (int j = 0; j < W; ++j) den += erow[j];
+                }
+                a.w[(size_t)t * a.k + slot] = ex / den * a.routed_scale;
+            }
+            atomicAdd(&cnt[gl * a.E + e], 1);
+        }
+    }
+    __syncthreads();
+    for (int x = tid; x < N; x += NT) {
+        const int gi = g0 + x / a.E, ee = x % a.E;
+        int32_t *hp = pick(a.hist, gi);
+        if (hp && cnt[x] > 0) atomicAdd(&hp[ee], cnt[x]);
+        if (a.blockcounts && gi == 0) a.blockcounts[(size_t)tile * a.E + ee] = cnt[x];
+    }
+}
+
+template <int NB>
+static hipError_t launch_gate_nb(const GateArgs &a, hipStream_t s) {
+    const int ntiles = (a.T + kTile - 1) / kTile;
+    const int ngroups = (a.G + a.gpw - 1) / a.gpw;
+    hipLaunchKernelGGL((gate_kernel<NB>), dim3(ntiles, ngroups), dim3(64 * kGateWaves), 0, s, a);
+    return hipGetLastError();
+}
+
+// gates per workgroup: up to 128 logit columns; one 32-column block when there are few token
+// tiles (the launch is latency-bound then and more, lighter workgroups finish sooner)
+int gate_pick_gpw(int T, int G, int E) {
+    const int ntiles = (T + kTile - 1) / kTile;
+    const int cols = ntiles < 64 ? 32 : 128;
+    int gpw = cols / E;
+    if (gpw < 1) gpw = 1;
+    if (gpw > G) gpw = G;
+    return gpw;
+}
+
+hipError_t launch_gate(const GateArgs &a, hipStream_t s) {
+    if (a.T <= 0 || a.G <= 0) return hipSuccess;
+    if (a.gpw < 1 || a.gpw * a.E > 128 || a.G > kMaxGates) return hipErrorInvalidValue;
+    const int nb = (std::min(a.gpw, a.G) * a.E + 31) / 32;
+    switch (nb) {
+        case 1: return launch_gate_nb<1>(a, s);
+        case 2: return launch_gate_nb<2>(a, s);
+        case 3: return launch_gate_nb<3>(a, s);
+        case 4: return launch_gate_nb<4>(a, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// stable grouping by expert: per-tile counts (from the gate kernel) -> scan -> scatter
+// ------------------------------------------------------------------------------------------
+
+// one wave: exclusive prefix over the tiles of expert e, returns the total
+__device__ __forceinline__ int scan_expert(const int32_t *__restrict__ bc, int ntiles, int E, int e, int lane,
+                                           int32_t *__restrict__ base_out) {
+    int carry = 0;
+    for (int c0 = 0; c0 < ntiles; c0 += 64) {
+        int b = c0 + lane;
+        int v = b < ntiles ? bc[(size_t)b * E + e] : 0;
+        int incl = v;
+        for (int off = 1; off < 64; off <<= 1) {
+            int o = __shfl_up(incl, off);
+            if (lane >= off) incl += o;
+        }
+        if (b < ntiles) base_out[(size_t)b * E + e] = carry + incl - v;
+        carry += __shfl(incl, 63);
+    }
+    return carry;
+}
+
+// one wave: stable scatter of the assignments of token tile b
+__device__ __forceinline__ void scatter_tile(const int32_t *__restrict__ ids, int T, int k, int E, int b, int lane,
+                                             int next, int32_t *__restrict__ perm,
+                                             int32_t *__restrict__ inv_perm) {
+    const int tok0 = b * kTile;
+    const int ntok = min(kTile, T - tok0);
+    const int a0 = tok0 * k, n = ntok * k;
+    // lane e keeps the next free position of expert e for this tile in `next`
+    for (int c0 = 0; c0 < n; c0 += 64) {
+        const int idx = c0 + lane;
+        const bool valid = idx < n;
+        const int e = valid ? ids[a0 + idx] : 0;
+        unsigned long long todo = __ballot(valid);
+        int pos = 0;
+        while (todo) {
+            const int leader = __ffsll((long long)todo) - 1;
+            const int le = __shfl(e, leader);
+            const bool mine = valid && e == le;
+            const unsigned long long m = __ballot(mine);
+            const int start = __shfl(next, le);
+            if (mine) pos = start + __popcll(m & ((1ull << lane) - 1ull));
+            if (lane == le) next += __popcll(m);
+            todo &= ~m;
+        }
+        if (valid) {
+            perm[pos] = a0 + idx;
+            inv_perm[a0 + idx] = pos;
+        }
+    }
+}
+
+// Hand the per-expert counts and the predicted demand histograms to the host through host-mapped
+// memory, then raise the sequence flag: the host polls the flag instead of synchronising the stream.
+__device__ __forceinline__ void export_meta(const GroupExport &ex, const int *total, int E) {
+    if (!ex.host_meta) return;  // uniform
+    for (int x = threadIdx.x; x < E; x += blockDim.x) ex.host_meta[x] = total[x];
+    for (int x = threadIdx.x; x < ex.n_hist; x += blockDim.x) ex.host_meta[kMetaHist + x] = ex.hist[x];
+    for (int x = threadIdx.x; x < ex.n_clear; x += blockDim.x) ex.hist[x] = 0;   // ready for the next layer
+    __threadfence_system();
+    __syncthreads();
+    if (threadIdx.x == 0) *reinterpret_cast<volatile int32_t *>(ex.host_meta + kMetaFlag) = ex.seq;
+}
+
+__global__ __launch_bounds__(1024) void group_scan_kernel(const int32_t *__restrict__ bc, int ntiles, int E,
+                                                          int32_t *__restrict__ blockbase,
+                                                          int32_t *__restrict__ counts,
+                                                          int32_t *__restrict__ offsets, GroupExport ex) {
+    __shared__ int total[kMaxE];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int e = wave; e < E; e += 16) {
+        int tot = scan_expert(bc, ntiles, E, e, lane, blockbase);
+        if (lane == 0) total[e] = tot;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int e = 0; e < E; ++e) {
+            counts[e] = total[e];
+            offsets[e] = run;
+            run += total[e];
+        }
+        offsets[E] = run;
+    }
+    export_meta(ex, total, E);
+}
+
+__global__ __launch_bounds__(64) void group_scatter_kernel(const int32_t *__restrict__ ids, int T, int k, int E,
+                                                           const int32_t *__restrict__ blockbase,
+                                                           const int32_t *__restrict__ offsets,
+                                                           int32_t *__restrict__ perm,
+                                                           int32_t *__restrict__ inv_perm) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    int next = (lane < E) ? offsets[lane] + blockbase[(size_t)b * E + lane] : 0;
+    scatter_tile(ids, T, k, E, b, lane, next, perm, inv_perm);
+}
+
+// scan + scatter in one workgroup for up to kGroupSmallTiles token tiles (prefixes stay in LDS)
+__global__ __launch_bounds__(1024) void group_small_kernel(const int32_t *__restrict__ bc, int ntiles,
+                                                           const int32_t *__restrict__ ids, int T, int k, int E,
+                                                           int32_t *__restrict__ counts,
+                                                           int32_t *__restrict__ offsets,
+                                                           int32_t *__restrict__ perm,
+                                                           int32_t *__restrict__ inv_perm, GroupExport ex) {
+    __shared__ int base[kGroupSmallTiles * kMaxE];
+    __shared__ int total[kMaxE];
+    __shared__ int offs[kMaxE + 1];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int e = wave; e < E; e += 16) {
+        int tot = scan_expert(bc, ntiles, E, e, lane, base);
+        if (lane == 0) total[e] = tot;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int e = 0; e < E; ++e) {
+            counts[e] = total[e];
+            offsets[e] = run;
+            offs[e] = run;
+            run += total[e];
+        }
+        offsets[E] = run;
+        offs[E] = run;
+    }
+    __syncthreads();
+    export_meta(ex, total, E);   // the host starts planning while the scatter below still runs
+    for (int b = wave; b < ntiles; b += 16) {
+        int next = (lane < E) ? offs[lane] + base[b * E + lane] : 0;
+        scatter_tile(ids, T, k, E, b, lane, next, perm, inv_perm);
+    }
+}
+
+hipError_t launch_group(const int32_t *blockcounts, const int32_t *ids, int T, int k, int E, int32_t *blockbase,
+                        int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
+                        const GroupExport &ex, hipStream_t s) {
+    if (T <= 0) return hipSuccess;
+    const int ntiles = (T + kTile - 1) / kTile;
+    if (ntiles <= kGroupSmallTiles) {
+        hipLaunchKernelGGL(group_small_kernel, dim3(1), dim3(1024), 0, s, blockcounts, ntiles, ids, T, k, E,
+                           counts, offsets, perm, inv_perm, ex);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(group_scan_kernel, dim3(1), dim3(1024), 0, s, blockcounts, ntiles, E, blockbase, counts,
+                       offsets, ex);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(group_scatter_kernel, dim3(ntiles), dim3(64), 0, s, ids, T, k, E, blockbase, offsets, perm,
+                       inv_perm);
+    return hipGetLastError();
+}
+
+}  // namespace ef

@@ -3,12 +3,14 @@
 Call sequencing and buffer ownership only; all arithmetic and all cache policy
 live in the library.  Per layer l:
 
-    ef_predict(l)   hidden -> gates of l+1..l+H     (demand histograms)
-    ef_route(l)     gate, softmax, biased top-k, grouping
-    -- one stream sync: counts and histograms reach the host --
+    ef_route_predict(l)  one pass over the hidden states: the layer's own gate (softmax, biased
+                         top-k, grouping) and the gates of l+1..l+H (demand histograms)
+    -- counts and histograms reach the host --
     ef_choose_horizon(l) -> H for the next layer, prefetch list
     ef_cache_swap_in(...) prefetches on the copy stream
     ef_moe_ffn(l)   resident groups first, misses swapped in and run after
+
+`layer` uses the library's composite ef_layer_step, `layer_separate_calls` spells the sequence out.
 
 Weights for benchmarks are random bf16 written straight in packed order (a
 permutation of i.i.d. draws is i.i.d.), optionally one small pool of layer
@@ -27,12 +29,14 @@ from . import synth
 class LayerLoop:
     def __init__(self, cfg: synth.MoEShape, n_layers: int, T: int, slots_per_layer: int,
                  pool_slots: int | None = None, store_layers: int = 2, h_max: int = 4, beta: float = 0.0,
-                 profile: bool = False, all_resident: bool = False, seed: int = 0):
+                 profile: bool = False, all_resident: bool = False, seed: int = 0,
+                 fixed_estimates: bool = False):
         self.cfg, self.L, self.T, self.beta = cfg, n_layers, T, beta
         E, k, d = cfg.E, cfg.k, cfg.d
         dev = "cuda"
         slots_total = n_layers * (E if all_resident else slots_per_layer) if pool_slots is None else pool_slots
-        flags = ef.EF_FLAG_PROFILE if profile else 0
+        flags = {False: 0, True: ef.EF_FLAG_PROFILE, "ffn_up": ef.EF_FLAG_PROFILE_FFN_UP}[profile]
+        flags |= ef.EF_FLAG_FIXED_ESTIMATES if fixed_estimates else 0
         self.ctx = ef.ef_create(n_layers=n_layers, d_model=d, n_experts=E, top_k=k, d_ff=cfg.F,
                                 d_ff_shared=cfg.F_shared, slots_total=slots_total,
                                 slots_per_layer_max=0 if all_resident or pool_slots is not None else slots_per_layer,
@@ -87,11 +91,16 @@ class LayerLoop:
         ef.ef_destroy(self.ctx)
 
     def layer(self, l: int, h: torch.Tensor, stream) -> None:
+        """One layer through the composite entry point (the library sequences the calls)."""
+        H = -1 if self.h_fixed is None else self.h_fixed
+        self.H = ef.ef_layer_step(self.ctx, l, h, self.T, self.beta, H, None, None, self.out, None, stream)
+
+    def layer_separate_calls(self, l: int, h: torch.Tensor, stream) -> None:
+        """The same layer through the separate entry points (what ef_layer_step does inside)."""
         E, T = self.cfg.E, self.T
         H = self.H if self.h_fixed is None else self.h_fixed
-        he = ef.ef_predict(self.ctx, l, h, T, H, None, None, self.beta, self.pred_ids, self.hist, stream)
-        ef.ef_route(self.ctx, l, h, T, self.beta, self.ids, self.w, self.counts, self.offsets, self.perm,
-                    self.inv_perm, stream)
+        he = ef.ef_route_predict(self.ctx, l, h, T, self.beta, H, None, None, self.ids, self.w, self.counts,
+                                 self.offsets, self.perm, self.inv_perm, self.pred_ids, self.hist, stream)
         self.meta_host.copy_(self.meta, non_blocking=True)
         stream.synchronize()
         mh = self.meta_host.numpy()

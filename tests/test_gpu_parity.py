@@ -100,6 +100,48 @@ def test_tiny_predict_with_delta_and_residency(oracle_mod):
         st.close()
 
 
+@pytest.mark.parametrize("cfg,T,H", [(synth.CONFIGS["tiny"], 64, 2), (SMALL_DEEPSEEK, 130, 4), (SMALL_DEEPSEEK, 130, 6),
+                                     (SMALL_QWEN, 77, 3)])
+def test_fused_route_predict_equals_separate_calls(oracle_mod, cfg, T, H):
+    """One pass over the hidden states gives bit-identical results to ef_route + ef_predict
+    (E=64 with H>=5 needs more gate columns than one launch holds: the launch is split)."""
+    say(f"fused route+predict {cfg.name} T={T} H={H}")
+    L = H + 1
+    st = LayerStack(cfg, L, slots_total=cfg.E, max_tokens=T, expert_layers=[0], h_max=min(H, 7))
+    try:
+        for l in range(L):
+            for e in np.nonzero(synth.residency(cfg, l, n_resident=3, most_popular=False))[0]:
+                ef.ef_cache_swap_in(st.ctx, l, int(e), 0, l)
+        h = synth.hidden(cfg, 9, T)
+        hd = dev_u16(h)
+        R = 4
+        delta, t2r = synth.delta(cfg, 0, R, H), synth.tok2req(cfg, T, R)
+        dd, td = torch.from_numpy(delta).cuda(), torch.from_numpy(t2r).cuda()
+        beta = 0.4
+        sep = to_np(st.route(0, hd, T, beta), T, cfg.k)
+        he, pids, phist = st.predict(0, hd, T, H, beta, delta, t2r)
+        assert he == H
+        o = st.route(0, hd, T, 0.0)     # fresh buffers, then overwritten by the fused call
+        fids = torch.full((H * T * cfg.k,), -1, dtype=torch.int32, device="cuda")
+        fhist = torch.full((H * cfg.E,), -1, dtype=torch.int32, device="cuda")
+        he2 = ef.ef_route_predict(st.ctx, 0, hd, T, beta, H, dd, td, o["ids"], o["w"], o["counts"], o["offsets"],
+                                  o["perm"], o["inv_perm"], fids, fhist, torch.cuda.current_stream())
+        fused = to_np(o, T, cfg.k)
+        assert he2 == H
+        for name in sep:
+            assert np.array_equal(sep[name], fused[name]), name
+        assert np.array_equal(fids.cpu().numpy().reshape(H, T, cfg.k), pids)
+        assert np.array_equal(fhist.cpu().numpy().reshape(H, cfg.E), phist)
+        # and the predictions themselves against the oracle
+        residents = [ef.ef_cache_query(st.ctx, 1 + j, cfg.E) for j in range(H)]
+        oids, ohist, ogap = oracle_mod.predict(h, st.gates[1:1 + H], st.biases[1:1 + H], cfg.k, beta, residents,
+                                               delta, t2r)
+        tie = ogap < helpers.TIE_GAP
+        assert np.array_equal(pids[~tie], oids[~tie])
+    finally:
+        st.close()
+
+
 @pytest.mark.parametrize("cfg,T", [(synth.CONFIGS["tiny"], 1), (synth.CONFIGS["tiny"], 31),
                                    (synth.CONFIGS["tiny"], 33), (synth.CONFIGS["tiny"], 100),
                                    (SMALL_QWEN, 77), (SMALL_QWEN, 3), (SMALL_DEEPSEEK, 130),
@@ -170,6 +212,37 @@ def test_outputs_do_not_depend_on_slots_or_phase_order(oracle_mod):
     for name in ("ids", "w", "perm"):
         assert np.array_equal(outs[0][0][name], outs[1][0][name]) and np.array_equal(outs[0][0][name], outs[2][0][name])
     assert np.array_equal(outs[0][1], outs[1][1]) and np.array_equal(outs[0][1], outs[2][1])
+
+
+@pytest.mark.parametrize("cfg_name,T", [("tiny", 64), ("tiny", 7)])
+def test_layer_step_equals_separate_calls(cfg_name, T):
+    """The composite entry point (host-mapped hand-over, flag polling) gives bit-identical outputs,
+    the same cache decisions and the same horizon as the separate entry points."""
+    from paper_2510_26730_amd.runner import LayerLoop
+    cfg = synth.CONFIGS[cfg_name]
+    say(f"ef_layer_step vs separate calls, {cfg_name} T={T}")
+    L = 3
+    loops = [LayerLoop(cfg, L, T, cfg.slots_per_layer, beta=0.5, seed=1, fixed_estimates=True) for _ in range(2)]
+    try:
+        stream = torch.cuda.current_stream()
+        for step in range(3):
+            hs = torch.from_numpy(synth.hidden_stack(cfg, L, step=step, T=T).view(np.int16)).cuda()
+            for l in range(L):
+                loops[0].layer(l, hs[l], stream)
+                loops[1].layer_separate_calls(l, hs[l], stream)
+                torch.cuda.synchronize()
+                assert torch.equal(loops[0].out, loops[1].out), (step, l)
+                assert loops[0].H == loops[1].H
+                for ll in range(L):
+                    assert np.array_equal(ef.ef_cache_query(loops[0].ctx, ll, cfg.E),
+                                          ef.ef_cache_query(loops[1].ctx, ll, cfg.E))
+        s0, s1 = ef.ef_get_stats(loops[0].ctx), ef.ef_get_stats(loops[1].ctx)
+        for key in ("hits", "misses", "prefetch_issued", "evictions", "bytes_copied", "layers_run"):
+            assert s0[key] == s1[key], key
+        assert s0["layers_run"] == 9
+    finally:
+        for lp in loops:
+            lp.close()
 
 
 def _sampled_layer_check(oracle_mod, st, layer, h, T, beta, res, n_sample, seed):
