@@ -32,36 +32,48 @@ WORKLOADS = {
 }
 
 
-def cpu_baseline(cfg, T, beta, budget_tokens):
-    """The oracle, as it stands, on a bounded sample of the same workload: routing of all T tokens
-    of one layer plus the expert FFN of `budget_tokens` of them; tokens/s scaled to the sample."""
+def cpu_baseline(cfg, T, beta, target_seconds):
+    """The oracle, as it stands, on a bounded sample of the same workload: whole passes (routing,
+    expert FFN, combine) over ONE layer of the workload at its real shape, for up to T tokens,
+    repeated until about `target_seconds` of CPU time have been spent."""
     import numpy as np
     import oracle
     from paper_2510_26730_amd import synth
     oracle.build()
+    n = min(T, 64)                       # tokens whose FFN is evaluated per pass
     h = synth.hidden(cfg, 0, T)
     Wg, b = synth.gate_weight(cfg, 0), synth.gate_bias(cfg, 0)
     res = synth.residency(cfg, 0)
-    n = min(budget_tokens, T)
-    toks = np.arange(n)
-    t0 = time.perf_counter()
-    r = oracle.route(h, Wg, b, cfg.k, beta, res, renorm=cfg.renorm)
-    t_route = time.perf_counter() - t0
-    ids_s = np.ascontiguousarray(r["ids"][toks])
-    used = sorted(set(ids_s.ravel().tolist()))
-    experts = [synth.expert_weights(cfg, 0, e) if e in used else None for e in range(cfg.E)]   # untimed: input generation
+    r0 = oracle.route(h, Wg, b, cfg.k, beta, res, renorm=cfg.renorm)
+    used = sorted(set(r0["ids"][:n].ravel().tolist()))
+    experts = [synth.expert_weights(cfg, 0, e) if e in used else None for e in range(cfg.E)]   # untimed: inputs
     shared = synth.shared_weights(cfg, 0)
-    t0 = time.perf_counter()
-    sub = oracle.route_from_ids(r["p"][toks], ids_s, cfg.E, cfg.renorm)
-    y = oracle.expert_ffn(np.ascontiguousarray(h[toks]), experts, ids_s, sub["perm"])
-    sh = None if shared is None else oracle.dense_ffn(np.ascontiguousarray(h[toks]), *shared)
-    oracle.combine(y, sub["w"], sub["inv_perm"], sh)
-    t_ffn = time.perf_counter() - t0
-    per_token = t_route / T + t_ffn / n
+    hs = np.ascontiguousarray(h[:n])
+
+    def one_pass():
+        t0 = time.perf_counter()
+        r = oracle.route(h, Wg, b, cfg.k, beta, res, renorm=cfg.renorm)
+        t_route = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        ids_s = np.ascontiguousarray(r["ids"][:n])
+        sub = oracle.route_from_ids(r["p"][:n], ids_s, cfg.E, cfg.renorm)
+        y = oracle.expert_ffn(hs, experts, ids_s, sub["perm"])
+        sh = None if shared is None else oracle.dense_ffn(hs, *shared)
+        oracle.combine(y, sub["w"], sub["inv_perm"], sh)
+        return t_route, time.perf_counter() - t0
+
+    tr, tf = one_pass()
+    reps = int(max(1, min(64, target_seconds / max(tr + tf, 1e-3))))
+    tot_r, tot_f = tr, tf
+    for _ in range(reps - 1):
+        a, c = one_pass()
+        tot_r += a
+        tot_f += c
+    per_token = tot_r / (reps * T) + tot_f / (reps * n)
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     return {"value": 1.0 / per_token, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"one layer: routing of {T} tokens ({t_route:.2f} s) + expert FFN and combine of {n} "
-                      f"tokens ({t_ffn:.2f} s), fp64, OpenMP over tokens"}
+            "sample": f"{reps} passes over one layer at full shape: routing of {T} tokens ({tot_r:.2f} s) + expert "
+                      f"FFN and combine of {n} tokens ({tot_f:.2f} s); fp64, OpenMP over tokens"}
 
 
 def main():
@@ -75,7 +87,10 @@ def main():
     ap.add_argument("--layers", type=int, default=None)
     ap.add_argument("--all-resident", action="store_true", help="cache holds every expert (no PCIe traffic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-tokens", type=int, default=16)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle baseline")
+    ap.add_argument("--calib-copy", type=int, default=0,
+                    help="MiB of a plain device-to-device copy done 4 times before the run (a kernel of known "
+                         "traffic, used to scale rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is a single-GPU hot path; run with --gpus 1 "
@@ -98,6 +113,13 @@ def main():
     L = args.layers or cfg.n_layers
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream()
+    if args.calib_copy > 0:
+        src = torch.empty(args.calib_copy << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     loop = LayerLoop(cfg, L, T, cfg.slots_per_layer, beta=beta, profile=False, all_resident=args.all_resident)
     n_in = 4                                          # distinct step inputs, cycled
@@ -143,8 +165,17 @@ def main():
     roof = None
     if dom:
         a = dom["GBps"]
+        # HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE scaled by
+        # a copy kernel), only if it was taken on this very workload; a counter run cannot happen in here
+        traffic = None
+        tag = f"TRAFFIC_BYTES_PER_LAUNCH ffn_gate_up_kernel {cfg.name} T={T} beta={beta} ="
+        pmc = os.path.join(ROOT, "profiles", "ffn_kernels_mixtral_decode_T64_pmc_traffic.md")
+        if os.path.exists(pmc) and not args.all_resident:
+            for line in open(pmc):
+                if line.startswith(tag):
+                    traffic = float(line.split("=")[-1])
         roof = {"bound": "hbm", "kernel": "ffn_gate_up_kernel", "achieved": a, "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": a / HBM_PEAK_GBPS, "traffic": None,
+                "unit": "GB/s", "frac": a / HBM_PEAK_GBPS, "traffic": traffic,
                 "avg_launch_us": dom["avg_us"], "alg_bytes_per_launch": dom["alg_bytes_per_launch"],
                 "launches": dom["launches"], "share_of_step_time": dom["share_of_step_time"]}
     result = {
@@ -168,7 +199,7 @@ def main():
     }
     loop.close()
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, T, beta, args.cpu_tokens)
+        result["cpu_baseline"] = cpu_baseline(cfg, T, beta, args.cpu_seconds)
     print(json.dumps(result))
 
 
