@@ -152,7 +152,7 @@ def main():
     dom = kernel_table(st, dt).get("ffn_up")
 
     # separate, untimed pass with every kernel bracketed: the per-kernel breakdown
-    ef.ef_set_profile(loop.ctx, 0xFF)
+    ef.ef_set_profile(loop.ctx, 0x3FF)
     ef.ef_reset_stats(loop.ctx)
     t1 = time.perf_counter()
     for s in range(2):

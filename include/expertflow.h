@@ -75,12 +75,13 @@ enum {
     EF_K_PREDICT = 0,  /* gate + top-k + histogram of the look-ahead layers */
     EF_K_ROUTE = 1,    /* gate + softmax + biased top-k + per-tile counts of the current layer */
     EF_K_GROUP = 2,    /* per-expert prefix over the tiles + stable scatter: counts, offsets, perm, inv_perm */
-    EF_K_RESERVED = 3,
+    EF_K_FFN_UP_TILED = 3,   /* first FFN half, groups with many tokens (matrix-core bound tiles) */
     EF_K_PACK = 4,     /* token permutation into per-expert operand tiles */
     EF_K_FFN_UP = 5,   /* grouped act = silu(X W1^T) * (X W3^T) */
     EF_K_FFN_DOWN = 6, /* grouped Y = act W2^T */
     EF_K_COMBINE = 7,  /* weighted un-permute */
-    EF_K_COUNT = 8
+    EF_K_FFN_DOWN_TILED = 8, /* second FFN half, groups with many tokens */
+    EF_K_COUNT = 10
 };
 
 typedef struct ef_ctx ef_ctx;

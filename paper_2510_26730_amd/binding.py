@@ -22,7 +22,8 @@ EF_FLAG_STRICT_RESIDENT = 2
 EF_FLAG_PROFILE = 4
 EF_FLAG_FIXED_ESTIMATES = 8
 EF_FLAG_PROFILE_FFN_UP = 16
-EF_KERNELS = ["predict", "route", "group", "reserved", "pack", "ffn_up", "ffn_down", "combine"]
+EF_KERNELS = ["predict", "route", "group", "ffn_up_tiled", "pack", "ffn_up", "ffn_down", "combine", "ffn_down_tiled",
+              "reserved"]
 EF_MAX_EXPERTS, EF_MAX_TOPK, EF_MAX_HORIZON = 64, 8, 7
 
 EXPORTS = [
@@ -51,8 +52,8 @@ class ef_stats(C.Structure):
         ("stall_seconds", C.c_double), ("layer_seconds", C.c_double), ("bandwidth_Bps", C.c_double),
         ("layer_seconds_est", C.c_double), ("miss_rate", C.c_double), ("horizon", C.c_int32),
         ("stall_counter", C.c_int32), ("overfetch_counter", C.c_int32), ("reserved_", C.c_int32),
-        ("kernel_seconds", C.c_double * 8), ("kernel_bytes", C.c_double * 8),
-        ("kernel_launches", C.c_int64 * 8),
+        ("kernel_seconds", C.c_double * 10), ("kernel_bytes", C.c_double * 10),
+        ("kernel_launches", C.c_int64 * 10),
     ]
 
     def as_dict(self):

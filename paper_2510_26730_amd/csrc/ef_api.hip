@@ -487,7 +487,7 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
         if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
     c->stall_ring.resize(128);
     c->layer_ring.resize(128);
-    if (g.flags & EF_FLAG_PROFILE) c->profile_mask = 0xFFu;
+    if (g.flags & EF_FLAG_PROFILE) c->profile_mask = 0x3FFu;
     else if (g.flags & EF_FLAG_PROFILE_FFN_UP) c->profile_mask = 1u << EF_K_FFN_UP;
     if (c->profile_mask) c->prof_ring.resize(1024);
     for (auto *ring : {&c->stall_ring, &c->layer_ring, &c->prof_ring})
@@ -720,8 +720,11 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
                  int ksg, long long y_plane, hipStream_t s) {
     if (groups.empty()) return EF_OK;
     const int d = c->cfg.d_model, k = c->cfg.top_k;
-    ef::GroupTable gu{}, dn{};
-    int n = 0, max_tiles = 1;
+    // groups with many tokens go to the tiled (matrix-core bound) kernels, the others to the
+    // weight-streaming kernels; at most two launches per FFN half
+    ef::GroupTable gu{}, big{};
+    int n = 0, nb = 0, max_tiles = 1;
+    const bool allow_tiled = tune("EF_TUNE_TILED", 1) != 0 && ksg == 1;
     for (const PhaseGroup &pg : groups) {
         int cnt, ts, F, ro;
         long long ao;
@@ -734,13 +737,47 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
             ro = offs_host[(size_t)pg.expert]; ao = act_off[(size_t)pg.expert];
             blob = c->pool + (size_t)pg.slot * c->expert_bytes;
         }
-        gu.tile_start[n] = ts; gu.n_tiles[n] = (cnt + ef::kTile - 1) / ef::kTile; gu.row_offset[n] = ro;
-        gu.count[n] = cnt; gu.F[n] = F; gu.act_off[n] = ao; gu.blob[n] = blob;
-        max_tiles = std::max(max_tiles, gu.n_tiles[n]);
-        ++n;
+        const int nt = (cnt + ef::kTile - 1) / ef::kTile;
+        const bool tiled = allow_tiled && ef::ffn_tiled_ok(d, F, nt);
+        ef::GroupTable &g = tiled ? big : gu;
+        int &i = tiled ? nb : n;
+        g.tile_start[i] = ts; g.n_tiles[i] = nt; g.row_offset[i] = ro;
+        g.count[i] = cnt; g.F[i] = F; g.act_off[i] = ao; g.blob[i] = blob;
+        if (!tiled) max_tiles = std::max(max_tiles, nt);
+        ++i;
     }
     gu.n_groups = n;
-    dn = gu;
+    big.n_groups = nb;
+    auto alg_bytes = [&](const ef::GroupTable &g, int cnt_groups, double &b_up, double &b_dn) {
+        for (int i = 0; i < cnt_groups; ++i) {
+            b_up += 4.0 * d * g.F[i] + 2.0 * g.count[i] * d + 2.0 * g.count[i] * g.F[i];
+            b_dn += 2.0 * d * g.F[i] + 2.0 * g.count[i] * g.F[i] + 4.0 * g.count[i] * d;
+        }
+    };
+    if (nb > 0) {
+        ef::GroupTable bdn = big;
+        int wg_up = 0, wg_dn = 0;
+        for (int i = 0; i < nb; ++i) {
+            big.wg_start[i] = wg_up;
+            bdn.wg_start[i] = wg_dn;
+            wg_up += ef::ffn_gate_up_tiled_wgs(big.F[i], big.n_tiles[i]);
+            wg_dn += ef::ffn_down_tiled_wgs(d, big.n_tiles[i]);
+        }
+        big.wg_start[nb] = wg_up;
+        bdn.wg_start[nb] = wg_dn;
+        double b_up = 0.0, b_dn = 0.0;
+        alg_bytes(big, nb, b_up, b_dn);
+        {
+            KernelTimer kt(c, s, EF_K_FFN_UP_TILED, b_up);
+            EF_HIP(c, ef::launch_ffn_gate_up_tiled(big, wg_up, c->xp, c->act, d, s));
+        }
+        {
+            KernelTimer kt(c, s, EF_K_FFN_DOWN_TILED, b_dn);
+            EF_HIP(c, ef::launch_ffn_down_tiled(bdn, wg_dn, c->act, c->y, d, s));
+        }
+    }
+    if (n == 0) return EF_OK;
+    ef::GroupTable dn = gu;
     const int tpp = max_tiles >= 2 ? 2 : 1;
     // K slices inside a workgroup of the first half: split while the launch has too few waves to
     // keep enough weight bytes in flight, as long as a slice keeps >= 16 fragments
@@ -760,10 +797,7 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
     gu.wg_start[n] = wg_gu;
     dn.wg_start[n] = wg_dn;
     double b_up = 0.0, b_dn = 0.0;
-    for (int i = 0; i < n; ++i) {
-        b_up += 4.0 * d * gu.F[i] + 2.0 * gu.count[i] * d + 2.0 * gu.count[i] * gu.F[i];
-        b_dn += 2.0 * d * gu.F[i] + 2.0 * gu.count[i] * gu.F[i] + 4.0 * gu.count[i] * d;
-    }
+    alg_bytes(gu, n, b_up, b_dn);
     {
         KernelTimer kt(c, s, EF_K_FFN_UP, b_up);
         EF_HIP(c, ef::launch_ffn_gate_up(gu, wg_gu, tpp, ks, c->xp, c->act, d, s));
@@ -837,6 +871,9 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         while (ksg < 8 && base_wgs * ksg < want && nkb_min / (ksg * 2 * 4) >= 32 &&
                y_plane * (ksg * 2) <= c->y_floats)
             ksg *= 2;
+        for (int e = 0; e < E; ++e)   // the tiled kernels write plane 0 only
+            if (ef::ffn_tiled_ok(d, c->cfg.d_ff, (counts_host[e] + ef::kTile - 1) / ef::kTile)) ksg = 1;
+        if (has_shared && ef::ffn_tiled_ok(d, c->cfg.d_ff_shared, (T + ef::kTile - 1) / ef::kTile)) ksg = 1;
         int forced = tune("EF_TUNE_DOWN_KSG", ksg);
         if (forced >= 1 && forced <= 8 && y_plane * forced <= c->y_floats) ksg = forced;
     }
@@ -1146,7 +1183,7 @@ extern "C" int ef_set_profile(ef_ctx *c, unsigned kinds_mask) {
             EF_HIP(c, hipEventCreate(&p.b));
         }
     }
-    c->profile_mask = kinds_mask & 0xFFu;
+    c->profile_mask = kinds_mask & 0x3FFu;
     return EF_OK;
 }
 

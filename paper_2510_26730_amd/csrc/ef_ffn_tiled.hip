@@ -1,0 +1,292 @@
+// Grouped SwiGLU expert FFN for groups with many tokens (prefill): matrix-core bound.
+//
+// When an expert sees hundreds of tokens every weight fragment is reused by many token tiles and
+// the two FFN halves are dense contractions: 256 x 256 output tiles per workgroup, 128 x 128 per
+// wave (4 x 4 MFMA 32x32x16 accumulators), operands staged through LDS.  All three operands
+// (expert weights, packed tokens, activations) are already stored as 1 KiB operand fragments, so
+// the global -> LDS copy is a plain contiguous copy and an LDS operand read is 64 lanes x 16
+// consecutive bytes (no bank conflicts, no swizzle).  Four LDS stage buffers are filled by direct
+// global -> LDS loads three stages ahead of the one feeding the matrix cores, one barrier per stage.
+// Workgroups that share a weight panel (same rows, different token panels) have consecutive ids,
+// so the panel is fetched from HBM once and served to the others by L2 / MALL.
+#include "ef_device.h"
+#include "ef_kernels.h"
+
+namespace ef {
+
+constexpr int kTileKS = 2;               // MFMA k-steps (16 columns each) per LDS stage
+constexpr int kStageFrags = 16 * kTileKS;  // fragments per stage: per k-step 8 of each operand
+constexpr int kTileStages = 4;           // LDS stage buffers (power of two)
+// s_waitcnt immediate "vmcnt <= 16, do not wait on expcnt / lgkmcnt" (gfx9 encoding: vmcnt[3:0] in bits
+// 3:0 and vmcnt[5:4] in bits 15:14, expcnt in 6:4, lgkmcnt in 11:8)
+constexpr int kWaitVm16 = (1 << 14) | (0x7 << 4) | (0xF << 8) | 0;
+constexpr int kWaitVm8 = (0 << 14) | (0x7 << 4) | (0xF << 8) | 8;
+static_assert(kStageFrags / 4 == 8, "the wait count assumes 8 loads per wave per stage");
+
+// ------------------------------------------------------------------------------------------
+// first half, tiled: act = silu(X W1^T) * (X W3^T) for (group, 4 row blocks, 8 token tiles)
+// operand A slots 0..7 = W1/W3 fragments of row blocks rb0..rb0+3 (slot = 2*rbl + which),
+// operand B slots 8..15 = packed-token fragments of tiles t0..t0+7
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256, 1) void ffn_gate_up_tiled_kernel(GroupTable gt, const uint4 *__restrict__ xp,
+                                                                    uint4 *__restrict__ act, int d) {
+    __shared__ __attribute__((aligned(16))) u32x4_t lds[kTileStages][kStageFrags][64];
+    const int wg = blockIdx.x;
+    int grp = 0;
+    while (grp + 1 < gt.n_groups && gt.wg_start[grp + 1] <= wg) ++grp;
+    const int local = wg - gt.wg_start[grp];
+    const int F = gt.F[grp];
+    const int ntiles = gt.n_tiles[grp];
+    const int mpanels = (ntiles + 7) >> 3;
+    const int mp = local % mpanels, np = local / mpanels;   // token panel fastest: neighbours share weights
+    const int rb0 = np * 4, t0 = mp * 8;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS DMA targets go through M0
+    const int wf = wave & 1, wt = wave >> 1;
+    const int nkb = d >> 4;
+    const int nstage = nkb / kTileKS;
+
+    // per-thread source of its 8 fragment quarters per stage: fragment q*4 + wave of the stage
+    const u32x4_t *src[kStageFrags / 4];
+#pragma unroll
+    for (int q = 0; q < kStageFrags / 4; ++q) {
+        const int fi = q * 4 + wave;              // 0 .. kStageFrags-1
+        const int ks = fi >> 4, slot = fi & 15;
+        const uint4 *p;
+        if (slot < 8) {
+            const int rbl = slot >> 1, which = slot & 1;
+            p = reinterpret_cast<const uint4 *>(gt.blob[grp]) + ((size_t)(rb0 + rbl) * 2 + which) * nkb * 64;
+        } else {
+            const int tile = min(t0 + (slot - 8), ntiles - 1);
+            p = xp + (size_t)(gt.tile_start[grp] + tile) * nkb * 64;
+        }
+        src[q] = reinterpret_cast<const u32x4_t *>(p + (size_t)ks * 64 + lane);
+    }
+
+    floatx16 acc[4][4];   // [operand-A fragment: W1 rb, W3 rb, W1 rb+1, W3 rb+1][token tile]
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) zero16(acc[i][j]);
+
+    const int AOFF = wf * 4, BOFF = wt * 4;
+    // Four LDS stage buffers filled by direct global -> LDS loads (no register staging): stages st+1,
+    // st+2 and st+3 are in flight while stage st feeds the matrix cores; one barrier per stage.
+    // Every wave issues kStageFrags/4 loads per stage, unconditionally (past the end the last stage
+    // is re-read, in bounds), so "my loads of stage st have landed" is a constant wait count.
+#define EF_TILED_ISSUE(st)                                                                           \
+    {                                                                                                \
+        const int stc_ = min((st), nstage - 1);                                                      \
+        const int buf_ = (st) & (kTileStages - 1);                                                   \
+        _Pragma("unroll") for (int q = 0; q < kStageFrags / 4; ++q)                                  \
+            __builtin_amdgcn_global_load_lds(src[q] + (size_t)stc_ * kTileKS * 64,                   \
+                                             &lds[buf_][q * 4 + wave][0], 16, 0, 0);                 \
+    }
+#define EF_TILED_READ(a, b, cur, ks)                                                              \
+    {                                                                                                \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) a[i] = lds[cur][(ks) * 16 + AOFF + i][lane];     \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) b[j] = lds[cur][(ks) * 16 + 8 + BOFF + j][lane]; \
+    }
+#define EF_TILED_MMA(a, b, i0)                                                                       \
+    _Pragma("unroll") for (int i = (i0); i < (i0) + 2; ++i)                                          \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) acc[i][j] = mfma32v(a[i], b[j], acc[i][j]);
+    static_assert(kTileKS == 2, "the loop below alternates two fragment register sets");
+    u32x4_t a0[4], b0[4], a1[4], b1[4];
+    EF_TILED_ISSUE(0)
+    EF_TILED_ISSUE(1)
+    EF_TILED_ISSUE(2)
+    __builtin_amdgcn_s_waitcnt(kWaitVm16);   // my part of stage 0 has landed
+    __syncthreads();                         // ... and everybody else's
+    EF_TILED_READ(a0, b0, 0, 0)
+    for (int st = 0; st < nstage; ++st) {
+        const int cur = st & (kTileStages - 1), nxt = (st + 1) & (kTileStages - 1);
+        // Operand fragments are read from LDS half a k-step ahead of their first use, between two
+        // halves of the previous k-step's MFMAs, so their latency hides behind matrix-core work and
+        // the wait in front of an MFMA block only covers reads issued a block earlier.  The
+        // scheduling barriers keep the compiler from sinking the reads back to their first use.
+        EF_TILED_MMA(a0, b0, 0)
+        __builtin_amdgcn_sched_barrier(0);
+        EF_TILED_READ(a1, b1, cur, 1)
+        __builtin_amdgcn_sched_barrier(0);
+        EF_TILED_MMA(a0, b0, 2)
+        __builtin_amdgcn_sched_barrier(0);
+        // stage st+1 must have landed: of the loads issued so far (stages st+1, st+2) at most the
+        // 8 of stage st+2 may still be outstanding
+        __builtin_amdgcn_s_waitcnt(kWaitVm8);
+        __syncthreads();   // every wave has issued its reads of stage st-1 long ago: its buffer is free
+        EF_TILED_ISSUE(st + 3)
+        EF_TILED_MMA(a1, b1, 0)
+        __builtin_amdgcn_sched_barrier(0);
+        EF_TILED_READ(a0, b0, nxt, 0)
+        __builtin_amdgcn_sched_barrier(0);
+        EF_TILED_MMA(a1, b1, 2)
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+#undef EF_TILED_READ
+#undef EF_TILED_MMA
+#undef EF_TILED_ISSUE
+
+    // epilogue: act fragments (paired order) of row blocks rb0 + 2*wf + {0,1}, tiles t0 + 4*wt + j
+    const int nkb2 = F >> 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int tile = t0 + wt * 4 + j;
+        if (tile >= ntiles) continue;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int rb = rb0 + wf * 2 + h;
+            uint4 *dst = act + gt.act_off[grp] + ((size_t)tile * nkb2 + rb * 2) * 64 + lane;
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                uint32_t pk[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float g0 = acc[2 * h][j][8 * s + 2 * q], g1 = acc[2 * h][j][8 * s + 2 * q + 1];
+                    const float v0 = g0 / (1.f + __expf(-g0)) * acc[2 * h + 1][j][8 * s + 2 * q];
+                    const float v1 = g1 / (1.f + __expf(-g1)) * acc[2 * h + 1][j][8 * s + 2 * q + 1];
+                    pk[q] = f32_to_bf16_bits(v0) | (f32_to_bf16_bits(v1) << 16);
+                }
+                dst[(size_t)s * 64] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+            }
+        }
+    }
+}
+
+hipError_t launch_ffn_gate_up_tiled(const GroupTable &gt, int total_wgs, const void *xp, void *act, int d,
+                                    hipStream_t s) {
+    if (total_wgs <= 0) return hipSuccess;
+    hipLaunchKernelGGL(ffn_gate_up_tiled_kernel, dim3(total_wgs), dim3(256), 0, s, gt,
+                       reinterpret_cast<const uint4 *>(xp), reinterpret_cast<uint4 *>(act), d);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// second half, tiled: Y = act W2^T for (group, 8 token tiles, 8 column blocks)
+// operand A slots 0..7 = activation fragments of tiles t0..t0+7,
+// operand B slots 8..15 = W2 fragments of column blocks cb0..cb0+7
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, const uint4 *__restrict__ act,
+                                                                 float *__restrict__ Y, int d) {
+    __shared__ __attribute__((aligned(16))) u32x4_t lds[kTileStages][kStageFrags][64];
+    const int wg = blockIdx.x;
+    int grp = 0;
+    while (grp + 1 < gt.n_groups && gt.wg_start[grp + 1] <= wg) ++grp;
+    const int local = wg - gt.wg_start[grp];
+    const int F = gt.F[grp];
+    const int ntiles = gt.n_tiles[grp];
+    const int mpanels = (ntiles + 7) >> 3;
+    const int mp = local % mpanels, np = local / mpanels;
+    const int cb0 = np * 8, t0 = mp * 8;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS DMA targets go through M0
+    const int wc = wave & 1, wt = wave >> 1;
+    const int nkb = F >> 4;
+    const int nstage = nkb / kTileKS;
+
+    const u32x4_t *src[kStageFrags / 4];
+#pragma unroll
+    for (int q = 0; q < kStageFrags / 4; ++q) {
+        const int fi = q * 4 + wave;
+        const int ks = fi >> 4, slot = fi & 15;
+        const uint4 *p;
+        if (slot < 8) {
+            const int tile = min(t0 + slot, ntiles - 1);
+            p = act + gt.act_off[grp] + (size_t)tile * nkb * 64;
+        } else {
+            p = reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(gt.blob[grp]) + (size_t)4 * d * F) +
+                (size_t)(cb0 + slot - 8) * nkb * 64;
+        }
+        src[q] = reinterpret_cast<const u32x4_t *>(p + (size_t)ks * 64 + lane);
+    }
+
+    floatx16 acc[4][4];   // [token tile][column block]
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) zero16(acc[i][j]);
+
+    const int AOFF = wt * 4, BOFF = wc * 4;
+    // Four LDS stage buffers filled by direct global -> LDS loads (no register staging): stages st+1,
+    // st+2 and st+3 are in flight while stage st feeds the matrix cores; one barrier per stage.
+    // Every wave issues kStageFrags/4 loads per stage, unconditionally (past the end the last stage
+    // is re-read, in bounds), so "my loads of stage st have landed" is a constant wait count.
+#define EF_TILED_ISSUE(st)                                                                           \
+    {                                                                                                \
+        const int stc_ = min((st), nstage - 1);                                                      \
+        const int buf_ = (st) & (kTileStages - 1);                                                   \
+        _Pragma("unroll") for (int q = 0; q < kStageFrags / 4; ++q)                                  \
+            __builtin_amdgcn_global_load_lds(src[q] + (size_t)stc_ * kTileKS * 64,                   \
+                                             &lds[buf_][q * 4 + wave][0], 16, 0, 0);                 \
+    }
+#define EF_TILED_READ(a, b, cur, ks)                                                              \
+    {                                                                                                \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) a[i] = lds[cur][(ks) * 16 + AOFF + i][lane];     \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) b[j] = lds[cur][(ks) * 16 + 8 + BOFF + j][lane]; \
+    }
+#define EF_TILED_MMA(a, b, i0)                                                                       \
+    _Pragma("unroll") for (int i = (i0); i < (i0) + 2; ++i)                                          \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) acc[i][j] = mfma32v(a[i], b[j], acc[i][j]);
+    static_assert(kTileKS == 2, "the loop below alternates two fragment register sets");
+    u32x4_t a0[4], b0[4], a1[4], b1[4];
+    EF_TILED_ISSUE(0)
+    EF_TILED_ISSUE(1)
+    EF_TILED_ISSUE(2)
+    __builtin_amdgcn_s_waitcnt(kWaitVm16);   // my part of stage 0 has landed
+    __syncthreads();                         // ... and everybody else's
+    EF_TILED_READ(a0, b0, 0, 0)
+    for (int st = 0; st < nstage; ++st) {
+        const int cur = st & (kTileStages - 1), nxt = (st + 1) & (kTileStages - 1);
+        // Operand fragments are read from LDS half a k-step ahead of their first use, between two
+        // halves of the previous k-step's MFMAs, so their latency hides behind matrix-core work and
+        // the wait in front of an MFMA block only covers reads issued a block earlier.  The
+        // scheduling barriers keep the compiler from sinking the reads back to their first use.
+        EF_TILED_MMA(a0, b0, 0)
+        __builtin_amdgcn_sched_barrier(0);
+        EF_TILED_READ(a1, b1, cur, 1)
+        __builtin_amdgcn_sched_barrier(0);
+        EF_TILED_MMA(a0, b0, 2)
+        __builtin_amdgcn_sched_barrier(0);
+        // stage st+1 must have landed: of the loads issued so far (stages st+1, st+2) at most the
+        // 8 of stage st+2 may still be outstanding
+        __builtin_amdgcn_s_waitcnt(kWaitVm8);
+        __syncthreads();   // every wave has issued its reads of stage st-1 long ago: its buffer is free
+        EF_TILED_ISSUE(st + 3)
+        EF_TILED_MMA(a1, b1, 0)
+        __builtin_amdgcn_sched_barrier(0);
+        EF_TILED_READ(a0, b0, nxt, 0)
+        __builtin_amdgcn_sched_barrier(0);
+        EF_TILED_MMA(a1, b1, 2)
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+#undef EF_TILED_READ
+#undef EF_TILED_MMA
+#undef EF_TILED_ISSUE
+
+    const int g = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int tile = t0 + wt * 4 + i;
+        if (tile >= ntiles) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int col = (cb0 + wc * 4 + j) * 32 + (lane & 31);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int tl = tile * kTile + 8 * (v >> 2) + 4 * g + (v & 3);
+                if (tl < gt.count[grp]) Y[(size_t)(gt.row_offset[grp] + tl) * d + col] = acc[i][j][v];
+            }
+        }
+    }
+}
+
+hipError_t launch_ffn_down_tiled(const GroupTable &gt, int total_wgs, const void *act, float *y, int d,
+                                 hipStream_t s) {
+    if (total_wgs <= 0) return hipSuccess;
+    hipLaunchKernelGGL(ffn_down_tiled_kernel, dim3(total_wgs), dim3(256), 0, s, gt,
+                       reinterpret_cast<const uint4 *>(act), y, d);
+    return hipGetLastError();
+}
+
+}  // namespace ef

@@ -82,6 +82,21 @@ hipError_t launch_ffn_down(const GroupTable &gt, int total_wgs, int tiles_per_pa
 hipError_t launch_combine(const float *y, int ksg, long long y_plane, const float *w, const int32_t *inv_perm,
                           int T, int k, int d, long long shared_row0, float *out, hipStream_t s);
 
+hipError_t launch_ffn_gate_up_tiled(const GroupTable &gt, int total_wgs, const void *xp, void *act, int d,
+                                    hipStream_t s);
+hipError_t launch_ffn_down_tiled(const GroupTable &gt, int total_wgs, const void *act, float *y, int d,
+                                 hipStream_t s);
+
+// The tiled (matrix-core bound) kernels take groups of at least kTiledMinTiles token tiles whose shapes
+// fit their 256 x 256 workgroup tiles: F a multiple of 128 (4 row blocks), d a multiple of 256 (8 column
+// blocks) and of 32 (whole k-step pairs).
+constexpr int kTiledMinTiles = 8;
+inline bool ffn_tiled_ok(int d, int F, int n_tiles) {
+    return n_tiles >= kTiledMinTiles && F % 128 == 0 && d % 256 == 0;
+}
+inline int ffn_gate_up_tiled_wgs(int F, int n_tiles) { return (F / 128) * ((n_tiles + 7) / 8); }
+inline int ffn_down_tiled_wgs(int d, int n_tiles) { return (d / 256) * ((n_tiles + 7) / 8); }
+
 // workgroups a group needs in the two FFN launches
 inline int ffn_gate_up_wgs(int F, int n_tiles, int tiles_per_pass, int ks) {
     int nrb = F / 32, rbw = 4 / ks;
