@@ -23,6 +23,19 @@ constexpr int kWaitVm16 = (1 << 14) | (0x7 << 4) | (0xF << 8) | 0;
 constexpr int kWaitVm8 = (0 << 14) | (0x7 << 4) | (0xF << 8) | 8;
 static_assert(kStageFrags / 4 == 8, "the wait count assumes 8 loads per wave per stage");
 
+// Index of a workgroup within its group -> (weight panel np, token panel mp).  Workgroups with the
+// same index mod 8 land on one XCD; consecutive ones there walk the token panels of
+// kTiledPanelBlock weight panels, so the panels an XCD works on at one time share its L2.
+// Returns false for the padding workgroups past the last weight panel.
+__device__ __forceinline__ bool tiled_panel(int local, int npanels, int mpanels, int &np, int &mp) {
+    const int xcd = local & 7, j = local >> 3;
+    const int blk = kTiledPanelBlock * mpanels;
+    const int jb = j / blk, jj = j - jb * blk;
+    np = (jb * 8 + xcd) * kTiledPanelBlock + jj / mpanels;
+    mp = jj % mpanels;
+    return np < npanels;
+}
+
 // ------------------------------------------------------------------------------------------
 // first half, tiled: act = silu(X W1^T) * (X W3^T) for (group, 4 row blocks, 8 token tiles)
 // operand A slots 0..7 = W1/W3 fragments of row blocks rb0..rb0+3 (slot = 2*rbl + which),
@@ -38,7 +51,8 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_tiled_kernel(GroupTable gt
     const int F = gt.F[grp];
     const int ntiles = gt.n_tiles[grp];
     const int mpanels = (ntiles + 7) >> 3;
-    const int mp = local % mpanels, np = local / mpanels;   // token panel fastest: neighbours share weights
+    int np, mp;
+    if (!tiled_panel(local, F >> 7, mpanels, np, mp)) return;
     const int rb0 = np * 4, t0 = mp * 8;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS DMA targets go through M0
@@ -87,9 +101,20 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_tiled_kernel(GroupTable gt
         _Pragma("unroll") for (int i = 0; i < 4; ++i) a[i] = lds[cur][(ks) * 16 + AOFF + i][lane];     \
         _Pragma("unroll") for (int j = 0; j < 4; ++j) b[j] = lds[cur][(ks) * 16 + 8 + BOFF + j][lane]; \
     }
-#define EF_TILED_MMA(a, b, i0)                                                                       \
-    _Pragma("unroll") for (int i = (i0); i < (i0) + 2; ++i)                                          \
-        _Pragma("unroll") for (int j = 0; j < 4; ++j) acc[i][j] = mfma32v(a[i], b[j], acc[i][j]);
+    // one k-step: 16 MFMAs on the current fragments while the 8 fragments of the next k-step are
+    // read from LDS, scheduled as 2 MFMAs, (1 LDS read, 1 MFMA) x 8, 6 MFMAs: no burst on either pipe,
+    // and the last read is issued six MFMAs before the next k-step needs the fragments
+#define EF_TILED_STEP(ac, bc, an, bn, buf, ks)                                                       \
+    EF_TILED_READ(an, bn, buf, ks)                                                                   \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                    \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) acc[i][j] = mfma32v(ac[i], bc[j], acc[i][j]);  \
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                               \
+    _Pragma("unroll") for (int r_ = 0; r_ < 8; ++r_) {                                               \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                           \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                           \
+    }                                                                                                \
+    __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);                                               \
+    __builtin_amdgcn_sched_barrier(0);
     static_assert(kTileKS == 2, "the loop below alternates two fragment register sets");
     u32x4_t a0[4], b0[4], a1[4], b1[4];
     EF_TILED_ISSUE(0)
@@ -100,31 +125,18 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_tiled_kernel(GroupTable gt
     EF_TILED_READ(a0, b0, 0, 0)
     for (int st = 0; st < nstage; ++st) {
         const int cur = st & (kTileStages - 1), nxt = (st + 1) & (kTileStages - 1);
-        // Operand fragments are read from LDS half a k-step ahead of their first use, between two
-        // halves of the previous k-step's MFMAs, so their latency hides behind matrix-core work and
-        // the wait in front of an MFMA block only covers reads issued a block earlier.  The
-        // scheduling barriers keep the compiler from sinking the reads back to their first use.
-        EF_TILED_MMA(a0, b0, 0)
-        __builtin_amdgcn_sched_barrier(0);
-        EF_TILED_READ(a1, b1, cur, 1)
-        __builtin_amdgcn_sched_barrier(0);
-        EF_TILED_MMA(a0, b0, 2)
-        __builtin_amdgcn_sched_barrier(0);
+        EF_TILED_STEP(a0, b0, a1, b1, cur, 1)
         // stage st+1 must have landed: of the loads issued so far (stages st+1, st+2) at most the
         // 8 of stage st+2 may still be outstanding
         __builtin_amdgcn_s_waitcnt(kWaitVm8);
         __syncthreads();   // every wave has issued its reads of stage st-1 long ago: its buffer is free
         EF_TILED_ISSUE(st + 3)
-        EF_TILED_MMA(a1, b1, 0)
         __builtin_amdgcn_sched_barrier(0);
-        EF_TILED_READ(a0, b0, nxt, 0)
-        __builtin_amdgcn_sched_barrier(0);
-        EF_TILED_MMA(a1, b1, 2)
-        __builtin_amdgcn_sched_barrier(0);
+        EF_TILED_STEP(a1, b1, a0, b0, nxt, 0)
     }
     __builtin_amdgcn_s_waitcnt(0);
 #undef EF_TILED_READ
-#undef EF_TILED_MMA
+#undef EF_TILED_STEP
 #undef EF_TILED_ISSUE
 
     // epilogue: act fragments (paired order) of row blocks rb0 + 2*wf + {0,1}, tiles t0 + 4*wt + j
@@ -176,7 +188,8 @@ __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, c
     const int F = gt.F[grp];
     const int ntiles = gt.n_tiles[grp];
     const int mpanels = (ntiles + 7) >> 3;
-    const int mp = local % mpanels, np = local / mpanels;
+    int np, mp;
+    if (!tiled_panel(local, d >> 8, mpanels, np, mp)) return;
     const int cb0 = np * 8, t0 = mp * 8;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS DMA targets go through M0
@@ -224,9 +237,20 @@ __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, c
         _Pragma("unroll") for (int i = 0; i < 4; ++i) a[i] = lds[cur][(ks) * 16 + AOFF + i][lane];     \
         _Pragma("unroll") for (int j = 0; j < 4; ++j) b[j] = lds[cur][(ks) * 16 + 8 + BOFF + j][lane]; \
     }
-#define EF_TILED_MMA(a, b, i0)                                                                       \
-    _Pragma("unroll") for (int i = (i0); i < (i0) + 2; ++i)                                          \
-        _Pragma("unroll") for (int j = 0; j < 4; ++j) acc[i][j] = mfma32v(a[i], b[j], acc[i][j]);
+    // one k-step: 16 MFMAs on the current fragments while the 8 fragments of the next k-step are
+    // read from LDS, scheduled as 2 MFMAs, (1 LDS read, 1 MFMA) x 8, 6 MFMAs: no burst on either pipe,
+    // and the last read is issued six MFMAs before the next k-step needs the fragments
+#define EF_TILED_STEP(ac, bc, an, bn, buf, ks)                                                       \
+    EF_TILED_READ(an, bn, buf, ks)                                                                   \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                    \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) acc[i][j] = mfma32v(ac[i], bc[j], acc[i][j]);  \
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                               \
+    _Pragma("unroll") for (int r_ = 0; r_ < 8; ++r_) {                                               \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                           \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                           \
+    }                                                                                                \
+    __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);                                               \
+    __builtin_amdgcn_sched_barrier(0);
     static_assert(kTileKS == 2, "the loop below alternates two fragment register sets");
     u32x4_t a0[4], b0[4], a1[4], b1[4];
     EF_TILED_ISSUE(0)
@@ -237,31 +261,18 @@ __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, c
     EF_TILED_READ(a0, b0, 0, 0)
     for (int st = 0; st < nstage; ++st) {
         const int cur = st & (kTileStages - 1), nxt = (st + 1) & (kTileStages - 1);
-        // Operand fragments are read from LDS half a k-step ahead of their first use, between two
-        // halves of the previous k-step's MFMAs, so their latency hides behind matrix-core work and
-        // the wait in front of an MFMA block only covers reads issued a block earlier.  The
-        // scheduling barriers keep the compiler from sinking the reads back to their first use.
-        EF_TILED_MMA(a0, b0, 0)
-        __builtin_amdgcn_sched_barrier(0);
-        EF_TILED_READ(a1, b1, cur, 1)
-        __builtin_amdgcn_sched_barrier(0);
-        EF_TILED_MMA(a0, b0, 2)
-        __builtin_amdgcn_sched_barrier(0);
+        EF_TILED_STEP(a0, b0, a1, b1, cur, 1)
         // stage st+1 must have landed: of the loads issued so far (stages st+1, st+2) at most the
         // 8 of stage st+2 may still be outstanding
         __builtin_amdgcn_s_waitcnt(kWaitVm8);
         __syncthreads();   // every wave has issued its reads of stage st-1 long ago: its buffer is free
         EF_TILED_ISSUE(st + 3)
-        EF_TILED_MMA(a1, b1, 0)
         __builtin_amdgcn_sched_barrier(0);
-        EF_TILED_READ(a0, b0, nxt, 0)
-        __builtin_amdgcn_sched_barrier(0);
-        EF_TILED_MMA(a1, b1, 2)
-        __builtin_amdgcn_sched_barrier(0);
+        EF_TILED_STEP(a1, b1, a0, b0, nxt, 0)
     }
     __builtin_amdgcn_s_waitcnt(0);
 #undef EF_TILED_READ
-#undef EF_TILED_MMA
+#undef EF_TILED_STEP
 #undef EF_TILED_ISSUE
 
     const int g = lane >> 5;

@@ -94,8 +94,18 @@ constexpr int kTiledMinTiles = 8;
 inline bool ffn_tiled_ok(int d, int F, int n_tiles) {
     return n_tiles >= kTiledMinTiles && F % 128 == 0 && d % 256 == 0;
 }
-inline int ffn_gate_up_tiled_wgs(int F, int n_tiles) { return (F / 128) * ((n_tiles + 7) / 8); }
-inline int ffn_down_tiled_wgs(int d, int n_tiles) { return (d / 256) * ((n_tiles + 7) / 8); }
+// Workgroups are dealt to the 8 XCDs round-robin by index, and each XCD has an L2 of its own.  The
+// tiled kernels therefore number a group's workgroups so that those an XCD runs side by side
+// (indices congruent mod 8, consecutive) form blocks of kTiledPanelBlock weight panels x all token
+// panels: a weight panel is then fetched into one L2 once and read by every token panel there.  The
+// count is padded to whole blocks; workgroups that fall past the last weight panel exit at once.
+constexpr int kTiledPanelBlock = 2;
+inline int ffn_tiled_wgs(int npanels, int n_tiles) {
+    const int per_round = 8 * kTiledPanelBlock;
+    return ((npanels + per_round - 1) / per_round) * per_round * ((n_tiles + 7) / 8);
+}
+inline int ffn_gate_up_tiled_wgs(int F, int n_tiles) { return ffn_tiled_wgs(F / 128, n_tiles); }
+inline int ffn_down_tiled_wgs(int d, int n_tiles) { return ffn_tiled_wgs(d / 256, n_tiles); }
 
 // workgroups a group needs in the two FFN launches
 inline int ffn_gate_up_wgs(int F, int n_tiles, int tiles_per_pass, int ks) {
