@@ -125,11 +125,13 @@ typedef struct ef_stats {
     int32_t horizon;            /* current look-ahead S */
     int32_t stall_counter, overfetch_counter;
     int32_t reserved_;
-    /* EF_FLAG_PROFILE only: summed event time, launches and algorithmic bytes (minimal HBM traffic
-     * the operation needs: operands read once, results written once) per kernel kind */
+    /* EF_FLAG_PROFILE only: summed event time, launches, algorithmic bytes (minimal HBM traffic the
+     * operation needs: operands read once, results written once) and, for the matrix-core kernels,
+     * algorithmic flops (2 per multiply-add of the contraction, padding rows not counted) per kind */
     double kernel_seconds[EF_K_COUNT];
     double kernel_bytes[EF_K_COUNT];
     int64_t kernel_launches[EF_K_COUNT];
+    double kernel_flops[EF_K_COUNT];
 } ef_stats;
 
 /* ---- utilities (host only, no device needed) -------------------------------------------- */

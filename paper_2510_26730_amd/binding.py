@@ -53,7 +53,7 @@ class ef_stats(C.Structure):
         ("layer_seconds_est", C.c_double), ("miss_rate", C.c_double), ("horizon", C.c_int32),
         ("stall_counter", C.c_int32), ("overfetch_counter", C.c_int32), ("reserved_", C.c_int32),
         ("kernel_seconds", C.c_double * 10), ("kernel_bytes", C.c_double * 10),
-        ("kernel_launches", C.c_int64 * 10),
+        ("kernel_launches", C.c_int64 * 10), ("kernel_flops", C.c_double * 10),
     ]
 
     def as_dict(self):

@@ -70,7 +70,7 @@ struct ef_ctx {
     std::vector<EventPair> stall_ring, layer_ring;
     size_t stall_next = 0, layer_next = 0;
     std::deque<EventPair> stall_pending, layer_pending;
-    struct ProfItem { EventPair p; int kind; double bytes; };
+    struct ProfItem { EventPair p; int kind; double bytes; double flops; };
     std::vector<EventPair> prof_ring;
     size_t prof_next = 0;
     std::deque<ProfItem> prof_pending;
@@ -179,6 +179,7 @@ void poll_prof(ef_ctx *c, bool wait) {
         if (hipEventElapsedTime(&ms, it.p.a, it.p.b) == hipSuccess) {
             c->st.kernel_seconds[it.kind] += ms * 1e-3;
             c->st.kernel_bytes[it.kind] += it.bytes;
+            c->st.kernel_flops[it.kind] += it.flops;
             c->st.kernel_launches[it.kind] += 1;
         }
         c->prof_pending.pop_front();
@@ -190,11 +191,11 @@ struct KernelTimer {
     ef_ctx *c;
     hipStream_t s;
     int kind;
-    double bytes;
+    double bytes, flops;
     EventPair p{nullptr, nullptr};
     bool on;
-    KernelTimer(ef_ctx *ctx, hipStream_t st, int k, double b)
-        : c(ctx), s(st), kind(k), bytes(b), on(((ctx->profile_mask >> k) & 1u) != 0) {
+    KernelTimer(ef_ctx *ctx, hipStream_t st, int k, double b, double f = 0.0)
+        : c(ctx), s(st), kind(k), bytes(b), flops(f), on(((ctx->profile_mask >> k) & 1u) != 0) {
         if (!on) return;
         if (c->prof_pending.size() >= c->prof_ring.size()) poll_prof(c, true);
         p = c->prof_ring[c->prof_next];
@@ -204,7 +205,7 @@ struct KernelTimer {
     ~KernelTimer() {
         if (!on) return;
         (void)hipEventRecord(p.b, s);
-        c->prof_pending.push_back({p, kind, bytes});
+        c->prof_pending.push_back({p, kind, bytes, flops});
     }
 };
 
@@ -765,14 +766,18 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
         }
         big.wg_start[nb] = wg_up;
         bdn.wg_start[nb] = wg_dn;
-        double b_up = 0.0, b_dn = 0.0;
+        double b_up = 0.0, b_dn = 0.0, f_up = 0.0, f_dn = 0.0;
         alg_bytes(big, nb, b_up, b_dn);
+        for (int i = 0; i < nb; ++i) {
+            f_up += 4.0 * big.count[i] * d * big.F[i];   // two d x F products, 2 flops per multiply-add
+            f_dn += 2.0 * big.count[i] * d * big.F[i];
+        }
         {
-            KernelTimer kt(c, s, EF_K_FFN_UP_TILED, b_up);
+            KernelTimer kt(c, s, EF_K_FFN_UP_TILED, b_up, f_up);
             EF_HIP(c, ef::launch_ffn_gate_up_tiled(big, wg_up, c->xp, c->act, d, s));
         }
         {
-            KernelTimer kt(c, s, EF_K_FFN_DOWN_TILED, b_dn);
+            KernelTimer kt(c, s, EF_K_FFN_DOWN_TILED, b_dn, f_dn);
             EF_HIP(c, ef::launch_ffn_down_tiled(bdn, wg_dn, c->act, c->y, d, s));
         }
     }

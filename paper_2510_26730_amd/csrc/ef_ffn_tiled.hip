@@ -168,6 +168,12 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_tiled_kernel(GroupTable gt
 hipError_t launch_ffn_gate_up_tiled(const GroupTable &gt, int total_wgs, const void *xp, void *act, int d,
                                     hipStream_t s) {
     if (total_wgs <= 0) return hipSuccess;
+    // the kernel's index mapping and the grid must come from the same workgroup count per group
+    for (int i = 0; i < gt.n_groups; ++i)
+        if (gt.wg_start[i + 1] - gt.wg_start[i] != ffn_gate_up_tiled_wgs(gt.F[i], gt.n_tiles[i]) ||
+            !ffn_tiled_ok(d, gt.F[i], gt.n_tiles[i]))
+            return hipErrorInvalidValue;
+    if (gt.wg_start[gt.n_groups] != total_wgs) return hipErrorInvalidValue;
     hipLaunchKernelGGL(ffn_gate_up_tiled_kernel, dim3(total_wgs), dim3(256), 0, s, gt,
                        reinterpret_cast<const uint4 *>(xp), reinterpret_cast<uint4 *>(act), d);
     return hipGetLastError();
@@ -295,6 +301,11 @@ __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, c
 hipError_t launch_ffn_down_tiled(const GroupTable &gt, int total_wgs, const void *act, float *y, int d,
                                  hipStream_t s) {
     if (total_wgs <= 0) return hipSuccess;
+    for (int i = 0; i < gt.n_groups; ++i)
+        if (gt.wg_start[i + 1] - gt.wg_start[i] != ffn_down_tiled_wgs(d, gt.n_tiles[i]) ||
+            !ffn_tiled_ok(d, gt.F[i], gt.n_tiles[i]))
+            return hipErrorInvalidValue;
+    if (gt.wg_start[gt.n_groups] != total_wgs) return hipErrorInvalidValue;
     hipLaunchKernelGGL(ffn_down_tiled_kernel, dim3(total_wgs), dim3(256), 0, s, gt,
                        reinterpret_cast<const uint4 *>(act), y, d);
     return hipGetLastError();
