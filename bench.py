@@ -87,6 +87,12 @@ def main():
     ap.add_argument("--beta", type=float, default=None)
     ap.add_argument("--layers", type=int, default=None)
     ap.add_argument("--all-resident", action="store_true", help="cache holds every expert (no PCIe traffic)")
+    ap.add_argument("--pool-slots", type=int, default=None,
+                    help="one global pool of this many cache slots shared by all layers instead of a per-layer quota")
+    ap.add_argument("--horizon", type=int, default=None, help="fixed look-ahead H (default: the adaptive horizon)")
+    ap.add_argument("--drift-tokens", type=int, default=0,
+                    help="re-draw the expert popularity ranks (gate biases) whenever the running token count "
+                         "crosses a multiple of this (0 = static popularity)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle baseline")
     ap.add_argument("--calib-copy", type=int, default=0,
@@ -122,7 +128,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    loop = LayerLoop(cfg, L, T, cfg.slots_per_layer, beta=beta, profile=False, all_resident=args.all_resident)
+    loop = LayerLoop(cfg, L, T, cfg.slots_per_layer, pool_slots=args.pool_slots, beta=beta, profile=False,
+                     all_resident=args.all_resident)
+    loop.h_fixed = args.horizon
     n_in = 4                                          # distinct step inputs, cycled
     hs = [torch.from_numpy(synth.hidden_stack(cfg, L, step=s, T=T).view("int16")).cuda() for s in range(n_in)]
     torch.cuda.synchronize()
@@ -141,8 +149,25 @@ def main():
                     out[name]["TFLOPps"] = flops / sec / 1e12 if sec > 0 else None
         return out
 
+    # popularity drift: a new permutation of the Zipf ranks per epoch, written into the registered bias
+    # buffers (E floats per layer, host arrays prepared before the timed region)
+    drift = {"tokens": 0, "epoch": 0}
+    n_epochs = 1 + ((args.warmup + args.steps + 2) * T) // args.drift_tokens if args.drift_tokens > 0 else 1
+    bias_epochs = [[torch.from_numpy(synth.gate_bias(cfg, l, ep)).pin_memory() for l in range(L)]
+                   for ep in range(1, n_epochs + 1)] if args.drift_tokens > 0 else []
+
+    def run_step(h):
+        if args.drift_tokens > 0:
+            drift["tokens"] += T
+            ep = drift["tokens"] // args.drift_tokens
+            if ep != drift["epoch"]:
+                drift["epoch"] = ep
+                for l in range(L):
+                    loop.gate_b[l].copy_(bias_epochs[(ep - 1) % len(bias_epochs)][l], non_blocking=True)
+        loop.step(h, stream)
+
     for s in range(args.warmup):
-        loop.step(hs[s % n_in], stream)
+        run_step(hs[s % n_in])
     torch.cuda.synchronize()
     # timed region: only the dominant kernel is bracketed with HIP events, on the stream it is launched
     # on: the weight-streaming first FFN half when experts see few tokens (decode), its matrix-core
@@ -152,10 +177,15 @@ def main():
     ef.ef_set_profile(loop.ctx, 1 << ef.EF_KERNELS.index(dom_name))
     ef.ef_reset_stats(loop.ctx)
     t0 = time.perf_counter()
+    marks = []
     for s in range(args.steps):
-        loop.step(hs[(args.warmup + s) % n_in], stream)
-    torch.cuda.synchronize()
+        run_step(hs[(args.warmup + s) % n_in])
+        marks.append(time.perf_counter())     # the host runs at most one layer ahead of the GPU (it waits
+    torch.cuda.synchronize()                  # for every layer's counts), so these bound each step's time
     dt = time.perf_counter() - t0
+    marks[-1] = t0 + dt
+    per_step = sorted(1e3 * (b - a) for a, b in zip([t0] + marks[:-1], marks))
+    pct = lambda q: per_step[min(len(per_step) - 1, int(q * len(per_step)))]
     st = ef.ef_get_stats(loop.ctx)
     dom = kernel_table(st, dt).get(dom_name)
 
@@ -184,7 +214,7 @@ def main():
         traffic = None
         tag = f"TRAFFIC_BYTES_PER_LAUNCH ffn_gate_up_kernel {cfg.name} T={T} beta={beta} ="
         pmc = os.path.join(ROOT, "profiles", "ffn_kernels_mixtral_decode_T64_pmc_traffic.md")
-        if os.path.exists(pmc) and not args.all_resident:
+        if os.path.exists(pmc) and not args.all_resident and args.pool_slots is None:
             for line in open(pmc):
                 if line.startswith(tag):
                     traffic = float(line.split("=")[-1])
@@ -198,10 +228,13 @@ def main():
         "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {L} layers, d={cfg.d}, E={cfg.E}, top-{cfg.k}, F={cfg.F}, "
-                               f"T={T} tokens/step, cache {'all experts' if args.all_resident else str(cfg.slots_per_layer) + ' slots/layer'}"
+                               f"T={T} tokens/step, cache {'all experts' if args.all_resident else (str(args.pool_slots) + '-slot pool' if args.pool_slots else str(cfg.slots_per_layer) + ' slots/layer')}"
                                f", beta={beta}, expert store = {loop.store_layers}-layer pinned pool reused cyclically",
-                   "tokens_per_step": T, "layers": L, "beta": beta},
+                   "tokens_per_step": T, "layers": L, "beta": beta,
+                   "horizon": "adaptive" if args.horizon is None else args.horizon,
+                   "drift_tokens": args.drift_tokens},
         "us_per_layer": 1e6 * dt / (L * args.steps),
+        "ms_per_step_p10_p50_p90": [pct(0.1), pct(0.5), pct(0.9)],
         "stall_frac": st["stall_seconds"] / dt,
         "cache": {"hits": st["hits"], "misses": st["misses"], "miss_rate": st["miss_rate"],
                   "prefetch_issued": st["prefetch_issued"], "bytes_copied": st["bytes_copied"],
