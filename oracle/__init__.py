@@ -211,6 +211,19 @@ def horizon(n_e, expert_bytes, bandwidth_Bps, layer_seconds, h_max):
     return int(lib().oracle_horizon(n_e, expert_bytes, bandwidth_Bps, layer_seconds, h_max))
 
 
+def token_dist(h, js=None):
+    """Per-token part of the intra-batch diversity (paper Sec. 2.2): s[j] = sum_{i<j} ||v_i - v_j||_2
+    for the listed tokens js (default: all, then s.sum() is Dist(t))."""
+    h = _u16(h)
+    T, d = h.shape
+    js_a = None if js is None else np.ascontiguousarray(js, dtype=np.int32)
+    n = T if js_a is None else len(js_a)
+    s = np.empty(n, dtype=np.float64)
+    lib().oracle_token_dist(_p(h, C.c_uint16), C.c_int(T), C.c_int(d), _p(js_a, C.c_int32), C.c_int(n),
+                            _p(s, C.c_double))
+    return s
+
+
 # ---------------------------------------------------------------------------
 # composites, in the method's order
 # ---------------------------------------------------------------------------

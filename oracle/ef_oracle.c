@@ -16,6 +16,8 @@
  *     additive bias beta on the selection score of resident experts);
  *   - expected activation count by cumulative probability and the step size
  *     S = N_e * E_s / (C_s * T_l): Sec. 3.2.1 and its equation;
+ *   - intra-batch diversity Dist(t), the sum of pairwise Euclidean distances
+ *     between the token embeddings of a batch: Sec. 2.2 (its equation);
  *   - the layer math itself (softmax over all experts, top-k, SwiGLU expert,
  *     weighted combine) is not written out in the paper; it is the standard
  *     definition for the model families the paper evaluates (Sec. 4.1).
@@ -319,4 +321,29 @@ int oracle_horizon(double n_e, double expert_bytes, double bandwidth_Bps, double
     if (s < 1.0) s = 1.0;
     if (s > (double)h_max) s = (double)h_max;
     return (int)s;
+}
+
+/*
+ * Intra-batch diversity (paper Sec. 2.2, equation of Dist(t)): the sum over all token pairs of
+ * the Euclidean distance between their embeddings.  Written per token so that large batches can
+ * be checked on a sample: for each listed j, s[j] = sum over i < j of ||v_i - v_j||_2, and
+ * Dist(t) = sum over all j of s[j].  `js` lists n token indices (NULL: all T tokens in order).
+ */
+void oracle_token_dist(const uint16_t *h, int T, int d, const int32_t *js, int n, double *s)
+{
+    if (js == NULL) n = T;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int q = 0; q < n; ++q) {
+        int j = js ? js[q] : q;
+        double acc = 0.0;
+        for (int i = 0; i < j; ++i) {
+            double sq = 0.0;
+            for (int c = 0; c < d; ++c) {
+                double diff = bf16_to_f64(h[(size_t)i * d + c]) - bf16_to_f64(h[(size_t)j * d + c]);
+                sq += diff * diff;
+            }
+            acc += sqrt(sq);
+        }
+        s[q] = acc;
+    }
 }

@@ -281,3 +281,42 @@ def test_expected_activations_by_brute_force(oracle_mod, tau):
         if tau == 1.0:
             assert n == int(np.count_nonzero(hist))
     assert oracle_mod.expected_activations(np.array([5, 1, 9, 0], np.int32), 1e-9)[0] == 1
+
+
+# ---------------------------------------------------------------------------
+# intra-batch diversity Dist(t) (paper Sec. 2.2)
+# ---------------------------------------------------------------------------
+
+def test_token_dist_matches_scipy_pdist(oracle_mod):
+    """Library routine: the sum of scipy's condensed pairwise Euclidean distances (fp64)."""
+    from scipy.spatial.distance import pdist, squareform
+    rng = np.random.default_rng(11)
+    h = synth.f32_to_bf16(rng.standard_normal((37, 96)).astype(np.float32))
+    v = synth.bf16_to_f32(h).astype(np.float64)
+    s = oracle_mod.token_dist(h)
+    assert s.shape == (37,)
+    assert abs(s.sum() - pdist(v, "euclidean").sum()) < 1e-9 * s.sum()
+    full = squareform(pdist(v, "euclidean"))
+    ref = np.array([full[j, :j].sum() for j in range(37)])       # earlier tokens only
+    np.testing.assert_allclose(s, ref, rtol=1e-12, atol=1e-12)
+    js = np.array([36, 0, 5], dtype=np.int32)                     # sampled form, any order
+    np.testing.assert_allclose(oracle_mod.token_dist(h, js), ref[js], rtol=1e-12, atol=1e-12)
+
+
+def test_token_dist_closed_forms(oracle_mod):
+    """Scaled basis vectors: ||a_i e_i - a_j e_j|| = sqrt(a_i^2 + a_j^2); duplicates add nothing;
+    one token has no pair; a translation of all tokens changes nothing (values exact in bf16)."""
+    a = np.array([1.0, 2.0, 0.5, 4.0, 3.0])
+    v = np.zeros((5, 8), dtype=np.float32)
+    v[np.arange(5), np.arange(5)] = a
+    h = synth.f32_to_bf16(v)
+    s = oracle_mod.token_dist(h)
+    ref = np.array([sum(np.hypot(a[i], a[j]) for i in range(j)) for j in range(5)])
+    np.testing.assert_allclose(s, ref, rtol=1e-14)
+    dup = synth.f32_to_bf16(np.tile(v[3], (6, 1)))
+    assert np.all(oracle_mod.token_dist(dup) == 0.0)
+    assert oracle_mod.token_dist(h[:1]).tolist() == [0.0]
+    shifted = synth.f32_to_bf16(v + 8.0)                          # small integers and halves stay exact
+    np.testing.assert_allclose(oracle_mod.token_dist(shifted), ref, rtol=1e-14)
+    # a plausible mistake (squared distances, or all pairs counted twice) fails these values
+    assert abs(s.sum() - sum(np.hypot(a[i], a[j]) for j in range(5) for i in range(j))) < 1e-12
