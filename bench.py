@@ -193,7 +193,15 @@ def main():
     ef.ef_set_profile(loop.ctx, 0x3FF)
     ef.ef_reset_stats(loop.ctx)
     t1 = time.perf_counter()
+    tok_dist = torch.empty(T, dtype=torch.float32, device="cuda")
+    dist = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ef.ef_token_dist(loop.ctx, hs[0][0], T, tok_dist, dist, stream)     # first call loads the kernels
+    torch.cuda.synchronize()
+    ef.ef_reset_stats(loop.ctx)
+    t1 = time.perf_counter()
     for s in range(2):
+        # the intra-batch diversity signal of the iteration's tokens (once per step, outside `value`)
+        ef.ef_token_dist(loop.ctx, hs[s % n_in][0], T, tok_dist, dist, stream)
         loop.step(hs[s % n_in], stream)
     torch.cuda.synchronize()
     kern = kernel_table(ef.ef_get_stats(loop.ctx), time.perf_counter() - t1)
@@ -242,6 +250,7 @@ def main():
                   "horizon": st["horizon"], "bandwidth_est_GBps": st["bandwidth_Bps"] / 1e9,
                   "layer_est_us": st["layer_seconds_est"] * 1e6},
         "kernels": kern,
+        "token_dist": float(dist.cpu()[0]),
         "roofline": roof,
     }
     loop.close()

@@ -81,6 +81,7 @@ enum {
     EF_K_FFN_DOWN = 6, /* grouped Y = act W2^T */
     EF_K_COMBINE = 7,  /* weighted un-permute */
     EF_K_FFN_DOWN_TILED = 8, /* second FFN half, groups with many tokens */
+    EF_K_DIST = 9,     /* intra-batch diversity Dist(t): norms, Gram tiles, reductions (one bracket) */
     EF_K_COUNT = 10
 };
 
@@ -257,6 +258,19 @@ int ef_choose_horizon(ef_ctx *ctx, int layer, const int32_t *hist_host, int H, i
 int ef_layer_step(ef_ctx *ctx, int layer, const void *hidden, int T, float beta, int H,
                   const float *delta, const int32_t *tok2req, float *out, int *H_next,
                   int32_t *counts_host_out, void *stream);
+
+/*
+ * Intra-batch diversity of the tokens of one iteration (paper Sec. 2.2, equation of Dist(t)): the sum
+ * over token pairs of the Euclidean distance between their embeddings, the runtime signal the paper
+ * names for the initial step size (Sec. 2.3.1, 3.1).  hidden [dev] [T, d_model] bf16 row-major, 16-byte
+ * aligned, 1 <= T <= max_tokens.  tok_dist [dev] [T] f32 (may be NULL) receives per token j the sum of
+ * ||v_i - v_j||_2 over the earlier tokens i < j; *dist [dev] f64 their total Dist(t).  fp32 inner
+ * products on the matrix cores, fp64 final sums in a fixed order (bit-reproducible).  Enqueues on
+ * `stream` only and uses the context's FFN scratch: not concurrent with ef_moe_ffn / ef_layer_step
+ * of the same context on another stream.  EF_EINVAL when T*top_k*d_model floats of scratch cannot
+ * hold the T*ceil(T/64) partial sums.
+ */
+int ef_token_dist(ef_ctx *ctx, const void *hidden, int T, float *tok_dist, double *dist, void *stream);
 
 /* Statistics; synchronises outstanding timing events first (not for the hot loop). */
 int ef_get_stats(ef_ctx *ctx, ef_stats *out);

@@ -23,13 +23,13 @@ EF_FLAG_PROFILE = 4
 EF_FLAG_FIXED_ESTIMATES = 8
 EF_FLAG_PROFILE_FFN_UP = 16
 EF_KERNELS = ["predict", "route", "group", "ffn_up_tiled", "pack", "ffn_up", "ffn_down", "combine", "ffn_down_tiled",
-              "reserved"]
+              "dist"]
 EF_MAX_EXPERTS, EF_MAX_TOPK, EF_MAX_HORIZON = 64, 8, 7
 
 EXPORTS = [
     "ef_strerror", "ef_expert_bytes", "ef_pack_expert", "ef_create", "ef_destroy", "ef_last_error",
     "ef_register_layer", "ef_predict", "ef_route", "ef_route_predict", "ef_moe_ffn", "ef_layer_step", "ef_cache_swap_in", "ef_cache_query",
-    "ef_choose_horizon", "ef_get_stats", "ef_reset_stats", "ef_set_profile", "ef_fake_advance_time",
+    "ef_choose_horizon", "ef_token_dist", "ef_get_stats", "ef_reset_stats", "ef_set_profile", "ef_fake_advance_time",
 ]
 
 
@@ -100,6 +100,7 @@ def lib():
         L.ef_cache_swap_in.argtypes = [vp, i32, i32, i32, i32, C.POINTER(i32)]
         L.ef_cache_query.argtypes = [vp, i32, vp]
         L.ef_choose_horizon.argtypes = [vp, i32, vp, i32, i32, C.POINTER(i32), vp, C.POINTER(i32)]
+        L.ef_token_dist.argtypes = [vp, vp, i32, vp, vp, vp]
         L.ef_get_stats.argtypes = [vp, C.POINTER(ef_stats)]
         L.ef_reset_stats.argtypes = [vp]
         L.ef_set_profile.argtypes = [vp, C.c_uint]
@@ -227,6 +228,11 @@ def ef_layer_step(ctx, layer, hidden, T, beta, H, delta, tok2req, out, counts_ho
     _check(ctx, lib().ef_layer_step(ctx, layer, _ptr(hidden), T, beta, H, _ptr(delta), _ptr(tok2req), _ptr(out),
                                     C.byref(hn), _ptr(counts_host), _stream(stream)))
     return hn.value
+
+
+def ef_token_dist(ctx, hidden, T, tok_dist, dist, stream=None):
+    """Dist(t) of the batch: tok_dist [T] f32 (or None) and dist [1] f64, both on the device."""
+    return _check(ctx, lib().ef_token_dist(ctx, _ptr(hidden), T, _ptr(tok_dist), _ptr(dist), _stream(stream)))
 
 
 def ef_cache_swap_in(ctx, layer, expert, priority=0, due_in=0):

@@ -641,6 +641,32 @@ extern "C" int ef_predict(ef_ctx *c, int layer, const void *hidden, int T, int H
                      nullptr, nullptr, topk_ids, hist, kNoExport, s);
 }
 
+extern "C" int ef_token_dist(ef_ctx *c, const void *hidden, int T, float *tok_dist, double *dist, void *stream) {
+    if (!c) return EF_EINVAL;
+    if (c->fake) return fail(c, EF_ENOSYS, "ef_token_dist: fake-copy context has no device");
+    if (T < 1 || T > c->cfg.max_tokens) return fail(c, EF_EINVAL, "ef_token_dist: T=%d outside 1..max_tokens", T);
+    if (!hidden || !dist) return fail(c, EF_EINVAL, "ef_token_dist: null pointer");
+    if (!aligned16(hidden)) return fail(c, EF_EINVAL, "ef_token_dist: hidden must be 16-byte aligned");
+    const int d = c->cfg.d_model;
+    const int ntiles = (T + ef::kTile - 1) / ef::kTile;
+    if (ntiles > c->max_tiles || (long long)ef::dist_scratch_floats(T) > c->y_floats)
+        return fail(c, EF_EINVAL, "ef_token_dist: T=%d needs more scratch than this context has", T);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    ef::PackTable pt{};
+    pt.n_groups = 1;
+    pt.tile_start[0] = 0;
+    pt.tile_start[1] = ntiles;
+    pt.row_offset[0] = -1;   // identity: packed row = token
+    pt.count[0] = T;
+    // flops of the strict upper triangle; bytes: tokens read once, packed copy written and read once
+    const double flops = (double)T * (T - 1) * d;
+    const double bytes = 6.0 * T * d + 8.0 * T;
+    KernelTimer kt(c, s, EF_K_DIST, bytes, flops);
+    EF_HIP(c, ef::launch_pack_x(pt, ntiles, static_cast<const uint16_t *>(hidden), d, 1, nullptr, c->xp, s));
+    EF_HIP(c, ef::launch_token_dist(static_cast<const uint16_t *>(hidden), T, d, c->xp, c->y, tok_dist, dist, s));
+    return EF_OK;
+}
+
 extern "C" int ef_route(ef_ctx *c, int layer, const void *hidden, int T, float beta, int32_t *topk_ids,
                         float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
                         void *stream) {

@@ -1,0 +1,187 @@
+// Intra-batch diversity Dist(t) = sum over token pairs of the Euclidean distance between their
+// embeddings (paper Sec. 2.2), computed per token: s[j] = sum_{i<j} ||v_i - v_j||_2.
+//
+// ||v_i - v_j||^2 = n_i + n_j - 2 <v_i, v_j>: the inner products are one T x T Gram matrix, a dense
+// contraction over d that runs on the matrix cores from the packed (operand-fragment) copy of the
+// tokens; only tiles that hold a pair i < j are computed.  Three steps on one stream:
+//   1. squared norms n_i in fp32 (bf16 products are exact in fp32), one wave per token;
+//   2. Gram tiles: a workgroup owns 128 rows i x 256 columns j, a wave 64 x 128 (2 x 4 MFMA
+//      32x32x16 accumulators); the epilogue turns inner products into distances, masks i >= j and
+//      columns past T, and adds the 64 rows of the wave per column: one partial per (64-row block,
+//      token j), no atomics;
+//   3. per token the partials of its row blocks are added in ascending order, and the per-token
+//      values are added in fixed order (workgroup tree, then one workgroup over the workgroup
+//      sums) into Dist(t) in fp64: the result does not depend on scheduling.
+#include "ef_device.h"
+#include "ef_kernels.h"
+
+namespace ef {
+
+// one wave per token: n[t] = sum_c x[t,c]^2 in fp32, lanes stride the row in 16-byte pieces
+__global__ __launch_bounds__(256) void dist_norm_kernel(const uint16_t *__restrict__ h, int T, int d,
+                                                        float *__restrict__ norms, int n_pad) {
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (t >= n_pad) return;
+    float acc = 0.f;
+    if (t < T) {
+        const uint4 *row = reinterpret_cast<const uint4 *>(h + (size_t)t * d);
+        for (int c = lane; c < (d >> 3); c += 64) {
+            const uint4 v = row[c];
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float lo = __builtin_bit_cast(float, w[q] << 16);
+                const float hi = __builtin_bit_cast(float, w[q] & 0xFFFF0000u);
+                acc += lo * lo;
+                acc += hi * hi;
+            }
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+    if (lane == 0) norms[t] = acc;   // rows of the padding up to whole tiles get 0
+}
+
+constexpr int kDistRowTiles = 4;   // token tiles (32 rows) of operand A per workgroup: 128 rows i
+constexpr int kDistColTiles = 8;   // token tiles of operand B per workgroup: 256 columns j
+
+// grid (column blocks, row blocks); xp = packed tokens [tile][d/16][1 KiB]
+__global__ __launch_bounds__(256, 2) void dist_tile_kernel(const uint4 *__restrict__ xp,
+                                                           const float *__restrict__ norms, int T, int d,
+                                                           float *__restrict__ part, int t_pad,
+                                                           int n_rowblk) {
+    const int JB = blockIdx.x, IB = blockIdx.y;
+    if (IB > 2 * JB + 1) return;   // every row of the block is >= every column: no pair i < j
+    const int ntiles = (T + kTile - 1) / kTile;
+    const int nkb = d >> 4;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int it0 = IB * kDistRowTiles + (wave >> 1) * 2;    // 2 row tiles of this wave
+    const int jt0 = JB * kDistColTiles + (wave & 1) * 4;     // 4 column tiles of this wave
+    const uint4 *a_src[2], *b_src[4];
+#pragma unroll
+    for (int a = 0; a < 2; ++a) a_src[a] = xp + (size_t)min(it0 + a, ntiles - 1) * nkb * 64 + lane;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) b_src[b] = xp + (size_t)min(jt0 + b, ntiles - 1) * nkb * 64 + lane;
+
+    floatx16 acc[2][4];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) zero16(acc[a][b]);
+
+    // two register stages of two k-steps each; the prefetch is unconditional (clamped, in bounds)
+    constexpr int UNR = 2;
+    u32x4_t fa0[2][UNR], fb0[4][UNR], fa1[2][UNR], fb1[4][UNR];
+#define EF_DIST_LOAD(fa, fb, kb)                                                                          \
+    {                                                                                                     \
+        _Pragma("unroll") for (int u = 0; u < UNR; ++u) {                                                 \
+            const int kk_ = min((kb) + u, nkb - 1);                                                       \
+            _Pragma("unroll") for (int a = 0; a < 2; ++a)                                                 \
+                fa[a][u] = *reinterpret_cast<const u32x4_t *>(a_src[a] + (size_t)kk_ * 64);               \
+            _Pragma("unroll") for (int b = 0; b < 4; ++b)                                                 \
+                fb[b][u] = *reinterpret_cast<const u32x4_t *>(b_src[b] + (size_t)kk_ * 64);               \
+        }                                                                                                 \
+    }
+#define EF_DIST_MMA(fa, fb, kb)                                                                           \
+    {                                                                                                     \
+        _Pragma("unroll") for (int u = 0; u < UNR; ++u)                                                   \
+            if ((kb) + u < nkb) {                                                                         \
+                _Pragma("unroll") for (int a = 0; a < 2; ++a)                                             \
+                    _Pragma("unroll") for (int b = 0; b < 4; ++b)                                         \
+                        acc[a][b] = mfma32v(fa[a][u], fb[b][u], acc[a][b]);                               \
+            }                                                                                             \
+    }
+    EF_DIST_LOAD(fa0, fb0, 0)
+    for (int kb = 0; kb < nkb; kb += 2 * UNR) {
+        EF_DIST_LOAD(fa1, fb1, kb + UNR)
+        EF_DIST_MMA(fa0, fb0, kb)
+        EF_DIST_LOAD(fa0, fb0, kb + 2 * UNR)
+        EF_DIST_MMA(fa1, fb1, kb + UNR)
+    }
+#undef EF_DIST_LOAD
+#undef EF_DIST_MMA
+
+    // accumulator lane l holds column l%32 and rows 8*(v/4) + 4*(l/32) + v%4: the sum over the
+    // wave's 64 rows of one column is 32 in-lane adds and one exchange between the lane halves
+    const int g = lane >> 5, c = lane & 31;
+    const int rowblk = IB * 2 + (wave >> 1);   // 64-row block of the partials
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const int j = (jt0 + b) * kTile + c;
+        const float nj = j < T ? norms[j] : 0.f;
+        float sum = 0.f;
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int i = (it0 + a) * kTile + 8 * (v >> 2) + 4 * g + (v & 3);
+                if (i < j && j < T) {
+                    const float sq = norms[i] + nj - 2.f * acc[a][b][v];
+                    sum += __builtin_sqrtf(fmaxf(sq, 0.f));
+                }
+            }
+        }
+        sum += __shfl_xor(sum, 32);
+        if (g == 0 && j < t_pad && rowblk < n_rowblk) part[(size_t)rowblk * t_pad + j] = sum;
+    }
+}
+
+// s[j] = partials of row blocks 0 .. j/64 in ascending order; workgroup sum in fp64 by a fixed tree
+__global__ __launch_bounds__(256) void dist_reduce_kernel(const float *__restrict__ part, int T, int t_pad,
+                                                          float *__restrict__ tok_dist,
+                                                          double *__restrict__ wg_sums) {
+    __shared__ double red[256];
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    double s = 0.0;
+    if (j < T) {
+        for (int rb = 0; rb <= (j >> 6); ++rb) s += (double)part[(size_t)rb * t_pad + j];
+        if (tok_dist) tok_dist[j] = (float)s;
+    }
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int off = 128; off >= 1; off >>= 1) {
+        if (threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) wg_sums[blockIdx.x] = red[0];
+}
+
+__global__ __launch_bounds__(64) void dist_final_kernel(const double *__restrict__ wg_sums, int n,
+                                                        double *__restrict__ dist) {
+    if (threadIdx.x != 0) return;
+    double s = 0.0;
+    for (int i = 0; i < n; ++i) s += wg_sums[i];
+    *dist = s;
+}
+
+size_t dist_scratch_floats(int T) {
+    const int t_pad = ((T + kTile - 1) / kTile) * kTile;
+    const int n_rowblk = (T + 63) / 64;
+    const int n_wg = (T + 255) / 256;
+    return (size_t)t_pad + (size_t)n_rowblk * t_pad + 2 * (size_t)n_wg + 2;
+}
+
+hipError_t launch_token_dist(const uint16_t *h, int T, int d, const void *xp, float *scratch, float *tok_dist,
+                             double *dist, hipStream_t s) {
+    if (T <= 0 || d % 64 != 0) return hipErrorInvalidValue;
+    const int ntiles = (T + kTile - 1) / kTile;
+    const int t_pad = ntiles * kTile;
+    const int n_rowblk = (T + 63) / 64;
+    const int n_wg = (T + 255) / 256;
+    float *norms = scratch;
+    float *part = scratch + t_pad;
+    // 8-byte aligned slot for the workgroup sums behind the partials
+    size_t off = (size_t)t_pad + (size_t)n_rowblk * t_pad;
+    off += off & 1;
+    double *wg_sums = reinterpret_cast<double *>(scratch + off);
+    hipLaunchKernelGGL(dist_norm_kernel, dim3((t_pad + 3) / 4), dim3(256), 0, s, h, T, d, norms, t_pad);
+    const int nJB = (ntiles + kDistColTiles - 1) / kDistColTiles;
+    const int nIB = (ntiles + kDistRowTiles - 1) / kDistRowTiles;
+    hipLaunchKernelGGL(dist_tile_kernel, dim3(nJB, nIB), dim3(256), 0, s, reinterpret_cast<const uint4 *>(xp),
+                       norms, T, d, part, t_pad, n_rowblk);
+    hipLaunchKernelGGL(dist_reduce_kernel, dim3(n_wg), dim3(256), 0, s, part, T, t_pad, tok_dist, wg_sums);
+    hipLaunchKernelGGL(dist_final_kernel, dim3(1), dim3(64), 0, s, wg_sums, n_wg, dist);
+    return hipGetLastError();
+}
+
+}  // namespace ef

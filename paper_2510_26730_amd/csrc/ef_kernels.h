@@ -82,6 +82,11 @@ hipError_t launch_ffn_down(const GroupTable &gt, int total_wgs, int tiles_per_pa
 hipError_t launch_combine(const float *y, int ksg, long long y_plane, const float *w, const int32_t *inv_perm,
                           int T, int k, int d, long long shared_row0, float *out, hipStream_t s);
 
+// Dist(t): scratch floats launch_token_dist needs for T tokens (norms, partials, workgroup sums)
+size_t dist_scratch_floats(int T);
+hipError_t launch_token_dist(const uint16_t *h, int T, int d, const void *xp, float *scratch, float *tok_dist,
+                             double *dist, hipStream_t s);
+
 hipError_t launch_ffn_gate_up_tiled(const GroupTable &gt, int total_wgs, const void *xp, void *act, int d,
                                     hipStream_t s);
 hipError_t launch_ffn_down_tiled(const GroupTable &gt, int total_wgs, const void *act, float *y, int d,
