@@ -55,6 +55,9 @@ struct ef_ctx {
     // scratch
     int32_t *blockcounts = nullptr, *blockbase = nullptr;
     void *xp = nullptr, *act = nullptr;
+    float *gate_part = nullptr;      // partial logits of K-split gate launches (small batches)
+    bool prepacked = false;          // ef_layer_step already enqueued the token packing of the coming ef_moe_ffn
+    size_t gate_part_floats = 0;
     float *y = nullptr;
     long long y_floats = 0;          // capacity of y: several K-slice planes when the batch is small
     int max_tiles = 0;
@@ -374,6 +377,7 @@ extern "C" int ef_destroy(ef_ctx *c) {
         if (c->blockcounts) (void)hipFree(c->blockcounts);
         if (c->blockbase) (void)hipFree(c->blockbase);
         if (c->xp) (void)hipFree(c->xp);
+        if (c->gate_part) (void)hipFree(c->gate_part);
         if (c->act) (void)hipFree(c->act);
         if (c->y) (void)hipFree(c->y);
         for (void *p : {(void *)c->st_ids, (void *)c->st_counts, (void *)c->st_offsets, (void *)c->st_perm,
@@ -453,6 +457,8 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
     if ((e = hipMalloc(&c->blockcounts, (size_t)ntile_tok * E * 4)) != hipSuccess) return bail(e, "blockcounts");
     if ((e = hipMalloc(&c->blockbase, (size_t)ntile_tok * E * 4)) != hipSuccess) return bail(e, "blockbase");
     if ((e = hipMalloc(&c->xp, xp_bytes)) != hipSuccess) return bail(e, "packed-token scratch");
+    c->gate_part_floats = (size_t)2 << 20;   // 8 MiB: 64 workgroups x 32 rows x 128 columns x 8 launches' worth
+    if ((e = hipMalloc(&c->gate_part, c->gate_part_floats * 4)) != hipSuccess) return bail(e, "gate partials");
     if ((e = hipMalloc(&c->act, act_bytes)) != hipSuccess) return bail(e, "activation scratch");
     if ((e = hipMalloc(&c->y, y_bytes)) != hipSuccess) return bail(e, "expert-output scratch");
 
@@ -581,6 +587,14 @@ int run_gates(ef_ctx *c, int layer, const void *hidden, int T, float beta, bool 
             }
         }
         a.gpw = ef::gate_pick_gpw(T, a.G, E);
+        a.ksplit = ef::gate_pick_ksplit(T, d, a.G, E, a.gpw, c->gate_part_floats);
+        {
+            const int forced = tune("EF_TUNE_GATE_KSPLIT", 0);
+            if (forced >= 1 && forced <= 16 &&
+                (size_t)ntiles * ((a.G + a.gpw - 1) / a.gpw) * forced * ef::kTile * 128 <= c->gate_part_floats)
+                a.ksplit = forced;
+        }
+        a.part = c->gate_part;
         const bool has_route = do_route && g0 == 0;
         {
             KernelTimer kt(c, s, has_route ? EF_K_ROUTE : EF_K_PREDICT,
@@ -744,14 +758,14 @@ struct PhaseGroup {
 int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, const int32_t *counts_host,
                  const std::vector<int> &offs_host, const std::vector<int> &tile_start,
                  const std::vector<long long> &act_off, int shared_tile_start, long long shared_act_off, int T,
-                 int ksg, long long y_plane, hipStream_t s) {
+                 int ksg, long long y_plane, bool use_tiled, hipStream_t s) {
     if (groups.empty()) return EF_OK;
     const int d = c->cfg.d_model, k = c->cfg.top_k;
     // groups with many tokens go to the tiled (matrix-core bound) kernels, the others to the
     // weight-streaming kernels; at most two launches per FFN half
     ef::GroupTable gu{}, big{};
     int n = 0, nb = 0, max_tiles = 1;
-    const bool allow_tiled = tune("EF_TUNE_TILED", 1) != 0 && ksg == 1;
+    const bool allow_tiled = use_tiled && ksg == 1;
     for (const PhaseGroup &pg : groups) {
         int cnt, ts, F, ro;
         long long ao;
@@ -845,6 +859,9 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
 extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const int32_t *topk_ids,
                           const float *topk_w, const int32_t *counts_host, const int32_t *offsets,
                           const int32_t *perm, const int32_t *inv_perm, float *out, void *stream) {
+    // set by ef_layer_step for the call it makes right afterwards; never survives this call
+    const bool prepacked = c && c->prepacked;
+    if (c) c->prepacked = false;
     int rc = check_ctx_layer(c, layer);
     if (rc) return rc;
     if (T < 0 || T > c->cfg.max_tokens) return fail(c, EF_EINVAL, "ef_moe_ffn: T=%d outside 0..max_tokens", T);
@@ -886,6 +903,23 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
     // split while the layer's launch would have too few workgroups, a slice keeps >= 32 fragments per
     // wave and the planes fit the scratch.  One value per call: every phase shares the planes.
     const long long y_plane = ((long long)T * k + (has_shared ? T : 0)) * d;
+    // Groups of at least 8 token tiles go to the matrix-core tiled kernels.  The two thresholds (total
+    // workgroups of the tiled launches) exist for tuning only: on the mixed batches measured (640 tokens
+    // with a 2048 x 5632 shared expert, 1056 tokens over 64 experts) the tiled kernels were equal to or
+    // 8 % faster than streaming the same groups in several passes, even at 150-200 workgroups.
+    bool use_tiled = false;
+    if (T > 0 && tune("EF_TUNE_TILED", 1) != 0) {
+        long long wg_up = 0, wg_dn = 0;
+        auto add = [&](int F, int cnt) {
+            const int nt = (cnt + ef::kTile - 1) / ef::kTile;
+            if (!ef::ffn_tiled_ok(d, F, nt)) return;
+            wg_up += ef::ffn_gate_up_tiled_wgs(F, nt);
+            wg_dn += ef::ffn_down_tiled_wgs(d, nt);
+        };
+        for (int e = 0; e < E; ++e) add(c->cfg.d_ff, counts_host[e]);
+        if (has_shared) add(c->cfg.d_ff_shared, T);
+        use_tiled = wg_up >= tune("EF_TUNE_TILED_MIN_UP", 1) && wg_dn >= tune("EF_TUNE_TILED_MIN_DOWN", 1);
+    }
     int ksg = 1;
     if (T > 0) {
         long long base_wgs = 0;
@@ -902,9 +936,7 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         while (ksg < 8 && base_wgs * ksg < want && nkb_min / (ksg * 2 * 4) >= 32 &&
                y_plane * (ksg * 2) <= c->y_floats)
             ksg *= 2;
-        for (int e = 0; e < E; ++e)   // the tiled kernels write plane 0 only
-            if (ef::ffn_tiled_ok(d, c->cfg.d_ff, (counts_host[e] + ef::kTile - 1) / ef::kTile)) ksg = 1;
-        if (has_shared && ef::ffn_tiled_ok(d, c->cfg.d_ff_shared, (T + ef::kTile - 1) / ef::kTile)) ksg = 1;
+        if (use_tiled) ksg = 1;   // the tiled kernels write plane 0 only
         int forced = tune("EF_TUNE_DOWN_KSG", ksg);
         if (forced >= 1 && forced <= 8 && y_plane * forced <= c->y_floats) ksg = forced;
     }
@@ -992,14 +1024,14 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         if (with_shared && has_shared) g.push_back({-1, -1});
         if (!c->fake) {
             int r = launch_phase(c, layer, g, counts_host, offs_host, tile_start, act_off, shared_tile_start,
-                                 shared_act_off, T, ksg, y_plane, s);
+                                 shared_act_off, T, ksg, y_plane, use_tiled, s);
             if (r) return r;
         }
         return mark_read(v);
     };
 
     if (T > 0) {
-        if (!c->fake) {
+        if (!c->fake && !prepacked) {
             // token permutation into per-expert tiles (all groups of this layer in one launch)
             ef::PackTable pt{};
             int n = 0;
@@ -1149,6 +1181,21 @@ extern "C" int ef_layer_step(ef_ctx *c, int layer, const void *hidden, int T, fl
     rc = run_gates(c, layer, hidden, T, beta, true, He, H, delta, tok2req, c->st_ids, c->st_w, c->st_counts,
                    c->st_offsets, c->st_perm, c->st_inv, c->st_pred_ids, c->st_pred_hist, ex, s);
     if (rc) return rc;
+    // the token packing only needs what the grouping kernel left on the device: enqueue it now, so it
+    // runs while the host waits for and digests the counts
+    bool did_pack = false;
+    if (tune("EF_TUNE_EARLY_PACK", 1) != 0) {
+        const int k = c->cfg.top_k, d = c->cfg.d_model;
+        const bool has_shared = c->cfg.d_ff_shared > 0;
+        const long long assignments = (long long)T * k;
+        const int bound = (int)((assignments + ef::kTile - 1) / ef::kTile) + (int)std::min<long long>(E, assignments) +
+                          (has_shared ? (T + ef::kTile - 1) / ef::kTile : 0);
+        const long long rows = assignments + (has_shared ? T : 0);
+        KernelTimer kt(c, s, EF_K_PACK, 4.0 * rows * d + 4.0 * T * k);
+        EF_HIP(c, ef::launch_pack_x_dev(c->st_counts, c->st_offsets, E, has_shared, T, std::min(bound, c->max_tiles),
+                                        static_cast<const uint16_t *>(hidden), d, k, c->st_perm, c->xp, s));
+        did_pack = true;
+    }
     // 2. wait for the flag (bounded: fall back to a stream synchronisation, then give up)
     volatile int32_t *flag = c->meta_host + ef::kMetaFlag;
     bool seen = false;
@@ -1180,6 +1227,7 @@ extern "C" int ef_layer_step(ef_ctx *c, int layer, const void *hidden, int T, fl
     }
     if (H_next) *H_next = Hn;
     // 4. grouped FFN: resident groups first, misses swapped in meanwhile, weighted un-permute
+    c->prepacked = did_pack;
     return ef_moe_ffn(c, layer, hidden, T, c->st_ids, c->st_w, counts_host, c->st_offsets, c->st_perm, c->st_inv,
                       out, stream);
 }

@@ -50,6 +50,61 @@ hipError_t launch_pack_x(const PackTable &pt, int total_tiles, const uint16_t *h
     return hipGetLastError();
 }
 
+// The same packing planned on the device: the tile -> (group, local tile) table is derived from the
+// per-expert counts the grouping kernel left in device memory (experts in id order, 32-row tiles,
+// the dense shared FFN last), so the launch needs nothing from the host and can be enqueued
+// before the host has read the counts.  grid.x is an upper bound of the tile count; surplus
+// workgroups exit.
+__global__ __launch_bounds__(256) void pack_x_dev_kernel(const int32_t *__restrict__ counts,
+                                                         const int32_t *__restrict__ offsets, int E, int has_shared,
+                                                         int T, const uint16_t *__restrict__ h, int d, int k,
+                                                         const int32_t *__restrict__ perm, uint4 *__restrict__ xp,
+                                                         int kb_per_wg) {
+    const int tile = blockIdx.x;
+    int first = 0, grp = -1;
+    for (int e = 0; e < E; ++e) {
+        const int nt = (counts[e] + kTile - 1) / kTile;
+        if (tile < first + nt) { grp = e; break; }
+        first += nt;
+    }
+    int count, row_offset;
+    if (grp >= 0) {
+        count = counts[grp];
+        row_offset = offsets[grp];
+    } else {
+        if (!has_shared || tile - first >= (T + kTile - 1) / kTile) return;
+        count = T;
+        row_offset = -1;
+    }
+    const int local = tile - first;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int g = lane >> 5, i = lane & 31;
+    const int r = local * kTile + i;
+    const bool valid = r < count;
+    int token = 0;
+    if (valid) token = row_offset < 0 ? r : perm[row_offset + r] / k;
+    const uint4 *src = reinterpret_cast<const uint4 *>(h + (size_t)token * d);
+    const int nkb = d >> 4;
+    uint4 *dst = xp + (size_t)tile * nkb * 64 + lane;
+    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    const int kb0 = blockIdx.y * kb_per_wg;
+    const int kb1 = min(nkb, kb0 + kb_per_wg);
+    for (int kb = kb0 + wave; kb < kb1; kb += 4) dst[(size_t)kb * 64] = valid ? src[kb * 2 + g] : zero4;
+}
+
+hipError_t launch_pack_x_dev(const int32_t *counts, const int32_t *offsets, int E, bool has_shared, int T,
+                             int max_tiles, const uint16_t *h, int d, int k, const int32_t *perm, void *xp,
+                             hipStream_t s) {
+    if (max_tiles <= 0) return hipSuccess;
+    const int nkb = d >> 4;
+    int chunks = 1;
+    while (max_tiles * chunks < 1024 && nkb / (chunks * 2) >= 8) chunks *= 2;
+    const int kb_per_wg = (nkb + chunks - 1) / chunks;
+    hipLaunchKernelGGL(pack_x_dev_kernel, dim3(max_tiles, chunks), dim3(256), 0, s, counts, offsets, E,
+                       has_shared ? 1 : 0, T, h, d, k, perm, reinterpret_cast<uint4 *>(xp), kb_per_wg);
+    return hipGetLastError();
+}
+
 // K loop of the first FFN half for NTL live token tiles: three register stages of UNR fragments per
 // operand; stages c+1 and c+2 are in flight while stage c feeds the matrix cores.  Every load is
 // unconditional (the last prefetch re-reads the final stage, in bounds).

@@ -32,6 +32,8 @@ struct GateArgs {
     int32_t *hist[kMaxGates];      // per gate: [E] accumulated with integer atomics, or null
     int32_t *blockcounts;          // [ntiles,E] per-tile counts of gate 0, or null
     int gpw;                       // gates per workgroup (gpw * E <= 128 logit columns)
+    int ksplit;                    // workgroups that share the K range of one (tile, gate group); >= 1
+    float *part;                   // ksplit > 1: [tiles][groups][ksplit][32][32 * column blocks] partial logits
 };
 
 // Grouped FFN launch: one group per active expert (+ one for the dense shared FFN).
@@ -69,12 +71,16 @@ struct PackTable {
 
 hipError_t launch_fill_i32(int32_t *p, int n, int32_t v, hipStream_t s);
 int gate_pick_gpw(int T, int G, int E);
+int gate_pick_ksplit(int T, int d, int G, int E, int gpw, size_t part_floats);
 hipError_t launch_gate(const GateArgs &a, hipStream_t s);
 hipError_t launch_group(const int32_t *blockcounts, const int32_t *ids, int T, int k, int E, int32_t *blockbase,
                         int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
                         const GroupExport &ex, hipStream_t s);
 hipError_t launch_pack_x(const PackTable &pt, int total_tiles, const uint16_t *h, int d, int k,
                          const int32_t *perm, void *xp, hipStream_t s);
+hipError_t launch_pack_x_dev(const int32_t *counts, const int32_t *offsets, int E, bool has_shared, int T,
+                             int max_tiles, const uint16_t *h, int d, int k, const int32_t *perm, void *xp,
+                             hipStream_t s);
 hipError_t launch_ffn_gate_up(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ks, const void *xp,
                               void *act, int d, hipStream_t s);
 hipError_t launch_ffn_down(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ksg, const void *act,

@@ -34,6 +34,7 @@ hipError_t launch_fill_i32(int32_t *p, int n, int32_t v, hipStream_t s) {
 // while the eight waves run their share of the MFMA steps of the current one from LDS.
 // ------------------------------------------------------------------------------------------
 constexpr int kGateWaves = 8;
+constexpr int kGateMaxSplit = 16;   // K splits of one (tile, gate group) across workgroups
 
 // arr[idx] of a by-value kernel-argument array without forcing the struct into scratch memory
 template <class T>
@@ -44,6 +45,11 @@ __device__ __forceinline__ T pick(const T (&arr)[kMaxGates], int idx) {
         if (idx == q) v = arr[q];
     return v;
 }
+
+template <int NB>
+__device__ __forceinline__ void gate_epilogue(const GateArgs &a, float (*logits)[NB * 32 + 1], int *cnt,
+                                              const float *sbias, float (*s_sc)[64], float (*s_z)[64],
+                                              int tile, int g0, int Gl);
 
 template <int NB>
 __global__ __launch_bounds__(64 * kGateWaves) void gate_kernel(GateArgs a) {
@@ -122,11 +128,15 @@ __global__ __launch_bounds__(64 * kGateWaves) void gate_kernel(GateArgs a) {
             rb[p][r] = *reinterpret_cast<const u32x4_t *>(bsrc[r] + min(col, a.d - 8));                \
         }                                                                                              \
     }
-    const int sbeg = 0, nstage = (a.d + KC - 1) / KC;
+    // K split across workgroups (grid.z) for batches of few token tiles: each workgroup takes a
+    // contiguous range of panels and leaves its partial logits to gate_finish_kernel
+    const int nstage_all = (a.d + KC - 1) / KC;
+    const int per_split = (nstage_all + a.ksplit - 1) / a.ksplit;
+    const int sbeg = blockIdx.z * per_split, nstage = min(nstage_all, sbeg + per_split);
     // prefetches are unconditional (past the end they re-read the last panel, in bounds) so that the
     // number of loads in flight is known at compile time and only the oldest panel is waited for
 #pragma unroll
-    for (int p = 0; p < PF; ++p) EF_GATE_GLOAD(p, min(sbeg + p, nstage - 1))
+    for (int p = 0; p < PF; ++p) EF_GATE_GLOAD(p, max(min(sbeg + p, nstage - 1), 0))
     for (int st0 = sbeg; st0 < nstage; st0 += PF) {
 #pragma unroll
         for (int p = 0; p < PF; ++p) {
@@ -145,7 +155,7 @@ __global__ __launch_bounds__(64 * kGateWaves) void gate_kernel(GateArgs a) {
                     *reinterpret_cast<u32x4_t *>(&Bs[(idx / C4) * LDK + (idx % C4) * 8]) = ok ? rb[p][r] : zero4v;
                 }
                 __syncthreads();
-                EF_GATE_GLOAD(p, min(st + PF, nstage - 1))
+                EF_GATE_GLOAD(p, max(min(st + PF, nstage - 1), 0))
 #pragma unroll
                 for (int q = 0; q < KSW; ++q) {
                     const int kcol = (wave * KSW + q) * 16 + 8 * g;
@@ -178,7 +188,25 @@ __global__ __launch_bounds__(64 * kGateWaves) void gate_kernel(GateArgs a) {
         __syncthreads();
     }
 
-    // per-token epilogue.  A sub-group of W lanes (W = power of two >= E) owns one token; a wave
+    if (a.ksplit > 1) {   // partial logits of this K range: [tile][group][split][32][NB*32]
+        float *dst = a.part + ((((size_t)tile * gridDim.y + blockIdx.y) * a.ksplit + blockIdx.z) * kTile) * (NB * 32);
+        for (int x = tid; x < kTile * NB * 32; x += NT) dst[x] = logits[x / (NB * 32)][x % (NB * 32)];
+        return;
+    }
+    gate_epilogue<NB>(a, logits, cnt, sbias, s_sc, s_z, tile, g0, Gl);
+}
+
+// per-token part of the gate kernels: selection scores, biased top-k, combine weights, counts.
+// `logits` holds the tile's router logits without the gate bias (sbias), `cnt` is zeroed.
+template <int NB>
+__device__ __forceinline__ void gate_epilogue(const GateArgs &a, float (*logits)[NB * 32 + 1], int *cnt,
+                                              const float *sbias, float (*s_sc)[64], float (*s_z)[64],
+                                              int tile, int g0, int Gl) {
+    constexpr int NW = kGateWaves, NT = 64 * NW;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int t0 = tile * kTile;
+    const int N = Gl * a.E;
+    // A sub-group of W lanes (W = power of two >= E) owns one token; a wave
     // handles 64/W tokens of ONE gate per round (the gate index is wave-uniform, so per-gate
     // arguments are scalar loads).  Selection is by rank: lane e counts, from an LDS copy of the
     // token's scores, how many experts beat it (greater score, or equal score and lower id); the k
@@ -269,12 +297,67 @@ __global__ __launch_bounds__(64 * kGateWaves) void gate_kernel(GateArgs a) {
     }
 }
 
+// second step of the K-split form: adds the partial logits of the splits in ascending order
+// (fixed, so results do not depend on scheduling) and runs the per-token epilogue
+template <int NB>
+__global__ __launch_bounds__(64 * kGateWaves) void gate_finish_kernel(GateArgs a) {
+    constexpr int NW = kGateWaves, NT = 64 * NW;
+    __shared__ float logits[kTile][NB * 32 + 1];
+    __shared__ int cnt[4 * 32];
+    __shared__ float sbias[4 * 32];
+    __shared__ __attribute__((aligned(16))) float s_sc[NW][64];
+    __shared__ __attribute__((aligned(16))) float s_z[NW][64];
+    const int tid = threadIdx.x;
+    const int tile = blockIdx.x;
+    const int g0 = blockIdx.y * a.gpw;
+    const int Gl = min(a.gpw, a.G - g0);
+    const int N = Gl * a.E;
+    for (int x = tid; x < NB * 32; x += NT) cnt[x] = 0;
+    for (int x = tid; x < N; x += NT) {
+        const float *bp = pick(a.bias, g0 + x / a.E);
+        sbias[x] = bp ? bp[x % a.E] : 0.f;
+    }
+    const float *src = a.part + (((size_t)tile * gridDim.y + blockIdx.y) * a.ksplit * kTile) * (NB * 32);
+    for (int x = tid; x < kTile * NB * 32; x += NT) {
+        float pz[kGateMaxSplit];   // all loads first (one latency), then the adds in split order
+#pragma unroll
+        for (int z = 0; z < kGateMaxSplit; ++z)
+            pz[z] = z < a.ksplit ? src[(size_t)z * kTile * NB * 32 + x] : 0.f;
+        float v = 0.f;
+#pragma unroll
+        for (int z = 0; z < kGateMaxSplit; ++z) v += pz[z];
+        logits[x / (NB * 32)][x % (NB * 32)] = v;
+    }
+    __syncthreads();
+    gate_epilogue<NB>(a, logits, cnt, sbias, s_sc, s_z, tile, g0, Gl);
+}
+
 template <int NB>
 static hipError_t launch_gate_nb(const GateArgs &a, hipStream_t s) {
     const int ntiles = (a.T + kTile - 1) / kTile;
     const int ngroups = (a.G + a.gpw - 1) / a.gpw;
-    hipLaunchKernelGGL((gate_kernel<NB>), dim3(ntiles, ngroups), dim3(64 * kGateWaves), 0, s, a);
+    hipLaunchKernelGGL((gate_kernel<NB>), dim3(ntiles, ngroups, a.ksplit), dim3(64 * kGateWaves), 0, s, a);
+    if (a.ksplit > 1)
+        hipLaunchKernelGGL((gate_finish_kernel<NB>), dim3(ntiles, ngroups), dim3(64 * kGateWaves), 0, s, a);
     return hipGetLastError();
+}
+
+// K splits of a gate launch: batches of few token tiles are bound by the latency of walking d in
+// panels inside one workgroup (the hidden states and gate rows are cold in L2 after the expert
+// weights of the previous layer streamed through, and only four panels are in flight), so the
+// panels are dealt to several workgroups per (tile, group), four panels each (one round trip),
+// whose partial logits a second, short kernel adds up.  `part_floats` is the scratch available.
+int gate_pick_ksplit(int T, int d, int G, int E, int gpw, size_t part_floats) {
+    const int ntiles = (T + kTile - 1) / kTile;
+    const int ngroups = (G + gpw - 1) / gpw;
+    const int nb = (std::min(gpw, G) * E + 31) / 32;
+    const int kc = nb == 1 ? 256 : 128;
+    const int nstage = (d + kc - 1) / kc;
+    int ks = 1;
+    while (ks < kGateMaxSplit && nstage / (ks * 2) >= 4 && ntiles * ngroups * ks < 64 &&
+           (size_t)ntiles * ngroups * (ks * 2) * kTile * nb * 32 <= part_floats)
+        ks *= 2;
+    return ks;
 }
 
 // gates per workgroup: up to 128 logit columns; one 32-column block when there are few token
@@ -291,6 +374,7 @@ int gate_pick_gpw(int T, int G, int E) {
 hipError_t launch_gate(const GateArgs &a, hipStream_t s) {
     if (a.T <= 0 || a.G <= 0) return hipSuccess;
     if (a.gpw < 1 || a.gpw * a.E > 128 || a.G > kMaxGates) return hipErrorInvalidValue;
+    if (a.ksplit < 1 || (a.ksplit > 1 && !a.part)) return hipErrorInvalidValue;
     const int nb = (std::min(a.gpw, a.G) * a.E + 31) / 32;
     switch (nb) {
         case 1: return launch_gate_nb<1>(a, s);

@@ -284,9 +284,15 @@ def test_full_size_mixtral_decode_layer(oracle_mod):
         st.close()
 
 
-def test_full_size_qwen_mixed_batch(oracle_mod):
+@pytest.mark.parametrize("force_tiled", [True, False])
+def test_full_size_qwen_mixed_batch(oracle_mod, monkeypatch, force_tiled):
+    """T = 640 with a shared expert of 20 token tiles: through the matrix-core tiled kernels (the
+    default for groups of at least 8 tiles) and, with the library's workgroup threshold raised,
+    through the weight-streaming kernels in several passes."""
     cfg = synth.CONFIGS["qwen15_moe"]
-    say("full size: Qwen1.5-MoE-shaped layer, T=640, shared expert")
+    if not force_tiled:
+        monkeypatch.setenv("EF_TUNE_TILED_MIN_UP", "1000000")
+    say(f"full size: Qwen1.5-MoE-shaped layer, T=640, shared expert, tiled kernels forced: {force_tiled}")
     st = LayerStack(cfg, 1, slots_total=cfg.E, max_tokens=640)
     try:
         res = synth.residency(cfg, 0)
