@@ -36,6 +36,12 @@ hipError_t launch_fill_i32(int32_t *p, int n, int32_t v, hipStream_t s) {
 constexpr int kGateWaves = 8;
 constexpr int kGateMaxSplit = 16;   // K splits of one (tile, gate group) across workgroups
 
+// orders the LDS writes of a wave before its later LDS reads (other lanes' data of the same wave)
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 // arr[idx] of a by-value kernel-argument array without forcing the struct into scratch memory
 template <class T>
 __device__ __forceinline__ T pick(const T (&arr)[kMaxGates], int idx) {
@@ -60,8 +66,14 @@ __global__ __launch_bounds__(64 * kGateWaves) void gate_kernel(GateArgs a) {
     constexpr int A_PER = 32 * C4 / NT;                // 16-byte loads per thread per panel
     constexpr int B_PER = NB * 32 * C4 / NT;
     constexpr int KSW = KC / 16 / NW;                  // MFMA k-steps per wave per panel
-    __shared__ __attribute__((aligned(16))) uint16_t As[32 * LDK];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[NB * 32 * LDK];
+    // operand panels; after the K loop the same memory holds the partial tiles of the wave reduction
+    constexpr int PANEL_BYTES = (1 + NB) * 32 * LDK * 2;
+    constexpr int RED_FLOATS = NB * 16 * 64;           // one wave's partial tile
+    constexpr int RED_BYTES = (NW / 2) * RED_FLOATS * 4;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[PANEL_BYTES > RED_BYTES ? PANEL_BYTES : RED_BYTES];
+    uint16_t *As = reinterpret_cast<uint16_t *>(smem);
+    uint16_t *Bs = As + 32 * LDK;
+    float *red = reinterpret_cast<float *>(smem);
     __shared__ float logits[kTile][NB * 32 + 1];
     __shared__ int cnt[4 * 32];
     __shared__ float sbias[4 * 32];
@@ -173,20 +185,39 @@ __global__ __launch_bounds__(64 * kGateWaves) void gate_kernel(GateArgs a) {
 
 #undef EF_GATE_GLOAD
 
-    // fixed-order reduction of the waves' partials (wave 0, 1, 2, ...) through LDS
-    for (int w = 0; w < NW; ++w) {
-        if (wave == w) {
+    // fixed-order tree over the waves' partial tiles through LDS: (w, w+4), then (w, w+2), then
+    // (0, 1); the last barrier of the K loop has retired every read of the operand panels
+    static_assert(NW == 8, "the reduction tree below is written for eight waves");
+    auto put = [&](int region) {
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    int row = 8 * (v >> 2) + 4 * g + (v & 3);
-                    if (w == 0) logits[row][nb * 32 + i] = acc[nb][v];
-                    else logits[row][nb * 32 + i] += acc[nb][v];
-                }
-        }
-        __syncthreads();
+            for (int v = 0; v < 16; ++v) red[region * RED_FLOATS + (nb * 16 + v) * 64 + lane] = acc[nb][v];
+    };
+    auto add = [&](int region) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[nb][v] += red[region * RED_FLOATS + (nb * 16 + v) * 64 + lane];
+    };
+    if (wave >= 4) put(wave - 4);
+    __syncthreads();
+    if (wave < 4) add(wave);
+    __syncthreads();
+    if (wave == 2 || wave == 3) put(wave - 2);
+    __syncthreads();
+    if (wave < 2) add(wave);
+    __syncthreads();
+    if (wave == 1) put(0);
+    __syncthreads();
+    if (wave == 0) {
+        add(0);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) logits[8 * (v >> 2) + 4 * g + (v & 3)][nb * 32 + i] = acc[nb][v];
     }
+    __syncthreads();
 
     if (a.ksplit > 1) {   // partial logits of this K range: [tile][group][split][32][NB*32]
         float *dst = a.part + ((((size_t)tile * gridDim.y + blockIdx.y) * a.ksplit + blockIdx.z) * kTile) * (NB * 32);
@@ -220,7 +251,9 @@ __device__ __forceinline__ void gate_epilogue(const GateArgs &a, float (*logits)
     const bool evalid = e < a.E;
     const float NEG_INF = -__builtin_inff();
 
-    for (int it = 0; it * NW < total_chunks; ++it) {   // same trip count for all waves (barriers inside)
+    // every wave works on its own rows of s_sc / s_z: the exchanges below need ordering inside the
+    // wave only (LDS operations of one wave execute in order), no workgroup barrier
+    for (int it = 0; it * NW < total_chunks; ++it) {
         const int chunk = it * NW + wave;
         const bool cact = chunk < total_chunks;
         const int gl = cact ? chunk / chunks_per_gate : 0;   // gate inside the group
@@ -241,7 +274,7 @@ __device__ __forceinline__ void gate_epilogue(const GateArgs &a, float (*logits)
         }
         s_sc[wave][lane] = sc;
         s_z[wave][lane] = z;
-        __syncthreads();
+        wave_lds_sync();
         const float4 *srow = reinterpret_cast<const float4 *>(&s_sc[wave][sub * W]);
         int rank = 0;
         for (int j = 0; j < W; j += 4) {
@@ -262,9 +295,9 @@ __device__ __forceinline__ void gate_epilogue(const GateArgs &a, float (*logits)
             }
             ex = (live && evalid) ? __expf(z - m) : 0.f;
         }
-        __syncthreads();
+        wave_lds_sync();
         if (want_w) s_z[wave][lane] = ex;
-        __syncthreads();
+        wave_lds_sync();
         const unsigned long long ball = __ballot(sel);
         const unsigned long long submask = (W == 64) ? ball : ((ball >> (sub * W)) & ((1ull << W) - 1ull));
         const int slot = __popcll(submask & ((1ull << e) - 1ull));   // ascending expert id
