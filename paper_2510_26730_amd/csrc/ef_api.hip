@@ -595,6 +595,13 @@ int run_gates(ef_ctx *c, int layer, const void *hidden, int T, float beta, bool 
                 a.ksplit = forced;
         }
         a.part = c->gate_part;
+        a.tsplit = 1;
+        {   // the two-kernel form also pays off without a K split when the per-token part dominates
+            const int ts = ef::gate_pick_tsplit(T, a.G, E, a.gpw);
+            const size_t need = (size_t)ntiles * ((a.G + a.gpw - 1) / a.gpw) * a.ksplit * ef::kTile * 128;
+            if (ts > 1 && need <= c->gate_part_floats && tune("EF_TUNE_GATE_TSPLIT", 1) != 0) a.tsplit = ts;
+        }
+        a.two_step = (a.ksplit > 1 || a.tsplit > 1) ? 1 : 0;
         const bool has_route = do_route && g0 == 0;
         {
             KernelTimer kt(c, s, has_route ? EF_K_ROUTE : EF_K_PREDICT,

@@ -33,7 +33,9 @@ struct GateArgs {
     int32_t *blockcounts;          // [ntiles,E] per-tile counts of gate 0, or null
     int gpw;                       // gates per workgroup (gpw * E <= 128 logit columns)
     int ksplit;                    // workgroups that share the K range of one (tile, gate group); >= 1
-    float *part;                   // ksplit > 1: [tiles][groups][ksplit][32][32 * column blocks] partial logits
+    int two_step;                  // 1: gate_kernel leaves partial logits, gate_finish_kernel does the per-token part
+    int tsplit;                    // two_step: workgroups that share the 32 tokens of a tile in the finish (1, 2, 4)
+    float *part;                   // two_step: [tiles][groups][ksplit][32][32 * column blocks] partial logits
 };
 
 // Grouped FFN launch: one group per active expert (+ one for the dense shared FFN).
@@ -72,6 +74,7 @@ struct PackTable {
 hipError_t launch_fill_i32(int32_t *p, int n, int32_t v, hipStream_t s);
 int gate_pick_gpw(int T, int G, int E);
 int gate_pick_ksplit(int T, int d, int G, int E, int gpw, size_t part_floats);
+int gate_pick_tsplit(int T, int G, int E, int gpw);
 hipError_t launch_gate(const GateArgs &a, hipStream_t s);
 hipError_t launch_group(const int32_t *blockcounts, const int32_t *ids, int T, int k, int E, int32_t *blockbase,
                         int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,

@@ -54,8 +54,8 @@ __device__ __forceinline__ T pick(const T (&arr)[kMaxGates], int idx) {
 
 template <int NB>
 __device__ __forceinline__ void gate_epilogue(const GateArgs &a, float (*logits)[NB * 32 + 1], int *cnt,
-                                              const float *sbias, float (*s_sc)[64], float (*s_z)[64],
-                                              int tile, int g0, int Gl);
+                                              const float *sbias, float (*s_sc)[64],
+                                              int tile, int g0, int Gl, int tok_lo, int tok_n, bool shared_tile);
 
 template <int NB>
 __global__ __launch_bounds__(64 * kGateWaves) void gate_kernel(GateArgs a) {
@@ -78,7 +78,6 @@ __global__ __launch_bounds__(64 * kGateWaves) void gate_kernel(GateArgs a) {
     __shared__ int cnt[4 * 32];
     __shared__ float sbias[4 * 32];
     __shared__ __attribute__((aligned(16))) float s_sc[NW][64];
-    __shared__ __attribute__((aligned(16))) float s_z[NW][64];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = lane >> 5, i = lane & 31;
@@ -219,20 +218,25 @@ __global__ __launch_bounds__(64 * kGateWaves) void gate_kernel(GateArgs a) {
     }
     __syncthreads();
 
-    if (a.ksplit > 1) {   // partial logits of this K range: [tile][group][split][32][NB*32]
+    if (a.two_step) {   // partial logits of this K range: [tile][group][split][32][NB*32]
+        if (a.tsplit > 1 && a.blockcounts && blockIdx.y == 0 && blockIdx.z == 0)   // added to atomically later
+            for (int x = tid; x < a.E; x += NT) a.blockcounts[(size_t)tile * a.E + x] = 0;
         float *dst = a.part + ((((size_t)tile * gridDim.y + blockIdx.y) * a.ksplit + blockIdx.z) * kTile) * (NB * 32);
         for (int x = tid; x < kTile * NB * 32; x += NT) dst[x] = logits[x / (NB * 32)][x % (NB * 32)];
         return;
     }
-    gate_epilogue<NB>(a, logits, cnt, sbias, s_sc, s_z, tile, g0, Gl);
+    gate_epilogue<NB>(a, logits, cnt, sbias, s_sc, tile, g0, Gl, 0, kTile, false);
 }
 
 // per-token part of the gate kernels: selection scores, biased top-k, combine weights, counts.
 // `logits` holds the tile's router logits without the gate bias (sbias), `cnt` is zeroed.
 template <int NB>
 __device__ __forceinline__ void gate_epilogue(const GateArgs &a, float (*logits)[NB * 32 + 1], int *cnt,
-                                              const float *sbias, float (*s_sc)[64], float (*s_z)[64],
-                                              int tile, int g0, int Gl) {
+                                              const float *sbias, float (*s_sc)[64],
+                                              int tile, int g0, int Gl, int tok_lo, int tok_n, bool shared_tile) {
+    // tokens tok_lo .. tok_lo + tok_n - 1 of the tile (tok_n a multiple of the tokens per wave round);
+    // shared_tile: other workgroups handle the tile's other tokens, so per-tile counts are added
+    // atomically to the (zeroed) table instead of stored
     constexpr int NW = kGateWaves, NT = 64 * NW;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int t0 = tile * kTile;
@@ -246,19 +250,19 @@ __device__ __forceinline__ void gate_epilogue(const GateArgs &a, float (*logits)
     while (W < a.E) W <<= 1;
     const int per_wave = 64 / W;
     const int sub = lane / W, e = lane % W;
-    const int chunks_per_gate = kTile / per_wave;
+    const int chunks_per_gate = tok_n / per_wave;
     const int total_chunks = Gl * chunks_per_gate;
     const bool evalid = e < a.E;
     const float NEG_INF = -__builtin_inff();
 
-    // every wave works on its own rows of s_sc / s_z: the exchanges below need ordering inside the
+    // every wave works on its own row of s_sc: the exchange below needs ordering inside the
     // wave only (LDS operations of one wave execute in order), no workgroup barrier
     for (int it = 0; it * NW < total_chunks; ++it) {
         const int chunk = it * NW + wave;
         const bool cact = chunk < total_chunks;
         const int gl = cact ? chunk / chunks_per_gate : 0;   // gate inside the group
         const int gi = g0 + gl;                              // gate of the launch
-        const int ti = (chunk % chunks_per_gate) * per_wave + sub;
+        const int ti = tok_lo + (chunk % chunks_per_gate) * per_wave + sub;
         const int t = t0 + ti;
         const bool live = cact && t < a.T;
         const bool want_w = cact && (a.w != nullptr) && gi == 0;  // wave-uniform
@@ -273,7 +277,6 @@ __device__ __forceinline__ void gate_epilogue(const GateArgs &a, float (*logits)
             }
         }
         s_sc[wave][lane] = sc;
-        s_z[wave][lane] = z;
         wave_lds_sync();
         const float4 *srow = reinterpret_cast<const float4 *>(&s_sc[wave][sub * W]);
         int rank = 0;
@@ -285,39 +288,23 @@ __device__ __forceinline__ void gate_epilogue(const GateArgs &a, float (*logits)
             rank += (v.w > sc || (v.w == sc && j + 3 < e)) ? 1 : 0;
         }
         const bool sel = live && evalid && rank < a.k;
-        float ex = 0.f;
-        if (want_w) {   // softmax over all experts, fp32: max, exp, sum (sum taken below)
-            const float4 *zrow = reinterpret_cast<const float4 *>(&s_z[wave][sub * W]);
-            float m = NEG_INF;
-            for (int j = 0; j < W; j += 4) {
-                const float4 v = zrow[j >> 2];
-                m = fmaxf(fmaxf(m, v.x), fmaxf(v.y, fmaxf(v.z, v.w)));
-            }
+        // softmax over all experts in fp32: max, exp and the denominator (all experts, or only the
+        // selected ones when the weights are renormalised) by butterfly exchanges inside the token's
+        // lane group, a fixed order
+        float ex = 0.f, den = 1.f;
+        if (want_w) {
+            float m = z;   // lanes without an expert hold -inf
+            for (int off = W >> 1; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
             ex = (live && evalid) ? __expf(z - m) : 0.f;
+            den = (a.renorm && !sel) ? 0.f : ex;
+            for (int off = W >> 1; off >= 1; off >>= 1) den += __shfl_xor(den, off);
         }
-        wave_lds_sync();
-        if (want_w) s_z[wave][lane] = ex;
-        wave_lds_sync();
         const unsigned long long ball = __ballot(sel);
         const unsigned long long submask = (W == 64) ? ball : ((ball >> (sub * W)) & ((1ull << W) - 1ull));
         const int slot = __popcll(submask & ((1ull << e) - 1ull));   // ascending expert id
         if (sel) {
             pick(a.ids, gi)[(size_t)t * a.k + slot] = e;
-            if (want_w) {
-                const float *erow = &s_z[wave][sub * W];
-                float den = 0.f;
-                if (a.renorm) {   // p_e / sum of selected p = ex_e / sum of selected ex, ascending id
-                    unsigned long long mm = submask;
-                    while (mm) {
-                        const int j = __ffsll((long long)mm) - 1;
-                        den += erow[j];
-                        mm &= mm - 1;
-                    }
-                } else {
-                    for (int j = 0; j < W; ++j) den += erow[j];
-                }
-                a.w[(size_t)t * a.k + slot] = ex / den * a.routed_scale;
-            }
+            if (want_w) a.w[(size_t)t * a.k + slot] = ex / den * a.routed_scale;
             atomicAdd(&cnt[gl * a.E + e], 1);
         }
     }
@@ -326,7 +313,10 @@ __device__ __forceinline__ void gate_epilogue(const GateArgs &a, float (*logits)
         const int gi = g0 + x / a.E, ee = x % a.E;
         int32_t *hp = pick(a.hist, gi);
         if (hp && cnt[x] > 0) atomicAdd(&hp[ee], cnt[x]);
-        if (a.blockcounts && gi == 0) a.blockcounts[(size_t)tile * a.E + ee] = cnt[x];
+        if (a.blockcounts && gi == 0) {
+            if (!shared_tile) a.blockcounts[(size_t)tile * a.E + ee] = cnt[x];
+            else if (cnt[x] > 0) atomicAdd(&a.blockcounts[(size_t)tile * a.E + ee], cnt[x]);
+        }
     }
 }
 
@@ -339,7 +329,6 @@ __global__ __launch_bounds__(64 * kGateWaves) void gate_finish_kernel(GateArgs a
     __shared__ int cnt[4 * 32];
     __shared__ float sbias[4 * 32];
     __shared__ __attribute__((aligned(16))) float s_sc[NW][64];
-    __shared__ __attribute__((aligned(16))) float s_z[NW][64];
     const int tid = threadIdx.x;
     const int tile = blockIdx.x;
     const int g0 = blockIdx.y * a.gpw;
@@ -362,7 +351,8 @@ __global__ __launch_bounds__(64 * kGateWaves) void gate_finish_kernel(GateArgs a
         logits[x / (NB * 32)][x % (NB * 32)] = v;
     }
     __syncthreads();
-    gate_epilogue<NB>(a, logits, cnt, sbias, s_sc, s_z, tile, g0, Gl);
+    const int tok_n = kTile / a.tsplit;
+    gate_epilogue<NB>(a, logits, cnt, sbias, s_sc, tile, g0, Gl, blockIdx.z * tok_n, tok_n, a.tsplit > 1);
 }
 
 template <int NB>
@@ -370,8 +360,9 @@ static hipError_t launch_gate_nb(const GateArgs &a, hipStream_t s) {
     const int ntiles = (a.T + kTile - 1) / kTile;
     const int ngroups = (a.G + a.gpw - 1) / a.gpw;
     hipLaunchKernelGGL((gate_kernel<NB>), dim3(ntiles, ngroups, a.ksplit), dim3(64 * kGateWaves), 0, s, a);
-    if (a.ksplit > 1)
-        hipLaunchKernelGGL((gate_finish_kernel<NB>), dim3(ntiles, ngroups), dim3(64 * kGateWaves), 0, s, a);
+    if (a.two_step)
+        hipLaunchKernelGGL((gate_finish_kernel<NB>), dim3(ntiles, ngroups, a.tsplit), dim3(64 * kGateWaves), 0, s,
+                           a);
     return hipGetLastError();
 }
 
@@ -380,6 +371,18 @@ static hipError_t launch_gate_nb(const GateArgs &a, hipStream_t s) {
 // weights of the previous layer streamed through, and only four panels are in flight), so the
 // panels are dealt to several workgroups per (tile, group), four panels each (one round trip),
 // whose partial logits a second, short kernel adds up.  `part_floats` is the scratch available.
+// Token split of the finishing kernel.  With more than 16 experts a token takes a whole wave round
+// of the epilogue (selection by rank costs E^2 compares per token), so the 32 tokens of a tile are
+// dealt to up to 4 workgroups when the launch would otherwise leave most of the chip idle.
+int gate_pick_tsplit(int T, int G, int E, int gpw) {
+    const int ntiles = (T + kTile - 1) / kTile;
+    const int ngroups = (G + gpw - 1) / gpw;
+    if (E <= 16) return 1;
+    int ts = 1;
+    while (ts < 4 && ntiles * ngroups * ts < 512) ts *= 2;
+    return ts;
+}
+
 int gate_pick_ksplit(int T, int d, int G, int E, int gpw, size_t part_floats) {
     const int ntiles = (T + kTile - 1) / kTile;
     const int ngroups = (G + gpw - 1) / gpw;
@@ -407,7 +410,9 @@ int gate_pick_gpw(int T, int G, int E) {
 hipError_t launch_gate(const GateArgs &a, hipStream_t s) {
     if (a.T <= 0 || a.G <= 0) return hipSuccess;
     if (a.gpw < 1 || a.gpw * a.E > 128 || a.G > kMaxGates) return hipErrorInvalidValue;
-    if (a.ksplit < 1 || (a.ksplit > 1 && !a.part)) return hipErrorInvalidValue;
+    if (a.ksplit < 1 || (a.ksplit > 1 && !a.two_step) || (a.two_step && !a.part)) return hipErrorInvalidValue;
+    if (a.tsplit != 1 && a.tsplit != 2 && a.tsplit != 4) return hipErrorInvalidValue;
+    if (a.tsplit > 1 && !a.two_step) return hipErrorInvalidValue;
     const int nb = (std::min(a.gpw, a.G) * a.E + 31) / 32;
     switch (nb) {
         case 1: return launch_gate_nb<1>(a, s);
