@@ -166,6 +166,47 @@ def expert_ffn(h, experts, ids, perm, pos_begin=0, pos_end=None, round_act=False
     return y
 
 
+def _ptr_array_any(ws, E, dtype):
+    arr = (C.c_void_p * E)()
+    keep = []
+    for e in range(E):
+        w = ws[e] if e < len(ws) else None
+        if w is None:
+            arr[e] = None
+        else:
+            w = np.ascontiguousarray(w)
+            assert w.dtype == dtype, w.dtype
+            keep.append(w)
+            arr[e] = w.ctypes.data
+    return arr, keep
+
+
+def expert_ffn_q4(h, experts, ids, perm, pos_begin=0, pos_end=None, round_act=False):
+    """As expert_ffn with 4-bit weights: experts[e] = (q1, s1, q3, s3, q2, s2) or None; q* uint8 codes
+    0..15 ([F,d], [F,d], [d,F]), s* bf16 scales per row and 128 inputs; w = (q - 8) * s."""
+    h = _u16(h)
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    perm = np.ascontiguousarray(perm, dtype=np.int32)
+    T, d = h.shape
+    k = ids.shape[1]
+    E = len(experts)
+    pos_end = perm.size if pos_end is None else pos_end
+    F = next(w[0].shape[0] for w in experts if w is not None)
+    assert d % 128 == 0 and F % 128 == 0
+    for pos in range(pos_begin, pos_end):
+        assert experts[int(ids.reshape(-1)[perm[pos]])] is not None, "missing expert weights"
+    arrs, keeps = [], []
+    for j, dt in enumerate([np.uint8, np.uint16, np.uint8, np.uint16, np.uint8, np.uint16]):
+        a, kp = _ptr_array_any([None if w is None else w[j] for w in experts], E, dt)
+        arrs.append(a)
+        keeps.append(kp)
+    y = np.empty((pos_end - pos_begin, d), dtype=np.float64)
+    lib().oracle_expert_ffn_q4(_p(h, C.c_uint16), C.c_int(d), C.c_int(F), C.c_int(k), *arrs,
+                               _p(ids, C.c_int32), _p(perm, C.c_int32), C.c_int(pos_begin),
+                               C.c_int(pos_end), C.c_int(int(round_act)), _p(y, C.c_double))
+    return y
+
+
 def dense_ffn(h, W1, W3, W2, round_act=False):
     h, W1, W3, W2 = _u16(h), _u16(W1), _u16(W3), _u16(W2)
     T, d = h.shape

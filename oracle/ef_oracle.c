@@ -18,6 +18,10 @@
  *     S = N_e * E_s / (C_s * T_l): Sec. 3.2.1 and its equation;
  *   - intra-batch diversity Dist(t), the sum of pairwise Euclidean distances
  *     between the token embeddings of a batch: Sec. 2.2 (its equation);
+ *   - 4-bit expert weights: the paper evaluates one model in GPTQ-Int4 form (Sec. 4.1) without
+ *     stating a format; here a weight is w = (q - 8) * s with a 4-bit code q in 0..15 and one bf16
+ *     scale s per row and group of 128 inputs ("parity unpinned": a format by fiat, pinned only
+ *     against a library fp64 product with the dequantised matrix);
  *   - the layer math itself (softmax over all experts, top-k, SwiGLU expert,
  *     weighted combine) is not written out in the paper; it is the standard
  *     definition for the model families the paper evaluates (Sec. 4.1).
@@ -345,5 +349,52 @@ void oracle_token_dist(const uint16_t *h, int T, int d, const int32_t *js, int n
             acc += sqrt(sq);
         }
         s[q] = acc;
+    }
+}
+
+/*
+ * Expert FFN with 4-bit weights.  A matrix M [R, C] is given as codes q [R, C] (one byte each,
+ * 0..15) and scales s [R, C/128] (bf16): M[r][c] = (q[r][c] - 8) * s[r][c/128].  Otherwise as
+ * oracle_expert_ffn: q1/s1, q3/s3 describe W1, W3 [F, d]; q2/s2 describe W2 [d, F]; arrays of E
+ * pointers, NULL for experts no evaluated position uses.
+ */
+static double q4_weight(const uint8_t *q, const uint16_t *s, int C, int r, int c)
+{
+    return ((double)q[(size_t)r * C + c] - 8.0) * bf16_to_f64(s[(size_t)r * (C / 128) + c / 128]);
+}
+
+void oracle_expert_ffn_q4(const uint16_t *h, int d, int F, int k,
+                          const uint8_t *const *q1, const uint16_t *const *s1,
+                          const uint8_t *const *q3, const uint16_t *const *s3,
+                          const uint8_t *const *q2, const uint16_t *const *s2,
+                          const int32_t *ids, const int32_t *perm, int pos_begin, int pos_end,
+                          int round_act, double *y /* [(pos_end-pos_begin), d] */)
+{
+#pragma omp parallel
+    {
+        double *act = (double *)malloc((size_t)F * sizeof(double));
+#pragma omp for schedule(dynamic, 1)
+        for (int pos = pos_begin; pos < pos_end; ++pos) {
+            int a = perm[pos];
+            int e = ids[a];
+            const uint16_t *x = h + (size_t)(a / k) * d;
+            double *out = y + (size_t)(pos - pos_begin) * d;
+            for (int f = 0; f < F; ++f) {
+                double g = 0.0, u = 0.0;
+                for (int i = 0; i < d; ++i) {
+                    double xi = bf16_to_f64(x[i]);
+                    g += q4_weight(q1[e], s1[e], d, f, i) * xi;
+                    u += q4_weight(q3[e], s3[e], d, f, i) * xi;
+                }
+                double v = g / (1.0 + exp(-g)) * u;
+                act[f] = round_act ? round_to_bf16(v) : v;
+            }
+            for (int c = 0; c < d; ++c) {
+                double acc = 0.0;
+                for (int f = 0; f < F; ++f) acc += q4_weight(q2[e], s2[e], F, c, f) * act[f];
+                out[c] = acc;
+            }
+        }
+        free(act);
     }
 }

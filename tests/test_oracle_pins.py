@@ -320,3 +320,57 @@ def test_token_dist_closed_forms(oracle_mod):
     np.testing.assert_allclose(oracle_mod.token_dist(shifted), ref, rtol=1e-14)
     # a plausible mistake (squared distances, or all pairs counted twice) fails these values
     assert abs(s.sum() - sum(np.hypot(a[i], a[j]) for j in range(5) for i in range(j))) < 1e-12
+
+
+# ---------------------------------------------------------------------------
+# 4-bit expert weights: w = (q - 8) * s, one scale per row and 128 inputs
+# ---------------------------------------------------------------------------
+
+def _q4_cfg():
+    import dataclasses as dc
+    return dc.replace(synth.CONFIGS["tiny"], name="tiny_q4", d=256, F=384, E=4, k=2)
+
+
+def test_q4_expert_ffn_matches_torch_on_dequantised_weights(oracle_mod):
+    """Library routine: torch fp64 matmul / silu with the dequantised matrices, grouped by expert."""
+    cfg = _q4_cfg()
+    T = 9
+    h = synth.hidden(cfg, 0, T)
+    experts = [synth.expert_weights_q4(cfg, 0, e) for e in range(cfg.E)]
+    rng = np.random.default_rng(3)
+    ids = np.stack([np.sort(rng.choice(cfg.E, cfg.k, replace=False)) for _ in range(T)]).astype(np.int32)
+    perm = oracle_mod.permute(ids, cfg.E)[2]
+    y = oracle_mod.expert_ffn_q4(h, experts, ids, perm)
+    x = torch.from_numpy(synth.bf16_to_f32(h).astype(np.float64))
+    for pos, a in enumerate(perm):
+        e = int(ids.reshape(-1)[a])
+        q1, s1, q3, s3, q2, s2 = experts[e]
+        W1 = torch.from_numpy(synth.dequant_q4(q1, s1))
+        W3 = torch.from_numpy(synth.dequant_q4(q3, s3))
+        W2 = torch.from_numpy(synth.dequant_q4(q2, s2))
+        xt = x[a // cfg.k]
+        ref = W2 @ (torch.nn.functional.silu(W1 @ xt) * (W3 @ xt))
+        np.testing.assert_allclose(y[pos], ref.numpy(), rtol=1e-10, atol=1e-12)
+
+
+def test_q4_special_codes(oracle_mod):
+    """Code 8 is zero; with all scales 1 and codes 9 the matrices are all-ones: closed form."""
+    import dataclasses as dc
+    cfg = dc.replace(synth.CONFIGS["tiny"], name="q4s", d=128, F=128, E=1, k=1)
+    h = synth.f32_to_bf16(np.full((2, 128), 0.5, dtype=np.float32))
+    one = synth.f32_to_bf16(np.ones((128, 1), dtype=np.float32))
+    ids = np.zeros((2, 1), dtype=np.int32)
+    perm = np.arange(2, dtype=np.int32)
+    q9 = np.full((128, 128), 9, dtype=np.uint8)
+    q8 = np.full((128, 128), 8, dtype=np.uint8)
+    y = oracle_mod.expert_ffn_q4(h, [(q9, one, q9, one, q9, one)], ids, perm)
+    g = 64.0                                           # 128 inputs of 0.5 through a row of ones
+    np.testing.assert_allclose(y, 128 * (g / (1 + np.exp(-g)) * g), rtol=1e-12)
+    y0 = oracle_mod.expert_ffn_q4(h, [(q9, one, q9, one, q8, one)], ids, perm)
+    assert np.all(y0 == 0.0)
+    # the scale belongs to the row and the 128-input group: doubling one W2 row doubles that output
+    two = one.copy()
+    two[5] = synth.f32_to_bf16(np.array([2.0], dtype=np.float32))
+    y2 = oracle_mod.expert_ffn_q4(h, [(q9, one, q9, one, q9, two)], ids, perm)
+    np.testing.assert_allclose(y2[:, 5], 2 * y[:, 5], rtol=1e-12)
+    np.testing.assert_allclose(np.delete(y2, 5, axis=1), np.delete(y, 5, axis=1), rtol=1e-12)
