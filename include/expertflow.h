@@ -106,6 +106,7 @@ typedef struct ef_config {
     uint32_t flags;
     float init_bandwidth_gbps;   /* starting value of the C_s estimate, GB/s */
     float init_layer_us;         /* starting value of the T_l estimate, microseconds */
+    int32_t weight_bits;         /* routed experts: 0 or 16 = bf16 blobs, 4 = 4-bit blobs (see ef_pack_expert_q4) */
 } ef_config;
 
 typedef struct ef_stats {
@@ -141,6 +142,27 @@ const char *ef_strerror(int code);
 
 /* bytes of one packed expert blob: 3*d*F*2; 0 if d % 64 or F % 32 is non-zero */
 size_t ef_expert_bytes(int d_model, int d_ff);
+
+/*
+ * 4-bit experts.  The paper evaluates one model in GPTQ-Int4 form (Sec. 4.1) without stating a
+ * format; here a weight is w = (q - 8) * s with a code q in 0..15 and one bf16 scale s per matrix
+ * row and group of 128 inputs.  An expert blob of ef_expert_bytes_q4(d,F) = 3*d*F/2 + 3*d*F/64
+ * bytes holds, in this order: for rb in 0..F/32-1, for kq in 0..d/64-1: the W1 "quad" of rows
+ * [32rb, 32rb+32) and inputs [64kq, 64kq+64), then the W3 quad; for cb in 0..d/32-1, for kq in
+ * 0..F/64-1: the W2 quad of rows [32cb, 32cb+32); the W1 / W3 scales [F/32][d/128][2][32] bf16;
+ * the W2 scales [d/32][F/128][32] bf16.  A quad is 64 lanes x 4 dwords: dword j of lane
+ * l = 32*g + i holds the eight codes of the operand fragment of k-step 4kq + j (natural order for
+ * W1 / W3, paired order for W2, as in the bf16 blob), code t at bits 4*(t/2) + 16*(t%2).
+ * The FFN kernels multiply code and scale in fp32 and round the product to bf16 for the matrix
+ * cores (relative error 2^-9 per weight).  Requires d_model and d_ff multiples of 128 and no
+ * shared expert; groups of any size run through the weight-streaming kernels.
+ */
+size_t ef_expert_bytes_q4(int d_model, int d_ff);   /* 0 if d_model % 128 or d_ff % 128 is non-zero */
+
+/* Pack codes q1, q3 [F,d], q2 [d,F] (one byte per code, 0..15) and scales s1, s3 [F, d/128],
+ * s2 [d, F/128] (bf16 bit patterns), all row-major [host], into blob [host] in the layout above. */
+int ef_pack_expert_q4(const uint8_t *q1, const uint16_t *s1, const uint8_t *q3, const uint16_t *s3,
+                      const uint8_t *q2, const uint16_t *s2, int d_model, int d_ff, void *blob);
 
 /* Pack row-major W1 [F,d], W3 [F,d], W2 [d,F] (bf16 bit patterns) [host] into blob [host],
  * ef_expert_bytes(d,F) bytes, in the layout described at the top.  Model-load-time helper. */

@@ -27,7 +27,7 @@ EF_KERNELS = ["predict", "route", "group", "ffn_up_tiled", "pack", "ffn_up", "ff
 EF_MAX_EXPERTS, EF_MAX_TOPK, EF_MAX_HORIZON = 64, 8, 7
 
 EXPORTS = [
-    "ef_strerror", "ef_expert_bytes", "ef_pack_expert", "ef_create", "ef_destroy", "ef_last_error",
+    "ef_strerror", "ef_expert_bytes", "ef_pack_expert", "ef_expert_bytes_q4", "ef_pack_expert_q4", "ef_create", "ef_destroy", "ef_last_error",
     "ef_register_layer", "ef_predict", "ef_route", "ef_route_predict", "ef_moe_ffn", "ef_layer_step", "ef_cache_swap_in", "ef_cache_query",
     "ef_choose_horizon", "ef_token_dist", "ef_get_stats", "ef_reset_stats", "ef_set_profile", "ef_fake_advance_time",
 ]
@@ -40,7 +40,7 @@ class ef_config(C.Structure):
         ("slots_per_layer_max", C.c_int32), ("max_tokens", C.c_int32), ("h_max", C.c_int32),
         ("renorm_topk", C.c_int32), ("routed_scale", C.c_float), ("cum_threshold", C.c_float),
         ("stall_thresh", C.c_int32), ("overfetch_thresh", C.c_int32), ("flags", C.c_uint32),
-        ("init_bandwidth_gbps", C.c_float), ("init_layer_us", C.c_float),
+        ("init_bandwidth_gbps", C.c_float), ("init_layer_us", C.c_float), ("weight_bits", C.c_int32),
     ]
 
 
@@ -86,6 +86,9 @@ def lib():
         L.ef_expert_bytes.restype = C.c_size_t
         L.ef_expert_bytes.argtypes = [i32, i32]
         L.ef_pack_expert.argtypes = [vp, vp, vp, i32, i32, vp]
+        L.ef_expert_bytes_q4.restype = C.c_size_t
+        L.ef_expert_bytes_q4.argtypes = [i32, i32]
+        L.ef_pack_expert_q4.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp]
         L.ef_create.argtypes = [C.POINTER(ef_config), C.POINTER(vp)]
         L.ef_destroy.argtypes = [vp]
         L.ef_last_error.restype = C.c_char_p
@@ -158,6 +161,27 @@ def ef_pack_expert(W1, W3, W2, blob=None):
     return out
 
 
+def ef_expert_bytes_q4(d, F):
+    return int(lib().ef_expert_bytes_q4(d, F))
+
+
+def ef_pack_expert_q4(q1, s1, q3, s3, q2, s2, blob=None):
+    """Codes q1, q3 [F,d], q2 [d,F] uint8 (0..15) and bf16 scales s1, s3 [F,d/128], s2 [d,F/128] (uint16)
+    -> packed 4-bit blob (numpy uint8, or written into `blob`)."""
+    F, d = q1.shape
+    assert q3.shape == (F, d) and q2.shape == (d, F)
+    assert s1.shape == (F, d // 128) and s3.shape == (F, d // 128) and s2.shape == (d, F // 128)
+    n = ef_expert_bytes_q4(d, F)
+    if n == 0:
+        raise EfError(EF_EINVAL, "d_model and d_ff must be multiples of 128")
+    out = np.empty(n, dtype=np.uint8) if blob is None else blob
+    q1, q3, q2 = (np.ascontiguousarray(q, dtype=np.uint8) for q in (q1, q3, q2))
+    s1, s3, s2 = (np.ascontiguousarray(x, dtype=np.uint16) for x in (s1, s3, s2))
+    _check(None, lib().ef_pack_expert_q4(_ptr(q1), _ptr(s1), _ptr(q3), _ptr(s3), _ptr(q2), _ptr(s2), d, F,
+                                         _ptr(out)))
+    return out
+
+
 # ---- context ----------------------------------------------------------------------------------
 
 def ef_create(**kw):
@@ -165,7 +189,7 @@ def ef_create(**kw):
     cfg = ef_config()
     defaults = dict(d_ff_shared=0, slots_per_layer_max=0, h_max=4, renorm_topk=1, routed_scale=1.0,
                     cum_threshold=0.9, stall_thresh=4, overfetch_thresh=4, flags=0,
-                    init_bandwidth_gbps=50.0, init_layer_us=200.0)
+                    init_bandwidth_gbps=50.0, init_layer_us=200.0, weight_bits=0)
     defaults.update(kw)
     for k, v in defaults.items():
         setattr(cfg, k, v)

@@ -56,6 +56,7 @@ struct ef_ctx {
     int32_t *blockcounts = nullptr, *blockbase = nullptr;
     void *xp = nullptr, *act = nullptr;
     float *gate_part = nullptr;      // partial logits of K-split gate launches (small batches)
+    bool q4 = false;                 // routed experts are 4-bit blobs
     bool prepacked = false;          // ef_layer_step already enqueued the token packing of the coming ef_moe_ffn
     size_t gate_part_floats = 0;
     float *y = nullptr;
@@ -355,6 +356,64 @@ extern "C" int ef_pack_expert(const uint16_t *W1, const uint16_t *W3, const uint
     return EF_OK;
 }
 
+extern "C" size_t ef_expert_bytes_q4(int d, int F) {
+    if (d <= 0 || F <= 0 || d % 128 != 0 || F % 128 != 0) return 0;
+    return (size_t)3 * d * F / 2 + (size_t)3 * d * F / 64;
+}
+
+extern "C" int ef_pack_expert_q4(const uint8_t *q1, const uint16_t *s1, const uint8_t *q3, const uint16_t *s3,
+                                 const uint8_t *q2, const uint16_t *s2, int d, int F, void *blob) {
+    if (!q1 || !s1 || !q3 || !s3 || !q2 || !s2 || !blob) return fail(nullptr, EF_EINVAL, "ef_pack_expert_q4: null pointer");
+    if (ef_expert_bytes_q4(d, F) == 0) return fail(nullptr, EF_EINVAL, "ef_pack_expert_q4: d %% 128 or F %% 128 != 0");
+    unsigned char *out = static_cast<unsigned char *>(blob);
+    // dword of one lane for one k-step: code t of the lane's eight values at bits 4*(t/2) + 16*(t%2)
+    auto pack8 = [](const uint8_t *v8) {
+        uint32_t x = 0;
+        for (int t = 0; t < 8; ++t) x |= (uint32_t)(v8[t] & 15u) << (4 * (t / 2) + 16 * (t % 2));
+        return x;
+    };
+    const int nqa = d / 64, nqb = F / 64;
+    uint32_t *A = reinterpret_cast<uint32_t *>(out);
+    for (int rb = 0; rb < F / 32; ++rb)
+        for (int kq = 0; kq < nqa; ++kq)
+            for (int which = 0; which < 2; ++which) {
+                const uint8_t *Q = which ? q3 : q1;
+                uint32_t *dst = A + (((size_t)rb * nqa + kq) * 2 + which) * 256;   // 64 lanes x 4 dwords
+                for (int lane = 0; lane < 64; ++lane) {
+                    const int g = lane >> 5, i = lane & 31;
+                    for (int j = 0; j < 4; ++j)   // natural order: columns kb*16 + 8g + t
+                        dst[lane * 4 + j] = pack8(Q + (size_t)(rb * 32 + i) * d + (kq * 4 + j) * 16 + 8 * g);
+                }
+            }
+    uint32_t *B = reinterpret_cast<uint32_t *>(out + (size_t)d * F);
+    for (int cb = 0; cb < d / 32; ++cb)
+        for (int kq = 0; kq < nqb; ++kq) {
+            uint32_t *dst = B + ((size_t)cb * nqb + kq) * 256;
+            for (int lane = 0; lane < 64; ++lane) {
+                const int g = lane >> 5, i = lane & 31;
+                for (int j = 0; j < 4; ++j) {   // paired order: columns kb*16 + 8*(t/4) + 4g + t%4
+                    const uint8_t *row = q2 + (size_t)(cb * 32 + i) * F + (kq * 4 + j) * 16;
+                    uint8_t v8[8];
+                    for (int t = 0; t < 8; ++t) v8[t] = row[8 * (t / 4) + 4 * g + t % 4];
+                    dst[lane * 4 + j] = pack8(v8);
+                }
+            }
+        }
+    uint16_t *SA = reinterpret_cast<uint16_t *>(out + (size_t)3 * d * F / 2);
+    for (int rb = 0; rb < F / 32; ++rb)
+        for (int kg = 0; kg < d / 128; ++kg)
+            for (int which = 0; which < 2; ++which)
+                for (int i = 0; i < 32; ++i)
+                    SA[(((size_t)rb * (d / 128) + kg) * 2 + which) * 32 + i] =
+                        (which ? s3 : s1)[(size_t)(rb * 32 + i) * (d / 128) + kg];
+    uint16_t *SB = reinterpret_cast<uint16_t *>(out + (size_t)3 * d * F / 2 + (size_t)d * F / 32);
+    for (int cb = 0; cb < d / 32; ++cb)
+        for (int kg = 0; kg < F / 128; ++kg)
+            for (int i = 0; i < 32; ++i)
+                SB[((size_t)cb * (F / 128) + kg) * 32 + i] = s2[(size_t)(cb * 32 + i) * (F / 128) + kg];
+    return EF_OK;
+}
+
 // =================================================================================================
 // context
 // =================================================================================================
@@ -400,6 +459,10 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
                     EF_MAX_TOPK, EF_MAX_EXPERTS);
     if (ef_expert_bytes(g.d_model, g.d_ff) == 0)
         return fail(nullptr, EF_EINVAL, "ef_create: d_model must be a multiple of 64 and d_ff of 32");
+    if (g.weight_bits != 0 && g.weight_bits != 16 && g.weight_bits != 4)
+        return fail(nullptr, EF_EINVAL, "ef_create: weight_bits must be 0, 16 or 4");
+    if (g.weight_bits == 4 && (ef_expert_bytes_q4(g.d_model, g.d_ff) == 0 || g.d_ff_shared != 0))
+        return fail(nullptr, EF_EINVAL, "ef_create: 4-bit experts need d_model and d_ff multiples of 128 and no shared expert");
     if (g.d_ff_shared < 0 || g.d_ff_shared % 32 != 0)
         return fail(nullptr, EF_EINVAL, "ef_create: d_ff_shared must be a non-negative multiple of 32");
     if (g.slots_total <= 0 || g.slots_per_layer_max < 0 || g.max_tokens <= 0)
@@ -414,7 +477,8 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
     ef_ctx *c = new (std::nothrow) ef_ctx();
     if (!c) return fail(nullptr, EF_ENOMEM, "ef_create: host allocation failed");
     c->cfg = g;
-    c->expert_bytes = ef_expert_bytes(g.d_model, g.d_ff);
+    c->q4 = g.weight_bits == 4;
+    c->expert_bytes = c->q4 ? ef_expert_bytes_q4(g.d_model, g.d_ff) : ef_expert_bytes(g.d_model, g.d_ff);
     c->fake = (g.flags & EF_FLAG_FAKE_COPY) != 0;
     c->layers.resize((size_t)g.n_layers);
     c->cache = new ef::ExpertCache(g.slots_total, g.slots_per_layer_max, g.n_layers, g.n_experts);
@@ -796,10 +860,12 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
     }
     gu.n_groups = n;
     big.n_groups = nb;
+    // weights: 2 bytes each, or half a byte plus one bf16 scale per 128
+    const double wb = c->q4 ? 0.5 + 2.0 / 128.0 : 2.0;
     auto alg_bytes = [&](const ef::GroupTable &g, int cnt_groups, double &b_up, double &b_dn) {
         for (int i = 0; i < cnt_groups; ++i) {
-            b_up += 4.0 * d * g.F[i] + 2.0 * g.count[i] * d + 2.0 * g.count[i] * g.F[i];
-            b_dn += 2.0 * d * g.F[i] + 2.0 * g.count[i] * g.F[i] + 4.0 * g.count[i] * d;
+            b_up += 2.0 * wb * d * g.F[i] + 2.0 * g.count[i] * d + 2.0 * g.count[i] * g.F[i];
+            b_dn += wb * d * g.F[i] + 2.0 * g.count[i] * g.F[i] + 4.0 * g.count[i] * d;
         }
     };
     if (nb > 0) {
@@ -852,11 +918,11 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
     alg_bytes(gu, n, b_up, b_dn);
     {
         KernelTimer kt(c, s, EF_K_FFN_UP, b_up);
-        EF_HIP(c, ef::launch_ffn_gate_up(gu, wg_gu, tpp, ks, c->xp, c->act, d, s));
+        EF_HIP(c, ef::launch_ffn_gate_up(gu, wg_gu, tpp, ks, c->q4, c->xp, c->act, d, s));
     }
     {
         KernelTimer kt(c, s, EF_K_FFN_DOWN, b_dn);
-        EF_HIP(c, ef::launch_ffn_down(dn, wg_dn, tpp, ksg, c->act, c->y, y_plane, d, s));
+        EF_HIP(c, ef::launch_ffn_down(dn, wg_dn, tpp, ksg, c->q4, c->act, c->y, y_plane, d, s));
     }
     return EF_OK;
 }
@@ -915,7 +981,7 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
     // with a 2048 x 5632 shared expert, 1056 tokens over 64 experts) the tiled kernels were equal to or
     // 8 % faster than streaming the same groups in several passes, even at 150-200 workgroups.
     bool use_tiled = false;
-    if (T > 0 && tune("EF_TUNE_TILED", 1) != 0) {
+    if (T > 0 && !c->q4 && tune("EF_TUNE_TILED", 1) != 0) {
         long long wg_up = 0, wg_dn = 0;
         auto add = [&](int F, int cnt) {
             const int nt = (cnt + ef::kTile - 1) / ef::kTile;

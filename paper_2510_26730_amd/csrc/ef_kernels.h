@@ -84,10 +84,10 @@ hipError_t launch_pack_x(const PackTable &pt, int total_tiles, const uint16_t *h
 hipError_t launch_pack_x_dev(const int32_t *counts, const int32_t *offsets, int E, bool has_shared, int T,
                              int max_tiles, const uint16_t *h, int d, int k, const int32_t *perm, void *xp,
                              hipStream_t s);
-hipError_t launch_ffn_gate_up(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ks, const void *xp,
-                              void *act, int d, hipStream_t s);
-hipError_t launch_ffn_down(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ksg, const void *act,
-                           float *y, long long y_plane, int d, hipStream_t s);
+hipError_t launch_ffn_gate_up(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ks, bool q4,
+                              const void *xp, void *act, int d, hipStream_t s);
+hipError_t launch_ffn_down(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ksg, bool q4,
+                           const void *act, float *y, long long y_plane, int d, hipStream_t s);
 hipError_t launch_combine(const float *y, int ksg, long long y_plane, const float *w, const int32_t *inv_perm,
                           int T, int k, int d, long long shared_row0, float *out, hipStream_t s);
 

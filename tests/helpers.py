@@ -19,18 +19,20 @@ class LayerStack:
     registered with a library context (gates on the device, packed experts in pinned memory)."""
 
     def __init__(self, cfg: synth.MoEShape, n_layers: int, slots_total: int, per_layer: int = 0,
-                 max_tokens: int = 64, expert_layers=None, h_max: int = 4, **create_kw):
-        self.cfg, self.n_layers = cfg, n_layers
+                 max_tokens: int = 64, expert_layers=None, h_max: int = 4, q4: bool = False, **create_kw):
+        self.cfg, self.n_layers, self.q4 = cfg, n_layers, q4
         self.gates = [synth.gate_weight(cfg, l) for l in range(n_layers)]
         self.biases = [synth.gate_bias(cfg, l) for l in range(n_layers)]
         self.expert_layers = list(range(n_layers)) if expert_layers is None else list(expert_layers)
-        self.experts = {l: [synth.expert_weights(cfg, l, e) for e in range(cfg.E)] for l in self.expert_layers}
+        make = synth.expert_weights_q4 if q4 else synth.expert_weights
+        self.experts = {l: [make(cfg, l, e) for e in range(cfg.E)] for l in self.expert_layers}
         self.shared = {l: synth.shared_weights(cfg, l) for l in self.expert_layers} if cfg.F_shared else {}
         self.ctx = ef.ef_create(n_layers=n_layers, d_model=cfg.d, n_experts=cfg.E, top_k=cfg.k, d_ff=cfg.F,
                                 d_ff_shared=cfg.F_shared, slots_total=slots_total,
                                 slots_per_layer_max=per_layer, max_tokens=max_tokens, h_max=h_max,
-                                renorm_topk=int(cfg.renorm), **create_kw)
-        self.es = ef.ef_expert_bytes(cfg.d, cfg.F)
+                                renorm_topk=int(cfg.renorm), weight_bits=4 if q4 else 0, **create_kw)
+        self.es = ef.ef_expert_bytes_q4(cfg.d, cfg.F) if q4 else ef.ef_expert_bytes(cfg.d, cfg.F)
+        pack = ef.ef_pack_expert_q4 if q4 else ef.ef_pack_expert
         self._keep = []
         for l in range(n_layers):
             gw, gb = dev_u16(self.gates[l]), torch.from_numpy(self.biases[l]).cuda()
@@ -38,7 +40,7 @@ class LayerStack:
             store = torch.empty(cfg.E * self.es, dtype=torch.uint8, pin_memory=True)
             sv = store.numpy()
             for e in range(cfg.E):
-                ef.ef_pack_expert(*self.experts[src][e], blob=sv[e * self.es:(e + 1) * self.es])
+                pack(*self.experts[src][e], blob=sv[e * self.es:(e + 1) * self.es])
             sh = None
             if cfg.F_shared:
                 sh = torch.from_numpy(ef.ef_pack_expert(*self.shared[src])).cuda()

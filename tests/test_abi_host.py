@@ -271,3 +271,39 @@ def test_feedback_loop_moves_the_horizon():
         assert st["stall_counter"] == 0 and st["overfetch_counter"] == 0
     finally:
         ef.ef_destroy(ctx)
+
+
+def test_pack_expert_q4_layout():
+    """The 4-bit blob against an independent reading of the layout the header describes."""
+    import dataclasses
+    from paper_2510_26730_amd import synth
+    cfg = dataclasses.replace(synth.CONFIGS["tiny"], d=256, F=384, F_shared=0)
+    q1, s1, q3, s3, q2, s2 = synth.expert_weights_q4(cfg, 0, 0)
+    blob = ef.ef_pack_expert_q4(q1, s1, q3, s3, q2, s2)
+    d, F = cfg.d, cfg.F
+    assert blob.size == ef.ef_expert_bytes_q4(d, F) == 3 * d * F // 2 + 3 * d * F // 64
+    assert ef.ef_expert_bytes_q4(192, 128) == 0 and ef.ef_expert_bytes_q4(128, 96) == 0
+
+    def codes(x):   # dword -> the eight codes t = 0..7
+        return [(int(x) >> (4 * (t // 2) + 16 * (t % 2))) & 15 for t in range(8)]
+
+    dw = blob[:d * F].view(np.uint32).reshape(F // 32, d // 64, 2, 64, 4)
+    rng = np.random.default_rng(0)
+    for _ in range(300):
+        rb, kq, which = rng.integers(F // 32), rng.integers(d // 64), rng.integers(2)
+        lane, j = rng.integers(64), rng.integers(4)
+        g, i = lane >> 5, lane & 31
+        c0 = (kq * 4 + j) * 16 + 8 * g
+        assert codes(dw[rb, kq, which, lane, j]) == (q1, q3)[which][rb * 32 + i, c0:c0 + 8].tolist()
+    dwb = blob[d * F:d * F + d * F // 2].view(np.uint32).reshape(d // 32, F // 64, 64, 4)
+    for _ in range(300):
+        cb, kq, lane, j = rng.integers(d // 32), rng.integers(F // 64), rng.integers(64), rng.integers(4)
+        g, i = lane >> 5, lane & 31
+        c0 = (kq * 4 + j) * 16
+        assert codes(dwb[cb, kq, lane, j]) == [int(q2[cb * 32 + i, c0 + 8 * (t // 4) + 4 * g + t % 4]) for t in range(8)]
+    off = 3 * d * F // 2
+    sa = blob[off:off + d * F // 32].view(np.uint16).reshape(F // 32, d // 128, 2, 32)
+    assert np.array_equal(sa[:, :, 0, :].transpose(0, 2, 1).reshape(F, d // 128), s1)
+    assert np.array_equal(sa[:, :, 1, :].transpose(0, 2, 1).reshape(F, d // 128), s3)
+    sb = blob[off + d * F // 32:].view(np.uint16).reshape(d // 32, F // 128, 32)
+    assert np.array_equal(sb.transpose(0, 2, 1).reshape(d, F // 128), s2)
