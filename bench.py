@@ -87,6 +87,10 @@ def main():
     ap.add_argument("--beta", type=float, default=None)
     ap.add_argument("--layers", type=int, default=None)
     ap.add_argument("--all-resident", action="store_true", help="cache holds every expert (no PCIe traffic)")
+    ap.add_argument("--int4", action="store_true",
+                    help="4-bit expert weights (code and bf16 scale per 128 inputs) instead of bf16: a variant "
+                         "beside the headline workload, 4x fewer bytes per expert over PCIe and from HBM")
+    ap.add_argument("--slots", type=int, default=None, help="cache slots per layer (default: the workload's quota)")
     ap.add_argument("--pool-slots", type=int, default=None,
                     help="one global pool of this many cache slots shared by all layers instead of a per-layer quota")
     ap.add_argument("--horizon", type=int, default=None, help="fixed look-ahead H (default: the adaptive horizon)")
@@ -128,8 +132,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    loop = LayerLoop(cfg, L, T, cfg.slots_per_layer, pool_slots=args.pool_slots, beta=beta, profile=False,
-                     all_resident=args.all_resident)
+    slots = args.slots or cfg.slots_per_layer
+    loop = LayerLoop(cfg, L, T, slots, pool_slots=args.pool_slots, beta=beta, profile=False,
+                     all_resident=args.all_resident, q4=args.int4)
     loop.h_fixed = args.horizon
     n_in = 4                                          # distinct step inputs, cycled
     hs = [torch.from_numpy(synth.hidden_stack(cfg, L, step=s, T=T).view("int16")).cuda() for s in range(n_in)]
@@ -222,7 +227,7 @@ def main():
         traffic = None
         tag = f"TRAFFIC_BYTES_PER_LAUNCH ffn_gate_up_kernel {cfg.name} T={T} beta={beta} ="
         pmc = os.path.join(ROOT, "profiles", "ffn_kernels_mixtral_decode_T64_pmc_traffic.md")
-        if os.path.exists(pmc) and not args.all_resident and args.pool_slots is None:
+        if os.path.exists(pmc) and not args.all_resident and args.pool_slots is None and not args.int4:
             for line in open(pmc):
                 if line.startswith(tag):
                     traffic = float(line.split("=")[-1])
@@ -234,10 +239,11 @@ def main():
         "metric": "MoE-layer tokens/s (route+predict+FFN) at 1 GPU",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16 (4-bit expert weights dequantised to bf16)" if args.int4 else "bf16",
+        "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {L} layers, d={cfg.d}, E={cfg.E}, top-{cfg.k}, F={cfg.F}, "
-                               f"T={T} tokens/step, cache {'all experts' if args.all_resident else (str(args.pool_slots) + '-slot pool' if args.pool_slots else str(cfg.slots_per_layer) + ' slots/layer')}"
-                               f", beta={beta}, expert store = {loop.store_layers}-layer pinned pool reused cyclically",
+                               f"T={T} tokens/step, cache {'all experts' if args.all_resident else (str(args.pool_slots) + '-slot pool' if args.pool_slots else str(slots) + ' slots/layer')}"
+                               f"{', 4-bit experts' if args.int4 else ''}, beta={beta}, expert store = {loop.store_layers}-layer pinned pool reused cyclically",
                    "tokens_per_step": T, "layers": L, "beta": beta,
                    "horizon": "adaptive" if args.horizon is None else args.horizon,
                    "drift_tokens": args.drift_tokens},

@@ -153,9 +153,11 @@ size_t ef_expert_bytes(int d_model, int d_ff);
  * the W2 scales [d/32][F/128][32] bf16.  A quad is 64 lanes x 4 dwords: dword j of lane
  * l = 32*g + i holds the eight codes of the operand fragment of k-step 4kq + j (natural order for
  * W1 / W3, paired order for W2, as in the bf16 blob), code t at bits 4*(t/2) + 16*(t%2).
- * The FFN kernels multiply code and scale in fp32 and round the product to bf16 for the matrix
- * cores (relative error 2^-9 per weight).  Requires d_model and d_ff multiples of 128 and no
- * shared expert; groups of any size run through the weight-streaming kernels.
+ * The FFN kernels form (q - 8) * s in fp16 (relative error <= 2^-12 per weight) and run the matrix
+ * cores in fp16 with fp32 accumulation: tokens are converted from bf16 to fp16 (exact for
+ * 2^-14 <= |x| < 65504; larger magnitudes overflow) and the intermediate activations are kept in
+ * fp16.  Requires d_model and d_ff multiples of 128 and no shared expert; groups of any size run
+ * through the weight-streaming kernels.
  */
 size_t ef_expert_bytes_q4(int d_model, int d_ff);   /* 0 if d_model % 128 or d_ff % 128 is non-zero */
 

@@ -747,7 +747,7 @@ extern "C" int ef_token_dist(ef_ctx *c, const void *hidden, int T, float *tok_di
     const double flops = (double)T * (T - 1) * d;
     const double bytes = 6.0 * T * d + 8.0 * T;
     KernelTimer kt(c, s, EF_K_DIST, bytes, flops);
-    EF_HIP(c, ef::launch_pack_x(pt, ntiles, static_cast<const uint16_t *>(hidden), d, 1, nullptr, c->xp, s));
+    EF_HIP(c, ef::launch_pack_x(pt, ntiles, static_cast<const uint16_t *>(hidden), d, 1, nullptr, c->xp, false, s));
     EF_HIP(c, ef::launch_token_dist(static_cast<const uint16_t *>(hidden), T, d, c->xp, c->y, tok_dist, dist, s));
     return EF_OK;
 }
@@ -909,8 +909,9 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
     for (int i = 0; i < n; ++i) {
         gu.wg_start[i] = wg_gu;
         dn.wg_start[i] = wg_dn;
-        wg_gu += ef::ffn_gate_up_wgs(gu.F[i], gu.n_tiles[i], tpp, ks);
-        wg_dn += ef::ffn_down_wgs(d, gu.n_tiles[i], tpp, ksg);
+        wg_gu += c->q4 ? ef::ffn_gate_up_q4_wgs(gu.F[i], gu.n_tiles[i], tpp)
+                       : ef::ffn_gate_up_wgs(gu.F[i], gu.n_tiles[i], tpp, ks);
+        wg_dn += c->q4 ? ef::ffn_down_q4_wgs(d, gu.n_tiles[i], tpp, ksg) : ef::ffn_down_wgs(d, gu.n_tiles[i], tpp, ksg);
     }
     gu.wg_start[n] = wg_gu;
     dn.wg_start[n] = wg_dn;
@@ -918,11 +919,13 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
     alg_bytes(gu, n, b_up, b_dn);
     {
         KernelTimer kt(c, s, EF_K_FFN_UP, b_up);
-        EF_HIP(c, ef::launch_ffn_gate_up(gu, wg_gu, tpp, ks, c->q4, c->xp, c->act, d, s));
+        if (c->q4) EF_HIP(c, ef::launch_ffn_gate_up_q4(gu, wg_gu, tpp, c->xp, c->act, d, s));
+        else EF_HIP(c, ef::launch_ffn_gate_up(gu, wg_gu, tpp, ks, c->xp, c->act, d, s));
     }
     {
         KernelTimer kt(c, s, EF_K_FFN_DOWN, b_dn);
-        EF_HIP(c, ef::launch_ffn_down(dn, wg_dn, tpp, ksg, c->q4, c->act, c->y, y_plane, d, s));
+        if (c->q4) EF_HIP(c, ef::launch_ffn_down_q4(dn, wg_dn, tpp, ksg, c->act, c->y, y_plane, d, s));
+        else EF_HIP(c, ef::launch_ffn_down(dn, wg_dn, tpp, ksg, c->act, c->y, y_plane, d, s));
     }
     return EF_OK;
 }
@@ -1001,13 +1004,16 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         if (has_shared) tmax = std::max(tmax, (T + ef::kTile - 1) / ef::kTile);
         const int tpp = tmax >= 2 ? 2 : 1;
         for (int e = 0; e < E; ++e)
-            if (counts_host[e] > 0)
-                base_wgs += ef::ffn_down_wgs(d, (counts_host[e] + ef::kTile - 1) / ef::kTile, tpp, 1);
+            if (counts_host[e] > 0) {
+                const int nt = (counts_host[e] + ef::kTile - 1) / ef::kTile;
+                base_wgs += c->q4 ? ef::ffn_down_q4_wgs(d, nt, tpp, 1) : ef::ffn_down_wgs(d, nt, tpp, 1);
+            }
         if (has_shared) base_wgs += ef::ffn_down_wgs(d, (T + ef::kTile - 1) / ef::kTile, tpp, 1);
         const int want = tune("EF_TUNE_DOWN_WGS", 256);
         const int nkb_min = std::min(c->cfg.d_ff, has_shared ? c->cfg.d_ff_shared : c->cfg.d_ff) / 16;
-        while (ksg < 8 && base_wgs * ksg < want && nkb_min / (ksg * 2 * 4) >= 32 &&
-               y_plane * (ksg * 2) <= c->y_floats)
+        // a slice keeps >= 32 fragments per wave (bf16: four waves split it again) or >= 6 quads (4-bit)
+        const int units = c->q4 ? nkb_min / 4 / 6 : nkb_min / 4 / 32;
+        while (ksg < 8 && base_wgs * ksg < want && units / (ksg * 2) >= 1 && y_plane * (ksg * 2) <= c->y_floats)
             ksg *= 2;
         if (use_tiled) ksg = 1;   // the tiled kernels write plane 0 only
         int forced = tune("EF_TUNE_DOWN_KSG", ksg);
@@ -1126,7 +1132,7 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
             int r = EF_OK;
             long long rows = (long long)T * k + (has_shared ? T : 0);
             KernelTimer kt(c, s, EF_K_PACK, 4.0 * rows * d + 4.0 * T * k);
-            hipError_t he = ef::launch_pack_x(pt, tiles, static_cast<const uint16_t *>(hidden), d, k, perm, c->xp, s);
+            hipError_t he = ef::launch_pack_x(pt, tiles, static_cast<const uint16_t *>(hidden), d, k, perm, c->xp, c->q4, s);
             if (he != hipSuccess) r = fail(c, EF_EHIP, "pack_x launch failed: %s", hipGetErrorString(he));
             if (r) { unpin_all(ready); unpin_all(loading); return r; }
         }
@@ -1266,7 +1272,7 @@ extern "C" int ef_layer_step(ef_ctx *c, int layer, const void *hidden, int T, fl
         const long long rows = assignments + (has_shared ? T : 0);
         KernelTimer kt(c, s, EF_K_PACK, 4.0 * rows * d + 4.0 * T * k);
         EF_HIP(c, ef::launch_pack_x_dev(c->st_counts, c->st_offsets, E, has_shared, T, std::min(bound, c->max_tiles),
-                                        static_cast<const uint16_t *>(hidden), d, k, c->st_perm, c->xp, s));
+                                        static_cast<const uint16_t *>(hidden), d, k, c->st_perm, c->xp, c->q4, s));
         did_pack = true;
     }
     // 2. wait for the flag (bounded: fall back to a stream synchronisation, then give up)

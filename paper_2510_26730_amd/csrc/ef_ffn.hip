@@ -15,9 +15,21 @@ namespace ef {
 // xp[tile][kb][lane (g,i)] = 8 bf16 of row i of the tile, columns kb*16 + 8g .. +8.
 // grid = (tiles, column chunks); a workgroup copies a 32-row x (16*kb_per_wg)-column panel.
 // ------------------------------------------------------------------------------------------
+// eight bf16 -> eight fp16 (exact for 2^-14 <= |x| < 65504): the 4-bit FFN kernels run the matrix cores in fp16
+__device__ __forceinline__ uint4 bf16x8_to_f16x8(uint4 v) {
+    typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const float lo = __builtin_bit_cast(float, w[q] << 16), hi = __builtin_bit_cast(float, w[q] & 0xFFFF0000u);
+        w[q] = __builtin_bit_cast(uint32_t, half2v{(_Float16)lo, (_Float16)hi});
+    }
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
 __global__ __launch_bounds__(256) void pack_x_kernel(PackTable pt, const uint16_t *__restrict__ h, int d, int k,
                                                      const int32_t *__restrict__ perm, uint4 *__restrict__ xp,
-                                                     int kb_per_wg) {
+                                                     int kb_per_wg, int f16) {
     const int tile = blockIdx.x;
     int grp = 0;
     while (grp + 1 < pt.n_groups && pt.tile_start[grp + 1] <= tile) ++grp;
@@ -34,11 +46,14 @@ __global__ __launch_bounds__(256) void pack_x_kernel(PackTable pt, const uint16_
     const uint4 zero4 = make_uint4(0, 0, 0, 0);
     const int kb0 = blockIdx.y * kb_per_wg;
     const int kb1 = min(nkb, kb0 + kb_per_wg);
-    for (int kb = kb0 + wave; kb < kb1; kb += 4) dst[(size_t)kb * 64] = valid ? src[kb * 2 + g] : zero4;
+    for (int kb = kb0 + wave; kb < kb1; kb += 4) {
+        uint4 v = valid ? src[kb * 2 + g] : zero4;
+        dst[(size_t)kb * 64] = f16 ? bf16x8_to_f16x8(v) : v;
+    }
 }
 
 hipError_t launch_pack_x(const PackTable &pt, int total_tiles, const uint16_t *h, int d, int k,
-                         const int32_t *perm, void *xp, hipStream_t s) {
+                         const int32_t *perm, void *xp, bool f16, hipStream_t s) {
     if (total_tiles <= 0) return hipSuccess;
     const int nkb = d >> 4;
     // enough workgroups to fill the chip at small tile counts, at least 8 fragments per workgroup
@@ -46,7 +61,7 @@ hipError_t launch_pack_x(const PackTable &pt, int total_tiles, const uint16_t *h
     while (total_tiles * chunks < 1024 && nkb / (chunks * 2) >= 8) chunks *= 2;
     const int kb_per_wg = (nkb + chunks - 1) / chunks;
     hipLaunchKernelGGL(pack_x_kernel, dim3(total_tiles, chunks), dim3(256), 0, s, pt, h, d, k, perm,
-                       reinterpret_cast<uint4 *>(xp), kb_per_wg);
+                       reinterpret_cast<uint4 *>(xp), kb_per_wg, f16 ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -59,7 +74,7 @@ __global__ __launch_bounds__(256) void pack_x_dev_kernel(const int32_t *__restri
                                                          const int32_t *__restrict__ offsets, int E, int has_shared,
                                                          int T, const uint16_t *__restrict__ h, int d, int k,
                                                          const int32_t *__restrict__ perm, uint4 *__restrict__ xp,
-                                                         int kb_per_wg) {
+                                                         int kb_per_wg, int f16) {
     const int tile = blockIdx.x;
     int first = 0, grp = -1;
     for (int e = 0; e < E; ++e) {
@@ -89,19 +104,22 @@ __global__ __launch_bounds__(256) void pack_x_dev_kernel(const int32_t *__restri
     const uint4 zero4 = make_uint4(0, 0, 0, 0);
     const int kb0 = blockIdx.y * kb_per_wg;
     const int kb1 = min(nkb, kb0 + kb_per_wg);
-    for (int kb = kb0 + wave; kb < kb1; kb += 4) dst[(size_t)kb * 64] = valid ? src[kb * 2 + g] : zero4;
+    for (int kb = kb0 + wave; kb < kb1; kb += 4) {
+        uint4 v = valid ? src[kb * 2 + g] : zero4;
+        dst[(size_t)kb * 64] = f16 ? bf16x8_to_f16x8(v) : v;
+    }
 }
 
 hipError_t launch_pack_x_dev(const int32_t *counts, const int32_t *offsets, int E, bool has_shared, int T,
                              int max_tiles, const uint16_t *h, int d, int k, const int32_t *perm, void *xp,
-                             hipStream_t s) {
+                             bool f16, hipStream_t s) {
     if (max_tiles <= 0) return hipSuccess;
     const int nkb = d >> 4;
     int chunks = 1;
     while (max_tiles * chunks < 1024 && nkb / (chunks * 2) >= 8) chunks *= 2;
     const int kb_per_wg = (nkb + chunks - 1) / chunks;
     hipLaunchKernelGGL(pack_x_dev_kernel, dim3(max_tiles, chunks), dim3(256), 0, s, counts, offsets, E,
-                       has_shared ? 1 : 0, T, h, d, k, perm, reinterpret_cast<uint4 *>(xp), kb_per_wg);
+                       has_shared ? 1 : 0, T, h, d, k, perm, reinterpret_cast<uint4 *>(xp), kb_per_wg, f16 ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -169,142 +187,6 @@ __device__ __forceinline__ void up_stream(const uint4 *__restrict__ w1, const ui
 #undef EF_UP_COMPUTE
 }
 
-
-// ------------------------------------------------------------------------------------------
-// 4-bit expert weights.  A "quad" is 1 KiB = 64 lanes x 4 dwords: dword j of lane (g, i) holds
-// the eight codes of k-step 4*kq + j for row (or column) i and k-group g, code t at bits
-// 4*(t/2) + 16*(t%2).  (x >> 4p) & 0x000F000F | 0x43004300 is then the pair of bf16 numbers
-// 128 + q for t = 2p, 2p + 1 (the code sits in the low mantissa bits of 128.0); one fp32
-// multiply-add per weight, (128 + q) * s - 136 s = (q - 8) * s, and a hardware round-to-nearest-even
-// conversion give the bf16 operand fragment.  A lane of an operand fragment holds one row (or
-// column) of the weight matrix, so it needs one scale per 128-input group.
-// ------------------------------------------------------------------------------------------
-typedef float float2v __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
-
-__device__ __forceinline__ u32x4_t dequant_q4(uint32_t x, float s, float m136s) {
-    u32x4_t out;
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const uint32_t pr = ((x >> (4 * p)) & 0x000F000Fu) | 0x43004300u;
-        float2v f;
-        f.x = __builtin_fmaf(__builtin_bit_cast(float, pr << 16), s, m136s);
-        f.y = __builtin_fmaf(__builtin_bit_cast(float, pr & 0xFFFF0000u), s, m136s);
-        out[p] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2v));
-    }
-    return out;
-}
-
-__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
-    return __builtin_bit_cast(float, (uint32_t)b << 16);
-}
-
-// K loop of the first FFN half over quads [q0, q1) with 4-bit W1 / W3: three register stages of one
-// quad per matrix (4 k-steps) plus the matching token fragments; prefetches are unconditional
-// (clamped to the last quad).  w13 points at this lane's dwords of the row block's first W1 quad
-// (W1 and W3 quads alternate, 128 uint4 per pair); sA at this lane's row in the row block's scales
-// [group][W1 | W3][32 rows].
-template <int TT, int NTL>
-__device__ __forceinline__ void up_stream_q4(const uint4 *__restrict__ w13, const uint16_t *__restrict__ sA,
-                                             const uint4 *__restrict__ x0, int nkb, int q0, int q1,
-                                             floatx16 (&G)[TT], floatx16 (&U)[TT]) {
-    u32x4_t q1A, q3A, xA[NTL][4], q1B, q3B, xB[NTL][4], q1C, q3C, xC[NTL][4];
-    uint16_t s1A, s3A, s1B, s3B, s1C, s3C;
-#define EF_UPQ_LOAD(qa, qb, x, sa, sb, kq)                                                               \
-    {                                                                                                    \
-        qa = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(w13 + (size_t)(kq) * 128));      \
-        qb = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(w13 + (size_t)(kq) * 128 + 64)); \
-        _Pragma("unroll") for (int tt = 0; tt < NTL; ++tt)                                               \
-            _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                \
-                x[tt][j] = *reinterpret_cast<const u32x4_t *>(x0 + ((size_t)tt * nkb + 4 * (kq) + j) * 64); \
-        sa = sA[(size_t)((kq) >> 1) * 64];                                                               \
-        sb = sA[(size_t)((kq) >> 1) * 64 + 32];                                                          \
-    }
-#define EF_UPQ_COMPUTE(qa, qb, x, sa, sb)                                                                \
-    {                                                                                                    \
-        const float f1_ = bf16_bits_to_f32(sa), f3_ = bf16_bits_to_f32(sb);                              \
-        const float m1_ = -136.f * f1_, m3_ = -136.f * f3_;                                              \
-        _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                  \
-            const u32x4_t a1_ = dequant_q4(qa[j], f1_, m1_), a3_ = dequant_q4(qb[j], f3_, m3_);          \
-            _Pragma("unroll") for (int tt = 0; tt < NTL; ++tt) {                                         \
-                G[tt] = mfma32v(a1_, x[tt][j], G[tt]);                                                   \
-                U[tt] = mfma32v(a3_, x[tt][j], U[tt]);                                                   \
-            }                                                                                            \
-        }                                                                                                \
-    }
-    const int n = q1 - q0;
-    if (n <= 0) return;
-    const int last = q1 - 1;
-    int kq = q0;
-    EF_UPQ_LOAD(q1A, q3A, xA, s1A, s3A, kq)
-    EF_UPQ_LOAD(q1B, q3B, xB, s1B, s3B, min(kq + 1, last))
-    int c = 0;
-    for (; c + 3 <= n; c += 3) {
-        EF_UPQ_LOAD(q1C, q3C, xC, s1C, s3C, min(kq + 2, last))
-        EF_UPQ_COMPUTE(q1A, q3A, xA, s1A, s3A)
-        EF_UPQ_LOAD(q1A, q3A, xA, s1A, s3A, min(kq + 3, last))
-        EF_UPQ_COMPUTE(q1B, q3B, xB, s1B, s3B)
-        EF_UPQ_LOAD(q1B, q3B, xB, s1B, s3B, min(kq + 4, last))
-        EF_UPQ_COMPUTE(q1C, q3C, xC, s1C, s3C)
-        kq += 3;
-    }
-    if (c < n) EF_UPQ_COMPUTE(q1A, q3A, xA, s1A, s3A)
-    if (c + 1 < n) EF_UPQ_COMPUTE(q1B, q3B, xB, s1B, s3B)
-#undef EF_UPQ_LOAD
-#undef EF_UPQ_COMPUTE
-}
-
-// K loop of the second FFN half over quads [q0, q1) with 4-bit W2 (operand B: a lane holds one
-// output column): w2q points at this lane's dwords of the first column block's first quad,
-// cb_stride (uint4) leads to the next column block; sB at this lane's column in the first column
-// block's scales [group][32 columns], sb_stride (elements) to the next column block.
-template <int TT, int NTL, int CBW>
-__device__ __forceinline__ void down_stream_q4(const uint4 *__restrict__ w2q, size_t cb_stride,
-                                               const uint16_t *__restrict__ sB, size_t sb_stride,
-                                               const uint4 *__restrict__ a0, int nkb, int q0, int q1,
-                                               floatx16 (&acc)[CBW][TT]) {
-    // two register stages (one quad per column block plus the activation fragments of its four k-steps)
-    u32x4_t bA[CBW], aA[NTL][4], bB[CBW], aB[NTL][4];
-    uint16_t sA_[CBW], sB_[CBW];
-#define EF_DNQ_LOAD(b, a, sc, kq)                                                                        \
-    {                                                                                                    \
-        _Pragma("unroll") for (int cw = 0; cw < CBW; ++cw) {                                             \
-            b[cw] = __builtin_nontemporal_load(                                                          \
-                reinterpret_cast<const u32x4_t *>(w2q + cw * cb_stride + (size_t)(kq) * 64));            \
-            sc[cw] = sB[cw * sb_stride + (size_t)((kq) >> 1) * 32];                                      \
-        }                                                                                                \
-        _Pragma("unroll") for (int tt = 0; tt < NTL; ++tt)                                               \
-            _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                \
-                a[tt][j] = *reinterpret_cast<const u32x4_t *>(a0 + ((size_t)tt * nkb + 4 * (kq) + j) * 64); \
-    }
-#define EF_DNQ_COMPUTE(b, a, sc)                                                                         \
-    {                                                                                                    \
-        _Pragma("unroll") for (int cw = 0; cw < CBW; ++cw) {                                             \
-            const float f_ = bf16_bits_to_f32(sc[cw]);                                                   \
-            const float m_ = -136.f * f_;                                                                \
-            _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                              \
-                const u32x4_t w_ = dequant_q4(b[cw][j], f_, m_);                                         \
-                _Pragma("unroll") for (int tt = 0; tt < NTL; ++tt)                                       \
-                    acc[cw][tt] = mfma32v(a[tt][j], w_, acc[cw][tt]);                                    \
-            }                                                                                            \
-        }                                                                                                \
-    }
-    const int n = q1 - q0;
-    if (n <= 0) return;
-    const int last = q1 - 1;
-    int kq = q0;
-    EF_DNQ_LOAD(bA, aA, sA_, kq)
-    for (int c = 0; c < n; c += 2) {
-        EF_DNQ_LOAD(bB, aB, sB_, min(kq + 1, last))
-        EF_DNQ_COMPUTE(bA, aA, sA_)
-        EF_DNQ_LOAD(bA, aA, sA_, min(kq + 2, last))
-        if (c + 1 < n) EF_DNQ_COMPUTE(bB, aB, sB_)
-        kq += 2;
-    }
-#undef EF_DNQ_LOAD
-#undef EF_DNQ_COMPUTE
-}
-
 // ------------------------------------------------------------------------------------------
 // first half: act = silu(X W1^T) * (X W3^T).
 //
@@ -315,7 +197,7 @@ __device__ __forceinline__ void down_stream_q4(const uint4 *__restrict__ w2q, si
 // order through LDS before the non-linear epilogue.  Loads are double-buffered in registers:
 // the fragments of chunk c+1 are in flight while chunk c feeds the matrix cores.
 // ------------------------------------------------------------------------------------------
-template <int TT, int KS, bool Q4>
+template <int TT, int KS>
 __global__ __launch_bounds__(256) void ffn_gate_up_kernel(GroupTable gt, const uint4 *__restrict__ xp,
                                                           uint4 *__restrict__ act, int d) {
     constexpr int RBW = 4 / KS;
@@ -343,18 +225,7 @@ __global__ __launch_bounds__(256) void ffn_gate_up_kernel(GroupTable gt, const u
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) { zero16(G[tt]); zero16(U[tt]); }
 
-    if (active && Q4) {
-        // 4-bit blob: W1 / W3 quads of the row block, then (after all quads of W1, W3 and W2) the scales
-        const int nq = d >> 6;
-        const int q0 = (int)((long long)ks * nq / KS), q1 = (int)((long long)(ks + 1) * nq / KS);
-        const char *blob = reinterpret_cast<const char *>(gt.blob[grp]);
-        const uint4 *w13 = reinterpret_cast<const uint4 *>(blob) + (size_t)rb * nq * 128 + lane;
-        const uint16_t *sA = reinterpret_cast<const uint16_t *>(blob + (size_t)3 * d * F / 2) +
-                             (size_t)rb * (d >> 7) * 64 + (lane & 31);
-        const uint4 *x0 = xp + (size_t)(gt.tile_start[grp] + pass * TT) * nkb * 64 + lane;
-        if (TT == 1 || ntl == 1) up_stream_q4<TT, 1>(w13, sA, x0, nkb, q0, q1, G, U);
-        else up_stream_q4<TT, TT>(w13, sA, x0, nkb, q0, q1, G, U);
-    } else if (active) {
+    if (active) {
         const uint4 *w1 = reinterpret_cast<const uint4 *>(gt.blob[grp]) + (size_t)rb * 2 * nkb * 64 + lane;
         const uint4 *w3 = w1 + (size_t)nkb * 64;
         const uint4 *x0 = xp + (size_t)(gt.tile_start[grp] + pass * TT) * nkb * 64 + lane;
@@ -421,31 +292,23 @@ __global__ __launch_bounds__(256) void ffn_gate_up_kernel(GroupTable gt, const u
     }
 }
 
-template <int TT, bool Q4>
+template <int TT>
 static hipError_t launch_up_tt(const GroupTable &gt, int total_wgs, int ks, const uint4 *x, uint4 *a, int d,
                                hipStream_t s) {
-    if (ks == 1) hipLaunchKernelGGL((ffn_gate_up_kernel<TT, 1, Q4>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
-    else if (ks == 2) hipLaunchKernelGGL((ffn_gate_up_kernel<TT, 2, Q4>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
-    else if (ks == 4) hipLaunchKernelGGL((ffn_gate_up_kernel<TT, 4, Q4>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
+    if (ks == 1) hipLaunchKernelGGL((ffn_gate_up_kernel<TT, 1>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
+    else if (ks == 2) hipLaunchKernelGGL((ffn_gate_up_kernel<TT, 2>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
+    else if (ks == 4) hipLaunchKernelGGL((ffn_gate_up_kernel<TT, 4>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
-hipError_t launch_ffn_gate_up(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ks, bool q4,
-                              const void *xp, void *act, int d, hipStream_t s) {
+hipError_t launch_ffn_gate_up(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ks, const void *xp,
+                              void *act, int d, hipStream_t s) {
     if (total_wgs <= 0) return hipSuccess;
     const uint4 *x = reinterpret_cast<const uint4 *>(xp);
     uint4 *a = reinterpret_cast<uint4 *>(act);
-    if (q4) {   // 4-bit weights: quads of 64 inputs, scale groups of 128
-        if (d % 128 != 0) return hipErrorInvalidValue;
-        for (int i = 0; i < gt.n_groups; ++i)
-            if (gt.F[i] % 128 != 0) return hipErrorInvalidValue;
-        if (tiles_per_pass == 1) return launch_up_tt<1, true>(gt, total_wgs, ks, x, a, d, s);
-        if (tiles_per_pass == 2) return launch_up_tt<2, true>(gt, total_wgs, ks, x, a, d, s);
-        return hipErrorInvalidValue;
-    }
-    if (tiles_per_pass == 1) return launch_up_tt<1, false>(gt, total_wgs, ks, x, a, d, s);
-    if (tiles_per_pass == 2) return launch_up_tt<2, false>(gt, total_wgs, ks, x, a, d, s);
+    if (tiles_per_pass == 1) return launch_up_tt<1>(gt, total_wgs, ks, x, a, d, s);
+    if (tiles_per_pass == 2) return launch_up_tt<2>(gt, total_wgs, ks, x, a, d, s);
     return hipErrorInvalidValue;
 }
 
@@ -520,7 +383,7 @@ __device__ __forceinline__ void down_stream(const uint4 *__restrict__ w2, size_t
 // un-permute sums the planes in order.  Activations are operand A (rows = tokens), W2 fragments
 // operand B (columns = outputs).
 // ------------------------------------------------------------------------------------------
-template <int TT, bool Q4>
+template <int TT>
 __global__ __launch_bounds__(256, 2) void ffn_down_kernel(GroupTable gt, const uint4 *__restrict__ act,
                                                        float *__restrict__ Y, int d, int ksg,
                                                        long long y_plane) {
@@ -553,18 +416,7 @@ __global__ __launch_bounds__(256, 2) void ffn_down_kernel(GroupTable gt, const u
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) zero16(acc[cw][tt]);
 
-    if (Q4) {
-        // 4-bit blob: W2 quads start after the W1 / W3 quads (d*F bytes), its scales after all scales of W1 / W3
-        const int nq = F >> 6;
-        const int q0 = (int)((long long)part * nq / nparts), q1 = (int)((long long)(part + 1) * nq / nparts);
-        const char *blob = reinterpret_cast<const char *>(gt.blob[grp]);
-        const size_t qstride = (size_t)nq * 64, sstride = (size_t)(F >> 7) * 32;
-        const uint4 *w2q = reinterpret_cast<const uint4 *>(blob + (size_t)d * F) + (size_t)cb0 * qstride + lane;
-        const uint16_t *sB = reinterpret_cast<const uint16_t *>(blob + (size_t)3 * d * F / 2 + (size_t)d * F / 32) +
-                             (size_t)cb0 * sstride + (lane & 31);
-        if (TT == 1 || ntl == 1) down_stream_q4<TT, 1, CBW>(w2q, qstride, sB, sstride, a0, nkb, q0, q1, acc);
-        else down_stream_q4<TT, TT, CBW>(w2q, qstride, sB, sstride, a0, nkb, q0, q1, acc);
-    } else if (TT == 1 || ntl == 1) down_stream<TT, 1, CBW, UNR>(w2, cb_stride, a0, nkb, k0, k1, acc);
+    if (TT == 1 || ntl == 1) down_stream<TT, 1, CBW, UNR>(w2, cb_stride, a0, nkb, k0, k1, acc);
     else down_stream<TT, TT, CBW, UNR>(w2, cb_stride, a0, nkb, k0, k1, acc);
 
     auto put = [&](float *r) {
@@ -609,23 +461,14 @@ __global__ __launch_bounds__(256, 2) void ffn_down_kernel(GroupTable gt, const u
     }
 }
 
-hipError_t launch_ffn_down(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ksg, bool q4,
-                           const void *act, float *y, long long y_plane, int d, hipStream_t s) {
+hipError_t launch_ffn_down(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ksg, const void *act,
+                           float *y, long long y_plane, int d, hipStream_t s) {
     if (total_wgs <= 0) return hipSuccess;
     const uint4 *a = reinterpret_cast<const uint4 *>(act);
-    if (q4) {
-        if (d % 128 != 0) return hipErrorInvalidValue;
-        for (int i = 0; i < gt.n_groups; ++i)
-            if (gt.F[i] % 128 != 0) return hipErrorInvalidValue;
-    }
-    if (tiles_per_pass == 1 && q4)
-        hipLaunchKernelGGL((ffn_down_kernel<1, true>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
-    else if (tiles_per_pass == 2 && q4)
-        hipLaunchKernelGGL((ffn_down_kernel<2, true>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
-    else if (tiles_per_pass == 1)
-        hipLaunchKernelGGL((ffn_down_kernel<1, false>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
+    if (tiles_per_pass == 1)
+        hipLaunchKernelGGL((ffn_down_kernel<1>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
     else if (tiles_per_pass == 2)
-        hipLaunchKernelGGL((ffn_down_kernel<2, false>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
+        hipLaunchKernelGGL((ffn_down_kernel<2>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

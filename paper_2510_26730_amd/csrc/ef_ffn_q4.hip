@@ -1,0 +1,371 @@
+// Grouped SwiGLU expert FFN with 4-bit expert weights (w = (q - 8) * s, one bf16 scale per matrix row
+// and group of 128 inputs), for groups of any size.
+//
+// With 4-bit weights a byte of weights meets four times as many token bytes as with bf16, so the
+// re-reads of the token (or activation) fragments, not the weight stream, would bound a kernel in
+// which every wave fetches its own copy.  Here the four waves of a workgroup work on the same
+// tokens and the same K range (different weight rows / output columns): each wave fetches a quarter
+// of the token fragments of a stage, the workgroup shares them through a small LDS ring, and only
+// the weight stream is private to a wave.  A stage is one "quad" of weights per matrix (four
+// k-steps, 64 inputs); weight quads, scales and the wave's share of token fragments sit in a
+// register ring of kDepth stages filled that many stages ahead with unconditional loads (clamped
+// addresses), one barrier per stage.  Dequantisation happens on the operand fragment, where a lane
+// holds one matrix row (column) and therefore needs one scale per group, and in fp16: the codes
+// become the fp16 numbers 1024 + q by bit operations, a packed subtraction gives q - 8 exactly and a
+// packed multiplication (q - 8) * s: four vector instructions per pair of weights where an fp32
+// route costs seven, which is what keeps these kernels on the memory side of the balance.  The
+// matrix cores therefore run in fp16 (fp32 accumulation): the packed tokens of a 4-bit context and
+// the intermediate activations are fp16 fragments (tokens convert exactly from bf16 for
+// 2^-14 <= |x| < 65504).
+#include "ef_device.h"
+#include "ef_kernels.h"
+
+namespace ef {
+
+typedef _Float16 q4_half2 __attribute__((ext_vector_type(2)));
+typedef _Float16 q4_half8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ floatx16 mfma32h(u32x4_t a, u32x4_t b, floatx16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(q4_half8, a), __builtin_bit_cast(q4_half8, b), c,
+                                                  0, 0, 0);
+}
+
+// dword x = eight codes of one lane for one k-step, code t at bits 4*(t/2) + 16*(t%2);
+// s2 = the lane's scale in both halves.  (x >> 4p) & 0x000F000F | 0x64006400 is the pair of fp16
+// numbers 1024 + q for t = 2p, 2p + 1; minus 1032 is q - 8 exactly; times s rounds once to fp16
+// (11 significant bits for a 4-bit integer times an 8-bit mantissa: relative error <= 2^-12).
+__device__ __forceinline__ u32x4_t dequant_q4(uint32_t x, q4_half2 s2) {
+    const q4_half2 off = {(_Float16)-1032.f, (_Float16)-1032.f};
+    u32x4_t out;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const uint32_t pr = ((x >> (4 * p)) & 0x000F000Fu) | 0x64006400u;
+        const q4_half2 w = (__builtin_bit_cast(q4_half2, pr) + off) * s2;
+        out[p] = __builtin_bit_cast(uint32_t, w);
+    }
+    return out;
+}
+
+// bf16 scale (exact in fp16 for 2^-14 <= |s| < 65504) in both halves of a packed pair
+__device__ __forceinline__ q4_half2 q4_scale(uint16_t b) {
+    const _Float16 h = (_Float16)__builtin_bit_cast(float, (uint32_t)b << 16);
+    return q4_half2{h, h};
+}
+
+constexpr int kQ4Depth = 6;   // register ring: stages in flight per wave
+constexpr int kQ4Lds = 4;     // LDS ring of shared token / activation fragments (stages)
+
+// ------------------------------------------------------------------------------------------
+// first half: act = silu(X W1^T) * (X W3^T).  Workgroup = (group, pass of TT token tiles, four
+// consecutive 32-row blocks of F), wave = one row block, whole K range.
+// ------------------------------------------------------------------------------------------
+template <int TT>
+__global__ __launch_bounds__(256, 1) void ffn_gate_up_q4_kernel(GroupTable gt, const uint4 *__restrict__ xp,
+                                                                uint4 *__restrict__ act, int d) {
+    constexpr int D = kQ4Depth;
+    __shared__ __attribute__((aligned(16))) u32x4_t xs[kQ4Lds][TT * 4][64];
+    const int wg = blockIdx.x;
+    int grp = 0;
+    while (grp + 1 < gt.n_groups && gt.wg_start[grp + 1] <= wg) ++grp;
+    const int local = wg - gt.wg_start[grp];
+    const int F = gt.F[grp];
+    const int rbw = (F >> 5) >> 2;               // workgroups per pass (F is a multiple of 128)
+    const int pass = local / rbw;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int rb = (local % rbw) * 4 + wave;
+    int ntl = gt.n_tiles[grp] - pass * TT;
+    if (ntl > TT) ntl = TT;
+    const int nkb = d >> 4, nq = d >> 6;
+
+    const char *blob = reinterpret_cast<const char *>(gt.blob[grp]);
+    const uint4 *w13 = reinterpret_cast<const uint4 *>(blob) + (size_t)rb * nq * 128 + lane;
+    const uint16_t *sA = reinterpret_cast<const uint16_t *>(blob + (size_t)3 * d * F / 2) +
+                         (size_t)rb * (d >> 7) * 64 + (lane & 31);
+    // this wave's share of the token fragments of a stage: k-step `wave` of each tile (tiles past the
+    // group's last one repeat it; their results are dropped)
+    const uint4 *xsrc[TT];
+#pragma unroll
+    for (int u = 0; u < TT; ++u)
+        xsrc[u] = xp + (size_t)(gt.tile_start[grp] + pass * TT + min(u, ntl - 1)) * nkb * 64 + lane;
+
+    floatx16 G[TT], U[TT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) { zero16(G[tt]); zero16(U[tt]); }
+
+    u32x4_t qa[D], qb[D], xr[D][TT];
+    uint16_t sa[D], sb[D];
+#define EF_Q4U_LOAD(slot, kq)                                                                             \
+    {                                                                                                     \
+        const int kc_ = min((kq), nq - 1);                                                                \
+        qa[slot] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(w13 + (size_t)kc_ * 128));       \
+        qb[slot] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(w13 + (size_t)kc_ * 128 + 64));  \
+        sa[slot] = sA[(size_t)(kc_ >> 1) * 64];                                                           \
+        sb[slot] = sA[(size_t)(kc_ >> 1) * 64 + 32];                                                      \
+        _Pragma("unroll") for (int u = 0; u < TT; ++u)                                                    \
+            xr[slot][u] = *reinterpret_cast<const u32x4_t *>(xsrc[u] + (size_t)(4 * kc_ + wave) * 64);    \
+    }
+#define EF_Q4U_SHARE(slot, st)                                                                            \
+    {                                                                                                     \
+        _Pragma("unroll") for (int u = 0; u < TT; ++u) xs[(st) & (kQ4Lds - 1)][u * 4 + wave][lane] = xr[slot][u]; \
+    }
+    // The MFMAs of a k-step are issued between the vector instructions that dequantise the next
+    // k-step's fragments (one MFMA, then a share of the ~40 vector instructions), so the matrix
+    // cores work while the wave converts: a wave issues in order and has the SIMD to itself, nothing
+    // else would overlap the two.
+#define EF_Q4U_COMPUTE(slot, st)                                                                          \
+    {                                                                                                     \
+        const q4_half2 f1_ = q4_scale(sa[slot]), f3_ = q4_scale(sb[slot]);                                \
+        u32x4_t xb_[TT][4];                                                                               \
+        _Pragma("unroll") for (int tt = 0; tt < TT; ++tt)                                                 \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) xb_[tt][j] = xs[(st) & (kQ4Lds - 1)][tt * 4 + j][lane]; \
+        u32x4_t a1_ = dequant_q4(qa[slot][0], f1_), a3_ = dequant_q4(qb[slot][0], f3_);                   \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                   \
+            u32x4_t n1_ = a1_, n3_ = a3_;                                                                 \
+            if (j < 3) { n1_ = dequant_q4(qa[slot][j + 1], f1_); n3_ = dequant_q4(qb[slot][j + 1], f3_); } \
+            _Pragma("unroll") for (int tt = 0; tt < TT; ++tt) {                                           \
+                G[tt] = mfma32h(a1_, xb_[tt][j], G[tt]);                                                  \
+                U[tt] = mfma32h(a3_, xb_[tt][j], U[tt]);                                                  \
+            }                                                                                             \
+            if (j < 3) {                                                                                  \
+                _Pragma("unroll") for (int q_ = 0; q_ < 2 * TT; ++q_) {                                   \
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                    \
+                    __builtin_amdgcn_sched_group_barrier(0x002, 40 / (2 * TT), 0);                        \
+                }                                                                                         \
+            }                                                                                             \
+            a1_ = n1_; a3_ = n3_;                                                                         \
+        }                                                                                                 \
+    }
+    // one stage: hand the next stage's token fragments to the workgroup, compute this one, refill the
+    // register slot just used, barrier (the next stage's fragments are visible; this stage's LDS
+    // buffer is overwritten three stages from now)
+#define EF_Q4U_STAGE(slot, next_slot, st)                                                                 \
+    {                                                                                                     \
+        EF_Q4U_SHARE(next_slot, (st) + 1)                                                                 \
+        EF_Q4U_COMPUTE(slot, st)                                                                          \
+        EF_Q4U_LOAD(slot, (st) + D)                                                                       \
+        __syncthreads();                                                                                  \
+    }
+    static_assert(D == 6, "the stage sequence below is written out for a ring of six");
+    EF_Q4U_LOAD(0, 0)
+    EF_Q4U_LOAD(1, 1)
+    EF_Q4U_LOAD(2, 2)
+    EF_Q4U_LOAD(3, 3)
+    EF_Q4U_LOAD(4, 4)
+    EF_Q4U_LOAD(5, 5)
+    EF_Q4U_SHARE(0, 0)
+    __syncthreads();
+    int st = 0;
+    for (; st + D <= nq; st += D) {
+        EF_Q4U_STAGE(0, 1, st)
+        EF_Q4U_STAGE(1, 2, st + 1)
+        EF_Q4U_STAGE(2, 3, st + 2)
+        EF_Q4U_STAGE(3, 4, st + 3)
+        EF_Q4U_STAGE(4, 5, st + 4)
+        EF_Q4U_STAGE(5, 0, st + 5)
+    }
+    if (st < nq) EF_Q4U_STAGE(0, 1, st)
+    if (st + 1 < nq) EF_Q4U_STAGE(1, 2, st + 1)
+    if (st + 2 < nq) EF_Q4U_STAGE(2, 3, st + 2)
+    if (st + 3 < nq) EF_Q4U_STAGE(3, 4, st + 3)
+    if (st + 4 < nq) EF_Q4U_STAGE(4, 5, st + 4)
+#undef EF_Q4U_LOAD
+#undef EF_Q4U_SHARE
+#undef EF_Q4U_COMPUTE
+#undef EF_Q4U_STAGE
+
+    // a lane holds 16 F-values of one token: the two paired-order fragments (fp16) the second half consumes
+    const int nkb2 = F >> 4;
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        if (tt >= ntl) break;
+        uint4 *dst = act + gt.act_off[grp] + ((size_t)(pass * TT + tt) * nkb2 + rb * 2) * 64 + lane;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            uint32_t pk[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float g0 = G[tt][8 * s + 2 * q], g1 = G[tt][8 * s + 2 * q + 1];
+                const float v0 = g0 / (1.f + __expf(-g0)) * U[tt][8 * s + 2 * q];
+                const float v1 = g1 / (1.f + __expf(-g1)) * U[tt][8 * s + 2 * q + 1];
+                pk[q] = __builtin_bit_cast(uint32_t, q4_half2{(_Float16)v0, (_Float16)v1});
+            }
+            dst[(size_t)s * 64] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        }
+    }
+}
+
+hipError_t launch_ffn_gate_up_q4(const GroupTable &gt, int total_wgs, int tiles_per_pass, const void *xp, void *act,
+                                 int d, hipStream_t s) {
+    if (total_wgs <= 0) return hipSuccess;
+    if (d % 128 != 0) return hipErrorInvalidValue;
+    for (int i = 0; i < gt.n_groups; ++i)
+        if (gt.F[i] % 128 != 0 || gt.n_tiles[i] <= 0 ||
+            gt.wg_start[i + 1] - gt.wg_start[i] != ffn_gate_up_q4_wgs(gt.F[i], gt.n_tiles[i], tiles_per_pass))
+            return hipErrorInvalidValue;
+    if (gt.wg_start[gt.n_groups] != total_wgs) return hipErrorInvalidValue;
+    const uint4 *x = reinterpret_cast<const uint4 *>(xp);
+    uint4 *a = reinterpret_cast<uint4 *>(act);
+    if (tiles_per_pass == 1) hipLaunchKernelGGL((ffn_gate_up_q4_kernel<1>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
+    else if (tiles_per_pass == 2) hipLaunchKernelGGL((ffn_gate_up_q4_kernel<2>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// second half: Y = act W2^T.  Workgroup = (group, pass of TT token tiles, eight consecutive
+// 32-column blocks of d, one of `ksg` K-slices), wave = two column blocks.  Activations are operand
+// A (rows = tokens), shared through LDS; W2 quads operand B (a lane holds one output column).
+// Each K-slice writes its own partial Y plane; the un-permute sums the planes in order.
+// ------------------------------------------------------------------------------------------
+template <int TT>
+__global__ __launch_bounds__(256, 1) void ffn_down_q4_kernel(GroupTable gt, const uint4 *__restrict__ act,
+                                                             float *__restrict__ Y, int d, int ksg,
+                                                             long long y_plane) {
+    constexpr int D = kQ4Depth, CBW = 2;
+    __shared__ __attribute__((aligned(16))) u32x4_t as[kQ4Lds][TT * 4][64];
+    const int wg = blockIdx.x;
+    int grp = 0;
+    while (grp + 1 < gt.n_groups && gt.wg_start[grp + 1] <= wg) ++grp;
+    const int local = wg - gt.wg_start[grp];
+    const int ncb = d >> 5, ncq = (ncb + 7) >> 3;
+    const int kslice = local % ksg;
+    const int cq = (local / ksg) % ncq, pass = (local / ksg) / ncq;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int cb0 = cq * 8 + wave * CBW;
+    const bool valid = cb0 < ncb;                 // d is a multiple of 64: both column blocks or none
+    const int cbc = valid ? cb0 : 0;              // waves past the last column load block 0 and drop the result
+    const int F = gt.F[grp];
+    const int nkb = F >> 4, nq = F >> 6;
+    const int q0 = (int)((long long)kslice * nq / ksg), q1 = (int)((long long)(kslice + 1) * nq / ksg);
+    int ntl = gt.n_tiles[grp] - pass * TT;
+    if (ntl > TT) ntl = TT;
+
+    const char *blob = reinterpret_cast<const char *>(gt.blob[grp]);
+    const size_t qstride = (size_t)nq * 64, sstride = (size_t)(F >> 7) * 32;
+    const uint4 *w2q = reinterpret_cast<const uint4 *>(blob + (size_t)d * F) + (size_t)cbc * qstride + lane;
+    const uint16_t *sB = reinterpret_cast<const uint16_t *>(blob + (size_t)3 * d * F / 2 + (size_t)d * F / 32) +
+                         (size_t)cbc * sstride + (lane & 31);
+    const uint4 *asrc[TT];
+#pragma unroll
+    for (int u = 0; u < TT; ++u)
+        asrc[u] = act + gt.act_off[grp] + (size_t)(pass * TT + min(u, ntl - 1)) * nkb * 64 + lane;
+
+    floatx16 acc[CBW][TT];
+#pragma unroll
+    for (int cw = 0; cw < CBW; ++cw)
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) zero16(acc[cw][tt]);
+
+    u32x4_t qw[D][CBW], ar[D][TT];
+    uint16_t sc[D][CBW];
+#define EF_Q4D_LOAD(slot, kq)                                                                             \
+    {                                                                                                     \
+        const int kc_ = min((kq), nq - 1);                                                                \
+        _Pragma("unroll") for (int cw = 0; cw < CBW; ++cw) {                                              \
+            qw[slot][cw] = __builtin_nontemporal_load(                                                    \
+                reinterpret_cast<const u32x4_t *>(w2q + cw * qstride + (size_t)kc_ * 64));                \
+            sc[slot][cw] = sB[cw * sstride + (size_t)(kc_ >> 1) * 32];                                    \
+        }                                                                                                 \
+        _Pragma("unroll") for (int u = 0; u < TT; ++u)                                                    \
+            ar[slot][u] = *reinterpret_cast<const u32x4_t *>(asrc[u] + (size_t)(4 * kc_ + wave) * 64);    \
+    }
+#define EF_Q4D_SHARE(slot, st)                                                                            \
+    {                                                                                                     \
+        _Pragma("unroll") for (int u = 0; u < TT; ++u) as[(st) & (kQ4Lds - 1)][u * 4 + wave][lane] = ar[slot][u]; \
+    }
+    // as in the first half: the MFMAs of one weight fragment are issued between the vector
+    // instructions that dequantise the next one
+#define EF_Q4D_COMPUTE(slot, st)                                                                          \
+    {                                                                                                     \
+        u32x4_t af_[TT][4];                                                                               \
+        _Pragma("unroll") for (int tt = 0; tt < TT; ++tt)                                                 \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) af_[tt][j] = as[(st) & (kQ4Lds - 1)][tt * 4 + j][lane]; \
+        q4_half2 f_[CBW];                                                                                 \
+        _Pragma("unroll") for (int cw = 0; cw < CBW; ++cw) f_[cw] = q4_scale(sc[slot][cw]);               \
+        u32x4_t w_ = dequant_q4(qw[slot][0][0], f_[0]);                                                   \
+        _Pragma("unroll") for (int idx = 0; idx < CBW * 4; ++idx) {                                       \
+            const int cw = idx >> 2, j = idx & 3;                                                         \
+            u32x4_t n_ = w_;                                                                              \
+            if (idx + 1 < CBW * 4) n_ = dequant_q4(qw[slot][(idx + 1) >> 2][(idx + 1) & 3], f_[(idx + 1) >> 2]); \
+            _Pragma("unroll") for (int tt = 0; tt < TT; ++tt) acc[cw][tt] = mfma32h(af_[tt][j], w_, acc[cw][tt]); \
+            if (idx + 1 < CBW * 4) {                                                                      \
+                _Pragma("unroll") for (int q_ = 0; q_ < TT; ++q_) {                                       \
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                    \
+                    __builtin_amdgcn_sched_group_barrier(0x002, 20 / TT, 0);                              \
+                }                                                                                         \
+            }                                                                                             \
+            w_ = n_;                                                                                      \
+        }                                                                                                 \
+    }
+#define EF_Q4D_STAGE(slot, next_slot, st)                                                                 \
+    {                                                                                                     \
+        EF_Q4D_SHARE(next_slot, (st) + 1)                                                                 \
+        EF_Q4D_COMPUTE(slot, st)                                                                          \
+        EF_Q4D_LOAD(slot, (st) + D)                                                                       \
+        __syncthreads();                                                                                  \
+    }
+    static_assert(D == 6, "the stage sequence below is written out for a ring of six");
+    EF_Q4D_LOAD(0, q0)
+    EF_Q4D_LOAD(1, q0 + 1)
+    EF_Q4D_LOAD(2, q0 + 2)
+    EF_Q4D_LOAD(3, q0 + 3)
+    EF_Q4D_LOAD(4, q0 + 4)
+    EF_Q4D_LOAD(5, q0 + 5)
+    EF_Q4D_SHARE(0, q0)
+    __syncthreads();
+    int st = q0;
+    for (; st + D <= q1; st += D) {
+        EF_Q4D_STAGE(0, 1, st)
+        EF_Q4D_STAGE(1, 2, st + 1)
+        EF_Q4D_STAGE(2, 3, st + 2)
+        EF_Q4D_STAGE(3, 4, st + 3)
+        EF_Q4D_STAGE(4, 5, st + 4)
+        EF_Q4D_STAGE(5, 0, st + 5)
+    }
+    if (st < q1) EF_Q4D_STAGE(0, 1, st)
+    if (st + 1 < q1) EF_Q4D_STAGE(1, 2, st + 1)
+    if (st + 2 < q1) EF_Q4D_STAGE(2, 3, st + 2)
+    if (st + 3 < q1) EF_Q4D_STAGE(3, 4, st + 3)
+    if (st + 4 < q1) EF_Q4D_STAGE(4, 5, st + 4)
+#undef EF_Q4D_LOAD
+#undef EF_Q4D_SHARE
+#undef EF_Q4D_COMPUTE
+#undef EF_Q4D_STAGE
+
+    if (!valid) return;
+    const int g = lane >> 5;
+    float *Yp = Y + (size_t)kslice * y_plane;
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        if (tt >= ntl) break;
+#pragma unroll
+        for (int cw = 0; cw < CBW; ++cw) {
+            const int col = (cb0 + cw) * 32 + (lane & 31);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int tl = (pass * TT + tt) * kTile + 8 * (v >> 2) + 4 * g + (v & 3);
+                if (tl < gt.count[grp]) Yp[(size_t)(gt.row_offset[grp] + tl) * d + col] = acc[cw][tt][v];
+            }
+        }
+    }
+}
+
+hipError_t launch_ffn_down_q4(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ksg, const void *act,
+                              float *y, long long y_plane, int d, hipStream_t s) {
+    if (total_wgs <= 0) return hipSuccess;
+    if (d % 128 != 0 || ksg < 1) return hipErrorInvalidValue;
+    for (int i = 0; i < gt.n_groups; ++i)
+        if (gt.F[i] % 128 != 0 || gt.n_tiles[i] <= 0 ||
+            gt.wg_start[i + 1] - gt.wg_start[i] != ffn_down_q4_wgs(d, gt.n_tiles[i], tiles_per_pass, ksg))
+            return hipErrorInvalidValue;
+    if (gt.wg_start[gt.n_groups] != total_wgs) return hipErrorInvalidValue;
+    const uint4 *a = reinterpret_cast<const uint4 *>(act);
+    if (tiles_per_pass == 1)
+        hipLaunchKernelGGL((ffn_down_q4_kernel<1>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
+    else if (tiles_per_pass == 2)
+        hipLaunchKernelGGL((ffn_down_q4_kernel<2>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+}  // namespace ef

@@ -79,17 +79,31 @@ hipError_t launch_gate(const GateArgs &a, hipStream_t s);
 hipError_t launch_group(const int32_t *blockcounts, const int32_t *ids, int T, int k, int E, int32_t *blockbase,
                         int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
                         const GroupExport &ex, hipStream_t s);
+// f16: write fp16 instead of bf16 fragments (contexts with 4-bit experts)
 hipError_t launch_pack_x(const PackTable &pt, int total_tiles, const uint16_t *h, int d, int k,
-                         const int32_t *perm, void *xp, hipStream_t s);
+                         const int32_t *perm, void *xp, bool f16, hipStream_t s);
 hipError_t launch_pack_x_dev(const int32_t *counts, const int32_t *offsets, int E, bool has_shared, int T,
                              int max_tiles, const uint16_t *h, int d, int k, const int32_t *perm, void *xp,
-                             hipStream_t s);
-hipError_t launch_ffn_gate_up(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ks, bool q4,
-                              const void *xp, void *act, int d, hipStream_t s);
-hipError_t launch_ffn_down(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ksg, bool q4,
-                           const void *act, float *y, long long y_plane, int d, hipStream_t s);
+                             bool f16, hipStream_t s);
+hipError_t launch_ffn_gate_up(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ks, const void *xp,
+                              void *act, int d, hipStream_t s);
+hipError_t launch_ffn_down(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ksg, const void *act,
+                           float *y, long long y_plane, int d, hipStream_t s);
 hipError_t launch_combine(const float *y, int ksg, long long y_plane, const float *w, const int32_t *inv_perm,
                           int T, int k, int d, long long shared_row0, float *out, hipStream_t s);
+
+// 4-bit expert weights (d and F multiples of 128): a workgroup of the first half takes four 32-row
+// blocks of F, one of the second half eight 32-column blocks of d and one of ksg K-slices
+inline int ffn_gate_up_q4_wgs(int F, int n_tiles, int tiles_per_pass) {
+    return (F / 128) * ((n_tiles + tiles_per_pass - 1) / tiles_per_pass);
+}
+inline int ffn_down_q4_wgs(int d, int n_tiles, int tiles_per_pass, int ksg) {
+    return ((d / 32 + 7) / 8) * ((n_tiles + tiles_per_pass - 1) / tiles_per_pass) * ksg;
+}
+hipError_t launch_ffn_gate_up_q4(const GroupTable &gt, int total_wgs, int tiles_per_pass, const void *xp, void *act,
+                                 int d, hipStream_t s);
+hipError_t launch_ffn_down_q4(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ksg, const void *act,
+                              float *y, long long y_plane, int d, hipStream_t s);
 
 // Dist(t): scratch floats launch_token_dist needs for T tokens (norms, partials, workgroup sums)
 size_t dist_scratch_floats(int T);

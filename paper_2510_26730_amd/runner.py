@@ -30,7 +30,7 @@ class LayerLoop:
     def __init__(self, cfg: synth.MoEShape, n_layers: int, T: int, slots_per_layer: int,
                  pool_slots: int | None = None, store_layers: int = 2, h_max: int = 4, beta: float = 0.0,
                  profile: bool = False, all_resident: bool = False, seed: int = 0,
-                 fixed_estimates: bool = False):
+                 fixed_estimates: bool = False, q4: bool = False):
         self.cfg, self.L, self.T, self.beta = cfg, n_layers, T, beta
         E, k, d = cfg.E, cfg.k, cfg.d
         dev = "cuda"
@@ -40,13 +40,27 @@ class LayerLoop:
         self.ctx = ef.ef_create(n_layers=n_layers, d_model=d, n_experts=E, top_k=k, d_ff=cfg.F,
                                 d_ff_shared=cfg.F_shared, slots_total=slots_total,
                                 slots_per_layer_max=0 if all_resident or pool_slots is not None else slots_per_layer,
-                                max_tokens=T, h_max=h_max, renorm_topk=int(cfg.renorm), flags=flags)
-        self.es = ef.ef_expert_bytes(d, cfg.F)
+                                max_tokens=T, h_max=h_max, renorm_topk=int(cfg.renorm), flags=flags,
+                                weight_bits=4 if q4 else 0)
+        self.q4 = q4
+        self.es = ef.ef_expert_bytes_q4(d, cfg.F) if q4 else ef.ef_expert_bytes(d, cfg.F)
         g = torch.Generator(device=dev)
         g.manual_seed(synth.BASE_SEED * 100 + cfg.cfg_id * 10 + seed)
         self.store_layers = min(store_layers, n_layers)
         self.stores = []
         for _ in range(self.store_layers):
+            if q4:
+                # 4-bit blobs drawn directly in packed order: uniform codes (every byte of the code sections
+                # holds two) and one constant scale, so that (q - 8) * s has the standard deviation w_std
+                st = torch.empty(E * self.es, dtype=torch.uint8, pin_memory=True)
+                ncode = 3 * d * cfg.F // 2
+                scale = torch.full(((self.es - ncode) // 2,), cfg.w_std / 4.61, dtype=torch.bfloat16, device=dev)
+                for e in range(E):
+                    codes = torch.randint(0, 256, (ncode,), generator=g, device=dev, dtype=torch.uint8)
+                    st[e * self.es:e * self.es + ncode].copy_(codes)
+                    st[e * self.es + ncode:(e + 1) * self.es].copy_(scale.view(torch.uint8))
+                self.stores.append(st)
+                continue
             st = torch.empty(E * self.es // 2, dtype=torch.bfloat16, pin_memory=True)
             for e in range(E):           # one expert at a time keeps the device staging buffer small
                 w = torch.randn(self.es // 2, generator=g, device=dev, dtype=torch.float32).mul_(cfg.w_std)
