@@ -52,7 +52,8 @@ __device__ __forceinline__ q4_half2 q4_scale(uint16_t b) {
     return q4_half2{h, h};
 }
 
-constexpr int kQ4Depth = 6;   // register ring: stages in flight per wave
+// register ring: stages in flight per wave (four were measured slower than six with two token tiles per pass)
+template <int TT> constexpr int q4_depth() { return 6; }
 constexpr int kQ4Lds = 4;     // LDS ring of shared token / activation fragments (stages)
 
 // ------------------------------------------------------------------------------------------
@@ -62,7 +63,7 @@ constexpr int kQ4Lds = 4;     // LDS ring of shared token / activation fragments
 template <int TT>
 __global__ __launch_bounds__(256, 1) void ffn_gate_up_q4_kernel(GroupTable gt, const uint4 *__restrict__ xp,
                                                                 uint4 *__restrict__ act, int d) {
-    constexpr int D = kQ4Depth;
+    constexpr int D = q4_depth<TT>();
     __shared__ __attribute__((aligned(16))) u32x4_t xs[kQ4Lds][TT * 4][64];
     const int wg = blockIdx.x;
     int grp = 0;
@@ -145,29 +146,18 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_q4_kernel(GroupTable gt, c
         EF_Q4U_LOAD(slot, (st) + D)                                                                       \
         __syncthreads();                                                                                  \
     }
-    static_assert(D == 6, "the stage sequence below is written out for a ring of six");
-    EF_Q4U_LOAD(0, 0)
-    EF_Q4U_LOAD(1, 1)
-    EF_Q4U_LOAD(2, 2)
-    EF_Q4U_LOAD(3, 3)
-    EF_Q4U_LOAD(4, 4)
-    EF_Q4U_LOAD(5, 5)
+#pragma unroll
+    for (int ring_ = 0; ring_ < D; ++ring_) EF_Q4U_LOAD(ring_, ring_)
     EF_Q4U_SHARE(0, 0)
     __syncthreads();
     int st = 0;
     for (; st + D <= nq; st += D) {
-        EF_Q4U_STAGE(0, 1, st)
-        EF_Q4U_STAGE(1, 2, st + 1)
-        EF_Q4U_STAGE(2, 3, st + 2)
-        EF_Q4U_STAGE(3, 4, st + 3)
-        EF_Q4U_STAGE(4, 5, st + 4)
-        EF_Q4U_STAGE(5, 0, st + 5)
+#pragma unroll
+        for (int ring_ = 0; ring_ < D; ++ring_) EF_Q4U_STAGE(ring_, (ring_ + 1) % D, st + ring_)
     }
-    if (st < nq) EF_Q4U_STAGE(0, 1, st)
-    if (st + 1 < nq) EF_Q4U_STAGE(1, 2, st + 1)
-    if (st + 2 < nq) EF_Q4U_STAGE(2, 3, st + 2)
-    if (st + 3 < nq) EF_Q4U_STAGE(3, 4, st + 3)
-    if (st + 4 < nq) EF_Q4U_STAGE(4, 5, st + 4)
+#pragma unroll
+    for (int ring_ = 0; ring_ < D - 1; ++ring_)
+        if (st + ring_ < nq) EF_Q4U_STAGE(ring_, ring_ + 1, st + ring_)
 #undef EF_Q4U_LOAD
 #undef EF_Q4U_SHARE
 #undef EF_Q4U_COMPUTE
@@ -221,7 +211,7 @@ template <int TT>
 __global__ __launch_bounds__(256, 1) void ffn_down_q4_kernel(GroupTable gt, const uint4 *__restrict__ act,
                                                              float *__restrict__ Y, int d, int ksg,
                                                              long long y_plane) {
-    constexpr int D = kQ4Depth, CBW = 2;
+    constexpr int D = q4_depth<TT>(), CBW = 2;
     __shared__ __attribute__((aligned(16))) u32x4_t as[kQ4Lds][TT * 4][64];
     const int wg = blockIdx.x;
     int grp = 0;
@@ -304,29 +294,18 @@ __global__ __launch_bounds__(256, 1) void ffn_down_q4_kernel(GroupTable gt, cons
         EF_Q4D_LOAD(slot, (st) + D)                                                                       \
         __syncthreads();                                                                                  \
     }
-    static_assert(D == 6, "the stage sequence below is written out for a ring of six");
-    EF_Q4D_LOAD(0, q0)
-    EF_Q4D_LOAD(1, q0 + 1)
-    EF_Q4D_LOAD(2, q0 + 2)
-    EF_Q4D_LOAD(3, q0 + 3)
-    EF_Q4D_LOAD(4, q0 + 4)
-    EF_Q4D_LOAD(5, q0 + 5)
+#pragma unroll
+    for (int ring_ = 0; ring_ < D; ++ring_) EF_Q4D_LOAD(ring_, q0 + ring_)
     EF_Q4D_SHARE(0, q0)
     __syncthreads();
     int st = q0;
     for (; st + D <= q1; st += D) {
-        EF_Q4D_STAGE(0, 1, st)
-        EF_Q4D_STAGE(1, 2, st + 1)
-        EF_Q4D_STAGE(2, 3, st + 2)
-        EF_Q4D_STAGE(3, 4, st + 3)
-        EF_Q4D_STAGE(4, 5, st + 4)
-        EF_Q4D_STAGE(5, 0, st + 5)
+#pragma unroll
+        for (int ring_ = 0; ring_ < D; ++ring_) EF_Q4D_STAGE(ring_, (ring_ + 1) % D, st + ring_)
     }
-    if (st < q1) EF_Q4D_STAGE(0, 1, st)
-    if (st + 1 < q1) EF_Q4D_STAGE(1, 2, st + 1)
-    if (st + 2 < q1) EF_Q4D_STAGE(2, 3, st + 2)
-    if (st + 3 < q1) EF_Q4D_STAGE(3, 4, st + 3)
-    if (st + 4 < q1) EF_Q4D_STAGE(4, 5, st + 4)
+#pragma unroll
+    for (int ring_ = 0; ring_ < D - 1; ++ring_)
+        if (st + ring_ < q1) EF_Q4D_STAGE(ring_, ring_ + 1, st + ring_)
 #undef EF_Q4D_LOAD
 #undef EF_Q4D_SHARE
 #undef EF_Q4D_COMPUTE
