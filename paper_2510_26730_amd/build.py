@@ -25,11 +25,23 @@ def is_stale() -> bool:
 
 
 def build(force: bool = True, extra_flags=()) -> str:
-    """Compile every HIP source for gfx950 and link the shared library."""
+    """Compile every HIP source for gfx950 (one compiler process per source, in parallel) and link the
+    shared library."""
     if not force and not is_stale():
         return LIB
-    cmd = [HIPCC, *FLAGS, *extra_flags, "-o", LIB] + [os.path.join(CSRC, f) for f in SOURCES]
-    subprocess.check_call(cmd)
+    from concurrent.futures import ThreadPoolExecutor
+    obj_dir = os.path.join(HERE, "_build")
+    os.makedirs(obj_dir, exist_ok=True)
+    compile_flags = [f for f in FLAGS if f != "-shared"]
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
+        subprocess.check_call([HIPCC, *compile_flags, *extra_flags, "-c", "-o", obj, os.path.join(CSRC, src)])
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1)) as ex:
+        objs = list(ex.map(compile_one, SOURCES))
+    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread", "-o", LIB, *objs])
     return LIB
 
 
