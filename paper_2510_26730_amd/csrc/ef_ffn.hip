@@ -43,11 +43,14 @@ __global__ __launch_bounds__(256) void pack_x_kernel(PackTable pt, const uint16_
     const uint4 *src = reinterpret_cast<const uint4 *>(h + (size_t)token * d);
     const int nkb = d >> 4;
     uint4 *dst = xp + (size_t)tile * nkb * 64 + lane;
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
     const int kb0 = blockIdx.y * kb_per_wg;
     const int kb1 = min(nkb, kb0 + kb_per_wg);
+    // Rows past the group's count are left as they are: every FFN kernel keeps tokens in separate
+    // operand columns (rows), so whatever such a row holds only reaches outputs that are never
+    // written.  Groups of a few tokens would otherwise spend most of this kernel storing zeros.
+    if (!valid) return;
     for (int kb = kb0 + wave; kb < kb1; kb += 4) {
-        uint4 v = valid ? src[kb * 2 + g] : zero4;
+        const uint4 v = src[kb * 2 + g];
         dst[(size_t)kb * 64] = f16 ? bf16x8_to_f16x8(v) : v;
     }
 }
@@ -76,12 +79,20 @@ __global__ __launch_bounds__(256) void pack_x_dev_kernel(const int32_t *__restri
                                                          const int32_t *__restrict__ perm, uint4 *__restrict__ xp,
                                                          int kb_per_wg, int f16) {
     const int tile = blockIdx.x;
-    int first = 0, grp = -1;
-    for (int e = 0; e < E; ++e) {
-        const int nt = (counts[e] + kTile - 1) / kTile;
-        if (tile < first + nt) { grp = e; break; }
-        first += nt;
+    // every wave finds the tile's group on its own: lane e holds the tile count of expert e (E <= 64), an
+    // inclusive scan across the lanes gives the first tile after each expert, a ballot the expert
+    const int ln = threadIdx.x & 63;
+    const int my_nt = ln < E ? (counts[ln] + kTile - 1) / kTile : 0;
+    int incl = my_nt;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(incl, off);
+        if (ln >= off) incl += o;
     }
+    const unsigned long long owns = __ballot(ln < E && tile >= incl - my_nt && tile < incl);
+    const int routed_tiles = __shfl(incl, 63);
+    const int grp = owns ? __ffsll((long long)owns) - 1 : -1;
+    const int first = grp >= 0 ? __shfl(incl - my_nt, grp) : routed_tiles;
     int count, row_offset;
     if (grp >= 0) {
         count = counts[grp];
@@ -101,11 +112,14 @@ __global__ __launch_bounds__(256) void pack_x_dev_kernel(const int32_t *__restri
     const uint4 *src = reinterpret_cast<const uint4 *>(h + (size_t)token * d);
     const int nkb = d >> 4;
     uint4 *dst = xp + (size_t)tile * nkb * 64 + lane;
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
     const int kb0 = blockIdx.y * kb_per_wg;
     const int kb1 = min(nkb, kb0 + kb_per_wg);
+    // Rows past the group's count are left as they are: every FFN kernel keeps tokens in separate
+    // operand columns (rows), so whatever such a row holds only reaches outputs that are never
+    // written.  Groups of a few tokens would otherwise spend most of this kernel storing zeros.
+    if (!valid) return;
     for (int kb = kb0 + wave; kb < kb1; kb += 4) {
-        uint4 v = valid ? src[kb * 2 + g] : zero4;
+        const uint4 v = src[kb * 2 + g];
         dst[(size_t)kb * 64] = f16 ? bf16x8_to_f16x8(v) : v;
     }
 }

@@ -445,6 +445,23 @@ __device__ __forceinline__ int scan_expert(const int32_t *__restrict__ bc, int n
     return carry;
 }
 
+// the same scan on counts already in LDS, in place: counts[b*E + e] becomes the exclusive prefix
+__device__ __forceinline__ int scan_expert_inplace(int *cnt, int ntiles, int E, int e, int lane) {
+    int carry = 0;
+    for (int c0 = 0; c0 < ntiles; c0 += 64) {
+        const int b = c0 + lane;
+        const int v = b < ntiles ? cnt[b * E + e] : 0;
+        int incl = v;
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(incl, off);
+            if (lane >= off) incl += o;
+        }
+        if (b < ntiles) cnt[b * E + e] = carry + incl - v;
+        carry += __shfl(incl, 63);
+    }
+    return carry;
+}
+
 // one wave: stable scatter of the assignments of token tile b
 __device__ __forceinline__ void scatter_tile(const int32_t *__restrict__ ids, int T, int k, int E, int b, int lane,
                                              int next, int32_t *__restrict__ perm,
@@ -532,21 +549,31 @@ __global__ __launch_bounds__(1024) void group_small_kernel(const int32_t *__rest
     __shared__ int total[kMaxE];
     __shared__ int offs[kMaxE + 1];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // one memory round trip brings the per-tile counts into LDS; the scans then run from there, in place
+    for (int x = threadIdx.x; x < ntiles * E; x += blockDim.x) base[x] = bc[x];
+    __syncthreads();
     for (int e = wave; e < E; e += 16) {
-        int tot = scan_expert(bc, ntiles, E, e, lane, base);
+        int tot = scan_expert_inplace(base, ntiles, E, e, lane);
         if (lane == 0) total[e] = tot;
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        int run = 0;
-        for (int e = 0; e < E; ++e) {
-            counts[e] = total[e];
-            offsets[e] = run;
-            offs[e] = run;
-            run += total[e];
+    if (wave == 0) {   // exclusive scan of the E <= 64 totals across the lanes of one wave
+        const int t = lane < E ? total[lane] : 0;
+        int incl = t;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(incl, off);
+            if (lane >= off) incl += o;
         }
-        offsets[E] = run;
-        offs[E] = run;
+        if (lane < E) {
+            counts[lane] = t;
+            offsets[lane] = incl - t;
+            offs[lane] = incl - t;
+        }
+        if (lane == 63) {
+            offsets[E] = incl;
+            offs[E] = incl;
+        }
     }
     __syncthreads();
     export_meta(ex, total, E);   // the host starts planning while the scatter below still runs
