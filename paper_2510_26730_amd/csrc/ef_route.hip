@@ -462,34 +462,37 @@ __device__ __forceinline__ int scan_expert_inplace(int *cnt, int ntiles, int E, 
     return carry;
 }
 
-// one wave: stable scatter of the assignments of token tile b
-__device__ __forceinline__ void scatter_tile(const int32_t *__restrict__ ids, int T, int k, int E, int b, int lane,
-                                             int next, int32_t *__restrict__ perm,
+// one wave: stable scatter of the assignments of token tile b.  nxt [64] (LDS, this wave's own) holds
+// the next free position of every expert for this tile.  Per chunk of 64 assignments the lanes with
+// the same expert are found with six ballots (one per bit of the expert id, E <= 64): a lane's
+// position is its expert's next free one plus the number of lower lanes with the same expert, and
+// the lowest such lane advances the expert's entry.  LDS operations of one wave execute in order,
+// so the chunks need no barrier between them.
+__device__ __forceinline__ void scatter_tile(const int32_t *__restrict__ ids, int T, int k, int b, int lane,
+                                             int *nxt, int32_t *__restrict__ perm,
                                              int32_t *__restrict__ inv_perm) {
     const int tok0 = b * kTile;
     const int ntok = min(kTile, T - tok0);
     const int a0 = tok0 * k, n = ntok * k;
-    // lane e keeps the next free position of expert e for this tile in `next`
     for (int c0 = 0; c0 < n; c0 += 64) {
         const int idx = c0 + lane;
         const bool valid = idx < n;
         const int e = valid ? ids[a0 + idx] : 0;
-        unsigned long long todo = __ballot(valid);
-        int pos = 0;
-        while (todo) {
-            const int leader = __ffsll((long long)todo) - 1;
-            const int le = __shfl(e, leader);
-            const bool mine = valid && e == le;
-            const unsigned long long m = __ballot(mine);
-            const int start = __shfl(next, le);
-            if (mine) pos = start + __popcll(m & ((1ull << lane) - 1ull));
-            if (lane == le) next += __popcll(m);
-            todo &= ~m;
+        unsigned long long same = __ballot(valid);
+#pragma unroll
+        for (int bit = 0; bit < 6; ++bit) {
+            const bool set = (e >> bit) & 1;
+            const unsigned long long bb = __ballot(valid && set);
+            same &= set ? bb : ~bb;
         }
         if (valid) {
+            const int pos = nxt[e] + __popcll(same & ((1ull << lane) - 1ull));
             perm[pos] = a0 + idx;
             inv_perm[a0 + idx] = pos;
         }
+        wave_lds_sync();
+        if (valid && (same & ((1ull << lane) - 1ull)) == 0) nxt[e] += __popcll(same);   // lowest lane of its expert
+        wave_lds_sync();
     }
 }
 
@@ -533,9 +536,11 @@ __global__ __launch_bounds__(64) void group_scatter_kernel(const int32_t *__rest
                                                            const int32_t *__restrict__ offsets,
                                                            int32_t *__restrict__ perm,
                                                            int32_t *__restrict__ inv_perm) {
+    __shared__ int nxt[64];
     const int b = blockIdx.x, lane = threadIdx.x;
-    int next = (lane < E) ? offsets[lane] + blockbase[(size_t)b * E + lane] : 0;
-    scatter_tile(ids, T, k, E, b, lane, next, perm, inv_perm);
+    nxt[lane] = (lane < E) ? offsets[lane] + blockbase[(size_t)b * E + lane] : 0;
+    wave_lds_sync();
+    scatter_tile(ids, T, k, b, lane, nxt, perm, inv_perm);
 }
 
 // scan + scatter in one workgroup for up to kGroupSmallTiles token tiles (prefixes stay in LDS)
@@ -548,6 +553,7 @@ __global__ __launch_bounds__(1024) void group_small_kernel(const int32_t *__rest
     __shared__ int base[kGroupSmallTiles * kMaxE];
     __shared__ int total[kMaxE];
     __shared__ int offs[kMaxE + 1];
+    __shared__ int nxt[16][64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     // one memory round trip brings the per-tile counts into LDS; the scans then run from there, in place
     for (int x = threadIdx.x; x < ntiles * E; x += blockDim.x) base[x] = bc[x];
@@ -578,8 +584,9 @@ __global__ __launch_bounds__(1024) void group_small_kernel(const int32_t *__rest
     __syncthreads();
     export_meta(ex, total, E);   // the host starts planning while the scatter below still runs
     for (int b = wave; b < ntiles; b += 16) {
-        int next = (lane < E) ? offs[lane] + base[b * E + lane] : 0;
-        scatter_tile(ids, T, k, E, b, lane, next, perm, inv_perm);
+        nxt[wave][lane] = (lane < E) ? offs[lane] + base[b * E + lane] : 0;
+        wave_lds_sync();
+        scatter_tile(ids, T, k, b, lane, nxt[wave], perm, inv_perm);
     }
 }
 
