@@ -27,7 +27,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0          # dense bf16, no structured sparsity
 WORKLOADS = {
     "mixtral_decode": ("mixtral_decode", 64, 16.0),
     "mixtral_prefill": ("mixtral_prefill", 8192, 0.0),
-    "deepseek_v2_lite": ("deepseek_v2_lite", 32, 4.0),
+    "deepseek_v2_lite": ("deepseek_v2_lite", 32, 6.0),
     "qwen15_moe": ("qwen15_moe", 640, 8.0),
     "tiny": ("tiny", 64, 0.5),
 }
