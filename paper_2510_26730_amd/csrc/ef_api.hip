@@ -502,9 +502,9 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
     const size_t act_bytes = (size_t)routed_tiles * ef::kTile * g.d_ff * 2 +
                              (size_t)shared_tiles * ef::kTile * g.d_ff_shared * 2;
     // expert outputs: one plane of (T*k [+T]) x d floats, times up to 8 K-slice planes while that stays
-    // under 64 MiB (small batches split K of the second FFN half across workgroups)
+    // under 256 MiB (small batches split K of the second FFN half across workgroups)
     const long long y_plane_max = (Tm * k + (g.d_ff_shared > 0 ? Tm : 0)) * d;
-    long long planes = std::max(1ll, std::min(8ll, (16ll << 20) / y_plane_max));
+    long long planes = std::max(1ll, std::min(8ll, (64ll << 20) / y_plane_max));
     c->y_floats = y_plane_max * planes;
     const size_t y_bytes = (size_t)c->y_floats * 4;
 
@@ -836,7 +836,7 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
     // weight-streaming kernels; at most two launches per FFN half
     ef::GroupTable gu{}, big{};
     int n = 0, nb = 0, max_tiles = 1;
-    const bool allow_tiled = use_tiled && ksg == 1;
+    const bool allow_tiled = use_tiled;
     for (const PhaseGroup &pg : groups) {
         int cnt, ts, F, ro;
         long long ao;
@@ -875,7 +875,7 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
             big.wg_start[i] = wg_up;
             bdn.wg_start[i] = wg_dn;
             wg_up += ef::ffn_gate_up_tiled_wgs(big.F[i], big.n_tiles[i]);
-            wg_dn += ef::ffn_down_tiled_wgs(d, big.n_tiles[i]);
+            wg_dn += ef::ffn_down_tiled_wgs(d, big.n_tiles[i]) * ksg;
         }
         big.wg_start[nb] = wg_up;
         bdn.wg_start[nb] = wg_dn;
@@ -891,7 +891,7 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
         }
         {
             KernelTimer kt(c, s, EF_K_FFN_DOWN_TILED, b_dn, f_dn);
-            EF_HIP(c, ef::launch_ffn_down_tiled(bdn, wg_dn, c->act, c->y, d, s));
+            EF_HIP(c, ef::launch_ffn_down_tiled(bdn, wg_dn, ksg, c->act, c->y, y_plane, d, s));
         }
     }
     if (n == 0) return EF_OK;
@@ -984,6 +984,8 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
     // with a 2048 x 5632 shared expert, 1056 tokens over 64 experts) the tiled kernels were equal to or
     // 8 % faster than streaming the same groups in several passes, even at 150-200 workgroups.
     bool use_tiled = false;
+    long long tiled_dn_wgs = 0;
+    int tiled_stages_min = 1 << 30;   // fewest K stages (32 columns each) among the tiled groups
     if (T > 0 && !c->q4 && tune("EF_TUNE_TILED", 1) != 0) {
         long long wg_up = 0, wg_dn = 0;
         auto add = [&](int F, int cnt) {
@@ -991,10 +993,12 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
             if (!ef::ffn_tiled_ok(d, F, nt)) return;
             wg_up += ef::ffn_gate_up_tiled_wgs(F, nt);
             wg_dn += ef::ffn_down_tiled_wgs(d, nt);
+            tiled_stages_min = std::min(tiled_stages_min, F / 32);
         };
         for (int e = 0; e < E; ++e) add(c->cfg.d_ff, counts_host[e]);
         if (has_shared) add(c->cfg.d_ff_shared, T);
         use_tiled = wg_up >= tune("EF_TUNE_TILED_MIN_UP", 1) && wg_dn >= tune("EF_TUNE_TILED_MIN_DOWN", 1);
+        tiled_dn_wgs = wg_dn;
     }
     int ksg = 1;
     if (T > 0) {
@@ -1015,7 +1019,14 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         const int units = c->q4 ? nkb_min / 4 / 6 : nkb_min / 4 / 32;
         while (ksg < 8 && base_wgs * ksg < want && units / (ksg * 2) >= 1 && y_plane * (ksg * 2) <= c->y_floats)
             ksg *= 2;
-        if (use_tiled) ksg = 1;   // the tiled kernels write plane 0 only
+        if (use_tiled) {
+            // the tiled second half decides: slices until its 256 x 256 tiles fill the chip, each slice
+            // keeping at least 16 stages; the streamed groups of the layer write the same planes
+            ksg = 1;
+            while (ksg < 8 && tiled_dn_wgs * ksg < 256 && tiled_stages_min / (ksg * 2) >= 16 &&
+                   y_plane * (ksg * 2) <= c->y_floats)
+                ksg *= 2;
+        }
         int forced = tune("EF_TUNE_DOWN_KSG", ksg);
         if (forced >= 1 && forced <= 8 && y_plane * forced <= c->y_floats) ksg = forced;
     }

@@ -185,7 +185,8 @@ hipError_t launch_ffn_gate_up_tiled(const GroupTable &gt, int total_wgs, const v
 // operand B slots 8..15 = W2 fragments of column blocks cb0..cb0+7
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, const uint4 *__restrict__ act,
-                                                                 float *__restrict__ Y, int d) {
+                                                                 float *__restrict__ Y, int d, int ksg,
+                                                                 long long y_plane) {
     __shared__ __attribute__((aligned(16))) u32x4_t lds[kTileStages][kStageFrags][64];
     const int wg = blockIdx.x;
     int grp = 0;
@@ -194,14 +195,18 @@ __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, c
     const int F = gt.F[grp];
     const int ntiles = gt.n_tiles[grp];
     const int mpanels = (ntiles + 7) >> 3;
+    // K slices across workgroups (one Y plane each, summed by the un-permute) when the tiles alone
+    // would leave most of the chip idle; neighbouring workgroups take the slices of one tile
+    const int kslice = local % ksg;
     int np, mp;
-    if (!tiled_panel(local, d >> 8, mpanels, np, mp)) return;
+    if (!tiled_panel(local / ksg, d >> 8, mpanels, np, mp)) return;
     const int cb0 = np * 8, t0 = mp * 8;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS DMA targets go through M0
     const int wc = wave & 1, wt = wave >> 1;
     const int nkb = F >> 4;
     const int nstage = nkb / kTileKS;
+    const int s0 = (int)((long long)kslice * nstage / ksg), s1 = (int)((long long)(kslice + 1) * nstage / ksg);
 
     const u32x4_t *src[kStageFrags / 4];
 #pragma unroll
@@ -259,13 +264,13 @@ __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, c
     __builtin_amdgcn_sched_barrier(0);
     static_assert(kTileKS == 2, "the loop below alternates two fragment register sets");
     u32x4_t a0[4], b0[4], a1[4], b1[4];
-    EF_TILED_ISSUE(0)
-    EF_TILED_ISSUE(1)
-    EF_TILED_ISSUE(2)
-    __builtin_amdgcn_s_waitcnt(kWaitVm16);   // my part of stage 0 has landed
+    EF_TILED_ISSUE(s0)
+    EF_TILED_ISSUE(s0 + 1)
+    EF_TILED_ISSUE(s0 + 2)
+    __builtin_amdgcn_s_waitcnt(kWaitVm16);   // my part of the first stage has landed
     __syncthreads();                         // ... and everybody else's
-    EF_TILED_READ(a0, b0, 0, 0)
-    for (int st = 0; st < nstage; ++st) {
+    EF_TILED_READ(a0, b0, s0 & (kTileStages - 1), 0)
+    for (int st = s0; st < s1; ++st) {
         const int cur = st & (kTileStages - 1), nxt = (st + 1) & (kTileStages - 1);
         EF_TILED_STEP(a0, b0, a1, b1, cur, 1)
         // stage st+1 must have landed: of the loads issued so far (stages st+1, st+2) at most the
@@ -282,6 +287,7 @@ __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, c
 #undef EF_TILED_ISSUE
 
     const int g = lane >> 5;
+    float *Yp = Y + (size_t)kslice * y_plane;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int tile = t0 + wt * 4 + i;
@@ -292,22 +298,23 @@ __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, c
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int tl = tile * kTile + 8 * (v >> 2) + 4 * g + (v & 3);
-                if (tl < gt.count[grp]) Y[(size_t)(gt.row_offset[grp] + tl) * d + col] = acc[i][j][v];
+                if (tl < gt.count[grp]) Yp[(size_t)(gt.row_offset[grp] + tl) * d + col] = acc[i][j][v];
             }
         }
     }
 }
 
-hipError_t launch_ffn_down_tiled(const GroupTable &gt, int total_wgs, const void *act, float *y, int d,
-                                 hipStream_t s) {
+hipError_t launch_ffn_down_tiled(const GroupTable &gt, int total_wgs, int ksg, const void *act, float *y,
+                                 long long y_plane, int d, hipStream_t s) {
     if (total_wgs <= 0) return hipSuccess;
+    if (ksg < 1) return hipErrorInvalidValue;
     for (int i = 0; i < gt.n_groups; ++i)
-        if (gt.wg_start[i + 1] - gt.wg_start[i] != ffn_down_tiled_wgs(d, gt.n_tiles[i]) ||
+        if (gt.wg_start[i + 1] - gt.wg_start[i] != ffn_down_tiled_wgs(d, gt.n_tiles[i]) * ksg ||
             !ffn_tiled_ok(d, gt.F[i], gt.n_tiles[i]))
             return hipErrorInvalidValue;
     if (gt.wg_start[gt.n_groups] != total_wgs) return hipErrorInvalidValue;
     hipLaunchKernelGGL(ffn_down_tiled_kernel, dim3(total_wgs), dim3(256), 0, s, gt,
-                       reinterpret_cast<const uint4 *>(act), y, d);
+                       reinterpret_cast<const uint4 *>(act), y, d, ksg, y_plane);
     return hipGetLastError();
 }
 
