@@ -20,7 +20,7 @@ constexpr int kTileStages = 4;           // LDS stage buffers (power of two)
 // s_waitcnt immediate "vmcnt <= 16, do not wait on expcnt / lgkmcnt" (gfx9 encoding: vmcnt[3:0] in bits
 // 3:0 and vmcnt[5:4] in bits 15:14, expcnt in 6:4, lgkmcnt in 11:8)
 constexpr int kWaitVm16 = (1 << 14) | (0x7 << 4) | (0xF << 8) | 0;
-constexpr int kWaitVm8 = (0 << 14) | (0x7 << 4) | (0xF << 8) | 8;
+constexpr int kWaitVm12 = (0 << 14) | (0x7 << 4) | (0xF << 8) | 12;
 static_assert(kStageFrags / 4 == 8, "the wait count assumes 8 loads per wave per stage");
 
 // Index of a workgroup within its group -> (weight panel np, token panel mp).  Workgroups with the
@@ -35,6 +35,86 @@ __device__ __forceinline__ bool tiled_panel(int local, int npanels, int mpanels,
     mp = jj % mpanels;
     return np < npanels;
 }
+
+// ------------------------------------------------------------------------------------------
+// The LDS pipeline shared by both kernels (they name their locals alike: lds, src, acc, wave, lane,
+// nstage, AOFF, BOFF).
+//
+// A direct global -> LDS load of 64 lanes x 16 bytes into LDS byte offset `lds_off` (wave-uniform,
+// passed through M0).  It is issued as inline assembly: the compiler then keeps it where the source
+// puts it relative to the LDS reads and adds no waits of its own for it, so every vmcnt wait on these
+// loads in this file is explicit.
+#define EF_TILED_DMA(gptr, lds_off)                                                                  \
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_off) : "memory")
+// LDS byte offset of fragment slot q*4 + wave of the buffer of stage st
+#define EF_TILED_DST(st, q) (lds_base + ((((st) & (kTileStages - 1)) * kStageFrags + (q) * 4 + wave) << 10))
+// all of a wave's loads of one stage in a burst (prologue only).  Every wave issues kStageFrags/4 loads
+// per stage, unconditionally (past the end the last stage is re-read, in bounds), so "my loads of
+// stage st have landed" is a constant wait count.
+#define EF_TILED_ISSUE(st)                                                                           \
+    {                                                                                                \
+        const int stc_ = min((st), nstage - 1);                                                      \
+        _Pragma("unroll") for (int q = 0; q < kStageFrags / 4; ++q)                                  \
+            EF_TILED_DMA(src[q] + (size_t)stc_ * kTileKS * 64, EF_TILED_DST(st, q));                 \
+    }
+#define EF_TILED_READ(a, b, cur, ks)                                                              \
+    {                                                                                                \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) a[i] = lds[cur][(ks) * 16 + AOFF + i][lane];     \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) b[j] = lds[cur][(ks) * 16 + 8 + BOFF + j][lane]; \
+    }
+// One k-step: 16 MFMAs on the current fragments (ac, bc) while the 8 fragments of the next k-step are
+// read from LDS into (an, bn) and half of the wave's loads of stage `st` are issued: four rounds of
+// four MFMAs with an LDS read after the first, second and fourth (the eight reads fill the first ten
+// MFMA slots, so the last one is issued six MFMAs before the next k-step waits for it) and a
+// global -> LDS load after the third.  A wave that issues its loads in a burst stalls at the issue
+// until the CU's address path (about 64 bytes per clock) has taken them, and its matrix core idles
+// meanwhile; one load per four MFMAs (128 clocks, four waves) stays below that rate.
+#define EF_TILED_RA(an, buf, ks, r) an[r] = lds[buf][(ks) * 16 + AOFF + (r)][lane];
+#define EF_TILED_RB(bn, buf, ks, r) bn[r] = lds[buf][(ks) * 16 + 8 + BOFF + (r)][lane];
+#define EF_TILED_ROUND(ac, bc, r, x0, x1, x3, st, half)                                              \
+    acc[r][0] = mfma32v(ac[r], bc[0], acc[r][0]);                                                    \
+    x0 __builtin_amdgcn_sched_barrier(0);                                                            \
+    acc[r][1] = mfma32v(ac[r], bc[1], acc[r][1]);                                                    \
+    x1 __builtin_amdgcn_sched_barrier(0);                                                            \
+    acc[r][2] = mfma32v(ac[r], bc[2], acc[r][2]);                                                    \
+    EF_TILED_DMA(src[(half) * 4 + (r)] + (size_t)stc_ * kTileKS * 64, EF_TILED_DST(st, (half) * 4 + (r))); \
+    __builtin_amdgcn_sched_barrier(0);                                                               \
+    acc[r][3] = mfma32v(ac[r], bc[3], acc[r][3]);                                                    \
+    x3 __builtin_amdgcn_sched_barrier(0);
+#define EF_TILED_STEP(ac, bc, an, bn, buf, ks, st, half)                                             \
+    {                                                                                                \
+        const int stc_ = min((st), nstage - 1);                                                      \
+        EF_TILED_ROUND(ac, bc, 0, EF_TILED_RA(an, buf, ks, 0), EF_TILED_RB(bn, buf, ks, 0),          \
+                       EF_TILED_RA(an, buf, ks, 1), st, half)                                        \
+        EF_TILED_ROUND(ac, bc, 1, EF_TILED_RB(bn, buf, ks, 1), EF_TILED_RA(an, buf, ks, 2),          \
+                       EF_TILED_RB(bn, buf, ks, 2), st, half)                                        \
+        EF_TILED_ROUND(ac, bc, 2, EF_TILED_RA(an, buf, ks, 3), EF_TILED_RB(bn, buf, ks, 3), , st, half) \
+        EF_TILED_ROUND(ac, bc, 3, , , , st, half)                                                    \
+    }
+// The main loop over stages [first, last): stage st feeds the matrix cores while the loads of stages
+// st+1 and st+2 are in flight and those of stage st+3 are being issued; one barrier per stage.
+#define EF_TILED_PIPELINE(first, last)                                                               \
+    static_assert(kTileKS == 2, "the loop alternates two fragment register sets");                   \
+    u32x4_t a0[4], b0[4], a1[4], b1[4];                                                              \
+    EF_TILED_ISSUE(first)                                                                            \
+    EF_TILED_ISSUE((first) + 1)                                                                      \
+    EF_TILED_ISSUE((first) + 2)                                                                      \
+    __builtin_amdgcn_s_waitcnt(kWaitVm16); /* my part of the first stage has landed */               \
+    __syncthreads();                       /* ... and everybody else's */                            \
+    EF_TILED_READ(a0, b0, (first) & (kTileStages - 1), 0)                                            \
+    for (int st = (first); st < (last); ++st) {                                                      \
+        const int cur = st & (kTileStages - 1), nxt = (st + 1) & (kTileStages - 1);                  \
+        /* the buffer of stage st+3 held stage st-1, whose last reads every wave finished before */  \
+        /* the barrier of the previous iteration */                                                  \
+        EF_TILED_STEP(a0, b0, a1, b1, cur, 1, st + 3, 0)                                             \
+        /* stage st+1 must have landed: of the loads issued after it (stage st+2 and half of */      \
+        /* stage st+3) all 12 may still be outstanding */                                            \
+        __builtin_amdgcn_s_waitcnt(kWaitVm12);                                                       \
+        __syncthreads();                                                                             \
+        __builtin_amdgcn_sched_barrier(0);                                                           \
+        EF_TILED_STEP(a1, b1, a0, b0, nxt, 0, st + 3, 1)                                             \
+    }                                                                                                \
+    __builtin_amdgcn_s_waitcnt(0);
 
 // ------------------------------------------------------------------------------------------
 // first half, tiled: act = silu(X W1^T) * (X W3^T) for (group, 4 row blocks, 8 token tiles)
@@ -84,60 +164,8 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_tiled_kernel(GroupTable gt
         for (int j = 0; j < 4; ++j) zero16(acc[i][j]);
 
     const int AOFF = wf * 4, BOFF = wt * 4;
-    // Four LDS stage buffers filled by direct global -> LDS loads (no register staging): stages st+1,
-    // st+2 and st+3 are in flight while stage st feeds the matrix cores; one barrier per stage.
-    // Every wave issues kStageFrags/4 loads per stage, unconditionally (past the end the last stage
-    // is re-read, in bounds), so "my loads of stage st have landed" is a constant wait count.
-#define EF_TILED_ISSUE(st)                                                                           \
-    {                                                                                                \
-        const int stc_ = min((st), nstage - 1);                                                      \
-        const int buf_ = (st) & (kTileStages - 1);                                                   \
-        _Pragma("unroll") for (int q = 0; q < kStageFrags / 4; ++q)                                  \
-            __builtin_amdgcn_global_load_lds(src[q] + (size_t)stc_ * kTileKS * 64,                   \
-                                             &lds[buf_][q * 4 + wave][0], 16, 0, 0);                 \
-    }
-#define EF_TILED_READ(a, b, cur, ks)                                                              \
-    {                                                                                                \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) a[i] = lds[cur][(ks) * 16 + AOFF + i][lane];     \
-        _Pragma("unroll") for (int j = 0; j < 4; ++j) b[j] = lds[cur][(ks) * 16 + 8 + BOFF + j][lane]; \
-    }
-    // one k-step: 16 MFMAs on the current fragments while the 8 fragments of the next k-step are
-    // read from LDS, scheduled as 2 MFMAs, (1 LDS read, 1 MFMA) x 8, 6 MFMAs: no burst on either pipe,
-    // and the last read is issued six MFMAs before the next k-step needs the fragments
-#define EF_TILED_STEP(ac, bc, an, bn, buf, ks)                                                       \
-    EF_TILED_READ(an, bn, buf, ks)                                                                   \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                    \
-        _Pragma("unroll") for (int j = 0; j < 4; ++j) acc[i][j] = mfma32v(ac[i], bc[j], acc[i][j]);  \
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                               \
-    _Pragma("unroll") for (int r_ = 0; r_ < 8; ++r_) {                                               \
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                           \
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                           \
-    }                                                                                                \
-    __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);                                               \
-    __builtin_amdgcn_sched_barrier(0);
-    static_assert(kTileKS == 2, "the loop below alternates two fragment register sets");
-    u32x4_t a0[4], b0[4], a1[4], b1[4];
-    EF_TILED_ISSUE(0)
-    EF_TILED_ISSUE(1)
-    EF_TILED_ISSUE(2)
-    __builtin_amdgcn_s_waitcnt(kWaitVm16);   // my part of stage 0 has landed
-    __syncthreads();                         // ... and everybody else's
-    EF_TILED_READ(a0, b0, 0, 0)
-    for (int st = 0; st < nstage; ++st) {
-        const int cur = st & (kTileStages - 1), nxt = (st + 1) & (kTileStages - 1);
-        EF_TILED_STEP(a0, b0, a1, b1, cur, 1)
-        // stage st+1 must have landed: of the loads issued so far (stages st+1, st+2) at most the
-        // 8 of stage st+2 may still be outstanding
-        __builtin_amdgcn_s_waitcnt(kWaitVm8);
-        __syncthreads();   // every wave has issued its reads of stage st-1 long ago: its buffer is free
-        EF_TILED_ISSUE(st + 3)
-        __builtin_amdgcn_sched_barrier(0);
-        EF_TILED_STEP(a1, b1, a0, b0, nxt, 0)
-    }
-    __builtin_amdgcn_s_waitcnt(0);
-#undef EF_TILED_READ
-#undef EF_TILED_STEP
-#undef EF_TILED_ISSUE
+    const unsigned lds_base = (unsigned)(size_t)&lds[0][0][0];   // LDS byte offset: the low half of its flat address
+    EF_TILED_PIPELINE(0, nstage)
 
     // epilogue: act fragments (paired order) of row blocks rb0 + 2*wf + {0,1}, tiles t0 + 4*wt + j
     const int nkb2 = F >> 4;
@@ -231,60 +259,8 @@ __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, c
         for (int j = 0; j < 4; ++j) zero16(acc[i][j]);
 
     const int AOFF = wt * 4, BOFF = wc * 4;
-    // Four LDS stage buffers filled by direct global -> LDS loads (no register staging): stages st+1,
-    // st+2 and st+3 are in flight while stage st feeds the matrix cores; one barrier per stage.
-    // Every wave issues kStageFrags/4 loads per stage, unconditionally (past the end the last stage
-    // is re-read, in bounds), so "my loads of stage st have landed" is a constant wait count.
-#define EF_TILED_ISSUE(st)                                                                           \
-    {                                                                                                \
-        const int stc_ = min((st), nstage - 1);                                                      \
-        const int buf_ = (st) & (kTileStages - 1);                                                   \
-        _Pragma("unroll") for (int q = 0; q < kStageFrags / 4; ++q)                                  \
-            __builtin_amdgcn_global_load_lds(src[q] + (size_t)stc_ * kTileKS * 64,                   \
-                                             &lds[buf_][q * 4 + wave][0], 16, 0, 0);                 \
-    }
-#define EF_TILED_READ(a, b, cur, ks)                                                              \
-    {                                                                                                \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) a[i] = lds[cur][(ks) * 16 + AOFF + i][lane];     \
-        _Pragma("unroll") for (int j = 0; j < 4; ++j) b[j] = lds[cur][(ks) * 16 + 8 + BOFF + j][lane]; \
-    }
-    // one k-step: 16 MFMAs on the current fragments while the 8 fragments of the next k-step are
-    // read from LDS, scheduled as 2 MFMAs, (1 LDS read, 1 MFMA) x 8, 6 MFMAs: no burst on either pipe,
-    // and the last read is issued six MFMAs before the next k-step needs the fragments
-#define EF_TILED_STEP(ac, bc, an, bn, buf, ks)                                                       \
-    EF_TILED_READ(an, bn, buf, ks)                                                                   \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                    \
-        _Pragma("unroll") for (int j = 0; j < 4; ++j) acc[i][j] = mfma32v(ac[i], bc[j], acc[i][j]);  \
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                               \
-    _Pragma("unroll") for (int r_ = 0; r_ < 8; ++r_) {                                               \
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                           \
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                           \
-    }                                                                                                \
-    __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);                                               \
-    __builtin_amdgcn_sched_barrier(0);
-    static_assert(kTileKS == 2, "the loop below alternates two fragment register sets");
-    u32x4_t a0[4], b0[4], a1[4], b1[4];
-    EF_TILED_ISSUE(s0)
-    EF_TILED_ISSUE(s0 + 1)
-    EF_TILED_ISSUE(s0 + 2)
-    __builtin_amdgcn_s_waitcnt(kWaitVm16);   // my part of the first stage has landed
-    __syncthreads();                         // ... and everybody else's
-    EF_TILED_READ(a0, b0, s0 & (kTileStages - 1), 0)
-    for (int st = s0; st < s1; ++st) {
-        const int cur = st & (kTileStages - 1), nxt = (st + 1) & (kTileStages - 1);
-        EF_TILED_STEP(a0, b0, a1, b1, cur, 1)
-        // stage st+1 must have landed: of the loads issued so far (stages st+1, st+2) at most the
-        // 8 of stage st+2 may still be outstanding
-        __builtin_amdgcn_s_waitcnt(kWaitVm8);
-        __syncthreads();   // every wave has issued its reads of stage st-1 long ago: its buffer is free
-        EF_TILED_ISSUE(st + 3)
-        __builtin_amdgcn_sched_barrier(0);
-        EF_TILED_STEP(a1, b1, a0, b0, nxt, 0)
-    }
-    __builtin_amdgcn_s_waitcnt(0);
-#undef EF_TILED_READ
-#undef EF_TILED_STEP
-#undef EF_TILED_ISSUE
+    const unsigned lds_base = (unsigned)(size_t)&lds[0][0][0];   // LDS byte offset: the low half of its flat address
+    EF_TILED_PIPELINE(s0, s1)
 
     const int g = lane >> 5;
     float *Yp = Y + (size_t)kslice * y_plane;
