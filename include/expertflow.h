@@ -296,6 +296,119 @@ int ef_layer_step(ef_ctx *ctx, int layer, const void *hidden, int T, float beta,
  */
 int ef_token_dist(ef_ctx *ctx, const void *hidden, int T, float *tok_dist, double *dist, void *stream);
 
+/* -------------------------------------------------------------------------------------------------
+ * Deviation predictor (paper Sec. 3.2.2 "Cross-Layer Prediction and Delta Adjustment", 3.2.3-3.2.5).
+ * Host code only (the paper runs this model on the CPU, asynchronously to the GPU kernels); all
+ * pointers below are host pointers.  The model is a random-forest regressor over activation logs: one
+ * example per (request, layer), features x = [e, S, l, prev_act] of length d_emb + 2 + L*M (Sec. 3.2.4),
+ * label y in {0,1}^M, squared-error criterion (Sec. 3.2.5).  Its prediction for a future layer becomes
+ * the `delta` rows of ef_predict / ef_route_predict / ef_layer_step.
+ * ------------------------------------------------------------------------------------------------- */
+typedef struct ef_forest ef_forest;
+
+typedef struct {
+    int n_features;       /* F = d_emb + 2 + L*M                                                  */
+    int n_outputs;        /* M experts per layer, 1..EF_MAX_EXPERTS                               */
+    int n_trees;          /* >= 1                                                                  */
+    int max_depth;        /* >= 1: a tree has at most 2^max_depth leaves                           */
+    int min_samples_leaf; /* >= 1                                                                  */
+    int n_threads;        /* trees are grown / evaluated in parallel; 0 = all hardware threads     */
+} ef_forest_config;
+
+int ef_forest_create(const ef_forest_config *cfg, ef_forest **out);
+int ef_forest_destroy(ef_forest *f);
+
+/*
+ * Sec. 3.2.4: feature vector of one (request, layer).  emb_table [V, d_emb] f32 row-major is the fixed
+ * random embedding table, token_ids [n_tok] (each in 0..V-1) the request's tokens; e = their mean row
+ * (summed in sequence order in fp64, rounded to f32).  prev_act [L*M] u8 holds, layer-major, the
+ * experts the request activated in the layers before `layer` (the caller leaves the rest zero).
+ * x [d_emb + 2 + L*M] f32 receives [e, S, layer, prev_act].
+ */
+int ef_delta_features(const float *emb_table, int V, int d_emb, const int32_t *token_ids, int n_tok,
+                      int S, int layer, const uint8_t *prev_act, int L, int M, float *x);
+
+/*
+ * Sec. 3.2.5: grow the forest.  X [N, F] f32 row-major, Y [N, M] u8 (0/1).  bootstrap [n_trees, N]
+ * i32 holds, per tree, the indices (0..N-1, with repetitions) of the samples it is grown on: the random
+ * draws are the caller's; NULL grows every tree on all N samples.  Every feature is considered at
+ * every node (the regressor default of the library the paper names).  A split maximises
+ * sum_m sL[m]^2/nL + sum_m sR[m]^2/nR over the node's samples (equivalently minimises the summed
+ * squared error), decided in exact integer arithmetic; ties go to the lower feature index, then the
+ * lower threshold; a node stays a leaf unless the best split strictly improves on it, both sides keep
+ * min_samples_leaf samples and its depth is below max_depth.  Threshold = midpoint of the two
+ * neighbouring feature values (fp64); x <= threshold goes left.  Deterministic for given inputs,
+ * whatever n_threads.  Replaces a previously fitted model.  1 <= N <= 2^20; every feature value finite
+ * (EF_EINVAL otherwise).
+ */
+int ef_forest_fit(ef_forest *f, const float *X, const uint8_t *Y, int N, const int32_t *bootstrap);
+
+/* Y_hat [n, M] f64 = mean over the trees (summed in tree order) of the leaf means.  EF_EINVAL before a fit. */
+int ef_forest_predict(const ef_forest *f, const float *X, int n, double *Y_hat);
+
+/*
+ * Inspection (tests, serialisation).  ef_forest_tree_size: number of nodes of tree t (negative error code
+ * on failure).  ef_forest_tree_export copies the nodes in creation order (node 0 is the root; children are
+ * created left subtree first): feature [nodes] i32 (-1 = leaf), threshold [nodes] f64, left / right
+ * [nodes] i32 (-1 at leaves), count [nodes] i32 (samples, repetitions counted), value [nodes, M] f64
+ * (mean label).  Any output pointer may be NULL.
+ */
+int ef_forest_tree_size(const ef_forest *f, int t);
+int ef_forest_tree_export(const ef_forest *f, int t, int32_t *feature, double *threshold, int32_t *left,
+                          int32_t *right, int32_t *count, double *value);
+
+/* Sec. 3.2.5: share of expert bits predicted correctly, a bit being predicted set when y_hat >= 0.5. */
+int ef_forest_bit_accuracy(const double *Y_hat, const uint8_t *Y, int n, int M, double *accuracy);
+
+/*
+ * The deviation added to the pre-gate logits (Sec. 3.2.2): delta[r, e] = gain * (y_hat[r, e] - mean_e
+ * y_hat[r, .]) as f32 (the mean summed in expert order in fp64).  A constant per row does not change a
+ * top-k, so only the centred prediction matters; the paper does not give the mapping (a reading).
+ */
+int ef_delta_from_activation(const double *Y_hat, int n_rows, int M, float gain, float *delta);
+
+/*
+ * Sec. 3.2.2's prediction cache and the asynchronous producer that fills it.  A prediction is keyed
+ * by (token id sequence, layer, step size S) and holds the forest's y_hat [M] for that request and
+ * layer; beyond `capacity` entries the least recently used one leaves (a hit refreshes its entry).
+ * ef_delta_cache_get returns 1 on a hit (y_hat copied out), 0 on a miss: the caller then uses a zero
+ * delta row, i.e. plain top-k of the router logits, the fallback the section names.  All calls are
+ * thread-safe.
+ */
+typedef struct ef_delta_cache ef_delta_cache;
+int ef_delta_cache_create(int capacity, int M, ef_delta_cache **out);
+int ef_delta_cache_destroy(ef_delta_cache *c);
+int ef_delta_cache_put(ef_delta_cache *c, const int32_t *token_ids, int n_tok, int layer, int S, const double *y_hat);
+int ef_delta_cache_get(ef_delta_cache *c, const int32_t *token_ids, int n_tok, int layer, int S, double *y_hat);
+int ef_delta_cache_counts(ef_delta_cache *c, long long *hits, long long *misses, long long *entries);
+
+/*
+ * Producer: n_threads worker threads evaluate the forest for submitted (request, layer) pairs and put the
+ * result into the cache, so the GPU loop never waits for the model.  The forest, the cache and the embedding
+ * table must outlive the producer and the forest must not be refitted while it runs.  ef_delta_submit copies
+ * its arguments, enqueues one job per layer in [layer_first, layer_first + n_layers) that is below L and not
+ * yet cached, and returns at once; prev_act [L*M] as in ef_delta_features (the same vector is used for every
+ * layer of the job: what the request has activated so far).  ef_delta_drain blocks until the queue is empty
+ * and the workers are idle.
+ */
+typedef struct ef_delta_producer ef_delta_producer;
+int ef_delta_producer_create(const ef_forest *f, ef_delta_cache *cache, const float *emb_table, int V, int d_emb,
+                             int L, int M, int n_threads, ef_delta_producer **out);
+int ef_delta_producer_destroy(ef_delta_producer *p);
+int ef_delta_submit(ef_delta_producer *p, const int32_t *token_ids, int n_tok, int S, int layer_first,
+                    int n_layers, const uint8_t *prev_act);
+int ef_delta_drain(ef_delta_producer *p);
+
+/*
+ * Assemble the delta argument of one predict call from the cache: for request r (token ids
+ * token_ids[tok_off[r] .. tok_off[r+1])) and look-ahead j = 0..H-1 the row delta[r, j, .] [E = M] f32 is
+ * ef_delta_from_activation of the cached prediction for layer `layer + 1 + j` and step size S, or zeros on
+ * a miss / past the last layer.  delta [R, H, M] (host; pinned or host-mapped memory lets the caller hand it
+ * to the device without a staging copy).  *n_hits (may be NULL) receives the number of rows found.
+ */
+int ef_delta_assemble(ef_delta_cache *c, const int32_t *token_ids, const int32_t *tok_off, int R, int layer,
+                      int S, int H, int L, float gain, float *delta, int *n_hits);
+
 /* Statistics; synchronises outstanding timing events first (not for the hot loop). */
 int ef_get_stats(ef_ctx *ctx, ef_stats *out);
 int ef_reset_stats(ef_ctx *ctx);

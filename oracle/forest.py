@@ -170,7 +170,9 @@ def bit_accuracy(yhat: np.ndarray, y: np.ndarray) -> float:
 
 
 def delta_from_activation(yhat: np.ndarray, gain: float) -> np.ndarray:
-    """Delta[..., e] = gain * (yhat[..., e] - mean_e yhat): float32, fp64 inside, mean summed in expert order."""
+    """Delta[..., e] = gain * (yhat[..., e] - mean_e yhat): float32, fp64 inside, mean summed in expert order;
+    the gain is a float32 parameter."""
+    gain = float(np.float32(gain))
     yhat = np.asarray(yhat, dtype=np.float64)
     mean = np.zeros(yhat.shape[:-1], dtype=np.float64)
     for e in range(yhat.shape[-1]):

@@ -30,6 +30,11 @@ EXPORTS = [
     "ef_strerror", "ef_expert_bytes", "ef_pack_expert", "ef_expert_bytes_q4", "ef_pack_expert_q4", "ef_create", "ef_destroy", "ef_last_error",
     "ef_register_layer", "ef_predict", "ef_route", "ef_route_predict", "ef_moe_ffn", "ef_layer_step", "ef_cache_swap_in", "ef_cache_query",
     "ef_choose_horizon", "ef_token_dist", "ef_get_stats", "ef_reset_stats", "ef_set_profile", "ef_fake_advance_time",
+    "ef_forest_create", "ef_forest_destroy", "ef_delta_features", "ef_forest_fit", "ef_forest_predict",
+    "ef_forest_tree_size", "ef_forest_tree_export", "ef_forest_bit_accuracy", "ef_delta_from_activation",
+    "ef_delta_cache_create", "ef_delta_cache_destroy", "ef_delta_cache_put", "ef_delta_cache_get",
+    "ef_delta_cache_counts", "ef_delta_producer_create", "ef_delta_producer_destroy", "ef_delta_submit",
+    "ef_delta_drain", "ef_delta_assemble",
 ]
 
 
@@ -62,6 +67,11 @@ class ef_stats(C.Structure):
             v = getattr(self, n)
             out[n] = list(v) if hasattr(v, "__len__") else v
         return out
+
+
+class ef_forest_config(C.Structure):
+    _fields_ = [("n_features", C.c_int32), ("n_outputs", C.c_int32), ("n_trees", C.c_int32),
+                ("max_depth", C.c_int32), ("min_samples_leaf", C.c_int32), ("n_threads", C.c_int32)]
 
 
 class EfError(RuntimeError):
@@ -108,6 +118,26 @@ def lib():
         L.ef_reset_stats.argtypes = [vp]
         L.ef_set_profile.argtypes = [vp, C.c_uint]
         L.ef_fake_advance_time.argtypes = [vp, C.c_double]
+        ll = C.c_longlong
+        L.ef_forest_create.argtypes = [C.POINTER(ef_forest_config), C.POINTER(vp)]
+        L.ef_forest_destroy.argtypes = [vp]
+        L.ef_delta_features.argtypes = [vp, i32, i32, vp, i32, i32, i32, vp, i32, i32, vp]
+        L.ef_forest_fit.argtypes = [vp, vp, vp, i32, vp]
+        L.ef_forest_predict.argtypes = [vp, vp, i32, vp]
+        L.ef_forest_tree_size.argtypes = [vp, i32]
+        L.ef_forest_tree_export.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
+        L.ef_forest_bit_accuracy.argtypes = [vp, vp, i32, i32, C.POINTER(C.c_double)]
+        L.ef_delta_from_activation.argtypes = [vp, i32, i32, f32, vp]
+        L.ef_delta_cache_create.argtypes = [i32, i32, C.POINTER(vp)]
+        L.ef_delta_cache_destroy.argtypes = [vp]
+        L.ef_delta_cache_put.argtypes = [vp, vp, i32, i32, i32, vp]
+        L.ef_delta_cache_get.argtypes = [vp, vp, i32, i32, i32, vp]
+        L.ef_delta_cache_counts.argtypes = [vp, C.POINTER(ll), C.POINTER(ll), C.POINTER(ll)]
+        L.ef_delta_producer_create.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, C.POINTER(vp)]
+        L.ef_delta_producer_destroy.argtypes = [vp]
+        L.ef_delta_submit.argtypes = [vp, vp, i32, i32, i32, i32, vp]
+        L.ef_delta_drain.argtypes = [vp]
+        L.ef_delta_assemble.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, vp, C.POINTER(i32)]
         _lib = L
     return _lib
 
@@ -299,3 +329,143 @@ def ef_set_profile(ctx, kinds_mask):
 
 def ef_fake_advance_time(ctx, seconds):
     return _check(ctx, lib().ef_fake_advance_time(ctx, seconds))
+
+
+# ---- deviation predictor (host side) ----------------------------------------------------------
+
+def _rc(rc, what):
+    if rc < 0:
+        raise EfError(rc, what)
+    return rc
+
+
+def _np(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def ef_forest_create(n_features, n_outputs, n_trees, max_depth, min_samples_leaf=1, n_threads=0):
+    cfg = ef_forest_config(n_features, n_outputs, n_trees, max_depth, min_samples_leaf, n_threads)
+    out = C.c_void_p()
+    _rc(lib().ef_forest_create(C.byref(cfg), C.byref(out)), "ef_forest_create")
+    return out
+
+
+def ef_forest_destroy(f):
+    return lib().ef_forest_destroy(f)
+
+
+def ef_delta_features(emb_table, token_ids, S, layer, prev_act, L, M):
+    emb_table = _np(emb_table, np.float32)
+    tok = _np(token_ids, np.int32)
+    prev = _np(prev_act, np.uint8).reshape(-1)
+    assert prev.size == L * M
+    x = np.empty(emb_table.shape[1] + 2 + L * M, dtype=np.float32)
+    _rc(lib().ef_delta_features(_ptr(emb_table), emb_table.shape[0], emb_table.shape[1], _ptr(tok), tok.size, S, layer,
+                                _ptr(prev), L, M, _ptr(x)), "ef_delta_features")
+    return x
+
+
+def ef_forest_fit(f, X, Y, bootstrap=None):
+    X, Y = _np(X, np.float32), _np(Y, np.uint8)
+    assert X.shape[0] == Y.shape[0]
+    b = None if bootstrap is None else _np(bootstrap, np.int32)
+    assert b is None or b.shape[1] == X.shape[0]
+    return _rc(lib().ef_forest_fit(f, _ptr(X), _ptr(Y), X.shape[0], _ptr(b)), "ef_forest_fit")
+
+
+def ef_forest_predict(f, X, n_outputs):
+    X = _np(X, np.float32)
+    out = np.empty((X.shape[0], n_outputs), dtype=np.float64)
+    _rc(lib().ef_forest_predict(f, _ptr(X), X.shape[0], _ptr(out)), "ef_forest_predict")
+    return out
+
+
+def ef_forest_tree_size(f, t):
+    return _rc(lib().ef_forest_tree_size(f, t), "ef_forest_tree_size")
+
+
+def ef_forest_tree_export(f, t, n_outputs):
+    n = ef_forest_tree_size(f, t)
+    tree = {"feature": np.empty(n, np.int32), "threshold": np.empty(n, np.float64), "left": np.empty(n, np.int32),
+            "right": np.empty(n, np.int32), "count": np.empty(n, np.int32), "value": np.empty((n, n_outputs), np.float64)}
+    _rc(lib().ef_forest_tree_export(f, t, *[_ptr(tree[k]) for k in ("feature", "threshold", "left", "right", "count",
+                                                                     "value")]), "ef_forest_tree_export")
+    return tree
+
+
+def ef_forest_bit_accuracy(Y_hat, Y):
+    Y_hat, Y = _np(Y_hat, np.float64), _np(Y, np.uint8)
+    acc = C.c_double()
+    _rc(lib().ef_forest_bit_accuracy(_ptr(Y_hat), _ptr(Y), Y.shape[0], Y.shape[1], C.byref(acc)), "ef_forest_bit_accuracy")
+    return acc.value
+
+
+def ef_delta_from_activation(Y_hat, gain):
+    Y_hat = _np(Y_hat, np.float64)
+    out = np.empty(Y_hat.shape, dtype=np.float32)
+    M = Y_hat.shape[-1]
+    _rc(lib().ef_delta_from_activation(_ptr(Y_hat), Y_hat.size // M, M, gain, _ptr(out)), "ef_delta_from_activation")
+    return out
+
+
+def ef_delta_cache_create(capacity, M):
+    out = C.c_void_p()
+    _rc(lib().ef_delta_cache_create(capacity, M, C.byref(out)), "ef_delta_cache_create")
+    return out
+
+
+def ef_delta_cache_destroy(c):
+    return lib().ef_delta_cache_destroy(c)
+
+
+def ef_delta_cache_put(c, token_ids, layer, S, y_hat):
+    tok, y = _np(token_ids, np.int32), _np(y_hat, np.float64)
+    return _rc(lib().ef_delta_cache_put(c, _ptr(tok), tok.size, layer, S, _ptr(y)), "ef_delta_cache_put")
+
+
+def ef_delta_cache_get(c, token_ids, layer, S, M):
+    """The cached prediction [M] or None."""
+    tok = _np(token_ids, np.int32)
+    y = np.empty(M, dtype=np.float64)
+    hit = _rc(lib().ef_delta_cache_get(c, _ptr(tok), tok.size, layer, S, _ptr(y)), "ef_delta_cache_get")
+    return y if hit else None
+
+
+def ef_delta_cache_counts(c):
+    h, m, e = C.c_longlong(), C.c_longlong(), C.c_longlong()
+    _rc(lib().ef_delta_cache_counts(c, C.byref(h), C.byref(m), C.byref(e)), "ef_delta_cache_counts")
+    return h.value, m.value, e.value
+
+
+def ef_delta_producer_create(forest, cache, emb_table, L, M, n_threads=0):
+    """emb_table must be a C-contiguous float32 array that the caller keeps alive."""
+    assert emb_table.dtype == np.float32 and emb_table.flags["C_CONTIGUOUS"]
+    out = C.c_void_p()
+    _rc(lib().ef_delta_producer_create(forest, cache, _ptr(emb_table), emb_table.shape[0], emb_table.shape[1], L, M,
+                                       n_threads, C.byref(out)), "ef_delta_producer_create")
+    return out
+
+
+def ef_delta_producer_destroy(p):
+    return lib().ef_delta_producer_destroy(p)
+
+
+def ef_delta_submit(p, token_ids, S, layer_first, n_layers, prev_act):
+    tok, prev = _np(token_ids, np.int32), _np(prev_act, np.uint8).reshape(-1)
+    return _rc(lib().ef_delta_submit(p, _ptr(tok), tok.size, S, layer_first, n_layers, _ptr(prev)), "ef_delta_submit")
+
+
+def ef_delta_drain(p):
+    return _rc(lib().ef_delta_drain(p), "ef_delta_drain")
+
+
+def ef_delta_assemble(c, token_ids, tok_off, layer, S, H, L, gain, M, out=None):
+    """(delta [R, H, M] float32, rows found).  `out` may be a caller-provided (e.g. pinned) array."""
+    tok, off = _np(token_ids, np.int32), _np(tok_off, np.int32)
+    R = off.size - 1
+    delta = np.empty((R, H, M), dtype=np.float32) if out is None else out
+    hits = C.c_int32()
+    _rc(lib().ef_delta_assemble(c, _ptr(tok), _ptr(off), R, layer, S, H, L, gain, _ptr(delta), C.byref(hits)),
+        "ef_delta_assemble")
+    return delta, hits.value
