@@ -97,6 +97,13 @@ def main():
     ap.add_argument("--drift-tokens", type=int, default=0,
                     help="re-draw the expert popularity ranks (gate biases) whenever the running token count "
                          "crosses a multiple of this (0 = static popularity)")
+    ap.add_argument("--delta-forest", action="store_true",
+                    help="measure the deviation predictor instead of the headline: activation logs of recurring "
+                         "prompts -> random forest on the host -> look-ahead recall with and without its deviation, "
+                         "and the layer loop's rate with the deviation path switched on")
+    ap.add_argument("--prompts", type=int, default=256, help="--delta-forest: size of the pool of recurring prompts")
+    ap.add_argument("--log-steps", type=int, default=24, help="--delta-forest: steps whose routing is logged for training")
+    ap.add_argument("--eval-steps", type=int, default=6, help="--delta-forest: fresh steps the look-ahead is scored on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle baseline")
     ap.add_argument("--calib-copy", type=int, default=0,
@@ -131,6 +138,21 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.delta_forest:
+        from paper_2510_26730_amd import delta_bench
+        L = args.layers or 8
+        H = args.horizon or 3
+        r = delta_bench.run(cfg, T, L, H, args.prompts, args.steps, args.warmup, args.log_steps, args.eval_steps)
+        w = r["layer_loop_with_delta"]
+        print(json.dumps({
+            "metric": "MoE-layer tokens/s (route+predict+FFN) at 1 GPU, look-ahead refined by the host forest's deviation",
+            "value": w["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": 1e-3 * w["us_per_layer"] * L, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": r["workload"], "tokens_per_step": T, "layers": L, "horizon": H},
+            "delta_forest": r}))
+        return
 
     slots = args.slots or cfg.slots_per_layer
     loop = LayerLoop(cfg, L, T, slots, pool_slots=args.pool_slots, beta=beta, profile=False,

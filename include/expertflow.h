@@ -387,9 +387,10 @@ int ef_delta_cache_counts(ef_delta_cache *c, long long *hits, long long *misses,
  * result into the cache, so the GPU loop never waits for the model.  The forest, the cache and the embedding
  * table must outlive the producer and the forest must not be refitted while it runs.  ef_delta_submit copies
  * its arguments, enqueues one job per layer in [layer_first, layer_first + n_layers) that is below L and not
- * yet cached, and returns at once; prev_act [L*M] as in ef_delta_features (the same vector is used for every
- * layer of the job: what the request has activated so far).  ef_delta_drain blocks until the queue is empty
- * and the workers are idle.
+ * yet cached, and returns at once.  prev_act [L*M] u8, layer-major: what the request has activated so far;
+ * for target layer t only the rows of layers < t - S enter the features (what is known when layer t is
+ * predicted S layers ahead, so that training examples built with the same rule see the same inputs), later
+ * rows count as zero.  ef_delta_drain blocks until the queue is empty and the workers are idle.
  */
 typedef struct ef_delta_producer ef_delta_producer;
 int ef_delta_producer_create(const ef_forest *f, ef_delta_cache *cache, const float *emb_table, int V, int d_emb,

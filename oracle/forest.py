@@ -52,17 +52,19 @@ def feature_vector(e: np.ndarray, S: int, layer: int, prev_act: np.ndarray) -> n
                            np.asarray(prev_act, dtype=np.float32).reshape(-1)])
 
 
-def examples_of_request(table, token_ids, S: int, actual: np.ndarray):
+def examples_of_request(table, token_ids, S: int, actual: np.ndarray, lag: int = 0):
     """One (x, y) per layer of one request, layers ascending.  actual [L, M] in {0,1}: the experts the
-    request activated in each layer.  prev_act of layer l holds the rows of the layers before l, zeros
-    from l on."""
+    request activated in each layer.  prev_act of layer l holds the rows of the layers before l - lag, zeros
+    from there on: lag = 0 is the paper's "all previous layers"; lag = S keeps what is known when layer l is
+    predicted S layers ahead (the rule the producer applies at run time)."""
     actual = np.asarray(actual, dtype=np.uint8)
     L, M = actual.shape
     e = pooled_embedding(table, token_ids)
     X, Y = [], []
     for l in range(L):
         prev = np.zeros((L, M), dtype=np.uint8)
-        prev[:l] = actual[:l]
+        known = max(0, l - lag)
+        prev[:known] = actual[:known]
         X.append(feature_vector(e, S, l, prev))
         Y.append(actual[l].copy())
     return np.stack(X), np.stack(Y)

@@ -417,6 +417,9 @@ struct ef_delta_producer {
                 queue.pop_front();
                 ++active;
             }
+            // only what is known when this layer is predicted S layers ahead: the rows of layers < layer - S
+            const int known = std::max(0, std::min(L, job.key.layer - job.key.S));
+            std::fill(job.prev_act.begin() + (size_t)known * M, job.prev_act.end(), (uint8_t)0);
             features_into(emb, d_emb, job.key.tokens.data(), (int)job.key.tokens.size(), job.key.S, job.key.layer,
                           job.prev_act.data(), L * M, x.data());
             forest_predict_row(forest, x.data(), y.data());

@@ -92,6 +92,8 @@ class LayerLoop:
         self.out = torch.empty(T, d, dtype=torch.float32, device=dev)
         self.H = 1
         self.h_fixed = None
+        self.delta = None        # [R, H, E] float32 on the device: deviation added to the look-ahead logits
+        self.tok2req = None      # [T] int32 on the device: request of each token (None: token t is request t)
         torch.cuda.synchronize()
         if all_resident:
             for l in range(n_layers):
@@ -107,13 +109,13 @@ class LayerLoop:
     def layer(self, l: int, h: torch.Tensor, stream) -> None:
         """One layer through the composite entry point (the library sequences the calls)."""
         H = -1 if self.h_fixed is None else self.h_fixed
-        self.H = ef.ef_layer_step(self.ctx, l, h, self.T, self.beta, H, None, None, self.out, None, stream)
+        self.H = ef.ef_layer_step(self.ctx, l, h, self.T, self.beta, H, self.delta, self.tok2req, self.out, None, stream)
 
     def layer_separate_calls(self, l: int, h: torch.Tensor, stream) -> None:
         """The same layer through the separate entry points (what ef_layer_step does inside)."""
         E, T = self.cfg.E, self.T
         H = self.H if self.h_fixed is None else self.h_fixed
-        he = ef.ef_route_predict(self.ctx, l, h, T, self.beta, H, None, None, self.ids, self.w, self.counts,
+        he = ef.ef_route_predict(self.ctx, l, h, T, self.beta, H, self.delta, self.tok2req, self.ids, self.w, self.counts,
                                  self.offsets, self.perm, self.inv_perm, self.pred_ids, self.hist, stream)
         self.meta_host.copy_(self.meta, non_blocking=True)
         stream.synchronize()

@@ -14,7 +14,8 @@ fixed-size chunks with one child stream per chunk, so the result does not
 depend on how many threads draw them.
 
 Stream ids: 0 hidden, 1 gate W, 2 expert W, 3 inter-layer noise,
-4 popularity permutation, 5 shared-expert W, 6 residency, 7 delta, 8 requests.
+4 popularity permutation, 5 shared-expert W, 6 residency, 7 delta, 8 requests,
+9 prompt pool, 10 feature embedding table, 11 bootstrap draws.
 """
 from __future__ import annotations
 
@@ -27,7 +28,7 @@ import numpy as np
 BASE_SEED = 26730
 _CHUNK = 1 << 22
 
-HIDDEN, GATE_W, EXPERT_W, NOISE, POPULARITY, SHARED_W, RESIDENCY, DELTA, REQUESTS = range(9)
+HIDDEN, GATE_W, EXPERT_W, NOISE, POPULARITY, SHARED_W, RESIDENCY, DELTA, REQUESTS, PROMPTS, FEATURE_EMB, BOOTSTRAP = range(12)
 
 
 @dataclasses.dataclass(frozen=True)
@@ -222,3 +223,44 @@ def tok2req(cfg: MoEShape, T: int, R: int) -> np.ndarray:
     for c in cuts:
         out[c:] += 1
     return out
+
+
+# ---------------------------------------------------------------------------
+# recurring prompts (stand-in for real prompts through a real, deterministic model): inputs of the
+# deviation predictor's logs.  A prompt is a short token id sequence; its hidden states in every layer
+# are a fixed function of the prompt, so a prompt that comes back activates the same experts again.
+# ---------------------------------------------------------------------------
+
+def prompt_pool(cfg: MoEShape, P: int, n_tok: int, V: int) -> np.ndarray:
+    """[P, n_tok] int32 token ids, uniform over the vocabulary 0..V-1."""
+    g = np.random.Generator(np.random.PCG64(_seq(cfg.cfg_id, PROMPTS, P, n_tok, V)))
+    return g.integers(0, V, size=(P, n_tok)).astype(np.int32)
+
+
+def prompt_draws(cfg: MoEShape, step: int, T: int, P: int, zipf_s: float = 1.1) -> np.ndarray:
+    """[T] int32: which prompt of the pool each of the T requests of a step carries; prompt p is drawn with
+    probability proportional to (p + 1)^-s."""
+    g = np.random.Generator(np.random.PCG64(_seq(cfg.cfg_id, PROMPTS, 1, step, T, P)))
+    w = (np.arange(1, P + 1, dtype=np.float64)) ** (-zipf_s)
+    return g.choice(P, size=T, p=w / w.sum()).astype(np.int32)
+
+
+def prompt_hidden(cfg: MoEShape, P: int, n_layers: int) -> np.ndarray:
+    """[n_layers, P, d] bf16: per prompt h_0 ~ N(0,1) and h_{l+1} = bf16(f32(h_l) + noise * N(0,1)), fixed per
+    (prompt, layer): the same recipe as hidden_stack, keyed by the prompt instead of the step."""
+    hs = [normal_bf16((P, cfg.d), (cfg.cfg_id, PROMPTS, 2, P))]
+    for l in range(1, n_layers):
+        n = normal_f32(P * cfg.d, (cfg.cfg_id, PROMPTS, 3, P, l), cfg.noise).reshape(P, cfg.d)
+        hs.append(f32_to_bf16(bf16_to_f32(hs[-1]) + n))
+    return np.stack(hs)
+
+
+def feature_embedding(cfg: MoEShape, V: int, d_emb: int) -> np.ndarray:
+    """[V, d_emb] float32 ~ N(0,1): the fixed random embedding table of the predictor's features."""
+    return normal_f32(V * d_emb, (cfg.cfg_id, FEATURE_EMB, V, d_emb)).reshape(V, d_emb)
+
+
+def bootstrap_indices(cfg: MoEShape, n_trees: int, N: int) -> np.ndarray:
+    """[n_trees, N] int32 uniform draws from 0..N-1 (the forest's bootstrap samples)."""
+    g = np.random.Generator(np.random.PCG64(_seq(cfg.cfg_id, BOOTSTRAP, n_trees, N)))
+    return g.integers(0, N, size=(n_trees, N)).astype(np.int32)

@@ -131,6 +131,11 @@ def test_features_follow_the_paper_layout():
         np.testing.assert_array_equal(prev[:l], actual[:l])
         assert not prev[l:].any()
         np.testing.assert_array_equal(Y[l], actual[l])
+    X2, _ = orf.examples_of_request(table, toks, S=2, actual=actual, lag=2)
+    for l in range(L):
+        prev = X2[l, d + 2:].reshape(L, M)
+        np.testing.assert_array_equal(prev[:max(0, l - 2)], actual[:max(0, l - 2)])
+        assert not prev[max(0, l - 2):].any()
 
 
 def test_bit_accuracy_and_delta_mapping():

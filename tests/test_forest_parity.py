@@ -158,7 +158,10 @@ def test_producer_fills_the_cache_and_assemble_builds_delta():
             prev[:layer + 1] = actual[:layer + 1]
             e = orf.pooled_embedding(table, toks)
             for j in range(H):
-                x = orf.feature_vector(e, S, layer + 1 + j, prev)
+                t = layer + 1 + j
+                masked = prev.copy()
+                masked[max(0, t - S):] = 0                       # rows of layers >= t - S are not known S ahead
+                x = orf.feature_vector(e, S, t, masked)
                 want = orf.delta_from_activation(orf.predict_forest(ref, x[None])[0], gain)
                 np.testing.assert_allclose(delta[r, j], want, rtol=0, atol=1e-6)
         # look-ahead past the last layer gives zero rows
