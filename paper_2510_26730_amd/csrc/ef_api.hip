@@ -521,7 +521,9 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
     if ((e = hipMalloc(&c->blockcounts, (size_t)ntile_tok * E * 4)) != hipSuccess) return bail(e, "blockcounts");
     if ((e = hipMalloc(&c->blockbase, (size_t)ntile_tok * E * 4)) != hipSuccess) return bail(e, "blockbase");
     if ((e = hipMalloc(&c->xp, xp_bytes)) != hipSuccess) return bail(e, "packed-token scratch");
-    c->gate_part_floats = (size_t)2 << 20;   // 8 MiB: 64 workgroups x 32 rows x 128 columns x 8 launches' worth
+    // partial logits of K-split gate launches: 8 MiB (64 workgroups x 32 rows x 128 columns x 8 splits), or four
+    // splits of every token tile of the largest batch
+    c->gate_part_floats = std::max((size_t)2 << 20, (size_t)ntile_tok * 4 * ef::kTile * 128);
     if ((e = hipMalloc(&c->gate_part, c->gate_part_floats * 4)) != hipSuccess) return bail(e, "gate partials");
     if ((e = hipMalloc(&c->act, act_bytes)) != hipSuccess) return bail(e, "activation scratch");
     if ((e = hipMalloc(&c->y, y_bytes)) != hipSuccess) return bail(e, "expert-output scratch");

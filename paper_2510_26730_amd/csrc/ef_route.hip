@@ -108,7 +108,10 @@ __global__ __launch_bounds__(64 * kGateWaves) void gate_kernel(GateArgs a) {
     for (int r = 0; r < B_PER; ++r) {
         const int n = (tid + r * NT) / C4;
         bok[r] = n < N;
-        bsrc[r] = pick(a.Wg, g0 + (bok[r] ? n / a.E : 0)) + (size_t)(bok[r] ? n % a.E : 0) * a.d;
+        // columns past N still load (the number of loads in flight stays a compile-time constant), from
+        // the valid rows in turn rather than all from one row
+        const int nn = n % N;
+        bsrc[r] = pick(a.Wg, g0 + nn / a.E) + (size_t)(nn % a.E) * a.d;
     }
 
     floatx16 acc[NB];
@@ -144,10 +147,25 @@ __global__ __launch_bounds__(64 * kGateWaves) void gate_kernel(GateArgs a) {
     const int nstage_all = (a.d + KC - 1) / KC;
     const int per_split = (nstage_all + a.ksplit - 1) / a.ksplit;
     const int sbeg = blockIdx.z * per_split, nstage = min(nstage_all, sbeg + per_split);
+    // Every workgroup walks its panels in a rotated order (start = 5 * tile mod count): with a common
+    // order all workgroups would read the same 512-byte column block of their 8 KiB-strided rows at
+    // the same time, and those addresses share most of their channel-select bits
+    const int nloc = max(nstage - sbeg, 1);
+    const int rot0 = (tile * 5) % nloc;
+    auto rot = [&](int st) {
+        int x = st - sbeg + rot0;
+        if (x >= nloc) x -= nloc;
+        return sbeg + x;
+    };
     // prefetches are unconditional (past the end they re-read the last panel, in bounds) so that the
     // number of loads in flight is known at compile time and only the oldest panel is waited for
+    // (issued strictly in panel order: the wait before the first panel's use may then leave the loads of
+    // the three younger panels outstanding, on the loop's entry as on its back edge)
 #pragma unroll
-    for (int p = 0; p < PF; ++p) EF_GATE_GLOAD(p, max(min(sbeg + p, nstage - 1), 0))
+    for (int p = 0; p < PF; ++p) {
+        EF_GATE_GLOAD(p, rot(max(min(sbeg + p, nstage - 1), sbeg)))
+        __builtin_amdgcn_sched_barrier(0);
+    }
     for (int st0 = sbeg; st0 < nstage; st0 += PF) {
 #pragma unroll
         for (int p = 0; p < PF; ++p) {
@@ -156,17 +174,17 @@ __global__ __launch_bounds__(64 * kGateWaves) void gate_kernel(GateArgs a) {
 #pragma unroll
                 for (int r = 0; r < A_PER; ++r) {
                     const int idx = tid + r * NT;   // rows past T and columns past d contribute zeros
-                    const bool ok = aok[r] && st < nstage && st * KC + (idx % C4) * 8 < a.d;
+                    const bool ok = aok[r] && st < nstage && rot(st) * KC + (idx % C4) * 8 < a.d;
                     *reinterpret_cast<u32x4_t *>(&As[(idx / C4) * LDK + (idx % C4) * 8]) = ok ? ra[p][r] : zero4v;
                 }
 #pragma unroll
                 for (int r = 0; r < B_PER; ++r) {
                     const int idx = tid + r * NT;
-                    const bool ok = bok[r] && st < nstage && st * KC + (idx % C4) * 8 < a.d;
+                    const bool ok = bok[r] && st < nstage && rot(st) * KC + (idx % C4) * 8 < a.d;
                     *reinterpret_cast<u32x4_t *>(&Bs[(idx / C4) * LDK + (idx % C4) * 8]) = ok ? rb[p][r] : zero4v;
                 }
                 __syncthreads();
-                EF_GATE_GLOAD(p, max(min(st + PF, nstage - 1), 0))
+                EF_GATE_GLOAD(p, rot(max(min(st + PF, nstage - 1), sbeg)))
 #pragma unroll
                 for (int q = 0; q < KSW; ++q) {
                     const int kcol = (wave * KSW + q) * 16 + 8 * g;
