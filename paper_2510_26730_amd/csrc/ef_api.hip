@@ -1261,6 +1261,8 @@ extern "C" int ef_layer_step(ef_ctx *c, int layer, const void *hidden, int T, fl
     int He = 0;
     if ((rc = check_predict_args(c, layer, T, H, &He, "ef_layer_step"))) return rc;
     if (T <= 0) return fail(c, EF_EINVAL, "ef_layer_step: T must be positive");
+    if ((long long)T * c->cfg.top_k >= (1ll << ef::kMetaValueBits))
+        return fail(c, EF_EINVAL, "ef_layer_step: T * top_k must be below 2^24");
     if (!hidden || !out) return fail(c, EF_EINVAL, "ef_layer_step: null pointer");
     if (!aligned16(hidden) || !aligned16(out)) return fail(c, EF_EINVAL, "ef_layer_step: hidden/out must be 16-byte aligned");
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -1288,28 +1290,40 @@ extern "C" int ef_layer_step(ef_ctx *c, int layer, const void *hidden, int T, fl
                                         static_cast<const uint16_t *>(hidden), d, k, c->st_perm, c->xp, c->q4, s));
         did_pack = true;
     }
-    // 2. wait for the flag (bounded: fall back to a stream synchronisation, then give up)
-    volatile int32_t *flag = c->meta_host + ef::kMetaFlag;
+    // 2. wait until every expected word carries this call's tag (bounded: fall back to a stream
+    //    synchronisation, then give up)
+    const volatile int32_t *mh = c->meta_host;
+    const uint32_t tag = (uint32_t)(seq & 0xFF);
+    const int n_hist = He * E;
+    auto arrived = [&]() {
+        for (int x = 0; x < E; ++x)
+            if (((uint32_t)mh[x] >> ef::kMetaValueBits) != tag) return false;
+        for (int x = 0; x < n_hist; ++x)
+            if (((uint32_t)mh[ef::kMetaHist + x] >> ef::kMetaValueBits) != tag) return false;
+        return true;
+    };
     bool seen = false;
     for (long long spin = 0; spin < (1ll << 34); ++spin) {
-        if (*flag == seq) { seen = true; break; }
+        if (arrived()) { seen = true; break; }
         __builtin_ia32_pause();
         if ((spin & 0xFFFFF) == 0xFFFFF && hipStreamQuery(s) == hipSuccess) break;   // stream drained
     }
     if (!seen) {
         EF_HIP(c, hipStreamSynchronize(s));
-        if (*flag != seq) return fail(c, EF_EHIP, "ef_layer_step: routing results never reached the host");
+        if (!arrived()) return fail(c, EF_EHIP, "ef_layer_step: routing results never reached the host");
     }
-    __atomic_thread_fence(__ATOMIC_ACQUIRE);
+    const int32_t value_mask = (1 << ef::kMetaValueBits) - 1;
     int32_t counts_host[EF_MAX_EXPERTS];
-    for (int e = 0; e < E; ++e) counts_host[e] = c->meta_host[e];
+    for (int e = 0; e < E; ++e) counts_host[e] = mh[e] & value_mask;
+    int32_t hist_host[EF_MAX_HORIZON * EF_MAX_EXPERTS];
+    for (int x = 0; x < n_hist; ++x) hist_host[x] = mh[ef::kMetaHist + x] & value_mask;
     if (counts_host_out) memcpy(counts_host_out, counts_host, (size_t)E * 4);
     // 3. horizon for the next layer and prefetches, issued before the FFN so the copies overlap it
     int Hn = c->horizon;
     if (He > 0) {
         int32_t lst[EF_MAX_HORIZON * EF_MAX_EXPERTS];
         int n = 0;
-        rc = ef_choose_horizon(c, layer, c->meta_host + ef::kMetaHist, He, T, &Hn, lst, &n);
+        rc = ef_choose_horizon(c, layer, hist_host, He, T, &Hn, lst, &n);
         if (rc) return rc;
         for (int i = 0; i < n; ++i) {
             const int j = lst[i] >> 16, e = lst[i] & 0xFFFF;

@@ -51,10 +51,11 @@ struct GroupTable {
     const void *blob[kMaxGroups];  // packed weights (cache slot or shared blob)
 };
 
-// Optional hand-over of counts and predicted histograms to the host (host-mapped memory + flag).
+// Optional hand-over of counts and predicted histograms to the host (host-mapped memory): every word is
+// (sequence tag << 24) | value, value < 2^24.
 constexpr int kMetaHist = kMaxE;                          // hist starts after the E counts
-constexpr int kMetaFlag = kMaxE + (kMaxGates - 1) * kMaxE; // sequence flag
-constexpr int kMetaInts = kMetaFlag + 1;
+constexpr int kMetaInts = kMaxE + (kMaxGates - 1) * kMaxE;
+constexpr int kMetaValueBits = 24;
 struct GroupExport {
     int32_t *host_meta;   // device view of the host-mapped buffer, or null
     int32_t *hist;        // [n_hist] device histograms to copy out; [n_clear] is zeroed afterwards
