@@ -615,6 +615,7 @@ int run_gates(ef_ctx *c, int layer, const void *hidden, int T, float beta, bool 
     if (He > 0 && !ex.host_meta) EF_HIP(c, ef::launch_fill_i32(pred_hist, He * E, 0, s));
     const int per_launch = ef::kMaxGates;
     const int total_gates = (do_route ? 1 : 0) + He;
+    bool grouped = false;
     for (int g0 = 0; g0 < total_gates; g0 += per_launch) {
         ef::GateArgs a{};
         a.h = static_cast<const uint16_t *>(hidden);
@@ -669,15 +670,26 @@ int run_gates(ef_ctx *c, int layer, const void *hidden, int T, float beta, bool 
         }
         a.two_step = (a.ksplit > 1 || a.tsplit > 1) ? 1 : 0;
         const bool has_route = do_route && g0 == 0;
+        // decode-sized batches with a K-split gate and few experts: its second step and the grouping run as
+        // one workgroup (with more than 16 experts a token takes a whole wave round of the epilogue, and the
+        // many workgroups of the separate second step are faster: 27 against 36 us at 64 experts)
+        const bool fused = has_route && total_gates <= per_launch && ntiles <= ef::kFusedMaxTiles && a.ksplit > 1 &&
+                           E <= 16 &&
+                           ef::gate_fused_lds_bytes(T, a.G, E, a.gpw) <= ef::kFusedMaxLds &&
+                           tune("EF_TUNE_FUSED_FINISH", 1) != 0;
+        if (fused) a.tsplit = 1;
         {
             KernelTimer kt(c, s, has_route ? EF_K_ROUTE : EF_K_PREDICT,
                            (double)T * d * 2 + (double)a.G * E * d * 2 + (double)a.G * T * k * 4 +
                                (has_route ? (double)T * k * 4 + (double)ntiles * E * 4 : 0.0) +
-                               (double)(a.G - (has_route ? 1 : 0)) * E * 4);
-            EF_HIP(c, ef::launch_gate(a, s));
+                               (double)(a.G - (has_route ? 1 : 0)) * E * 4 +
+                               (fused ? (double)(2 * E + 1) * 4 + (double)T * k * 12 : 0.0));
+            if (fused) EF_HIP(c, ef::launch_gate_fused(a, counts, offsets, perm, inv_perm, ex, s));
+            else EF_HIP(c, ef::launch_gate(a, s));
         }
+        if (fused) grouped = true;
     }
-    if (do_route) {
+    if (do_route && !grouped) {
         KernelTimer kt(c, s, EF_K_GROUP, (double)ntiles * E * 8 + (double)(2 * E + 1) * 4 + (double)T * k * 12);
         EF_HIP(c, ef::launch_group(c->blockcounts, topk_ids, T, k, E, c->blockbase, counts, offsets, perm,
                                    inv_perm, ex, s));

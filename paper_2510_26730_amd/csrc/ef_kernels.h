@@ -77,6 +77,12 @@ int gate_pick_gpw(int T, int G, int E);
 int gate_pick_ksplit(int T, int d, int G, int E, int gpw, size_t part_floats);
 int gate_pick_tsplit(int T, int G, int E, int gpw);
 hipError_t launch_gate(const GateArgs &a, hipStream_t s);
+// decode-sized batches: K-split gate, then its second step and the grouping fused in one workgroup
+constexpr int kFusedMaxTiles = 2;
+constexpr size_t kFusedMaxLds = 48 * 1024;   // dynamic LDS of the fused kernel (logits of all pairs)
+size_t gate_fused_lds_bytes(int T, int G, int E, int gpw);
+hipError_t launch_gate_fused(const GateArgs &a, int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
+                             const GroupExport &ex, hipStream_t s);
 hipError_t launch_group(const int32_t *blockcounts, const int32_t *ids, int T, int k, int E, int32_t *blockbase,
                         int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
                         const GroupExport &ex, hipStream_t s);

@@ -609,6 +609,209 @@ __global__ __launch_bounds__(1024) void group_small_kernel(const int32_t *__rest
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Decode-sized batches (at most kFusedMaxTiles token tiles) with a K-split gate: the second step of
+// the gate (sum of the partial logits, per-token epilogue) for every (tile, gate group) and the
+// grouping, in ONE workgroup of 16 waves.  The per-tile expert counts never leave LDS, and one
+// kernel launch with its dependency gap and one memory round trip disappear from the layer's
+// critical path.  Arithmetic and orders are those of gate_finish_kernel + group_small_kernel.
+// Dynamic LDS: the logits of all pairs, [pairs][kTile][NB*32 + 1] floats.
+// ------------------------------------------------------------------------------------------
+template <int NB>
+__global__ __launch_bounds__(1024) void gate_finish_group_kernel(GateArgs a, int32_t *__restrict__ counts,
+                                                                 int32_t *__restrict__ offsets,
+                                                                 int32_t *__restrict__ perm,
+                                                                 int32_t *__restrict__ inv_perm, GroupExport ex) {
+    constexpr int NW = 16, NT = 64 * NW, ROW = NB * 32 + 1;
+    extern __shared__ float fz_logits[];                       // [pairs][kTile][ROW]
+    __shared__ int cnt[kFusedMaxTiles * kMaxGates * kMaxE];    // [(tile, gate)][expert]
+    __shared__ float sbias[kMaxGates * kMaxE];                 // [gate][expert]
+    __shared__ __attribute__((aligned(16))) float s_sc[NW][64];
+    __shared__ int base[kFusedMaxTiles * kMaxE];
+    __shared__ int total[kMaxE];
+    __shared__ int offs[kMaxE + 1];
+    __shared__ int nxt[NW][64];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int E = a.E, G = a.G;
+    const int ntiles = (a.T + kTile - 1) / kTile;
+    const int ngroups = (G + a.gpw - 1) / a.gpw;
+    const int pairs = ntiles * ngroups;
+
+    for (int x = tid; x < ntiles * G * E; x += NT) cnt[x] = 0;
+    for (int x = tid; x < G * E; x += NT) {
+        const float *bp = pick(a.bias, x / E);
+        sbias[x] = bp ? bp[x % E] : 0.f;
+    }
+    // partial logits of pair (tile, group): [split][kTile][NB*32], pairs in (tile, group) order
+    for (int idx = tid; idx < pairs * kTile * NB * 32; idx += NT) {
+        const int pair = idx / (kTile * NB * 32), x = idx % (kTile * NB * 32);
+        const float *src = a.part + (size_t)pair * a.ksplit * kTile * (NB * 32);
+        float pz[kGateMaxSplit];   // all loads first (one latency), then the adds in split order
+#pragma unroll
+        for (int z = 0; z < kGateMaxSplit; ++z) pz[z] = z < a.ksplit ? src[(size_t)z * kTile * NB * 32 + x] : 0.f;
+        float v = 0.f;
+#pragma unroll
+        for (int z = 0; z < kGateMaxSplit; ++z) v += pz[z];
+        fz_logits[(size_t)(pair * kTile + x / (NB * 32)) * ROW + x % (NB * 32)] = v;
+    }
+    __syncthreads();
+
+    // per-token epilogue over all (tile, gate, token chunk) triples, dealt to the 16 waves
+    {
+        int W = 8;
+        while (W < E) W <<= 1;
+        const int per_wave = 64 / W;
+        const int sub = lane / W, e = lane % W;
+        const int cpg = kTile / per_wave;                  // chunks per (tile, gate)
+        const int total_chunks = ntiles * G * cpg;
+        const bool evalid = e < E;
+        const float NEG_INF = -__builtin_inff();
+        for (int it = 0; it * NW < total_chunks; ++it) {
+            const int chunk = it * NW + wave;
+            const bool cact = chunk < total_chunks;
+            const int tile = cact ? chunk / (G * cpg) : 0;
+            const int gi = cact ? (chunk / cpg) % G : 0;
+            const int grp = gi / a.gpw, gl = gi - grp * a.gpw;
+            const int ti = (chunk % cpg) * per_wave + sub;
+            const int t = tile * kTile + ti;
+            const bool live = cact && t < a.T;
+            const bool want_w = cact && (a.w != nullptr) && gi == 0;  // wave-uniform
+            float z = NEG_INF;
+            if (live && evalid)
+                z = fz_logits[(size_t)((tile * ngroups + grp) * kTile + ti) * ROW + gl * E + e] + sbias[gi * E + e];
+            float sc = z;
+            if (live && evalid) {
+                if ((pick(a.resident, gi) >> e) & 1ull) sc += a.beta;
+                if (a.delta && gi >= a.delta_gate_begin) {
+                    int req = a.tok2req ? a.tok2req[t] : 0;
+                    sc += a.delta[(size_t)req * a.delta_req_stride + (gi - a.delta_gate_begin) * E + e];
+                }
+            }
+            s_sc[wave][lane] = sc;
+            wave_lds_sync();
+            const float4 *srow = reinterpret_cast<const float4 *>(&s_sc[wave][sub * W]);
+            int rank = 0;
+            for (int j = 0; j < W; j += 4) {
+                const float4 v = srow[j >> 2];
+                rank += (v.x > sc || (v.x == sc && j + 0 < e)) ? 1 : 0;
+                rank += (v.y > sc || (v.y == sc && j + 1 < e)) ? 1 : 0;
+                rank += (v.z > sc || (v.z == sc && j + 2 < e)) ? 1 : 0;
+                rank += (v.w > sc || (v.w == sc && j + 3 < e)) ? 1 : 0;
+            }
+            const bool sel = live && evalid && rank < a.k;
+            float exv = 0.f, den = 1.f;
+            if (want_w) {
+                float m = z;   // lanes without an expert hold -inf
+                for (int off = W >> 1; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+                exv = (live && evalid) ? __expf(z - m) : 0.f;
+                den = (a.renorm && !sel) ? 0.f : exv;
+                for (int off = W >> 1; off >= 1; off >>= 1) den += __shfl_xor(den, off);
+            }
+            const unsigned long long ball = __ballot(sel);
+            const unsigned long long submask = (W == 64) ? ball : ((ball >> (sub * W)) & ((1ull << W) - 1ull));
+            const int slot = __popcll(submask & ((1ull << e) - 1ull));   // ascending expert id
+            if (sel) {
+                pick(a.ids, gi)[(size_t)t * a.k + slot] = e;
+                if (want_w) a.w[(size_t)t * a.k + slot] = exv / den * a.routed_scale;
+                atomicAdd(&cnt[(tile * G + gi) * E + e], 1);
+            }
+            wave_lds_sync();   // the wave's row of s_sc is rewritten in the next round
+        }
+    }
+    __syncthreads();
+
+    // demand histograms of the look-ahead gates: to the host hand-over straight from LDS, or added to
+    // the caller's (zeroed) device arrays
+    const int tag = (int)((unsigned)(ex.seq & 0xFF) << 24);
+    for (int x = tid; x < G * E; x += NT) {
+        const int gi = x / E, ee = x % E;
+        int sum = 0;
+        for (int b = 0; b < ntiles; ++b) sum += cnt[(b * G + gi) * E + ee];
+        int32_t *hp = pick(a.hist, gi);
+        if (!hp) continue;
+        if (ex.host_meta) {
+            const int at = (int)(hp - ex.hist) + ee;           // position inside the exported histograms
+            if (at >= 0 && at < ex.n_hist) reinterpret_cast<volatile int32_t *>(ex.host_meta)[kMetaHist + at] = tag | sum;
+        } else if (sum > 0) {
+            atomicAdd(&hp[ee], sum);
+        }
+    }
+    // grouping of the routed gate (gate 0) from its per-tile counts
+    for (int x = tid; x < ntiles * E; x += NT) base[x] = cnt[((x / E) * G) * E + x % E];
+    __syncthreads();
+    for (int e = wave; e < E; e += NW) {
+        const int tot = scan_expert_inplace(base, ntiles, E, e, lane);
+        if (lane == 0) total[e] = tot;
+    }
+    __syncthreads();
+    if (wave == 0) {   // exclusive scan of the E <= 64 totals across the lanes of one wave
+        const int t = lane < E ? total[lane] : 0;
+        int incl = t;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(incl, off);
+            if (lane >= off) incl += o;
+        }
+        if (lane < E) {
+            counts[lane] = t;
+            offsets[lane] = incl - t;
+            offs[lane] = incl - t;
+        }
+        if (lane == 63) {
+            offsets[E] = incl;
+            offs[E] = incl;
+        }
+    }
+    __syncthreads();
+    if (ex.host_meta)   // the host starts planning while the scatter below still runs
+        for (int x = tid; x < E; x += NT) reinterpret_cast<volatile int32_t *>(ex.host_meta)[x] = tag | total[x];
+    // the scatter reads the ids the epilogue above stored: same workgroup, ordered by the barriers
+    for (int b = wave; b < ntiles; b += NW) {
+        nxt[wave][lane] = (lane < E) ? offs[lane] + base[b * E + lane] : 0;
+        wave_lds_sync();
+        scatter_tile(pick(a.ids, 0), a.T, a.k, b, lane, nxt[wave], perm, inv_perm);
+    }
+}
+
+size_t gate_fused_lds_bytes(int T, int G, int E, int gpw) {
+    const int ntiles = (T + kTile - 1) / kTile, ngroups = (G + gpw - 1) / gpw;
+    const int nb = (std::min(gpw, G) * E + 31) / 32;
+    return (size_t)ntiles * ngroups * kTile * (nb * 32 + 1) * sizeof(float);
+}
+
+template <int NB>
+static hipError_t launch_gate_fused_nb(const GateArgs &a, int32_t *counts, int32_t *offsets, int32_t *perm,
+                                       int32_t *inv_perm, const GroupExport &ex, hipStream_t s) {
+    const int ntiles = (a.T + kTile - 1) / kTile;
+    const int ngroups = (a.G + a.gpw - 1) / a.gpw;
+    hipLaunchKernelGGL((gate_kernel<NB>), dim3(ntiles, ngroups, a.ksplit), dim3(64 * kGateWaves), 0, s, a);
+    hipLaunchKernelGGL((gate_finish_group_kernel<NB>), dim3(1), dim3(1024),
+                       gate_fused_lds_bytes(a.T, a.G, a.E, a.gpw), s, a, counts, offsets, perm, inv_perm, ex);
+    return hipGetLastError();
+}
+
+// K-split gate + fused finish/grouping.  The first gate must be the routed one (ids[0], w, renorm).
+hipError_t launch_gate_fused(const GateArgs &a, int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
+                             const GroupExport &ex, hipStream_t s) {
+    const int ntiles = (a.T + kTile - 1) / kTile;
+    if (a.T <= 0 || ntiles > kFusedMaxTiles || a.G < 1 || a.G > kMaxGates || !a.two_step || a.tsplit != 1 ||
+        !a.part || a.ksplit < 1 || a.ksplit > kGateMaxSplit || a.gpw < 1 || a.gpw * a.E > 128 || !a.ids[0] ||
+        gate_fused_lds_bytes(a.T, a.G, a.E, a.gpw) > kFusedMaxLds)
+        return hipErrorInvalidValue;
+    if (ex.host_meta)   // exported histograms must be the arrays the look-ahead gates point at
+        for (int gi = 0; gi < a.G; ++gi)
+            if (a.hist[gi] && (a.hist[gi] < ex.hist || a.hist[gi] + a.E > ex.hist + ex.n_hist))
+                return hipErrorInvalidValue;
+    const int nb = (std::min(a.gpw, a.G) * a.E + 31) / 32;
+    switch (nb) {
+        case 1: return launch_gate_fused_nb<1>(a, counts, offsets, perm, inv_perm, ex, s);
+        case 2: return launch_gate_fused_nb<2>(a, counts, offsets, perm, inv_perm, ex, s);
+        case 3: return launch_gate_fused_nb<3>(a, counts, offsets, perm, inv_perm, ex, s);
+        case 4: return launch_gate_fused_nb<4>(a, counts, offsets, perm, inv_perm, ex, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 hipError_t launch_group(const int32_t *blockcounts, const int32_t *ids, int T, int k, int E, int32_t *blockbase,
                         int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
                         const GroupExport &ex, hipStream_t s) {

@@ -284,6 +284,44 @@ def test_full_size_mixtral_decode_layer(oracle_mod):
         st.close()
 
 
+@pytest.mark.parametrize("T,H", [(64, 3), (33, 1), (1, 2)])
+def test_decode_gate_second_step_fused_with_grouping_equals_separate_kernels(monkeypatch, T, H):
+    """Decode-sized batches of the headline shape take the K-split gate followed by ONE workgroup that sums the
+    partial logits, runs the per-token epilogue and groups the tokens; with the fusion switched off the same
+    partial logits go through the separate second-step and grouping kernels.  Same arithmetic in the same
+    order: every output must be bit-identical (ids, weights, counts, offsets, permutation, look-ahead ids and
+    histograms), also through the layer-step hand-over to the host."""
+    cfg = dataclasses.replace(synth.CONFIGS["mixtral_decode"], F=64, name="mixtral_gate")   # routing only: tiny experts
+    say(f"decode gate paths: T={T} H={H}")
+    L = H + 1
+    outs = []
+    for fused in ("1", "0"):
+        monkeypatch.setenv("EF_TUNE_FUSED_FINISH", fused)
+        st = LayerStack(cfg, L, slots_total=cfg.E, max_tokens=64, expert_layers=[0], h_max=H)
+        try:
+            for l in range(L):
+                for e in np.nonzero(synth.residency(cfg, l, n_resident=2, most_popular=False))[0]:
+                    ef.ef_cache_swap_in(st.ctx, l, int(e), 0, l)
+            hd = dev_u16(synth.hidden(cfg, 3, T))
+            R = 3
+            dd = torch.from_numpy(synth.delta(cfg, 0, R, H)).cuda()
+            td = torch.from_numpy(synth.tok2req(cfg, T, R)).cuda()
+            o = st.route(0, hd, T, 0.0)
+            fids = torch.full((H * T * cfg.k,), -1, dtype=torch.int32, device="cuda")
+            fhist = torch.full((H * cfg.E,), -1, dtype=torch.int32, device="cuda")
+            he = ef.ef_route_predict(st.ctx, 0, hd, T, 0.7, H, dd, td, o["ids"], o["w"], o["counts"], o["offsets"],
+                                     o["perm"], o["inv_perm"], fids, fhist, torch.cuda.current_stream())
+            assert he == H
+            got = to_np(o, T, cfg.k)
+            got["pred_ids"], got["pred_hist"] = fids.cpu().numpy(), fhist.cpu().numpy()
+            assert got["pred_hist"].reshape(H, cfg.E).sum(axis=1).tolist() == [T * cfg.k] * H
+            outs.append(got)
+        finally:
+            st.close()
+    for name in outs[0]:
+        assert np.array_equal(outs[0][name], outs[1][name]), name
+
+
 @pytest.mark.parametrize("force_tiled", [True, False])
 def test_full_size_qwen_mixed_batch(oracle_mod, monkeypatch, force_tiled):
     """T = 640 with a shared expert of 20 token tiles: through the matrix-core tiled kernels (the
