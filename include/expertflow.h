@@ -269,12 +269,13 @@ int ef_choose_horizon(ef_ctx *ctx, int layer, const int32_t *hist_host, int H, i
                       int *H_next, int32_t *prefetch_list, int *n_prefetch);
 
 /*
- * One whole layer of the method in one call, in the paper's order (Sec. 3.1 overview, 3.2, 3.3.2, 3.4):
+ * One whole layer of the method in one call (Sec. 3.1 overview, 3.2, 3.3.2, 3.4):
  * ef_route_predict with look-ahead H (H < 0: the controller's current horizon) into library-owned
  * buffers; the grouping kernel hands counts and demand histograms to the host through host-mapped
- * memory and the call polls a flag instead of synchronising the stream; ef_choose_horizon; one
- * ef_cache_swap_in(prefetch) per entry of its list (EF_EBUSY skips that prefetch); ef_moe_ffn.
- * Results are those of the separate calls.  *H_next (may be NULL) receives the horizon chosen for the
+ * memory and the call polls for them instead of synchronising the stream; ef_moe_ffn (enqueued first:
+ * the GPU is idle until then); ef_choose_horizon; one ef_cache_swap_in(prefetch) per entry of its list
+ * (EF_EBUSY skips that prefetch), whose copies overlap the FFN that is running by then.
+ * Results are those of the separate calls made in that order.  *H_next (may be NULL) receives the horizon chosen for the
  * next layer, counts_host_out [host] [E] (may be NULL) the per-expert token counts.  out [dev]
  * [T,d] f32 is valid after the caller synchronises `stream`.  The call blocks the host until the
  * routing kernels of this layer have finished (not until the FFN has).  T must be positive.

@@ -1330,7 +1330,13 @@ extern "C" int ef_layer_step(ef_ctx *c, int layer, const void *hidden, int T, fl
     int32_t hist_host[EF_MAX_HORIZON * EF_MAX_EXPERTS];
     for (int x = 0; x < n_hist; ++x) hist_host[x] = mh[ef::kMetaHist + x] & value_mask;
     if (counts_host_out) memcpy(counts_host_out, counts_host, (size_t)E * 4);
-    // 3. horizon for the next layer and prefetches, issued before the FFN so the copies overlap it
+    // 3. grouped FFN first (resident groups, misses swapped in meanwhile, weighted un-permute): the GPU has
+    //    nothing to do until these launches are enqueued, so everything else the host decides comes after
+    c->prepacked = did_pack;
+    rc = ef_moe_ffn(c, layer, hidden, T, c->st_ids, c->st_w, counts_host, c->st_offsets, c->st_perm, c->st_inv, out,
+                    stream);
+    if (rc) return rc;
+    // 4. horizon for the next layer and prefetches: the copies overlap the FFN that is now running
     int Hn = c->horizon;
     if (He > 0) {
         int32_t lst[EF_MAX_HORIZON * EF_MAX_EXPERTS];
@@ -1344,10 +1350,7 @@ extern "C" int ef_layer_step(ef_ctx *c, int layer, const void *hidden, int T, fl
         }
     }
     if (H_next) *H_next = Hn;
-    // 4. grouped FFN: resident groups first, misses swapped in meanwhile, weighted un-permute
-    c->prepacked = did_pack;
-    return ef_moe_ffn(c, layer, hidden, T, c->st_ids, c->st_w, counts_host, c->st_offsets, c->st_perm, c->st_inv,
-                      out, stream);
+    return EF_OK;
 }
 
 extern "C" int ef_get_stats(ef_ctx *c, ef_stats *out) {

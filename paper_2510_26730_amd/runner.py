@@ -120,6 +120,10 @@ class LayerLoop:
         self.meta_host.copy_(self.meta, non_blocking=True)
         stream.synchronize()
         mh = self.meta_host.numpy()
+        # the FFN is enqueued first (the GPU is idle until then); the prefetch copies decided afterwards
+        # overlap it
+        ef.ef_moe_ffn(self.ctx, l, h, T, self.ids, self.w, mh[:E], self.offsets, self.perm, self.inv_perm,
+                      self.out, stream)
         if he > 0:
             self.H, lst = ef.ef_choose_horizon(self.ctx, l, mh[E:E + he * E].reshape(he, E), T)
             for j, e in lst:
@@ -128,8 +132,6 @@ class LayerLoop:
                 except ef.EfError as err:       # a full, pinned cache is not an error for a prefetch
                     if err.code != ef.EF_EBUSY:
                         raise
-        ef.ef_moe_ffn(self.ctx, l, h, T, self.ids, self.w, mh[:E], self.offsets, self.perm, self.inv_perm,
-                      self.out, stream)
 
     def step(self, hidden_stack: torch.Tensor, stream) -> None:
         """hidden_stack [L, T, d] bf16 on the device: the inputs of the L layers of this step."""
