@@ -202,6 +202,9 @@ def main():
     ntile_avg = T * cfg.k / max(1, cfg.E) / 32.0
     dom_name = "ffn_up_tiled" if ntile_avg >= 8 else "ffn_up"
     ef.ef_set_profile(loop.ctx, 1 << ef.EF_KERNELS.index(dom_name))
+    # every 4th launch of it (events between kernels cost the stream 2-3 us each); with fewer than 64 launches
+    # in the timed region, every launch
+    ef.ef_set_profile_sampling(loop.ctx, 4 if L * args.steps >= 64 else 1)
     ef.ef_reset_stats(loop.ctx)
     t0 = time.perf_counter()
     marks = []
@@ -218,6 +221,7 @@ def main():
 
     # separate, untimed pass with every kernel bracketed: the per-kernel breakdown
     ef.ef_set_profile(loop.ctx, 0x3FF)
+    ef.ef_set_profile_sampling(loop.ctx, 1)
     ef.ef_reset_stats(loop.ctx)
     t1 = time.perf_counter()
     tok_dist = torch.empty(T, dtype=torch.float32, device="cuda")

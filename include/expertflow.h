@@ -419,6 +419,12 @@ int ef_reset_stats(ef_ctx *ctx);
  * 0 = none (overrides the EF_FLAG_PROFILE* flags given at creation). */
 int ef_set_profile(ef_ctx *ctx, unsigned kinds_mask);
 
+/* Bracket only every `every`-th launch of each selected kind (default 1 = all).  An event record between two
+ * kernels costs the stream a bubble of 2-3 us; a sample of the launches gives the same average duration
+ * while the run being measured stays close to an unmeasured one.  Launch counts, times, bytes and flops in
+ * ef_stats then cover the sampled launches only. */
+int ef_set_profile_sampling(ef_ctx *ctx, int every);
+
 /* Fake-copy contexts only: advance the fake clock; copies complete after bytes/bandwidth seconds. */
 int ef_fake_advance_time(ef_ctx *ctx, double seconds);
 

@@ -29,7 +29,8 @@ EF_MAX_EXPERTS, EF_MAX_TOPK, EF_MAX_HORIZON = 64, 8, 7
 EXPORTS = [
     "ef_strerror", "ef_expert_bytes", "ef_pack_expert", "ef_expert_bytes_q4", "ef_pack_expert_q4", "ef_create", "ef_destroy", "ef_last_error",
     "ef_register_layer", "ef_predict", "ef_route", "ef_route_predict", "ef_moe_ffn", "ef_layer_step", "ef_cache_swap_in", "ef_cache_query",
-    "ef_choose_horizon", "ef_token_dist", "ef_get_stats", "ef_reset_stats", "ef_set_profile", "ef_fake_advance_time",
+    "ef_choose_horizon", "ef_token_dist", "ef_get_stats", "ef_reset_stats", "ef_set_profile", "ef_set_profile_sampling",
+    "ef_fake_advance_time",
     "ef_forest_create", "ef_forest_destroy", "ef_delta_features", "ef_forest_fit", "ef_forest_predict",
     "ef_forest_tree_size", "ef_forest_tree_export", "ef_forest_bit_accuracy", "ef_delta_from_activation",
     "ef_delta_cache_create", "ef_delta_cache_destroy", "ef_delta_cache_put", "ef_delta_cache_get",
@@ -117,6 +118,7 @@ def lib():
         L.ef_get_stats.argtypes = [vp, C.POINTER(ef_stats)]
         L.ef_reset_stats.argtypes = [vp]
         L.ef_set_profile.argtypes = [vp, C.c_uint]
+        L.ef_set_profile_sampling.argtypes = [vp, i32]
         L.ef_fake_advance_time.argtypes = [vp, C.c_double]
         ll = C.c_longlong
         L.ef_forest_create.argtypes = [C.POINTER(ef_forest_config), C.POINTER(vp)]
@@ -325,6 +327,10 @@ def ef_reset_stats(ctx):
 
 def ef_set_profile(ctx, kinds_mask):
     return _check(ctx, lib().ef_set_profile(ctx, kinds_mask))
+
+
+def ef_set_profile_sampling(ctx, every):
+    return _check(ctx, lib().ef_set_profile_sampling(ctx, every))
 
 
 def ef_fake_advance_time(ctx, seconds):

@@ -79,7 +79,10 @@ struct ef_ctx {
     size_t prof_next = 0;
     std::deque<ProfItem> prof_pending;
     unsigned profile_mask = 0;       // bit per kernel kind that is bracketed with events
+    int profile_every = 1;           // bracket every n-th launch of a selected kernel kind
+    long long profile_seen[EF_K_COUNT] = {};
     bool layer_open = false;
+    long long layer_calls = 0;       // layers started (every kLayerTimerEvery-th is timed)
     EventPair layer_cur{nullptr, nullptr};
     // estimators and feedback
     double bw_Bps = 50e9, layer_s = 200e-6;
@@ -125,6 +128,10 @@ int tune(const char *name, int dflt) {
 
 void ema(double &est, double sample, double alpha = 0.25) { est = (1.0 - alpha) * est + alpha * sample; }
 
+// Every kLayerTimerEvery-th layer is bracketed with events for the T_l estimate: an event record between two
+// kernels costs the stream a bubble of 2-3 us, and the estimate is a moving average anyway.
+constexpr long long kLayerTimerEvery = 4;
+
 // ---- completion polling ---------------------------------------------------------------------
 
 void poll_copy(ef_ctx *c, int slot) {
@@ -167,7 +174,7 @@ void poll_pairs(ef_ctx *c, bool wait) {
         if (q != hipSuccess) { (void)hipGetLastError(); break; }
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess && ms > 0.f) {
-            c->st.layer_seconds += ms * 1e-3;
+            c->st.layer_seconds += ms * 1e-3 * (double)kLayerTimerEvery;   // a sample stands for its neighbours
             if (!(c->cfg.flags & EF_FLAG_FIXED_ESTIMATES)) ema(c->layer_s, ms * 1e-3);
         }
         c->layer_pending.pop_front();
@@ -200,6 +207,7 @@ struct KernelTimer {
     bool on;
     KernelTimer(ef_ctx *ctx, hipStream_t st, int k, double b, double f = 0.0)
         : c(ctx), s(st), kind(k), bytes(b), flops(f), on(((ctx->profile_mask >> k) & 1u) != 0) {
+        if (on && ctx->profile_every > 1) on = (ctx->profile_seen[k]++ % ctx->profile_every) == 0;
         if (!on) return;
         if (c->prof_pending.size() >= c->prof_ring.size()) poll_prof(c, true);
         p = c->prof_ring[c->prof_next];
@@ -711,6 +719,7 @@ int check_predict_args(ef_ctx *c, int layer, int T, int H, int *He_out, const ch
 
 int open_layer_timer(ef_ctx *c, hipStream_t s) {
     poll_pairs(c, false);
+    if ((c->layer_calls++ % kLayerTimerEvery) != 0) return EF_OK;
     c->layer_cur = next_pair(c->layer_ring, c->layer_next, c->layer_pending);
     EF_HIP(c, hipEventRecord(c->layer_cur.a, s));
     c->layer_open = true;
@@ -1096,14 +1105,43 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         loading.push_back({e, slot});
     }
 
+    // A slot may be overwritten once the kernels that read it have finished: an event recorded behind them
+    // is what a later swap-in waits for.  One event behind the layer's last kernel serves every slot of the
+    // layer; only when misses are still waiting for a slot (phase C) must each phase's slots be released as
+    // soon as that phase's kernels are enqueued.
+    const bool eager_marks = !deferred.empty();
+    std::vector<int> read_slots;
+    struct PinGuard {   // an error return between the phases must not leave the collected slots pinned
+        ef_ctx *c;
+        std::vector<int> *v;
+        ~PinGuard() { for (int slot : *v) c->cache->pin(slot, false); }
+    } pin_guard{c, &read_slots};
     auto mark_read = [&](const std::vector<PhaseGroup> &v) -> int {
         if (c->fake) { unpin_all(v); return EF_OK; }
+        if (!eager_marks) {
+            for (const auto &g : v)
+                if (g.expert >= 0) read_slots.push_back(g.slot);
+            return EF_OK;   // still pinned: released behind the layer's last kernel
+        }
         hipEvent_t ev = c->read_ring[c->read_next];
         c->read_next = (c->read_next + 1) % c->read_ring.size();
         EF_HIP(c, hipEventRecord(ev, s));
         for (const auto &g : v)
             if (g.expert >= 0) c->slots[(size_t)g.slot].last_read = ev;
         unpin_all(v);
+        return EF_OK;
+    };
+    auto release_read_slots = [&]() -> int {
+        if (read_slots.empty()) return EF_OK;
+        hipEvent_t ev = c->read_ring[c->read_next];
+        c->read_next = (c->read_next + 1) % c->read_ring.size();
+        hipError_t he = hipEventRecord(ev, s);
+        for (int slot : read_slots) {
+            c->slots[(size_t)slot].last_read = ev;
+            c->cache->pin(slot, false);
+        }
+        read_slots.clear();
+        if (he != hipSuccess) return fail(c, EF_EHIP, "hipEventRecord failed: %s", hipGetErrorString(he));
         return EF_OK;
     };
     auto wait_loaded = [&](const std::vector<PhaseGroup> &v) -> int {
@@ -1196,6 +1234,7 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
                                          has_shared ? (long long)T * k : -1ll, out, s));
         }
     }
+    if ((rc = release_read_slots())) return rc;
     if (!c->fake && c->layer_open) {
         EF_HIP(c, hipEventRecord(c->layer_cur.b, s));
         c->layer_pending.push_back(c->layer_cur);
@@ -1384,6 +1423,14 @@ extern "C" int ef_set_profile(ef_ctx *c, unsigned kinds_mask) {
         }
     }
     c->profile_mask = kinds_mask & 0x3FFu;
+    return EF_OK;
+}
+
+extern "C" int ef_set_profile_sampling(ef_ctx *c, int every) {
+    if (!c) return fail(nullptr, EF_EINVAL, "null context");
+    if (every < 1) return fail(c, EF_EINVAL, "ef_set_profile_sampling: every must be >= 1");
+    c->profile_every = every;
+    for (auto &n : c->profile_seen) n = 0;
     return EF_OK;
 }
 
