@@ -1230,8 +1230,21 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         if (!c->fake) {
             KernelTimer kt(c, s, EF_K_COMBINE, 4.0 * ((double)T * k + (has_shared ? T : 0)) * d + 4.0 * T * d +
                                                    8.0 * T * k);
+            // the layer's last kernel carries the read marker of the slots collected above
+            hipEvent_t done = nullptr;
+            if (!read_slots.empty()) {
+                done = c->read_ring[c->read_next];
+                c->read_next = (c->read_next + 1) % c->read_ring.size();
+            }
             EF_HIP(c, ef::launch_combine(c->y, ksg, y_plane, topk_w, inv_perm, T, k, d,
-                                         has_shared ? (long long)T * k : -1ll, out, s));
+                                         has_shared ? (long long)T * k : -1ll, out, done, s));
+            if (done) {
+                for (int slot : read_slots) {
+                    c->slots[(size_t)slot].last_read = done;
+                    c->cache->pin(slot, false);
+                }
+                read_slots.clear();
+            }
         }
     }
     if ((rc = release_read_slots())) return rc;

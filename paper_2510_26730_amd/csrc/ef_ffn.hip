@@ -5,6 +5,8 @@
 // sees few tokens (decode); every weight fragment is then used exactly once.  The kernels are
 // therefore built around long, contiguous, software-pipelined 1 KiB fragment streams per wave and
 // enough waves in flight; the matrix cores only have to keep up.
+#include <hip/hip_ext.h>
+
 #include "ef_device.h"
 #include "ef_kernels.h"
 
@@ -522,11 +524,17 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
     *reinterpret_cast<float4 *>(out + (size_t)t * d + c) = acc;
 }
 
+// `done` (may be null): an event that completes with this kernel.  It rides on the kernel's own completion
+// signal, which costs the stream nothing, where a separate event record behind the kernel costs 2-3 us.
 hipError_t launch_combine(const float *y, int ksg, long long y_plane, const float *w, const int32_t *inv_perm,
-                          int T, int k, int d, long long shared_row0, float *out, hipStream_t s) {
+                          int T, int k, int d, long long shared_row0, float *out, hipEvent_t done, hipStream_t s) {
     if (T <= 0) return hipSuccess;
-    hipLaunchKernelGGL(combine_kernel, dim3(T, (d + 1023) / 1024), dim3(256), 0, s, y, ksg, y_plane, w, inv_perm,
-                       T, k, d, shared_row0, out);
+    if (done)
+        hipExtLaunchKernelGGL(combine_kernel, dim3(T, (d + 1023) / 1024), dim3(256), 0, s, nullptr, done, 0, y, ksg,
+                              y_plane, w, inv_perm, T, k, d, shared_row0, out);
+    else
+        hipLaunchKernelGGL(combine_kernel, dim3(T, (d + 1023) / 1024), dim3(256), 0, s, y, ksg, y_plane, w, inv_perm,
+                           T, k, d, shared_row0, out);
     return hipGetLastError();
 }
 
