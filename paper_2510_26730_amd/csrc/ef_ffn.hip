@@ -406,7 +406,7 @@ __global__ __launch_bounds__(256, 2) void ffn_down_kernel(GroupTable gt, const u
     constexpr int CBW = kDownColBlocks;
     constexpr int UNR = 2;
     constexpr int REGION = CBW * TT * 16 * 64;   // floats of one wave's partial
-    __shared__ float red[2 * REGION];
+    __shared__ float red[4 * REGION];
     const int wg = blockIdx.x;
     int grp = 0;
     while (grp + 1 < gt.n_groups && gt.wg_start[grp + 1] <= wg) ++grp;
@@ -435,45 +435,31 @@ __global__ __launch_bounds__(256, 2) void ffn_down_kernel(GroupTable gt, const u
     if (TT == 1 || ntl == 1) down_stream<TT, 1, CBW, UNR>(w2, cb_stride, a0, nkb, k0, k1, acc);
     else down_stream<TT, TT, CBW, UNR>(w2, cb_stride, a0, nkb, k0, k1, acc);
 
-    auto put = [&](float *r) {
+    // The four waves' partial tiles meet in LDS; every wave then sums a quarter of the tile in the fixed
+    // order (p0 + p2) + (p1 + p3) and stores that quarter, so the adds and the stores of the epilogue run on
+    // all four waves (one barrier) instead of a three-step tree that leaves one wave to store everything.
 #pragma unroll
-        for (int cw = 0; cw < CBW; ++cw)
+    for (int cw = 0; cw < CBW; ++cw)
 #pragma unroll
-            for (int tt = 0; tt < TT; ++tt)
+        for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) r[((cw * TT + tt) * 16 + v) * 64 + lane] = acc[cw][tt][v];
-    };
-    auto add = [&](const float *r) {
-#pragma unroll
-        for (int cw = 0; cw < CBW; ++cw)
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[cw][tt][v] += r[((cw * TT + tt) * 16 + v) * 64 + lane];
-    };
-    if (wave >= 2) put(red + (wave - 2) * REGION);
+            for (int v = 0; v < 16; ++v) red[wave * REGION + ((cw * TT + tt) * 16 + v) * 64 + lane] = acc[cw][tt][v];
     __syncthreads();
-    if (wave < 2) add(red + wave * REGION);
-    __syncthreads();
-    if (wave == 1) put(red);
-    __syncthreads();
-    if (wave != 0) return;
-    add(red);
 
     const int g = lane >> 5;
     float *Yp = Y + (size_t)kslice * y_plane;
+    constexpr int UNITS = CBW * TT * 16;          // 64-lane slices of the tile; a quarter per wave
+    static_assert(UNITS % 4 == 0, "the tile is dealt to four waves");
 #pragma unroll
-    for (int tt = 0; tt < TT; ++tt) {
-        if (tt >= ntl) break;
-#pragma unroll
-        for (int cw = 0; cw < CBW; ++cw) {
-            const int col = (cb0 + cw) * 32 + (lane & 31);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int tl = (pass * TT + tt) * kTile + 8 * (v >> 2) + 4 * g + (v & 3);
-                if (tl < gt.count[grp]) Yp[(size_t)(gt.row_offset[grp] + tl) * d + col] = acc[cw][tt][v];
-            }
-        }
+    for (int q = 0; q < UNITS / 4; ++q) {
+        const int u = wave * (UNITS / 4) + q;
+        const int cw = u / (TT * 16), tt = (u / 16) % TT, v = u % 16;
+        const float *r = red + u * 64 + lane;
+        const float sum = (r[0] + r[2 * REGION]) + (r[REGION] + r[3 * REGION]);
+        if (tt >= ntl) continue;
+        const int col = (cb0 + cw) * 32 + (lane & 31);
+        const int tl = (pass * TT + tt) * kTile + 8 * (v >> 2) + 4 * g + (v & 3);
+        if (tl < gt.count[grp]) Yp[(size_t)(gt.row_offset[grp] + tl) * d + col] = sum;
     }
 }
 
