@@ -75,15 +75,15 @@ def run(cfg, T: int, L: int, H: int, P: int, steps: int, warmup: int, log_steps:
         return hits, total
 
     # ---- 1. activation logs from the kernels' routing of log_steps steps -----------------------------------
-    def examples(pid, act):                      # act [T, L, E]; one example per (request, layer), lag = S
+    def examples(pid, act, step_size):           # act [T, L, E]; one example per (request, layer), lag = step size
         X = np.empty((T * L, d_emb + 2 + L * E), dtype=np.float32)
         Y = np.empty((T * L, E), dtype=np.uint8)
         for t in range(T):
             for l in range(L):
                 prev = np.zeros((L, E), dtype=np.uint8)
-                known = max(0, l - S)
+                known = max(0, l - step_size)
                 prev[:known] = act[t, :known]
-                X[t * L + l] = ef.ef_delta_features(table, pool[pid[t]], S, l, prev, L, E)
+                X[t * L + l] = ef.ef_delta_features(table, pool[pid[t]], step_size, l, prev, L, E)
                 Y[t * L + l] = act[t, l]
         return X, Y
 
@@ -92,9 +92,10 @@ def run(cfg, T: int, L: int, H: int, P: int, steps: int, warmup: int, log_steps:
     for s in range(log_steps):
         pid, h = batch(s)
         actual, _ = route_pass(h)
-        X, Y = examples(pid, multi_hot(actual))
-        Xs.append(X)
-        Ys.append(Y)
+        for step_size in range(1, H + 1):        # the step size is a feature: one set of examples per value
+            X, Y = examples(pid, multi_hot(actual), step_size)
+            Xs.append(X)
+            Ys.append(Y)
     X, Y = np.concatenate(Xs), np.concatenate(Ys)
     t_logs = time.perf_counter() - t0
 
@@ -115,7 +116,7 @@ def run(cfg, T: int, L: int, H: int, P: int, steps: int, warmup: int, log_steps:
     # ---- 3. look-ahead quality on fresh steps: plain look-ahead against look-ahead + deviation -----------------
     base_hits = base_tot = None
     gain_hits = {g: np.zeros(H, dtype=np.int64) for g in gains}
-    acc_num = acc_den = 0.0
+    acc_num, acc_den = np.zeros(H + 1), np.zeros(H + 1)       # bit accuracy per step size (Sec. 3.2.5)
     seen = set(np.concatenate([synth.prompt_draws(cfg, s, T, P, cfg.zipf_s) for s in range(log_steps)]).tolist())
     n_seen = n_req = 0
     for s in range(log_steps, log_steps + eval_steps):
@@ -128,9 +129,10 @@ def run(cfg, T: int, L: int, H: int, P: int, steps: int, warmup: int, log_steps:
         base_hits = hh if base_hits is None else base_hits + hh
         base_tot = tt if base_tot is None else base_tot + tt
         act = multi_hot(actual)
-        Xe, Ye = examples(pid, act)
-        acc_num += ef.ef_forest_bit_accuracy(ef.ef_forest_predict(forest, Xe, E), Ye) * Ye.size
-        acc_den += Ye.size
+        for step_size in range(1, H + 1):
+            Xe, Ye = examples(pid, act, step_size)
+            acc_num[step_size] += ef.ef_forest_bit_accuracy(ef.ef_forest_predict(forest, Xe, E), Ye) * Ye.size
+            acc_den[step_size] += Ye.size
         for g in gains:
             def delta_of_layer(l, actual_so_far, g=g):
                 known = np.zeros((T, L, E), dtype=np.uint8)
@@ -214,7 +216,8 @@ def run(cfg, T: int, L: int, H: int, P: int, steps: int, warmup: int, log_steps:
         "log_steps": log_steps, "examples": int(X.shape[0]), "features": int(X.shape[1]),
         "log_collection_s": t_logs, "fit_s": t_fit, "trees": n_trees, "max_depth": max_depth, "nodes_per_tree": nodes,
         "eval_steps": eval_steps, "share_of_eval_requests_seen_in_logs": n_seen / max(1, n_req),
-        "bit_accuracy_eval": acc_num / acc_den,
+        "bit_accuracy_eval": float(acc_num.sum() / acc_den.sum()),
+        "bit_accuracy_by_step_size": {str(ss): float(acc_num[ss] / acc_den[ss]) for ss in range(1, H + 1)},
         "lookahead_recall_plain": (base_hits / base_tot).tolist(),
         "lookahead_recall_with_delta": {str(g): (gain_hits[g] / base_tot).tolist() for g in gains},
         "best_gain": best_gain,

@@ -22,6 +22,7 @@ def test_deviation_refines_the_lookahead_on_recurring_prompts():
     refined = r["lookahead_recall_with_delta"]["2.0"]
     assert len(plain) == 2 and all(0.0 < p <= 1.0 for p in plain)
     assert sum(refined) >= sum(plain)
-    assert r["examples"] == 10 * 32 * 3 and r["features"] == 16 + 2 + 3 * cfg.E
+    assert r["examples"] == 10 * 32 * 3 * 2 and r["features"] == 16 + 2 + 3 * cfg.E
+    assert set(r["bit_accuracy_by_step_size"]) == {"1", "2"}
     assert 0.5 < r["bit_accuracy_eval"] <= 1.0
     assert r["layer_loop_with_delta"]["delta_rows_found"] > 0.0
