@@ -69,31 +69,53 @@ __device__ __forceinline__ bool tiled_panel(int local, int npanels, int mpanels,
 // global -> LDS load after the third.  A wave that issues its loads in a burst stalls at the issue
 // until the CU's address path (about 64 bytes per clock) has taken them, and its matrix core idles
 // meanwhile; one load per four MFMAs (128 clocks, four waves) stays below that rate.
-#define EF_TILED_RA(an, buf, ks, r) an[r] = lds[buf][(ks) * 16 + AOFF + (r)][lane];
-#define EF_TILED_RB(bn, buf, ks, r) bn[r] = lds[buf][(ks) * 16 + 8 + BOFF + (r)][lane];
-#define EF_TILED_ROUND(ac, bc, r, x0, x1, x3, st, half)                                              \
-    acc[r][0] = mfma32v(ac[r], bc[0], acc[r][0]);                                                    \
+//
+// NLA / NLB (literals 0..4): only the first NLA operand-A fragments and the first NLB operand-B fragments
+// of the wave are live; the MFMAs and LDS reads of the others are left out.  The token tiles are one of
+// the two operands, and the last token panel of a group is rarely full: the kernels are limited by power,
+// so matrix-core work on tiles that do not exist costs real throughput.  Loads and barriers are the same in
+// every variant (the waves of a workgroup run different ones side by side).
+#define EF_TILED_MF(ac, bc, r, j, NLA, NLB)                                                          \
+    if ((r) < (NLA) && (j) < (NLB)) acc[r][j] = mfma32v(ac[r], bc[j], acc[r][j]);
+#define EF_TILED_RA(an, buf, ks, r, NLA) if ((r) < (NLA)) an[r] = lds[buf][(ks) * 16 + AOFF + (r)][lane];
+#define EF_TILED_RB(bn, buf, ks, r, NLB) if ((r) < (NLB)) bn[r] = lds[buf][(ks) * 16 + 8 + BOFF + (r)][lane];
+#define EF_TILED_ROUND(ac, bc, r, x0, x1, x3, st, half, NLA, NLB)                                    \
+    EF_TILED_MF(ac, bc, r, 0, NLA, NLB)                                                              \
     x0 __builtin_amdgcn_sched_barrier(0);                                                            \
-    acc[r][1] = mfma32v(ac[r], bc[1], acc[r][1]);                                                    \
+    EF_TILED_MF(ac, bc, r, 1, NLA, NLB)                                                              \
     x1 __builtin_amdgcn_sched_barrier(0);                                                            \
-    acc[r][2] = mfma32v(ac[r], bc[2], acc[r][2]);                                                    \
+    EF_TILED_MF(ac, bc, r, 2, NLA, NLB)                                                              \
     EF_TILED_DMA(src[(half) * 4 + (r)] + (size_t)stc_ * kTileKS * 64, EF_TILED_DST(st, (half) * 4 + (r))); \
     __builtin_amdgcn_sched_barrier(0);                                                               \
-    acc[r][3] = mfma32v(ac[r], bc[3], acc[r][3]);                                                    \
+    EF_TILED_MF(ac, bc, r, 3, NLA, NLB)                                                              \
     x3 __builtin_amdgcn_sched_barrier(0);
-#define EF_TILED_STEP(ac, bc, an, bn, buf, ks, st, half)                                             \
+#define EF_TILED_STEP(ac, bc, an, bn, buf, ks, st, half, NLA, NLB)                                   \
     {                                                                                                \
         const int stc_ = min((st), nstage - 1);                                                      \
-        EF_TILED_ROUND(ac, bc, 0, EF_TILED_RA(an, buf, ks, 0), EF_TILED_RB(bn, buf, ks, 0),          \
-                       EF_TILED_RA(an, buf, ks, 1), st, half)                                        \
-        EF_TILED_ROUND(ac, bc, 1, EF_TILED_RB(bn, buf, ks, 1), EF_TILED_RA(an, buf, ks, 2),          \
-                       EF_TILED_RB(bn, buf, ks, 2), st, half)                                        \
-        EF_TILED_ROUND(ac, bc, 2, EF_TILED_RA(an, buf, ks, 3), EF_TILED_RB(bn, buf, ks, 3), , st, half) \
-        EF_TILED_ROUND(ac, bc, 3, , , , st, half)                                                    \
+        EF_TILED_ROUND(ac, bc, 0, EF_TILED_RA(an, buf, ks, 0, NLA), EF_TILED_RB(bn, buf, ks, 0, NLB), \
+                       EF_TILED_RA(an, buf, ks, 1, NLA), st, half, NLA, NLB)                         \
+        EF_TILED_ROUND(ac, bc, 1, EF_TILED_RB(bn, buf, ks, 1, NLB), EF_TILED_RA(an, buf, ks, 2, NLA), \
+                       EF_TILED_RB(bn, buf, ks, 2, NLB), st, half, NLA, NLB)                         \
+        EF_TILED_ROUND(ac, bc, 2, EF_TILED_RA(an, buf, ks, 3, NLA), EF_TILED_RB(bn, buf, ks, 3, NLB), , st, half, \
+                       NLA, NLB)                                                                     \
+        EF_TILED_ROUND(ac, bc, 3, , , , st, half, NLA, NLB)                                          \
     }
 // The main loop over stages [first, last): stage st feeds the matrix cores while the loads of stages
 // st+1 and st+2 are in flight and those of stage st+3 are being issued; one barrier per stage.
-#define EF_TILED_PIPELINE(first, last)                                                               \
+#define EF_TILED_LOOP(first, last, NLA, NLB)                                                         \
+    for (int st = (first); st < (last); ++st) {                                                      \
+        const int cur = st & (kTileStages - 1), nxt = (st + 1) & (kTileStages - 1);                  \
+        /* the buffer of stage st+3 held stage st-1, whose last reads every wave finished before */  \
+        /* the barrier of the previous iteration */                                                  \
+        EF_TILED_STEP(a0, b0, a1, b1, cur, 1, st + 3, 0, NLA, NLB)                                   \
+        /* stage st+1 must have landed: of the loads issued after it (stage st+2 and half of */      \
+        /* stage st+3) all 12 may still be outstanding */                                            \
+        __builtin_amdgcn_s_waitcnt(kWaitVm12);                                                       \
+        __syncthreads();                                                                             \
+        __builtin_amdgcn_sched_barrier(0);                                                           \
+        EF_TILED_STEP(a1, b1, a0, b0, nxt, 0, st + 3, 1, NLA, NLB)                                   \
+    }
+#define EF_TILED_PROLOGUE(first)                                                                     \
     static_assert(kTileKS == 2, "the loop alternates two fragment register sets");                   \
     u32x4_t a0[4], b0[4], a1[4], b1[4];                                                              \
     EF_TILED_ISSUE(first)                                                                            \
@@ -101,18 +123,27 @@ __device__ __forceinline__ bool tiled_panel(int local, int npanels, int mpanels,
     EF_TILED_ISSUE((first) + 2)                                                                      \
     __builtin_amdgcn_s_waitcnt(kWaitVm16); /* my part of the first stage has landed */               \
     __syncthreads();                       /* ... and everybody else's */                            \
-    EF_TILED_READ(a0, b0, (first) & (kTileStages - 1), 0)                                            \
-    for (int st = (first); st < (last); ++st) {                                                      \
-        const int cur = st & (kTileStages - 1), nxt = (st + 1) & (kTileStages - 1);                  \
-        /* the buffer of stage st+3 held stage st-1, whose last reads every wave finished before */  \
-        /* the barrier of the previous iteration */                                                  \
-        EF_TILED_STEP(a0, b0, a1, b1, cur, 1, st + 3, 0)                                             \
-        /* stage st+1 must have landed: of the loads issued after it (stage st+2 and half of */      \
-        /* stage st+3) all 12 may still be outstanding */                                            \
-        __builtin_amdgcn_s_waitcnt(kWaitVm12);                                                       \
-        __syncthreads();                                                                             \
-        __builtin_amdgcn_sched_barrier(0);                                                           \
-        EF_TILED_STEP(a1, b1, a0, b0, nxt, 0, st + 3, 1)                                             \
+    EF_TILED_READ(a0, b0, (first) & (kTileStages - 1), 0)
+// `live` (wave-uniform, 0..4): live token tiles of the wave; they are operand B in the first half ...
+#define EF_TILED_PIPELINE_TILES_B(first, last, live)                                                 \
+    EF_TILED_PROLOGUE(first)                                                                         \
+    switch (live) {                                                                                  \
+        case 4: EF_TILED_LOOP(first, last, 4, 4) break;                                              \
+        case 3: EF_TILED_LOOP(first, last, 4, 3) break;                                              \
+        case 2: EF_TILED_LOOP(first, last, 4, 2) break;                                              \
+        case 1: EF_TILED_LOOP(first, last, 4, 1) break;                                              \
+        default: EF_TILED_LOOP(first, last, 4, 0) break;                                             \
+    }                                                                                                \
+    __builtin_amdgcn_s_waitcnt(0);
+// ... and operand A in the second
+#define EF_TILED_PIPELINE_TILES_A(first, last, live)                                                 \
+    EF_TILED_PROLOGUE(first)                                                                         \
+    switch (live) {                                                                                  \
+        case 4: EF_TILED_LOOP(first, last, 4, 4) break;                                              \
+        case 3: EF_TILED_LOOP(first, last, 3, 4) break;                                              \
+        case 2: EF_TILED_LOOP(first, last, 2, 4) break;                                              \
+        case 1: EF_TILED_LOOP(first, last, 1, 4) break;                                              \
+        default: EF_TILED_LOOP(first, last, 0, 4) break;                                             \
     }                                                                                                \
     __builtin_amdgcn_s_waitcnt(0);
 
@@ -165,7 +196,9 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_tiled_kernel(GroupTable gt
 
     const int AOFF = wf * 4, BOFF = wt * 4;
     const unsigned lds_base = (unsigned)(size_t)&lds[0][0][0];   // LDS byte offset: the low half of its flat address
-    EF_TILED_PIPELINE(0, nstage)
+    // token tiles t0 + 4*wt .. +3 of this wave that exist (wave-uniform)
+    const int live = max(0, min(4, ntiles - (t0 + BOFF)));
+    EF_TILED_PIPELINE_TILES_B(0, nstage, live)
 
     // epilogue: act fragments (paired order) of row blocks rb0 + 2*wf + {0,1}, tiles t0 + 4*wt + j
     const int nkb2 = F >> 4;
@@ -260,7 +293,9 @@ __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, c
 
     const int AOFF = wt * 4, BOFF = wc * 4;
     const unsigned lds_base = (unsigned)(size_t)&lds[0][0][0];   // LDS byte offset: the low half of its flat address
-    EF_TILED_PIPELINE(s0, s1)
+    // token tiles t0 + 4*wt .. +3 of this wave that exist (wave-uniform)
+    const int live = max(0, min(4, ntiles - (t0 + AOFF)));
+    EF_TILED_PIPELINE_TILES_A(s0, s1, live)
 
     const int g = lane >> 5;
     float *Yp = Y + (size_t)kslice * y_plane;
