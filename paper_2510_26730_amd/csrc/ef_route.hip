@@ -358,7 +358,9 @@ __global__ __launch_bounds__(64 * kGateWaves) void gate_finish_kernel(GateArgs a
         sbias[x] = bp ? bp[x % a.E] : 0.f;
     }
     const float *src = a.part + (((size_t)tile * gridDim.y + blockIdx.y) * a.ksplit * kTile) * (NB * 32);
-    for (int x = tid; x < kTile * NB * 32; x += NT) {
+    // only the rows of the tokens this workgroup finishes (a token split leaves the others to its siblings)
+    const int tok_n = kTile / a.tsplit, x_lo = blockIdx.z * tok_n * (NB * 32);
+    for (int x = x_lo + tid; x < x_lo + tok_n * NB * 32; x += NT) {
         float pz[kGateMaxSplit];   // all loads first (one latency), then the adds in split order
 #pragma unroll
         for (int z = 0; z < kGateMaxSplit; ++z)
@@ -369,7 +371,6 @@ __global__ __launch_bounds__(64 * kGateWaves) void gate_finish_kernel(GateArgs a
         logits[x / (NB * 32)][x % (NB * 32)] = v;
     }
     __syncthreads();
-    const int tok_n = kTile / a.tsplit;
     gate_epilogue<NB>(a, logits, cnt, sbias, s_sc, tile, g0, Gl, blockIdx.z * tok_n, tok_n, a.tsplit > 1);
 }
 
