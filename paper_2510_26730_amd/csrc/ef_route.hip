@@ -481,6 +481,18 @@ __device__ __forceinline__ int scan_expert_inplace(int *cnt, int ntiles, int E, 
     return carry;
 }
 
+// the same exclusive prefix over the tiles of expert e by one thread, for batches of a few tiles
+constexpr int kGroupSerialTiles = 4;
+__device__ __forceinline__ int scan_expert_serial(int *cnt, int ntiles, int E, int e) {
+    int run = 0;
+    for (int b = 0; b < ntiles; ++b) {
+        const int v = cnt[b * E + e];
+        cnt[b * E + e] = run;
+        run += v;
+    }
+    return run;
+}
+
 // one wave: stable scatter of the assignments of token tile b.  nxt [64] (LDS, this wave's own) holds
 // the next free position of every expert for this tile.  Per chunk of 64 assignments the lanes with
 // the same expert are found with six ballots (one per bit of the expert id, E <= 64): a lane's
@@ -578,9 +590,13 @@ __global__ __launch_bounds__(1024) void group_small_kernel(const int32_t *__rest
     // one memory round trip brings the per-tile counts into LDS; the scans then run from there, in place
     for (int x = threadIdx.x; x < ntiles * E; x += blockDim.x) base[x] = bc[x];
     __syncthreads();
-    for (int e = wave; e < E; e += 16) {
-        int tot = scan_expert_inplace(base, ntiles, E, e, lane);
-        if (lane == 0) total[e] = tot;
+    if (ntiles <= kGroupSerialTiles) {   // a few tiles: one thread per expert walks them (no shuffle rounds)
+        if (threadIdx.x < (unsigned)E) total[threadIdx.x] = scan_expert_serial(base, ntiles, E, threadIdx.x);
+    } else {
+        for (int e = wave; e < E; e += 16) {
+            int tot = scan_expert_inplace(base, ntiles, E, e, lane);
+            if (lane == 0) total[e] = tot;
+        }
     }
     __syncthreads();
     if (wave == 0) {   // exclusive scan of the E <= 64 totals across the lanes of one wave
@@ -740,10 +756,7 @@ __global__ __launch_bounds__(1024) void gate_finish_group_kernel(GateArgs a, int
     // grouping of the routed gate (gate 0) from its per-tile counts
     for (int x = tid; x < ntiles * E; x += NT) base[x] = cnt[((x / E) * G) * E + x % E];
     __syncthreads();
-    for (int e = wave; e < E; e += NW) {
-        const int tot = scan_expert_inplace(base, ntiles, E, e, lane);
-        if (lane == 0) total[e] = tot;
-    }
+    if (tid < E) total[tid] = scan_expert_serial(base, ntiles, E, tid);   // at most kFusedMaxTiles tiles
     __syncthreads();
     if (wave == 0) {   // exclusive scan of the E <= 64 totals across the lanes of one wave
         const int t = lane < E ? total[lane] : 0;
