@@ -919,7 +919,9 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
     }
     if (n == 0) return EF_OK;
     ef::GroupTable dn = gu;
-    const int tpp = max_tiles >= 2 ? 2 : 1;
+    // token tiles per pass over a group's weights: groups of three or more tiles (too few for the tiled
+    // kernels) take passes of four, which halves the re-reads of their weights (bf16 kernels only)
+    const int tpp = (max_tiles >= 3 && !c->q4 && tune("EF_TUNE_TPP4", 1) != 0) ? 4 : max_tiles >= 2 ? 2 : 1;
     // K slices inside a workgroup of the first half: split while the launch has too few waves to
     // keep enough weight bytes in flight, as long as a slice keeps >= 16 fragments
     long long units = 0;
@@ -928,10 +930,19 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
     const int want_waves = tune("EF_TUNE_UP_WAVES", 768), nkb = d / 16;
     while (ks < 4 && units * ks < want_waves && nkb / (ks * 2) >= 16) ks *= 2;
     ks = tune("EF_TUNE_UP_KS", ks);
+    // passes of four tiles: the kernels whose four waves share the token / activation fragments through LDS
+    // (per-wave copies of them would be twice the weights' bytes from L2)
+    bool shared = tpp == 4 && !c->q4 && tune("EF_TUNE_SHARED", 1) != 0;
+    for (int i = 0; i < n && shared; ++i) shared = gu.F[i] % 128 == 0;
     int wg_gu = 0, wg_dn = 0;
     for (int i = 0; i < n; ++i) {
         gu.wg_start[i] = wg_gu;
         dn.wg_start[i] = wg_dn;
+        if (shared) {
+            wg_gu += ef::ffn_gate_up_shared_wgs(gu.F[i], gu.n_tiles[i], tpp);
+            wg_dn += ef::ffn_down_shared_wgs(d, gu.n_tiles[i], tpp, ksg);
+            continue;
+        }
         wg_gu += c->q4 ? ef::ffn_gate_up_q4_wgs(gu.F[i], gu.n_tiles[i], tpp)
                        : ef::ffn_gate_up_wgs(gu.F[i], gu.n_tiles[i], tpp, ks);
         wg_dn += c->q4 ? ef::ffn_down_q4_wgs(d, gu.n_tiles[i], tpp, ksg) : ef::ffn_down_wgs(d, gu.n_tiles[i], tpp, ksg);
@@ -942,12 +953,14 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
     alg_bytes(gu, n, b_up, b_dn);
     {
         KernelTimer kt(c, s, EF_K_FFN_UP, b_up);
-        if (c->q4) EF_HIP(c, ef::launch_ffn_gate_up_q4(gu, wg_gu, tpp, c->xp, c->act, d, s));
+        if (shared) EF_HIP(c, ef::launch_ffn_gate_up_shared(gu, wg_gu, tpp, c->xp, c->act, d, s));
+        else if (c->q4) EF_HIP(c, ef::launch_ffn_gate_up_q4(gu, wg_gu, tpp, c->xp, c->act, d, s));
         else EF_HIP(c, ef::launch_ffn_gate_up(gu, wg_gu, tpp, ks, c->xp, c->act, d, s));
     }
     {
         KernelTimer kt(c, s, EF_K_FFN_DOWN, b_dn);
-        if (c->q4) EF_HIP(c, ef::launch_ffn_down_q4(dn, wg_dn, tpp, ksg, c->act, c->y, y_plane, d, s));
+        if (shared) EF_HIP(c, ef::launch_ffn_down_shared(dn, wg_dn, tpp, ksg, c->act, c->y, y_plane, d, s));
+        else if (c->q4) EF_HIP(c, ef::launch_ffn_down_q4(dn, wg_dn, tpp, ksg, c->act, c->y, y_plane, d, s));
         else EF_HIP(c, ef::launch_ffn_down(dn, wg_dn, tpp, ksg, c->act, c->y, y_plane, d, s));
     }
     return EF_OK;
@@ -1029,13 +1042,16 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         int tmax = 1;
         for (int e = 0; e < E; ++e) tmax = std::max(tmax, (counts_host[e] + ef::kTile - 1) / ef::kTile);
         if (has_shared) tmax = std::max(tmax, (T + ef::kTile - 1) / ef::kTile);
-        const int tpp = tmax >= 2 ? 2 : 1;
+        const int tpp = (tmax >= 3 && !c->q4) ? 4 : tmax >= 2 ? 2 : 1;
         for (int e = 0; e < E; ++e)
             if (counts_host[e] > 0) {
                 const int nt = (counts_host[e] + ef::kTile - 1) / ef::kTile;
-                base_wgs += c->q4 ? ef::ffn_down_q4_wgs(d, nt, tpp, 1) : ef::ffn_down_wgs(d, nt, tpp, 1);
+                base_wgs += c->q4 ? ef::ffn_down_q4_wgs(d, nt, tpp, 1)
+                            : tpp == 4 ? ef::ffn_down_shared_wgs(d, nt, tpp, 1) : ef::ffn_down_wgs(d, nt, tpp, 1);
             }
-        if (has_shared) base_wgs += ef::ffn_down_wgs(d, (T + ef::kTile - 1) / ef::kTile, tpp, 1);
+        if (has_shared)
+            base_wgs += tpp == 4 ? ef::ffn_down_shared_wgs(d, (T + ef::kTile - 1) / ef::kTile, tpp, 1)
+                                 : ef::ffn_down_wgs(d, (T + ef::kTile - 1) / ef::kTile, tpp, 1);
         const int want = tune("EF_TUNE_DOWN_WGS", 256);
         const int nkb_min = std::min(c->cfg.d_ff, has_shared ? c->cfg.d_ff_shared : c->cfg.d_ff) / 16;
         // a slice keeps >= 32 fragments per wave (bf16: four waves split it again) or >= 6 quads (4-bit)

@@ -217,7 +217,7 @@ template <int TT, int KS>
 __global__ __launch_bounds__(256) void ffn_gate_up_kernel(GroupTable gt, const uint4 *__restrict__ xp,
                                                           uint4 *__restrict__ act, int d) {
     constexpr int RBW = 4 / KS;
-    constexpr int UNR = (TT == 1) ? 4 : 2;    // fragments per operand per pipeline stage (register budget)
+    constexpr int UNR = (TT == 1) ? 4 : (TT == 2) ? 2 : 1;   // fragments per operand per pipeline stage (register budget)
     constexpr int REGION = TT * 2 * 16 * 64;  // floats of one wave's partial (G and U of TT tiles)
     __shared__ float red[(KS > 1) ? 2 * REGION : 1];
 
@@ -248,6 +248,8 @@ __global__ __launch_bounds__(256) void ffn_gate_up_kernel(GroupTable gt, const u
         // the number of live token tiles is wave-uniform: pick a loop whose loads are unconditional,
         // so the compiler knows how many are in flight and waits only for the oldest stage
         if (TT == 1 || ntl == 1) up_stream<TT, 1, UNR>(w1, w3, x0, nkb, k0, k1, G, U);
+        else if (TT == 2 || ntl == 2) up_stream<TT, 2, UNR>(w1, w3, x0, nkb, k0, k1, G, U);
+        else if (ntl == 3) up_stream<TT, (TT > 2 ? 3 : TT), UNR>(w1, w3, x0, nkb, k0, k1, G, U);
         else up_stream<TT, TT, UNR>(w1, w3, x0, nkb, k0, k1, G, U);
     }
 
@@ -325,6 +327,7 @@ hipError_t launch_ffn_gate_up(const GroupTable &gt, int total_wgs, int tiles_per
     uint4 *a = reinterpret_cast<uint4 *>(act);
     if (tiles_per_pass == 1) return launch_up_tt<1>(gt, total_wgs, ks, x, a, d, s);
     if (tiles_per_pass == 2) return launch_up_tt<2>(gt, total_wgs, ks, x, a, d, s);
+    if (tiles_per_pass == 4) return launch_up_tt<4>(gt, total_wgs, ks, x, a, d, s);
     return hipErrorInvalidValue;
 }
 
@@ -404,8 +407,9 @@ __global__ __launch_bounds__(256, 2) void ffn_down_kernel(GroupTable gt, const u
                                                        float *__restrict__ Y, int d, int ksg,
                                                        long long y_plane) {
     constexpr int CBW = kDownColBlocks;
-    constexpr int UNR = 2;
-    constexpr int REGION = CBW * TT * 16 * 64;   // floats of one wave's partial
+    constexpr int UNR = TT > 2 ? 1 : 2;
+    constexpr int TH = TT > 2 ? 2 : TT;          // token tiles per round of the epilogue (LDS budget)
+    constexpr int REGION = CBW * TH * 16 * 64;   // floats of one wave's partial of one round
     __shared__ float red[4 * REGION];
     const int wg = blockIdx.x;
     int grp = 0;
@@ -433,33 +437,40 @@ __global__ __launch_bounds__(256, 2) void ffn_down_kernel(GroupTable gt, const u
         for (int tt = 0; tt < TT; ++tt) zero16(acc[cw][tt]);
 
     if (TT == 1 || ntl == 1) down_stream<TT, 1, CBW, UNR>(w2, cb_stride, a0, nkb, k0, k1, acc);
+    else if (TT == 2 || ntl == 2) down_stream<TT, 2, CBW, UNR>(w2, cb_stride, a0, nkb, k0, k1, acc);
+    else if (ntl == 3) down_stream<TT, (TT > 2 ? 3 : TT), CBW, UNR>(w2, cb_stride, a0, nkb, k0, k1, acc);
     else down_stream<TT, TT, CBW, UNR>(w2, cb_stride, a0, nkb, k0, k1, acc);
 
     // The four waves' partial tiles meet in LDS; every wave then sums a quarter of the tile in the fixed
     // order (p0 + p2) + (p1 + p3) and stores that quarter, so the adds and the stores of the epilogue run on
-    // all four waves (one barrier) instead of a three-step tree that leaves one wave to store everything.
-#pragma unroll
-    for (int cw = 0; cw < CBW; ++cw)
-#pragma unroll
-        for (int tt = 0; tt < TT; ++tt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) red[wave * REGION + ((cw * TT + tt) * 16 + v) * 64 + lane] = acc[cw][tt][v];
-    __syncthreads();
-
+    // all four waves instead of a three-step tree that leaves one wave to store everything.  Passes of four
+    // token tiles take two such rounds of two tiles (the partials of all four would not fit the LDS budget).
     const int g = lane >> 5;
     float *Yp = Y + (size_t)kslice * y_plane;
-    constexpr int UNITS = CBW * TT * 16;          // 64-lane slices of the tile; a quarter per wave
+    constexpr int UNITS = CBW * TH * 16;          // 64-lane slices of a round's tile; a quarter per wave
     static_assert(UNITS % 4 == 0, "the tile is dealt to four waves");
 #pragma unroll
-    for (int q = 0; q < UNITS / 4; ++q) {
-        const int u = wave * (UNITS / 4) + q;
-        const int cw = u / (TT * 16), tt = (u / 16) % TT, v = u % 16;
-        const float *r = red + u * 64 + lane;
-        const float sum = (r[0] + r[2 * REGION]) + (r[REGION] + r[3 * REGION]);
-        if (tt >= ntl) continue;
-        const int col = (cb0 + cw) * 32 + (lane & 31);
-        const int tl = (pass * TT + tt) * kTile + 8 * (v >> 2) + 4 * g + (v & 3);
-        if (tl < gt.count[grp]) Yp[(size_t)(gt.row_offset[grp] + tl) * d + col] = sum;
+    for (int round = 0; round < TT / TH; ++round) {
+        if (round > 0) __syncthreads();           // the previous round's partials have been read
+#pragma unroll
+        for (int cw = 0; cw < CBW; ++cw)
+#pragma unroll
+            for (int th = 0; th < TH; ++th)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    red[wave * REGION + ((cw * TH + th) * 16 + v) * 64 + lane] = acc[cw][round * TH + th][v];
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < UNITS / 4; ++q) {
+            const int u = wave * (UNITS / 4) + q;
+            const int cw = u / (TH * 16), tt = round * TH + (u / 16) % TH, v = u % 16;
+            const float *r = red + u * 64 + lane;
+            const float sum = (r[0] + r[2 * REGION]) + (r[REGION] + r[3 * REGION]);
+            if (tt >= ntl) continue;
+            const int col = (cb0 + cw) * 32 + (lane & 31);
+            const int tl = (pass * TT + tt) * kTile + 8 * (v >> 2) + 4 * g + (v & 3);
+            if (tl < gt.count[grp]) Yp[(size_t)(gt.row_offset[grp] + tl) * d + col] = sum;
+        }
     }
 }
 
@@ -471,6 +482,8 @@ hipError_t launch_ffn_down(const GroupTable &gt, int total_wgs, int tiles_per_pa
         hipLaunchKernelGGL((ffn_down_kernel<1>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
     else if (tiles_per_pass == 2)
         hipLaunchKernelGGL((ffn_down_kernel<2>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
+    else if (tiles_per_pass == 4)
+        hipLaunchKernelGGL((ffn_down_kernel<4>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
