@@ -341,10 +341,17 @@ def test_full_size_qwen_mixed_batch(oracle_mod, monkeypatch, force_tiled):
         st.close()
 
 
-def test_full_size_deepseek_prefill(oracle_mod):
+@pytest.mark.parametrize("streamed_form", ["shared4", "plain4", "plain2"])
+def test_full_size_deepseek_prefill(oracle_mod, monkeypatch, streamed_form):
     """DeepSeek-V2-Lite-shaped layer at its three batch shapes: 32 decode tokens, 1024 prefill tokens and
     the mixed 1056 (shared experts through the tiled kernels from 256 tokens on, routed experts
-    streamed)."""
+    streamed).  The routed experts of the larger batches hold 3-7 token tiles: by default they take passes of
+    four tiles through the kernels that share fragments in LDS; the other two forms (plain kernels with
+    passes of four, or of two tiles) are forced through the library's tuning variables."""
+    if streamed_form != "shared4":
+        monkeypatch.setenv("EF_TUNE_SHARED", "0")
+    if streamed_form == "plain2":
+        monkeypatch.setenv("EF_TUNE_TPP4", "0")
     cfg = synth.CONFIGS["deepseek_v2_lite"]
     st = LayerStack(cfg, 1, slots_total=cfg.E, max_tokens=1056)
     try:
