@@ -168,6 +168,49 @@ def test_ragged_shapes_full_layer(oracle_mod, cfg, T):
         st.close()
 
 
+def drawn_shapes(n_cases=12):
+    """Seeded draw of layer shapes and batch sizes that no named configuration has: expert counts that are
+    not powers of two, top-k up to the library's maximum, hidden sizes at the smallest legal granularity,
+    batches from one token to several 32-token tiles with a ragged tail."""
+    g = np.random.Generator(np.random.PCG64(20251026))
+    out = []
+    for i in range(n_cases):
+        E = int(g.choice([3, 5, 8, 12, 16, 24, 40, 60, 64]))
+        k = int(g.integers(1, min(E, 8) + 1))
+        d = 64 * int(g.integers(1, 7))
+        F = 32 * int(g.integers(1, 10))
+        Fs = 32 * int(g.integers(0, 5)) if i % 2 else 0
+        T = int(g.choice([1, 2, 7, 31, 32, 33, 63, 65, 97, 128, 161, 255, 300]))
+        beta = float(g.choice([0.0, 0.25, 1.0, 4.0]))
+        out.append((dataclasses.replace(synth.CONFIGS["tiny"], name=f"drawn{i}", cfg_id=900 + i, d=d, E=E, k=k, F=F,
+                                        F_shared=Fs, T=T, renorm=bool(i % 3), w_std=0.05), T, beta))
+    return out
+
+
+@pytest.mark.parametrize("cfg,T,beta", drawn_shapes(), ids=lambda v: getattr(v, "name", str(v)))
+def test_drawn_shapes_full_layer(oracle_mod, cfg, T, beta):
+    say(f"drawn {cfg.name} T={T} E={cfg.E} k={cfg.k} d={cfg.d} F={cfg.F} Fs={cfg.F_shared} beta={beta} "
+        f"renorm={cfg.renorm}")
+    n_res = max(1, cfg.E // 3)
+    st = LayerStack(cfg, 1, slots_total=cfg.E, max_tokens=max(T, 8))
+    try:
+        res = synth.residency(cfg, 0, n_resident=n_res, most_popular=False)
+        for e in np.nonzero(res)[0]:
+            ef.ef_cache_swap_in(st.ctx, 0, int(e), 0, 0)
+        h = synth.hidden(cfg, 5, T)
+        hd = dev_u16(h)
+        r = st.route(0, hd, T, beta)
+        got = to_np(r, T, cfg.k)
+        ora = oracle_mod.route(h, st.gates[0], st.biases[0], cfg.k, beta, res, renorm=cfg.renorm)
+        _, nties = check_route(got, ora, cfg.E, cfg.k, cfg.renorm, oracle_mod=oracle_mod)
+        out = st.ffn(0, hd, T, r)
+        full = oracle_layer(oracle_mod, st, 0, h, beta, res, forced_ids=got["ids"])
+        e1, e2 = float_close(out, full["out"])
+        say(f"  near-ties {nties}, max abs {e1:.2e}, rel l2 {e2:.2e}")
+    finally:
+        st.close()
+
+
 def test_empty_batch(oracle_mod):
     cfg = synth.CONFIGS["tiny"]
     say("T=0")
