@@ -278,7 +278,7 @@ def main():
         "stall_frac": st["stall_seconds"] / dt,
         "cache": {"hits": st["hits"], "misses": st["misses"], "miss_rate": st["miss_rate"],
                   "prefetch_issued": st["prefetch_issued"], "bytes_copied": st["bytes_copied"],
-                  "pcie_GBps": st["bytes_copied"] / st["copy_seconds"] / 1e9 if st["copy_seconds"] > 0 else None,
+                  "pcie_GBps": st["bytes_timed"] / st["copy_seconds"] / 1e9 if st["copy_seconds"] > 0 else None,
                   "horizon": st["horizon"], "bandwidth_est_GBps": st["bandwidth_Bps"] / 1e9,
                   "layer_est_us": st["layer_seconds_est"] * 1e6},
         "kernels": kern,

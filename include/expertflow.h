@@ -116,9 +116,13 @@ typedef struct ef_stats {
     int64_t prefetch_redundant; /* prefetch requests for experts already resident ("overfetch") */
     int64_t evictions;
     int64_t bytes_copied;       /* host-to-device expert bytes */
+    int64_t bytes_timed;        /* bytes of the copies that copy_seconds covers: a copy whose slot is handed to
+                                   the next copy before it was seen complete is counted above but not timed */
     int64_t layers_run;         /* ef_moe_ffn calls */
     int64_t tokens_run;         /* sum of T over ef_moe_ffn calls */
-    double copy_seconds;        /* summed duration of completed copies (copy-stream events) */
+    double copy_seconds;        /* summed duration of the timed copies (copy-stream events around each copy; copies
+                                   on the two copy streams overlap and share the link, so bytes_timed /
+                                   copy_seconds is the mean rate of one copy, not the link's aggregate) */
     double stall_seconds;       /* time the compute stream spent waiting for swap-ins */
     double layer_seconds;       /* summed ef_route..ef_moe_ffn layer time (compute-stream events) */
     double bandwidth_Bps;       /* current C_s estimate */

@@ -53,7 +53,7 @@ class ef_config(C.Structure):
 class ef_stats(C.Structure):
     _fields_ = [
         ("hits", C.c_int64), ("misses", C.c_int64), ("prefetch_issued", C.c_int64),
-        ("prefetch_redundant", C.c_int64), ("evictions", C.c_int64), ("bytes_copied", C.c_int64),
+        ("prefetch_redundant", C.c_int64), ("evictions", C.c_int64), ("bytes_copied", C.c_int64), ("bytes_timed", C.c_int64),
         ("layers_run", C.c_int64), ("tokens_run", C.c_int64), ("copy_seconds", C.c_double),
         ("stall_seconds", C.c_double), ("layer_seconds", C.c_double), ("bandwidth_Bps", C.c_double),
         ("layer_seconds_est", C.c_double), ("miss_rate", C.c_double), ("horizon", C.c_int32),

@@ -146,6 +146,7 @@ void poll_copy(ef_ctx *c, int slot) {
         if (hipEventElapsedTime(&ms, s.copy_start, s.ready) == hipSuccess && ms > 0.f) {
             double sec = ms * 1e-3;
             c->st.copy_seconds += sec;
+            c->st.bytes_timed += (int64_t)s.copy_bytes;
             if (!(c->cfg.flags & EF_FLAG_FIXED_ESTIMATES)) ema(c->bw_Bps, (double)s.copy_bytes / sec);
         }
         s.copy_pending = false;
@@ -262,6 +263,7 @@ int swap_in_impl(ef_ctx *c, int layer, int expert, int priority, int due_in, int
         s.fake_ready_at = start + (double)bytes / c->bw_Bps;
         c->fake_engine_free[q] = s.fake_ready_at;
         c->st.copy_seconds += (double)bytes / c->bw_Bps;
+        c->st.bytes_timed += (int64_t)bytes;
     } else {
         hipStream_t cs = c->copy_stream[q];
         hipError_t e = hipSuccess;

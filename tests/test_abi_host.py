@@ -181,6 +181,7 @@ def test_moe_ffn_swaps_in_misses_and_reports_busy_when_nothing_can_be_freed():
         st = ef.ef_get_stats(ctx)
         assert st["misses"] == 5 and st["hits"] == 0 and st["layers_run"] == 1
         assert st["bytes_copied"] == 5 * ef.ef_expert_bytes(64, 32)
+        assert st["bytes_timed"] == st["bytes_copied"] and st["copy_seconds"] > 0     # modelled copies are all timed
         assert ef.ef_cache_query(ctx, 0, 8).sum() == 2
         assert abs(st["miss_rate"] - 1.0) < 1e-12
         run_layer(ctx, 0, [int(e) for e in np.nonzero(ef.ef_cache_query(ctx, 0, 8))[0]])

@@ -283,6 +283,8 @@ def test_layer_step_equals_separate_calls(cfg_name, T):
         for key in ("hits", "misses", "prefetch_issued", "evictions", "bytes_copied", "layers_run"):
             assert s0[key] == s1[key], key
         assert s0["layers_run"] == 9
+        for st in (s0, s1):      # timed copies are a subset of the copies; a finished run has timed at least one
+            assert 0 < st["bytes_timed"] <= st["bytes_copied"] and st["copy_seconds"] > 0
     finally:
         for lp in loops:
             lp.close()
