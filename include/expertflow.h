@@ -160,8 +160,11 @@ size_t ef_expert_bytes(int d_model, int d_ff);
  * The FFN kernels form (q - 8) * s in fp16 (relative error <= 2^-12 per weight) and run the matrix
  * cores in fp16 with fp32 accumulation: tokens are converted from bf16 to fp16 (exact for
  * 2^-14 <= |x| < 65504; larger magnitudes overflow) and the intermediate activations are kept in
- * fp16.  Requires d_model and d_ff multiples of 128 and no shared expert; groups of any size run
- * through the weight-streaming kernels.
+ * fp16.  Requires d_model and d_ff multiples of 128 and no shared expert.  Groups of up to 7 token
+ * tiles run through weight-streaming kernels that dequantise on the operand fragment; larger groups
+ * (prefill) are first expanded to a 16-bit blob of the same fp16 values (q - 8) * s in a staging
+ * area the context owns (one blob per expert that can reach that size in one call) and then run
+ * through the tiled matrix-core kernels in fp16.
  */
 size_t ef_expert_bytes_q4(int d_model, int d_ff);   /* 0 if d_model % 128 or d_ff % 128 is non-zero */
 

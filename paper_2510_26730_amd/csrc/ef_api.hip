@@ -57,6 +57,8 @@ struct ef_ctx {
     void *xp = nullptr, *act = nullptr;
     float *gate_part = nullptr;      // partial logits of K-split gate launches (small batches)
     bool q4 = false;                 // routed experts are 4-bit blobs
+    char *q4_stage = nullptr;        // 16-bit copies of the 4-bit experts that go through the tiled kernels in a phase
+    int q4_stage_slots = 0;          // how many such copies fit (as many experts as can reach the tiled size at once)
     bool prepacked = false;          // ef_layer_step already enqueued the token packing of the coming ef_moe_ffn
     size_t gate_part_floats = 0;
     float *y = nullptr;
@@ -449,6 +451,7 @@ extern "C" int ef_destroy(ef_ctx *c) {
         if (c->gate_part) (void)hipFree(c->gate_part);
         if (c->act) (void)hipFree(c->act);
         if (c->y) (void)hipFree(c->y);
+        if (c->q4_stage) (void)hipFree(c->q4_stage);
         for (void *p : {(void *)c->st_ids, (void *)c->st_counts, (void *)c->st_offsets, (void *)c->st_perm,
                         (void *)c->st_inv, (void *)c->st_pred_ids, (void *)c->st_pred_hist, (void *)c->st_w})
             if (p) (void)hipFree(p);
@@ -537,6 +540,15 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
     if ((e = hipMalloc(&c->gate_part, c->gate_part_floats * 4)) != hipSuccess) return bail(e, "gate partials");
     if ((e = hipMalloc(&c->act, act_bytes)) != hipSuccess) return bail(e, "activation scratch");
     if ((e = hipMalloc(&c->y, y_bytes)) != hipSuccess) return bail(e, "expert-output scratch");
+    if (c->q4 && ef::ffn_tiled_ok(d, g.d_ff, ef::kTiledMinTiles)) {
+        // 4-bit experts with enough tokens for the tiled kernels are expanded to 16 bits first; a group needs
+        // more than (kTiledMinTiles - 1) tiles of tokens, so at most this many groups of one call qualify
+        const long long can = Tm * k / ((ef::kTiledMinTiles - 1) * ef::kTile + 1);
+        c->q4_stage_slots = (int)std::min<long long>(E, can);
+        if (c->q4_stage_slots > 0 &&
+            (e = hipMalloc(&c->q4_stage, (size_t)c->q4_stage_slots * ef_expert_bytes(d, g.d_ff))) != hipSuccess)
+            return bail(e, "16-bit staging of 4-bit experts");
+    }
 
     {
         const size_t n = (size_t)Tm * k;
@@ -860,6 +872,7 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
     // groups with many tokens go to the tiled (matrix-core bound) kernels, the others to the
     // weight-streaming kernels; at most two launches per FFN half
     ef::GroupTable gu{}, big{};
+    ef::DequantTable dq{};
     int n = 0, nb = 0, max_tiles = 1;
     const bool allow_tiled = use_tiled;
     for (const PhaseGroup &pg : groups) {
@@ -875,9 +888,14 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
             blob = c->pool + (size_t)pg.slot * c->expert_bytes;
         }
         const int nt = (cnt + ef::kTile - 1) / ef::kTile;
-        const bool tiled = allow_tiled && ef::ffn_tiled_ok(d, F, nt);
+        const bool tiled = allow_tiled && ef::ffn_tiled_ok(d, F, nt) && (!c->q4 || nb < c->q4_stage_slots);
         ef::GroupTable &g = tiled ? big : gu;
         int &i = tiled ? nb : n;
+        if (tiled && c->q4) {   // the tiled kernels read a 16-bit copy written just before them on the same stream
+            void *copy = c->q4_stage + (size_t)nb * ef_expert_bytes(d, F);
+            dq.F[nb] = F; dq.src[nb] = blob; dq.dst[nb] = copy;
+            blob = copy;
+        }
         g.tile_start[i] = ts; g.n_tiles[i] = nt; g.row_offset[i] = ro;
         g.count[i] = cnt; g.F[i] = F; g.act_off[i] = ao; g.blob[i] = blob;
         if (!tiled) max_tiles = std::max(max_tiles, nt);
@@ -911,12 +929,16 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
             f_dn += 2.0 * big.count[i] * d * big.F[i];
         }
         {
-            KernelTimer kt(c, s, EF_K_FFN_UP_TILED, b_up, f_up);
-            EF_HIP(c, ef::launch_ffn_gate_up_tiled(big, wg_up, c->xp, c->act, d, s));
+            KernelTimer kt(c, s, EF_K_FFN_UP_TILED, b_up, f_up);   // 4-bit: the expansion is timed with the first half
+            if (c->q4) {
+                dq.n = nb;
+                EF_HIP(c, ef::launch_dequant_q4(dq, d, s));
+            }
+            EF_HIP(c, ef::launch_ffn_gate_up_tiled(big, wg_up, c->xp, c->act, d, c->q4, s));
         }
         {
             KernelTimer kt(c, s, EF_K_FFN_DOWN_TILED, b_dn, f_dn);
-            EF_HIP(c, ef::launch_ffn_down_tiled(bdn, wg_dn, ksg, c->act, c->y, y_plane, d, s));
+            EF_HIP(c, ef::launch_ffn_down_tiled(bdn, wg_dn, ksg, c->act, c->y, y_plane, d, c->q4, s));
         }
     }
     if (n == 0) return EF_OK;
@@ -1024,7 +1046,7 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
     bool use_tiled = false;
     long long tiled_dn_wgs = 0;
     int tiled_stages_min = 1 << 30;   // fewest K stages (32 columns each) among the tiled groups
-    if (T > 0 && !c->q4 && tune("EF_TUNE_TILED", 1) != 0) {
+    if (T > 0 && (!c->q4 || c->q4_stage_slots > 0) && tune("EF_TUNE_TILED", 1) != 0) {
         long long wg_up = 0, wg_dn = 0;
         auto add = [&](int F, int cnt) {
             const int nt = (cnt + ef::kTile - 1) / ef::kTile;

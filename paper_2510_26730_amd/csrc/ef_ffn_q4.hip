@@ -17,6 +17,8 @@
 // matrix cores therefore run in fp16 (fp32 accumulation): the packed tokens of a 4-bit context and
 // the intermediate activations are fp16 fragments (tokens convert exactly from bf16 for
 // 2^-14 <= |x| < 65504).
+#include <algorithm>
+
 #include "ef_device.h"
 #include "ef_kernels.h"
 
@@ -344,6 +346,69 @@ hipError_t launch_ffn_down_q4(const GroupTable &gt, int total_wgs, int tiles_per
     else if (tiles_per_pass == 2)
         hipLaunchKernelGGL((ffn_down_q4_kernel<2>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
     else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// 4-bit blob -> 16-bit blob of the bf16 layout holding the fp16 numbers (q - 8) * s.
+// One wave per quad position: (rb, kq) of W1 and W3 together (two quads in, eight fragments out), then
+// (cb, kq) of W2 (one quad in, four fragments out).  A quad's dword j of lane l is the fragment of k-step
+// 4*kq + j of the same lane, so reads and writes are whole 1 KiB rows of 64 lanes.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void dequant_q4_kernel(DequantTable t, int d) {
+    const int grp = blockIdx.y;
+    const int F = t.F[grp];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int nq = d >> 6, nq2 = F >> 6, nkb = d >> 4, nkb2 = F >> 4;
+    const int nA = (F >> 5) * nq, nB = (d >> 5) * nq2;
+    const int u = blockIdx.x * 4 + wave;
+    if (u >= nA + nB) return;
+    const char *blob = reinterpret_cast<const char *>(t.src[grp]);
+    uint4 *out = reinterpret_cast<uint4 *>(t.dst[grp]);
+    if (u < nA) {
+        const int rb = u / nq, kq = u - rb * nq;
+        const uint4 *q = reinterpret_cast<const uint4 *>(blob) + ((size_t)rb * nq + kq) * 128 + lane;
+        const uint16_t *sc = reinterpret_cast<const uint16_t *>(blob + (size_t)3 * d * F / 2) +
+                             ((size_t)rb * (d >> 7) + (kq >> 1)) * 64 + (lane & 31);
+        const uint4 q1 = q[0], q3 = q[64];
+        const q4_half2 f1 = q4_scale(sc[0]), f3 = q4_scale(sc[32]);
+        uint4 *o1 = out + ((size_t)rb * 2 * nkb + 4 * kq) * 64 + lane;
+        uint4 *o3 = o1 + (size_t)nkb * 64;
+        const uint32_t c1[4] = {q1.x, q1.y, q1.z, q1.w}, c3[4] = {q3.x, q3.y, q3.z, q3.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const u32x4_t a = dequant_q4(c1[j], f1), b = dequant_q4(c3[j], f3);
+            o1[(size_t)j * 64] = make_uint4(a[0], a[1], a[2], a[3]);
+            o3[(size_t)j * 64] = make_uint4(b[0], b[1], b[2], b[3]);
+        }
+    } else {
+        const int v = u - nA;
+        const int cb = v / nq2, kq = v - cb * nq2;
+        const uint4 *q = reinterpret_cast<const uint4 *>(blob + (size_t)d * F) + ((size_t)cb * nq2 + kq) * 64 + lane;
+        const uint16_t *sc = reinterpret_cast<const uint16_t *>(blob + (size_t)3 * d * F / 2 + (size_t)d * F / 32) +
+                             ((size_t)cb * (F >> 7) + (kq >> 1)) * 32 + (lane & 31);
+        const uint4 q2 = q[0];
+        const q4_half2 f2 = q4_scale(sc[0]);
+        uint4 *o2 = reinterpret_cast<uint4 *>(reinterpret_cast<char *>(out) + (size_t)4 * d * F) +
+                    ((size_t)cb * nkb2 + 4 * kq) * 64 + lane;
+        const uint32_t c2[4] = {q2.x, q2.y, q2.z, q2.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const u32x4_t a = dequant_q4(c2[j], f2);
+            o2[(size_t)j * 64] = make_uint4(a[0], a[1], a[2], a[3]);
+        }
+    }
+}
+
+hipError_t launch_dequant_q4(const DequantTable &t, int d, hipStream_t s) {
+    if (t.n <= 0) return hipSuccess;
+    if (t.n > kMaxGroups || d <= 0 || d % 128 != 0) return hipErrorInvalidValue;
+    int units = 0;
+    for (int i = 0; i < t.n; ++i) {
+        if (t.F[i] <= 0 || t.F[i] % 128 != 0 || !t.src[i] || !t.dst[i]) return hipErrorInvalidValue;
+        units = std::max(units, (t.F[i] / 32) * (d / 64) + (d / 32) * (t.F[i] / 64));
+    }
+    hipLaunchKernelGGL(dequant_q4_kernel, dim3((units + 3) / 4, t.n), dim3(256), 0, s, t, d);
     return hipGetLastError();
 }
 

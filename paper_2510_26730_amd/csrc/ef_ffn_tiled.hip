@@ -57,6 +57,24 @@ __device__ __forceinline__ bool tiled_panel(int local, int npanels, int mpanels,
         _Pragma("unroll") for (int q = 0; q < kStageFrags / 4; ++q)                                  \
             EF_TILED_DMA(src[q] + (size_t)stc_ * kTileKS * 64, EF_TILED_DST(st, q));                 \
     }
+// HALF: operands are fp16 fragments (contexts with 4-bit experts: tokens, activations and the dequantised
+// weights are fp16) instead of bf16; accumulation is fp32 either way.
+typedef _Float16 tiled_half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 tiled_half2 __attribute__((ext_vector_type(2)));
+template <bool HALF>
+__device__ __forceinline__ floatx16 tiled_mfma(u32x4_t a, u32x4_t b, floatx16 c) {
+    if constexpr (HALF)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(tiled_half8, a),
+                                                      __builtin_bit_cast(tiled_half8, b), c, 0, 0, 0);
+    else
+        return mfma32v(a, b, c);
+}
+template <bool HALF>
+__device__ __forceinline__ uint32_t tiled_pack2(float v0, float v1) {
+    if constexpr (HALF) return __builtin_bit_cast(uint32_t, tiled_half2{(_Float16)v0, (_Float16)v1});
+    else return f32_to_bf16_bits(v0) | (f32_to_bf16_bits(v1) << 16);
+}
+
 #define EF_TILED_READ(a, b, cur, ks)                                                              \
     {                                                                                                \
         _Pragma("unroll") for (int i = 0; i < 4; ++i) a[i] = lds[cur][(ks) * 16 + AOFF + i][lane];     \
@@ -76,7 +94,7 @@ __device__ __forceinline__ bool tiled_panel(int local, int npanels, int mpanels,
 // so matrix-core work on tiles that do not exist costs real throughput.  Loads and barriers are the same in
 // every variant (the waves of a workgroup run different ones side by side).
 #define EF_TILED_MF(ac, bc, r, j, NLA, NLB)                                                          \
-    if ((r) < (NLA) && (j) < (NLB)) acc[r][j] = mfma32v(ac[r], bc[j], acc[r][j]);
+    if ((r) < (NLA) && (j) < (NLB)) acc[r][j] = tiled_mfma<HALF>(ac[r], bc[j], acc[r][j]);
 #define EF_TILED_RA(an, buf, ks, r, NLA) if ((r) < (NLA)) an[r] = lds[buf][(ks) * 16 + AOFF + (r)][lane];
 #define EF_TILED_RB(bn, buf, ks, r, NLB) if ((r) < (NLB)) bn[r] = lds[buf][(ks) * 16 + 8 + BOFF + (r)][lane];
 #define EF_TILED_ROUND(ac, bc, r, x0, x1, x3, st, half, NLA, NLB)                                    \
@@ -152,6 +170,7 @@ __device__ __forceinline__ bool tiled_panel(int local, int npanels, int mpanels,
 // operand A slots 0..7 = W1/W3 fragments of row blocks rb0..rb0+3 (slot = 2*rbl + which),
 // operand B slots 8..15 = packed-token fragments of tiles t0..t0+7
 // ------------------------------------------------------------------------------------------
+template <bool HALF>
 __global__ __launch_bounds__(256, 1) void ffn_gate_up_tiled_kernel(GroupTable gt, const uint4 *__restrict__ xp,
                                                                     uint4 *__restrict__ act, int d) {
     __shared__ __attribute__((aligned(16))) u32x4_t lds[kTileStages][kStageFrags][64];
@@ -218,7 +237,7 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_tiled_kernel(GroupTable gt
                     const float g0 = acc[2 * h][j][8 * s + 2 * q], g1 = acc[2 * h][j][8 * s + 2 * q + 1];
                     const float v0 = g0 / (1.f + __expf(-g0)) * acc[2 * h + 1][j][8 * s + 2 * q];
                     const float v1 = g1 / (1.f + __expf(-g1)) * acc[2 * h + 1][j][8 * s + 2 * q + 1];
-                    pk[q] = f32_to_bf16_bits(v0) | (f32_to_bf16_bits(v1) << 16);
+                    pk[q] = tiled_pack2<HALF>(v0, v1);
                 }
                 dst[(size_t)s * 64] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
             }
@@ -227,7 +246,7 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_tiled_kernel(GroupTable gt
 }
 
 hipError_t launch_ffn_gate_up_tiled(const GroupTable &gt, int total_wgs, const void *xp, void *act, int d,
-                                    hipStream_t s) {
+                                    bool f16, hipStream_t s) {
     if (total_wgs <= 0) return hipSuccess;
     // the kernel's index mapping and the grid must come from the same workgroup count per group
     for (int i = 0; i < gt.n_groups; ++i)
@@ -235,8 +254,12 @@ hipError_t launch_ffn_gate_up_tiled(const GroupTable &gt, int total_wgs, const v
             !ffn_tiled_ok(d, gt.F[i], gt.n_tiles[i]))
             return hipErrorInvalidValue;
     if (gt.wg_start[gt.n_groups] != total_wgs) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(ffn_gate_up_tiled_kernel, dim3(total_wgs), dim3(256), 0, s, gt,
-                       reinterpret_cast<const uint4 *>(xp), reinterpret_cast<uint4 *>(act), d);
+    if (f16)
+        hipLaunchKernelGGL(ffn_gate_up_tiled_kernel<true>, dim3(total_wgs), dim3(256), 0, s, gt,
+                           reinterpret_cast<const uint4 *>(xp), reinterpret_cast<uint4 *>(act), d);
+    else
+        hipLaunchKernelGGL(ffn_gate_up_tiled_kernel<false>, dim3(total_wgs), dim3(256), 0, s, gt,
+                           reinterpret_cast<const uint4 *>(xp), reinterpret_cast<uint4 *>(act), d);
     return hipGetLastError();
 }
 
@@ -245,6 +268,7 @@ hipError_t launch_ffn_gate_up_tiled(const GroupTable &gt, int total_wgs, const v
 // operand A slots 0..7 = activation fragments of tiles t0..t0+7,
 // operand B slots 8..15 = W2 fragments of column blocks cb0..cb0+7
 // ------------------------------------------------------------------------------------------
+template <bool HALF>
 __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, const uint4 *__restrict__ act,
                                                                  float *__restrict__ Y, int d, int ksg,
                                                                  long long y_plane) {
@@ -316,7 +340,7 @@ __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, c
 }
 
 hipError_t launch_ffn_down_tiled(const GroupTable &gt, int total_wgs, int ksg, const void *act, float *y,
-                                 long long y_plane, int d, hipStream_t s) {
+                                 long long y_plane, int d, bool f16, hipStream_t s) {
     if (total_wgs <= 0) return hipSuccess;
     if (ksg < 1) return hipErrorInvalidValue;
     for (int i = 0; i < gt.n_groups; ++i)
@@ -324,8 +348,12 @@ hipError_t launch_ffn_down_tiled(const GroupTable &gt, int total_wgs, int ksg, c
             !ffn_tiled_ok(d, gt.F[i], gt.n_tiles[i]))
             return hipErrorInvalidValue;
     if (gt.wg_start[gt.n_groups] != total_wgs) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(ffn_down_tiled_kernel, dim3(total_wgs), dim3(256), 0, s, gt,
-                       reinterpret_cast<const uint4 *>(act), y, d, ksg, y_plane);
+    if (f16)
+        hipLaunchKernelGGL(ffn_down_tiled_kernel<true>, dim3(total_wgs), dim3(256), 0, s, gt,
+                           reinterpret_cast<const uint4 *>(act), y, d, ksg, y_plane);
+    else
+        hipLaunchKernelGGL(ffn_down_tiled_kernel<false>, dim3(total_wgs), dim3(256), 0, s, gt,
+                           reinterpret_cast<const uint4 *>(act), y, d, ksg, y_plane);
     return hipGetLastError();
 }
 

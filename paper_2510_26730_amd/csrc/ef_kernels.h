@@ -111,16 +111,28 @@ hipError_t launch_ffn_gate_up_q4(const GroupTable &gt, int total_wgs, int tiles_
                                  int d, hipStream_t s);
 hipError_t launch_ffn_down_q4(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ksg, const void *act,
                               float *y, long long y_plane, int d, hipStream_t s);
+// Expands 4-bit expert blobs into 16-bit blobs of the bf16 layout whose elements are the fp16 numbers
+// (q - 8) * s, the same values the 4-bit kernels form on the fly: large groups then run through the
+// tiled matrix-core kernels, which read every weight many times.
+struct DequantTable {
+    int n;
+    int F[kMaxGroups];
+    const void *src[kMaxGroups];   // 4-bit blob (cache slot)
+    void *dst[kMaxGroups];         // 3*d*F*2 bytes each
+};
+hipError_t launch_dequant_q4(const DequantTable &t, int d, hipStream_t s);
 
 // Dist(t): scratch floats launch_token_dist needs for T tokens (norms, partials, workgroup sums)
 size_t dist_scratch_floats(int T);
 hipError_t launch_token_dist(const uint16_t *h, int T, int d, const void *xp, float *scratch, float *tok_dist,
                              double *dist, hipStream_t s);
 
+// f16: the blobs, packed tokens and activations hold fp16 instead of bf16 (4-bit contexts: the blobs are
+// the staging copies launch_dequant_q4 wrote)
 hipError_t launch_ffn_gate_up_tiled(const GroupTable &gt, int total_wgs, const void *xp, void *act, int d,
-                                    hipStream_t s);
+                                    bool f16, hipStream_t s);
 hipError_t launch_ffn_down_tiled(const GroupTable &gt, int total_wgs, int ksg, const void *act, float *y,
-                                 long long y_plane, int d, hipStream_t s);
+                                 long long y_plane, int d, bool f16, hipStream_t s);
 
 // The tiled (matrix-core bound) kernels take groups of at least kTiledMinTiles token tiles whose shapes
 // fit their 256 x 256 workgroup tiles: F a multiple of 128 (4 row blocks), d a multiple of 256 (8 column

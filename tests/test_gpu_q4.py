@@ -102,6 +102,53 @@ def test_q4_full_size_mixtral_decode(oracle_mod):
         st.close()
 
 
+@pytest.mark.parametrize("kw,T,tiled", [
+    (dict(d=256, F=128), 1500, True),            # every expert above 8 tiles, smallest shape the tiled kernels take
+    (dict(d=512, F=384), 900, True),             # popularity skew: some experts tiled, the others streamed in passes
+    (dict(d=512, F=384), 900, False),            # the same batch with the tiled kernels switched off
+    (dict(d=384, F=256), 1500, True),            # d not a multiple of 256: stays on the streaming kernels
+])
+def test_q4_large_groups_through_tiled_kernels(oracle_mod, monkeypatch, kw, T, tiled):
+    """Groups of 8 token tiles or more: the 4-bit blobs are expanded to fp16 blobs and go through the
+    matrix-core tiled kernels; smaller groups of the same layer keep the streaming kernels."""
+    cfg = q4_shape("tiny", name="tiny_q4_prefill", **kw)
+    if not tiled:
+        monkeypatch.setenv("EF_TUNE_TILED", "0")
+    say(f"q4 large groups d={cfg.d} F={cfg.F} E={cfg.E} k={cfg.k} T={T} tiled={tiled}")
+    st = LayerStack(cfg, 1, slots_total=cfg.E, max_tokens=T, q4=True, flags=ef.EF_FLAG_PROFILE)
+    try:
+        for e in range(cfg.E):
+            ef.ef_cache_swap_in(st.ctx, 0, e, 0, 0)
+        res = ef.ef_cache_query(st.ctx, 0, cfg.E)
+        layer_check(oracle_mod, st, synth.hidden(cfg, 0, T), T, 0.0, res)
+        launches = dict(zip(ef.EF_KERNELS, ef.ef_get_stats(st.ctx)["kernel_launches"]))
+        say(f"  launches {launches}")
+        expect_tiled = tiled and cfg.d % 256 == 0
+        assert (launches["ffn_up_tiled"] > 0) == expect_tiled and (launches["ffn_down_tiled"] > 0) == expect_tiled
+    finally:
+        st.close()
+
+
+def test_q4_full_size_mixtral_prefill(oracle_mod):
+    """The prefill shape with 4-bit experts (T = 8192, every expert far above 8 tiles: expansion to fp16 and
+    the tiled kernels, the configuration `bench.py --workload mixtral_prefill --int4 --all-resident` times);
+    sampled tokens."""
+    cfg = q4_shape("mixtral_prefill", name="mixtral_prefill_q4")
+    T = 8192
+    say(f"q4 full size: Mixtral-shaped prefill layer, T={T}")
+    st = LayerStack(cfg, 1, slots_total=8, max_tokens=T, q4=True, flags=ef.EF_FLAG_PROFILE)
+    try:
+        for e in range(cfg.E):
+            ef.ef_cache_swap_in(st.ctx, 0, e, 0, 0)
+        res = ef.ef_cache_query(st.ctx, 0, cfg.E)
+        toks = np.sort(np.random.default_rng(T).permutation(T)[:4])
+        layer_check(oracle_mod, st, synth.hidden(cfg, 0, T), T, 0.0, res, toks)
+        launches = dict(zip(ef.EF_KERNELS, ef.ef_get_stats(st.ctx)["kernel_launches"]))
+        assert launches["ffn_up_tiled"] == 1 and launches["ffn_down_tiled"] == 1
+    finally:
+        st.close()
+
+
 def test_q4_create_rejects_bad_shapes():
     for kw in (dict(d_model=192, d_ff=128), dict(d_model=128, d_ff=96), dict(d_model=128, d_ff=128, d_ff_shared=128)):
         args = dict(n_layers=1, d_model=128, n_experts=4, top_k=2, d_ff=128, slots_total=4, max_tokens=8,
