@@ -265,7 +265,7 @@ def main():
         "metric": "MoE-layer tokens/s (route+predict+FFN) at 1 GPU",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16 (4-bit expert weights dequantised to bf16)" if args.int4 else "bf16",
+        "vs_baseline": None, "dtype": "f16 (4-bit expert weights dequantised to fp16, fp32 accumulation)" if args.int4 else "bf16",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {L} layers, d={cfg.d}, E={cfg.E}, top-{cfg.k}, F={cfg.F}, "
                                f"T={T} tokens/step, cache {'all experts' if args.all_resident else (str(args.pool_slots) + '-slot pool' if args.pool_slots else str(slots) + ' slots/layer')}"

@@ -160,7 +160,8 @@ size_t ef_expert_bytes(int d_model, int d_ff);
  * The FFN kernels form (q - 8) * s in fp16 (relative error <= 2^-12 per weight) and run the matrix
  * cores in fp16 with fp32 accumulation: tokens are converted from bf16 to fp16 (exact for
  * 2^-14 <= |x| < 65504; larger magnitudes overflow) and the intermediate activations are kept in
- * fp16.  Requires d_model and d_ff multiples of 128 and no shared expert.  Groups of up to 7 token
+ * fp16.  Requires d_model, d_ff and d_ff_shared multiples of 128; with a shared FFN its blob is a
+ * 4-bit blob too (ef_pack_expert_q4 with d_ff_shared).  Groups of up to 7 token
  * tiles run through weight-streaming kernels that dequantise on the operand fragment; larger groups
  * (prefill) are first expanded to a 16-bit blob of the same fp16 values (q - 8) * s in a staging
  * area the context owns (one blob per expert that can reach that size in one call) and then run
@@ -189,7 +190,8 @@ const char *ef_last_error(ef_ctx *ctx);
 /* Register one layer.  gate_w [dev] [E,d] bf16 row-major; gate_b [dev] [E] f32 or NULL;
  * experts [pinned] E consecutive packed blobs (the authoritative copy; must outlive the context;
  * with EF_FLAG_FAKE_COPY any non-NULL value); shared_blob [dev] packed blob of the dense SwiGLU
- * with hidden d_ff_shared, or NULL.  The library keeps the pointers, it copies nothing. */
+ * with hidden d_ff_shared (in the context's weight format: bf16 or 4-bit), or NULL.  The library
+ * keeps the pointers, it copies nothing. */
 int ef_register_layer(ef_ctx *ctx, int layer, const void *gate_w, const float *gate_b,
                       const void *experts, const void *shared_blob);
 

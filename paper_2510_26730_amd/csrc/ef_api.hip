@@ -58,7 +58,8 @@ struct ef_ctx {
     float *gate_part = nullptr;      // partial logits of K-split gate launches (small batches)
     bool q4 = false;                 // routed experts are 4-bit blobs
     char *q4_stage = nullptr;        // 16-bit copies of the 4-bit experts that go through the tiled kernels in a phase
-    int q4_stage_slots = 0;          // how many such copies fit (as many experts as can reach the tiled size at once)
+    int q4_stage_slots = 0;          // how many such copies fit (as many groups as can reach the tiled size at once)
+    size_t q4_stage_bytes = 0;       // bytes of one copy (the larger of routed and shared FFN)
     bool prepacked = false;          // ef_layer_step already enqueued the token packing of the coming ef_moe_ffn
     size_t gate_part_floats = 0;
     float *y = nullptr;
@@ -474,8 +475,9 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
         return fail(nullptr, EF_EINVAL, "ef_create: d_model must be a multiple of 64 and d_ff of 32");
     if (g.weight_bits != 0 && g.weight_bits != 16 && g.weight_bits != 4)
         return fail(nullptr, EF_EINVAL, "ef_create: weight_bits must be 0, 16 or 4");
-    if (g.weight_bits == 4 && (ef_expert_bytes_q4(g.d_model, g.d_ff) == 0 || g.d_ff_shared != 0))
-        return fail(nullptr, EF_EINVAL, "ef_create: 4-bit experts need d_model and d_ff multiples of 128 and no shared expert");
+    if (g.weight_bits == 4 && (ef_expert_bytes_q4(g.d_model, g.d_ff) == 0 ||
+                               (g.d_ff_shared != 0 && ef_expert_bytes_q4(g.d_model, g.d_ff_shared) == 0)))
+        return fail(nullptr, EF_EINVAL, "ef_create: 4-bit experts need d_model, d_ff and d_ff_shared multiples of 128");
     if (g.d_ff_shared < 0 || g.d_ff_shared % 32 != 0)
         return fail(nullptr, EF_EINVAL, "ef_create: d_ff_shared must be a non-negative multiple of 32");
     if (g.slots_total <= 0 || g.slots_per_layer_max < 0 || g.max_tokens <= 0)
@@ -540,13 +542,17 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
     if ((e = hipMalloc(&c->gate_part, c->gate_part_floats * 4)) != hipSuccess) return bail(e, "gate partials");
     if ((e = hipMalloc(&c->act, act_bytes)) != hipSuccess) return bail(e, "activation scratch");
     if ((e = hipMalloc(&c->y, y_bytes)) != hipSuccess) return bail(e, "expert-output scratch");
-    if (c->q4 && ef::ffn_tiled_ok(d, g.d_ff, ef::kTiledMinTiles)) {
-        // 4-bit experts with enough tokens for the tiled kernels are expanded to 16 bits first; a group needs
-        // more than (kTiledMinTiles - 1) tiles of tokens, so at most this many groups of one call qualify
-        const long long can = Tm * k / ((ef::kTiledMinTiles - 1) * ef::kTile + 1);
-        c->q4_stage_slots = (int)std::min<long long>(E, can);
+    if (c->q4) {
+        // 4-bit groups with enough tokens for the tiled kernels are expanded to 16 bits first.  A group needs more
+        // than (kTiledMinTiles - 1) tiles of tokens, so at most `can` routed experts of one call qualify, plus the
+        // shared FFN (every token).
+        const long long need = (ef::kTiledMinTiles - 1) * ef::kTile + 1;
+        if (ef::ffn_tiled_ok(d, g.d_ff, ef::kTiledMinTiles)) c->q4_stage_slots = (int)std::min<long long>(E, Tm * k / need);
+        if (g.d_ff_shared > 0 && ef::ffn_tiled_ok(d, g.d_ff_shared, ef::kTiledMinTiles) && Tm >= need)
+            c->q4_stage_slots += 1;
+        c->q4_stage_bytes = ef_expert_bytes(d, std::max(g.d_ff, g.d_ff_shared));
         if (c->q4_stage_slots > 0 &&
-            (e = hipMalloc(&c->q4_stage, (size_t)c->q4_stage_slots * ef_expert_bytes(d, g.d_ff))) != hipSuccess)
+            (e = hipMalloc(&c->q4_stage, (size_t)c->q4_stage_slots * c->q4_stage_bytes)) != hipSuccess)
             return bail(e, "16-bit staging of 4-bit experts");
     }
 
@@ -892,7 +898,7 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
         ef::GroupTable &g = tiled ? big : gu;
         int &i = tiled ? nb : n;
         if (tiled && c->q4) {   // the tiled kernels read a 16-bit copy written just before them on the same stream
-            void *copy = c->q4_stage + (size_t)nb * ef_expert_bytes(d, F);
+            void *copy = c->q4_stage + (size_t)nb * c->q4_stage_bytes;
             dq.F[nb] = F; dq.src[nb] = blob; dq.dst[nb] = copy;
             blob = copy;
         }
@@ -1074,8 +1080,9 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
                             : tpp == 4 ? ef::ffn_down_shared_wgs(d, nt, tpp, 1) : ef::ffn_down_wgs(d, nt, tpp, 1);
             }
         if (has_shared)
-            base_wgs += tpp == 4 ? ef::ffn_down_shared_wgs(d, (T + ef::kTile - 1) / ef::kTile, tpp, 1)
-                                 : ef::ffn_down_wgs(d, (T + ef::kTile - 1) / ef::kTile, tpp, 1);
+            base_wgs += c->q4 ? ef::ffn_down_q4_wgs(d, (T + ef::kTile - 1) / ef::kTile, tpp, 1)
+                        : tpp == 4 ? ef::ffn_down_shared_wgs(d, (T + ef::kTile - 1) / ef::kTile, tpp, 1)
+                                   : ef::ffn_down_wgs(d, (T + ef::kTile - 1) / ef::kTile, tpp, 1);
         const int want = tune("EF_TUNE_DOWN_WGS", 256);
         const int nkb_min = std::min(c->cfg.d_ff, has_shared ? c->cfg.d_ff_shared : c->cfg.d_ff) / 16;
         // a slice keeps >= 32 fragments per wave (bf16: four waves split it again) or >= 6 quads (4-bit)

@@ -67,7 +67,16 @@ class LayerLoop:
                 st[e * (self.es // 2):(e + 1) * (self.es // 2)].copy_(w.to(torch.bfloat16))
             self.stores.append(st)
         self.shared = []
-        if cfg.F_shared:
+        if cfg.F_shared and q4:
+            nb = ef.ef_expert_bytes_q4(d, cfg.F_shared)
+            ncode = 3 * d * cfg.F_shared // 2
+            for _ in range(self.store_layers):
+                sb = torch.empty(nb, dtype=torch.uint8, device=dev)
+                sb[:ncode] = torch.randint(0, 256, (ncode,), generator=g, device=dev, dtype=torch.uint8)
+                sb[ncode:] = torch.full(((nb - ncode) // 2,), cfg.w_std / 4.61, dtype=torch.bfloat16,
+                                        device=dev).view(torch.uint8)
+                self.shared.append(sb)
+        elif cfg.F_shared:
             n = 3 * d * cfg.F_shared
             for _ in range(self.store_layers):
                 self.shared.append((torch.randn(n, generator=g, device=dev) * cfg.w_std).to(torch.bfloat16))

@@ -167,19 +167,30 @@ def expert_weights(cfg: MoEShape, layer: int, e: int):
     return w1, w3, w2
 
 
+def _draw_q4(cfg: MoEShape, F: int, key: tuple):
+    out = []
+    for which, (rows, cols) in ((1, (F, cfg.d)), (3, (F, cfg.d)), (2, (cfg.d, F))):
+        n = rows * cols
+        z = normal_f32(n, key + (which, 4)).reshape(rows, cols)
+        q = np.clip(np.rint(z * 2.5) + 8.0, 0.0, 15.0).astype(np.uint8)
+        u = normal_f32(rows * (cols // 128), key + (which, 5))
+        sc = (cfg.w_std / 2.5) * (1.0 + 0.1 * np.clip(u, -3.0, 3.0))
+        out += [q, f32_to_bf16(sc.reshape(rows, cols // 128))]
+    return tuple(out)
+
+
 def expert_weights_q4(cfg: MoEShape, layer: int, e: int):
     """4-bit form of an expert: (q1, s1, q3, s3, q2, s2); codes uint8 in 0..15 drawn as a clipped, rounded
     normal around 8, one bf16 scale per row and 128 inputs, so that (q - 8) * s ~ N(0, w_std^2) like the
     bf16 experts.  Codes and scales are drawn directly (no quantiser): they are inputs."""
-    out = []
-    for which, (rows, cols) in ((1, (cfg.F, cfg.d)), (3, (cfg.F, cfg.d)), (2, (cfg.d, cfg.F))):
-        n = rows * cols
-        z = normal_f32(n, (cfg.cfg_id, EXPERT_W, layer, e, which, 4)).reshape(rows, cols)
-        q = np.clip(np.rint(z * 2.5) + 8.0, 0.0, 15.0).astype(np.uint8)
-        u = normal_f32(rows * (cols // 128), (cfg.cfg_id, EXPERT_W, layer, e, which, 5))
-        sc = (cfg.w_std / 2.5) * (1.0 + 0.1 * np.clip(u, -3.0, 3.0))
-        out += [q, f32_to_bf16(sc.reshape(rows, cols // 128))]
-    return tuple(out)
+    return _draw_q4(cfg, cfg.F, (cfg.cfg_id, EXPERT_W, layer, e))
+
+
+def shared_weights_q4(cfg: MoEShape, layer: int):
+    """4-bit form of the always-resident dense SwiGLU of hidden F_shared, drawn like a 4-bit expert."""
+    if cfg.F_shared == 0:
+        return None
+    return _draw_q4(cfg, cfg.F_shared, (cfg.cfg_id, SHARED_W, layer))
 
 
 def dequant_q4(q: np.ndarray, s: np.ndarray) -> np.ndarray:

@@ -26,7 +26,8 @@ class LayerStack:
         self.expert_layers = list(range(n_layers)) if expert_layers is None else list(expert_layers)
         make = synth.expert_weights_q4 if q4 else synth.expert_weights
         self.experts = {l: [make(cfg, l, e) for e in range(cfg.E)] for l in self.expert_layers}
-        self.shared = {l: synth.shared_weights(cfg, l) for l in self.expert_layers} if cfg.F_shared else {}
+        make_shared = synth.shared_weights_q4 if q4 else synth.shared_weights
+        self.shared = {l: make_shared(cfg, l) for l in self.expert_layers} if cfg.F_shared else {}
         self.ctx = ef.ef_create(n_layers=n_layers, d_model=cfg.d, n_experts=cfg.E, top_k=cfg.k, d_ff=cfg.F,
                                 d_ff_shared=cfg.F_shared, slots_total=slots_total,
                                 slots_per_layer_max=per_layer, max_tokens=max_tokens, h_max=h_max,
@@ -43,7 +44,12 @@ class LayerStack:
                 pack(*self.experts[src][e], blob=sv[e * self.es:(e + 1) * self.es])
             sh = None
             if cfg.F_shared:
-                sh = torch.from_numpy(ef.ef_pack_expert(*self.shared[src])).cuda()
+                if q4:
+                    sb = np.empty(ef.ef_expert_bytes_q4(cfg.d, cfg.F_shared), dtype=np.uint8)
+                    ef.ef_pack_expert_q4(*self.shared[src], blob=sb)
+                    sh = torch.from_numpy(sb).cuda()
+                else:
+                    sh = torch.from_numpy(ef.ef_pack_expert(*self.shared[src])).cuda()
             ef.ef_register_layer(self.ctx, l, gw, gb, store, sh)
             self._keep += [gw, gb, store, sh]
 

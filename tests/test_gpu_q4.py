@@ -43,7 +43,11 @@ def layer_check(oracle_mod, st, h, T, beta, res, toks=None):
     ids_s = np.ascontiguousarray(got["ids"][toks])
     sub = oracle_mod.route_from_ids(ora["p"][toks], ids_s, cfg.E, cfg.renorm)
     y = oracle_mod.expert_ffn_q4(hs, st.experts[0], ids_s, sub["perm"])
-    ref = oracle_mod.combine(y, sub["w"], sub["inv_perm"], None)
+    shared = None
+    if cfg.F_shared:        # the dense shared FFN is a 4-bit expert every token goes through with weight 1
+        n = len(toks)
+        shared = oracle_mod.expert_ffn_q4(hs, [st.shared[0]], np.zeros((n, 1), dtype=np.int32), np.arange(n))
+    ref = oracle_mod.combine(y, sub["w"], sub["inv_perm"], shared)
     e1, e2 = float_close(out[toks], ref)
     say(f"  near-ties {nties}, {len(toks)} tokens: max abs {e1:.2e}, rel l2 {e2:.2e}, |ref| rms {np.sqrt((ref ** 2).mean()):.2f}")
 
@@ -149,8 +153,45 @@ def test_q4_full_size_mixtral_prefill(oracle_mod):
         st.close()
 
 
+@pytest.mark.parametrize("T,tiled_shared", [(130, False), (1, False), (300, True), (515, True)])
+def test_q4_shared_ffn(oracle_mod, T, tiled_shared):
+    """DeepSeek-like layer whose routed experts and dense shared FFN are all 4-bit: the shared group streams
+    with the routed ones while it has fewer than 8 token tiles and takes the expansion + tiled kernels above."""
+    cfg = dataclasses.replace(synth.CONFIGS["deepseek_v2_lite"], name="deepseek_q4_shared", d=256, F=128, F_shared=384)
+    say(f"q4 shared FFN d={cfg.d} F={cfg.F} Fs={cfg.F_shared} E={cfg.E} k={cfg.k} T={T}")
+    st = LayerStack(cfg, 1, slots_total=cfg.E, max_tokens=max(T, 64), q4=True, flags=ef.EF_FLAG_PROFILE)
+    try:
+        for e in range(cfg.E):
+            ef.ef_cache_swap_in(st.ctx, 0, e, 0, 0)
+        res = ef.ef_cache_query(st.ctx, 0, cfg.E)
+        layer_check(oracle_mod, st, synth.hidden(cfg, 0, T), T, 0.0, res)
+        launches = dict(zip(ef.EF_KERNELS, ef.ef_get_stats(st.ctx)["kernel_launches"]))
+        assert (launches["ffn_up_tiled"] > 0) == tiled_shared and (launches["ffn_down_tiled"] > 0) == tiled_shared
+    finally:
+        st.close()
+
+
+def test_q4_full_size_qwen_mixed_batch(oracle_mod):
+    """Qwen1.5-MoE-shaped layer, T = 640, 60 routed experts and the 5632-wide shared FFN all 4-bit
+    (`bench.py --workload qwen15_moe --int4`): shared FFN expanded and tiled, routed experts streamed; sampled tokens."""
+    cfg = dataclasses.replace(synth.CONFIGS["qwen15_moe"], name="qwen15_moe_q4")
+    T = 640
+    say(f"q4 full size: Qwen-shaped layer, T={T}, shared FFN {cfg.F_shared}")
+    st = LayerStack(cfg, 1, slots_total=cfg.E, max_tokens=T, q4=True, flags=ef.EF_FLAG_PROFILE)
+    try:
+        for e in range(cfg.E):
+            ef.ef_cache_swap_in(st.ctx, 0, e, 0, 0)
+        res = ef.ef_cache_query(st.ctx, 0, cfg.E)
+        toks = np.sort(np.random.default_rng(T).permutation(T)[:6])
+        layer_check(oracle_mod, st, synth.hidden(cfg, 0, T), T, 0.0, res, toks)
+        launches = dict(zip(ef.EF_KERNELS, ef.ef_get_stats(st.ctx)["kernel_launches"]))
+        assert launches["ffn_up_tiled"] == 1 and launches["ffn_down_tiled"] == 1 and launches["ffn_up"] == 1
+    finally:
+        st.close()
+
+
 def test_q4_create_rejects_bad_shapes():
-    for kw in (dict(d_model=192, d_ff=128), dict(d_model=128, d_ff=96), dict(d_model=128, d_ff=128, d_ff_shared=128)):
+    for kw in (dict(d_model=192, d_ff=128), dict(d_model=128, d_ff=96), dict(d_model=128, d_ff=128, d_ff_shared=96)):
         args = dict(n_layers=1, d_model=128, n_experts=4, top_k=2, d_ff=128, slots_total=4, max_tokens=8,
                     weight_bits=4)
         args.update(kw)
