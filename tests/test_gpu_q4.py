@@ -190,6 +190,25 @@ def test_q4_full_size_qwen_mixed_batch(oracle_mod):
         st.close()
 
 
+def test_q4_large_groups_in_phases(oracle_mod):
+    """More active experts (of 8+ token tiles each) than the three cache slots: the call works in phases that
+    reuse the slots and the fp16 staging copies; every phase expands its own experts before its tiled launches."""
+    cfg = q4_shape("tiny", name="tiny_q4_phases", d=256, F=256)
+    T = 1500
+    say(f"q4 large groups in phases d={cfg.d} F={cfg.F} E={cfg.E} k={cfg.k} T={T}, 3 slots")
+    st = LayerStack(cfg, 1, slots_total=3, max_tokens=T, q4=True, flags=ef.EF_FLAG_PROFILE)
+    try:
+        res = ef.ef_cache_query(st.ctx, 0, cfg.E)
+        assert res.sum() == 0
+        layer_check(oracle_mod, st, synth.hidden(cfg, 0, T), T, 0.0, res)
+        stats = ef.ef_get_stats(st.ctx)
+        launches = dict(zip(ef.EF_KERNELS, stats["kernel_launches"]))
+        say(f"  misses {stats['misses']}, launches {launches}")
+        assert stats["misses"] > 3 and launches["ffn_up_tiled"] >= 2 and launches["ffn_down_tiled"] >= 2    # more experts than slots
+    finally:
+        st.close()
+
+
 def test_q4_create_rejects_bad_shapes():
     for kw in (dict(d_model=192, d_ff=128), dict(d_model=128, d_ff=96), dict(d_model=128, d_ff=128, d_ff_shared=96)):
         args = dict(n_layers=1, d_model=128, n_experts=4, top_k=2, d_ff=128, slots_total=4, max_tokens=8,
