@@ -100,12 +100,13 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_q4_kernel(GroupTable gt, c
 #define EF_Q4U_LOAD(slot, kq)                                                                             \
     {                                                                                                     \
         const int kc_ = min((kq), nq - 1);                                                                \
+        _Pragma("unroll") for (int u = 0; u < TT; ++u)                                                    \
+            xr[slot][u] = *reinterpret_cast<const u32x4_t *>(xsrc[u] + (size_t)(4 * kc_ + wave) * 64);    \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
         qa[slot] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(w13 + (size_t)kc_ * 128));       \
         qb[slot] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(w13 + (size_t)kc_ * 128 + 64));  \
         sa[slot] = sA[(size_t)(kc_ >> 1) * 64];                                                           \
         sb[slot] = sA[(size_t)(kc_ >> 1) * 64 + 32];                                                      \
-        _Pragma("unroll") for (int u = 0; u < TT; ++u)                                                    \
-            xr[slot][u] = *reinterpret_cast<const u32x4_t *>(xsrc[u] + (size_t)(4 * kc_ + wave) * 64);    \
     }
 #define EF_Q4U_SHARE(slot, st)                                                                            \
     {                                                                                                     \
@@ -253,13 +254,14 @@ __global__ __launch_bounds__(256, 1) void ffn_down_q4_kernel(GroupTable gt, cons
 #define EF_Q4D_LOAD(slot, kq)                                                                             \
     {                                                                                                     \
         const int kc_ = min((kq), nq - 1);                                                                \
+        _Pragma("unroll") for (int u = 0; u < TT; ++u)                                                    \
+            ar[slot][u] = *reinterpret_cast<const u32x4_t *>(asrc[u] + (size_t)(4 * kc_ + wave) * 64);    \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
         _Pragma("unroll") for (int cw = 0; cw < CBW; ++cw) {                                              \
             qw[slot][cw] = __builtin_nontemporal_load(                                                    \
                 reinterpret_cast<const u32x4_t *>(w2q + cw * qstride + (size_t)kc_ * 64));                \
             sc[slot][cw] = sB[cw * sstride + (size_t)(kc_ >> 1) * 32];                                    \
         }                                                                                                 \
-        _Pragma("unroll") for (int u = 0; u < TT; ++u)                                                    \
-            ar[slot][u] = *reinterpret_cast<const u32x4_t *>(asrc[u] + (size_t)(4 * kc_ + wave) * 64);    \
     }
 #define EF_Q4D_SHARE(slot, st)                                                                            \
     {                                                                                                     \

@@ -13,17 +13,17 @@
 
 namespace ef {
 
-constexpr int kShDepth = 3;   // register ring: stages in flight per wave
+constexpr int kShDepth = 3;   // register ring: stages in flight per wave (one workgroup per CU); the variants that
+                              // fit two workgroups per CU (<= 256 registers) keep two stages
 constexpr int kShLds = 4;     // LDS ring of shared token / activation fragments (stages, power of two)
 
 // ------------------------------------------------------------------------------------------
 // first half: act = silu(X W1^T) * (X W3^T).  Workgroup = (group, pass of TT token tiles, four
 // consecutive 32-row blocks of F), wave = one row block, whole K range in stages of four k-blocks.
 // ------------------------------------------------------------------------------------------
-template <int TT>
-__global__ __launch_bounds__(256, 1) void ffn_gate_up_shared_kernel(GroupTable gt, const uint4 *__restrict__ xp,
+template <int TT, int D, int OCC>
+__global__ __launch_bounds__(256, OCC) void ffn_gate_up_shared_kernel(GroupTable gt, const uint4 *__restrict__ xp,
                                                                     uint4 *__restrict__ act, int d) {
-    constexpr int D = kShDepth;
     __shared__ __attribute__((aligned(16))) u32x4_t xs[kShLds][TT * 4][64];
     const int wg = blockIdx.x;
     int grp = 0;
@@ -52,16 +52,19 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_shared_kernel(GroupTable g
     for (int tt = 0; tt < TT; ++tt) { zero16(G[tt]); zero16(U[tt]); }
 
     u32x4_t wa[D][4], wb[D][4], xr[D][TT];
-    // every load is unconditional (past the end the last stage is re-read, in bounds)
+    // every load is unconditional (past the end the last stage is re-read, in bounds).  The token fragments are
+    // requested before the weights: they are handed to the workgroup one stage before the weights of their
+    // stage are used, and loads return in issue order, so waiting for them must not mean waiting for those weights
 #define EF_SHU_LOAD(slot, kq)                                                                            \
     {                                                                                                    \
         const int kc_ = min((kq), nq - 1);                                                               \
+        _Pragma("unroll") for (int u = 0; u < TT; ++u)                                                   \
+            xr[slot][u] = *reinterpret_cast<const u32x4_t *>(xsrc[u] + (size_t)(4 * kc_ + wave) * 64);   \
+        __builtin_amdgcn_sched_barrier(0);                                                               \
         _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                  \
             wa[slot][j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(w1 + (size_t)(4 * kc_ + j) * 64)); \
             wb[slot][j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(w3 + (size_t)(4 * kc_ + j) * 64)); \
         }                                                                                                \
-        _Pragma("unroll") for (int u = 0; u < TT; ++u)                                                   \
-            xr[slot][u] = *reinterpret_cast<const u32x4_t *>(xsrc[u] + (size_t)(4 * kc_ + wave) * 64);   \
     }
 #define EF_SHU_SHARE(slot, st)                                                                           \
     {                                                                                                    \
@@ -125,7 +128,7 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_shared_kernel(GroupTable g
     }
 }
 
-hipError_t launch_ffn_gate_up_shared(const GroupTable &gt, int total_wgs, int tiles_per_pass, const void *xp,
+hipError_t launch_ffn_gate_up_shared(const GroupTable &gt, int total_wgs, int tiles_per_pass, int occ, const void *xp,
                                      void *act, int d, hipStream_t s) {
     if (total_wgs <= 0) return hipSuccess;
     if (d % 64 != 0) return hipErrorInvalidValue;
@@ -137,9 +140,11 @@ hipError_t launch_ffn_gate_up_shared(const GroupTable &gt, int total_wgs, int ti
     const uint4 *x = reinterpret_cast<const uint4 *>(xp);
     uint4 *a = reinterpret_cast<uint4 *>(act);
     if (tiles_per_pass == 2)
-        hipLaunchKernelGGL((ffn_gate_up_shared_kernel<2>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
+        hipLaunchKernelGGL((ffn_gate_up_shared_kernel<2, kShDepth, 1>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
+    else if (tiles_per_pass == 4 && occ == 2)
+        hipLaunchKernelGGL((ffn_gate_up_shared_kernel<4, 2, 2>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
     else if (tiles_per_pass == 4)
-        hipLaunchKernelGGL((ffn_gate_up_shared_kernel<4>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
+        hipLaunchKernelGGL((ffn_gate_up_shared_kernel<4, kShDepth, 1>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
@@ -150,11 +155,11 @@ hipError_t launch_ffn_gate_up_shared(const GroupTable &gt, int total_wgs, int ti
 // A (rows = tokens), shared through LDS; W2 fragments operand B (a lane holds one output column).
 // Each K-slice writes its own partial Y plane; the un-permute sums the planes in order.
 // ------------------------------------------------------------------------------------------
-template <int TT>
-__global__ __launch_bounds__(256, 1) void ffn_down_shared_kernel(GroupTable gt, const uint4 *__restrict__ act,
+template <int TT, int D, int OCC>
+__global__ __launch_bounds__(256, OCC) void ffn_down_shared_kernel(GroupTable gt, const uint4 *__restrict__ act,
                                                                  float *__restrict__ Y, int d, int ksg,
                                                                  long long y_plane) {
-    constexpr int D = kShDepth, CBW = 2;
+    constexpr int CBW = 2;
     __shared__ __attribute__((aligned(16))) u32x4_t as[kShLds][TT * 4][64];
     const int wg = blockIdx.x;
     int grp = 0;
@@ -191,12 +196,13 @@ __global__ __launch_bounds__(256, 1) void ffn_down_shared_kernel(GroupTable gt, 
 #define EF_SHD_LOAD(slot, kq)                                                                            \
     {                                                                                                    \
         const int kc_ = min((kq), nq - 1);                                                               \
+        _Pragma("unroll") for (int u = 0; u < TT; ++u)                                                   \
+            ar[slot][u] = *reinterpret_cast<const u32x4_t *>(asrc[u] + (size_t)(4 * kc_ + wave) * 64);   \
+        __builtin_amdgcn_sched_barrier(0);                                                               \
         _Pragma("unroll") for (int cw = 0; cw < CBW; ++cw)                                               \
             _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                \
                 wq[slot][cw][j] = __builtin_nontemporal_load(                                            \
                     reinterpret_cast<const u32x4_t *>(w2 + cw * cb_stride + (size_t)(4 * kc_ + j) * 64)); \
-        _Pragma("unroll") for (int u = 0; u < TT; ++u)                                                   \
-            ar[slot][u] = *reinterpret_cast<const u32x4_t *>(asrc[u] + (size_t)(4 * kc_ + wave) * 64);   \
     }
 #define EF_SHD_SHARE(slot, st)                                                                           \
     {                                                                                                    \
@@ -254,7 +260,7 @@ __global__ __launch_bounds__(256, 1) void ffn_down_shared_kernel(GroupTable gt, 
     }
 }
 
-hipError_t launch_ffn_down_shared(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ksg, const void *act,
+hipError_t launch_ffn_down_shared(const GroupTable &gt, int total_wgs, int tiles_per_pass, int occ, int ksg, const void *act,
                                   float *y, long long y_plane, int d, hipStream_t s) {
     if (total_wgs <= 0) return hipSuccess;
     if (d % 64 != 0 || ksg < 1) return hipErrorInvalidValue;
@@ -265,9 +271,11 @@ hipError_t launch_ffn_down_shared(const GroupTable &gt, int total_wgs, int tiles
     if (gt.wg_start[gt.n_groups] != total_wgs) return hipErrorInvalidValue;
     const uint4 *a = reinterpret_cast<const uint4 *>(act);
     if (tiles_per_pass == 2)
-        hipLaunchKernelGGL((ffn_down_shared_kernel<2>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
+        hipLaunchKernelGGL((ffn_down_shared_kernel<2, kShDepth, 1>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
+    else if (tiles_per_pass == 4 && occ == 2)
+        hipLaunchKernelGGL((ffn_down_shared_kernel<4, 2, 2>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
     else if (tiles_per_pass == 4)
-        hipLaunchKernelGGL((ffn_down_shared_kernel<4>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
+        hipLaunchKernelGGL((ffn_down_shared_kernel<4, kShDepth, 1>), dim3(total_wgs), dim3(256), 0, s, gt, a, y, d, ksg, y_plane);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

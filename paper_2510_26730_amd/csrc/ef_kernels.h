@@ -167,9 +167,9 @@ inline int ffn_gate_up_shared_wgs(int F, int n_tiles, int tiles_per_pass) {
 inline int ffn_down_shared_wgs(int d, int n_tiles, int tiles_per_pass, int ksg) {
     return ((d / 32 + 7) / 8) * ((n_tiles + tiles_per_pass - 1) / tiles_per_pass) * ksg;
 }
-hipError_t launch_ffn_gate_up_shared(const GroupTable &gt, int total_wgs, int tiles_per_pass, const void *xp,
+hipError_t launch_ffn_gate_up_shared(const GroupTable &gt, int total_wgs, int tiles_per_pass, int occ, const void *xp,
                                      void *act, int d, hipStream_t s);
-hipError_t launch_ffn_down_shared(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ksg, const void *act,
+hipError_t launch_ffn_down_shared(const GroupTable &gt, int total_wgs, int tiles_per_pass, int occ, int ksg, const void *act,
                                   float *y, long long y_plane, int d, hipStream_t s);
 inline int ffn_down_wgs(int d, int n_tiles, int tiles_per_pass, int ksg) {
     return (d / 32 / kDownColBlocks) * ((n_tiles + tiles_per_pass - 1) / tiles_per_pass) * ksg;
