@@ -257,15 +257,15 @@ def test_outputs_do_not_depend_on_slots_or_phase_order(oracle_mod):
     assert np.array_equal(outs[0][1], outs[1][1]) and np.array_equal(outs[0][1], outs[2][1])
 
 
-@pytest.mark.parametrize("cfg_name,T", [("tiny", 64), ("tiny", 7)])
-def test_layer_step_equals_separate_calls(cfg_name, T):
+@pytest.mark.parametrize("cfg_name,T,q4", [("tiny", 64, False), ("tiny", 7, False), ("tiny", 64, True), ("tiny", 300, True)])
+def test_layer_step_equals_separate_calls(cfg_name, T, q4):
     """The composite entry point (host-mapped hand-over, flag polling) gives bit-identical outputs,
     the same cache decisions and the same horizon as the separate entry points."""
     from paper_2510_26730_amd.runner import LayerLoop
     cfg = synth.CONFIGS[cfg_name]
-    say(f"ef_layer_step vs separate calls, {cfg_name} T={T}")
+    say(f"ef_layer_step vs separate calls, {cfg_name} T={T} 4-bit experts: {q4}")
     L = 3
-    loops = [LayerLoop(cfg, L, T, cfg.slots_per_layer, beta=0.5, seed=1, fixed_estimates=True) for _ in range(2)]
+    loops = [LayerLoop(cfg, L, T, cfg.slots_per_layer, beta=0.5, seed=1, fixed_estimates=True, q4=q4) for _ in range(2)]
     try:
         stream = torch.cuda.current_stream()
         for step in range(3):
