@@ -29,9 +29,10 @@ static_assert(kStageFrags / 4 == 8, "the wait count assumes 8 loads per wave per
 // Returns false for the padding workgroups past the last weight panel.
 __device__ __forceinline__ bool tiled_panel(int local, int npanels, int mpanels, int &np, int &mp) {
     const int xcd = local & 7, j = local >> 3;
-    const int blk = kTiledPanelBlock * mpanels;
+    const int pb = tiled_panel_block(npanels);
+    const int blk = pb * mpanels;
     const int jb = j / blk, jj = j - jb * blk;
-    np = (jb * 8 + xcd) * kTiledPanelBlock + jj / mpanels;
+    np = (jb * 8 + xcd) * pb + jj / mpanels;
     mp = jj % mpanels;
     return np < npanels;
 }

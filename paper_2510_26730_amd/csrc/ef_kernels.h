@@ -147,8 +147,11 @@ inline bool ffn_tiled_ok(int d, int F, int n_tiles) {
 // panels: a weight panel is then fetched into one L2 once and read by every token panel there.  The
 // count is padded to whole blocks; workgroups that fall past the last weight panel exit at once.
 constexpr int kTiledPanelBlock = 2;
+// With fewer than 16 weight panels (d = 2048 gives the second half 8) blocks of two would leave half of the
+// XCDs without a panel: such launches deal single panels.
+__host__ __device__ inline int tiled_panel_block(int npanels) { return npanels >= 8 * kTiledPanelBlock ? kTiledPanelBlock : 1; }
 inline int ffn_tiled_wgs(int npanels, int n_tiles) {
-    const int per_round = 8 * kTiledPanelBlock;
+    const int per_round = 8 * tiled_panel_block(npanels);
     return ((npanels + per_round - 1) / per_round) * per_round * ((n_tiles + 7) / 8);
 }
 inline int ffn_gate_up_tiled_wgs(int F, int n_tiles) { return ffn_tiled_wgs(F / 128, n_tiles); }
