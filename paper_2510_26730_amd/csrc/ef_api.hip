@@ -894,7 +894,8 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
             blob = c->pool + (size_t)pg.slot * c->expert_bytes;
         }
         const int nt = (cnt + ef::kTile - 1) / ef::kTile;
-        const bool tiled = allow_tiled && ef::ffn_tiled_ok(d, F, nt) && (!c->q4 || nb < c->q4_stage_slots);
+        const bool tiled = allow_tiled && ef::ffn_tiled_ok(d, F, nt) && nt >= tune("EF_TUNE_TILED_MIN_TILES", 8) &&
+                           (!c->q4 || nb < c->q4_stage_slots);
         ef::GroupTable &g = tiled ? big : gu;
         int &i = tiled ? nb : n;
         if (tiled && c->q4) {   // the tiled kernels read a 16-bit copy written just before them on the same stream
@@ -920,9 +921,17 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
     if (nb > 0) {
         ef::GroupTable bdn = big;
         int wg_up = 0, wg_dn = 0;
+        // each group's panel blocks are dealt to the XCDs starting where the previous group's stopped
+        int blocks_up = 0, blocks_dn = 0;
+        const int rot_on = tune("EF_TUNE_TILED_ROT", 1);
         for (int i = 0; i < nb; ++i) {
             big.wg_start[i] = wg_up;
             bdn.wg_start[i] = wg_dn;
+            big.xcd_rot[i] = rot_on ? blocks_up & 7 : 0;
+            bdn.xcd_rot[i] = rot_on ? blocks_dn & 7 : 0;
+            const int pu = big.F[i] / 128, pd = d / 256;
+            blocks_up += (pu + ef::tiled_panel_block(pu) - 1) / ef::tiled_panel_block(pu);
+            blocks_dn += (pd + ef::tiled_panel_block(pd) - 1) / ef::tiled_panel_block(pd);
             wg_up += ef::ffn_gate_up_tiled_wgs(big.F[i], big.n_tiles[i]);
             wg_dn += ef::ffn_down_tiled_wgs(d, big.n_tiles[i]) * ksg;
         }
@@ -1059,7 +1068,7 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         long long wg_up = 0, wg_dn = 0;
         auto add = [&](int F, int cnt) {
             const int nt = (cnt + ef::kTile - 1) / ef::kTile;
-            if (!ef::ffn_tiled_ok(d, F, nt)) return;
+            if (!ef::ffn_tiled_ok(d, F, nt) || nt < tune("EF_TUNE_TILED_MIN_TILES", 8)) return;
             wg_up += ef::ffn_gate_up_tiled_wgs(F, nt);
             wg_dn += ef::ffn_down_tiled_wgs(d, nt);
             tiled_stages_min = std::min(tiled_stages_min, F / 32);

@@ -27,8 +27,10 @@ static_assert(kStageFrags / 4 == 8, "the wait count assumes 8 loads per wave per
 // same index mod 8 land on one XCD; consecutive ones there walk the token panels of
 // kTiledPanelBlock weight panels, so the panels an XCD works on at one time share its L2.
 // Returns false for the padding workgroups past the last weight panel.
-__device__ __forceinline__ bool tiled_panel(int local, int npanels, int mpanels, int &np, int &mp) {
-    const int xcd = local & 7, j = local >> 3;
+__device__ __forceinline__ bool tiled_panel(int local, int rot, int npanels, int mpanels, int &np, int &mp) {
+    // `rot`: the XCD that takes the group's first panel block.  Groups whose panels do not fill a round of
+    // eight XCDs would otherwise all start on XCD 0 and overfill its 32 compute units while others idle.
+    const int xcd = (local - rot) & 7, j = local >> 3;
     const int pb = tiled_panel_block(npanels);
     const int blk = pb * mpanels;
     const int jb = j / blk, jj = j - jb * blk;
@@ -183,7 +185,7 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_tiled_kernel(GroupTable gt
     const int ntiles = gt.n_tiles[grp];
     const int mpanels = (ntiles + 7) >> 3;
     int np, mp;
-    if (!tiled_panel(local, F >> 7, mpanels, np, mp)) return;
+    if (!tiled_panel(local, gt.xcd_rot[grp], F >> 7, mpanels, np, mp)) return;
     const int rb0 = np * 4, t0 = mp * 8;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS DMA targets go through M0
@@ -285,7 +287,7 @@ __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, c
     // would leave most of the chip idle; neighbouring workgroups take the slices of one tile
     const int kslice = local % ksg;
     int np, mp;
-    if (!tiled_panel(local / ksg, d >> 8, mpanels, np, mp)) return;
+    if (!tiled_panel(local / ksg, gt.xcd_rot[grp], d >> 8, mpanels, np, mp)) return;
     const int cb0 = np * 8, t0 = mp * 8;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS DMA targets go through M0

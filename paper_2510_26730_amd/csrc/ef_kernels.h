@@ -49,6 +49,7 @@ struct GroupTable {
     int F[kMaxGroups];             // FFN hidden dim of the group
     long long act_off[kMaxGroups]; // first 16-byte unit of the group's activation fragments
     const void *blob[kMaxGroups];  // packed weights (cache slot or shared blob)
+    int xcd_rot[kMaxGroups];       // tiled kernels: the group's first weight panel goes to this XCD (0..7)
 };
 
 // Optional hand-over of counts and predicted histograms to the host (host-mapped memory): every word is
