@@ -129,6 +129,12 @@ int tune(const char *name, int dflt) {
     return (v && *v) ? atoi(v) : dflt;
 }
 
+// Routed groups take the tiled kernels from this many token tiles on (the kernels accept 8).  A group of 8 or 9
+// tiles is one 256-token panel (plus an almost empty one): its weight panels are read by a single workgroup
+// each, cold from HBM with three stages in flight, and such workgroups outlast those of a group with several
+// token panels in the same launch; the streaming kernels serve them better (Qwen-shaped T = 640: 8 % of the layer).
+int tiled_min_routed() { return std::max(ef::kTiledMinTiles, tune("EF_TUNE_TILED_MIN_TILES", 10)); }
+
 void ema(double &est, double sample, double alpha = 0.25) { est = (1.0 - alpha) * est + alpha * sample; }
 
 // Every kLayerTimerEvery-th layer is bracketed with events for the T_l estimate: an event record between two
@@ -894,7 +900,7 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
             blob = c->pool + (size_t)pg.slot * c->expert_bytes;
         }
         const int nt = (cnt + ef::kTile - 1) / ef::kTile;
-        const bool tiled = allow_tiled && ef::ffn_tiled_ok(d, F, nt) && nt >= tune("EF_TUNE_TILED_MIN_TILES", 8) &&
+        const bool tiled = allow_tiled && ef::ffn_tiled_ok(d, F, nt) && (pg.expert < 0 || nt >= tiled_min_routed()) &&
                            (!c->q4 || nb < c->q4_stage_slots);
         ef::GroupTable &g = tiled ? big : gu;
         int &i = tiled ? nb : n;
@@ -921,17 +927,27 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
     if (nb > 0) {
         ef::GroupTable bdn = big;
         int wg_up = 0, wg_dn = 0;
-        // each group's panel blocks are dealt to the XCDs starting where the previous group's stopped
-        int blocks_up = 0, blocks_dn = 0;
+        // Workgroups go to the XCDs round-robin by index and hold one of an XCD's 32 compute units for their whole
+        // K loop.  A group's panel blocks (block b -> XCD rot + b) are dealt from the start XCD that leaves the
+        // fullest XCD of the first half's launch least full, so groups of a few panels do not pile up on XCD 0.
+        int load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         const int rot_on = tune("EF_TUNE_TILED_ROT", 1);
         for (int i = 0; i < nb; ++i) {
             big.wg_start[i] = wg_up;
             bdn.wg_start[i] = wg_dn;
-            big.xcd_rot[i] = rot_on ? blocks_up & 7 : 0;
-            bdn.xcd_rot[i] = rot_on ? blocks_dn & 7 : 0;
-            const int pu = big.F[i] / 128, pd = d / 256;
-            blocks_up += (pu + ef::tiled_panel_block(pu) - 1) / ef::tiled_panel_block(pu);
-            blocks_dn += (pd + ef::tiled_panel_block(pd) - 1) / ef::tiled_panel_block(pd);
+            const int pu = big.F[i] / 128, pbu = ef::tiled_panel_block(pu), nblk = (pu + pbu - 1) / pbu;
+            const int mp = (big.n_tiles[i] + 7) / 8;
+            int best = 0, best_max = 1 << 30;
+            for (int rot = 0; rot < (rot_on ? 8 : 1); ++rot) {
+                int trial[8], mx = 0;
+                for (int x = 0; x < 8; ++x) trial[x] = load[x];
+                for (int b = 0; b < nblk; ++b) trial[(rot + b) & 7] += std::min(pbu, pu - b * pbu) * mp;
+                for (int x = 0; x < 8; ++x) mx = std::max(mx, trial[x]);
+                if (mx < best_max) { best_max = mx; best = rot; }
+            }
+            for (int b = 0; b < nblk; ++b) load[(best + b) & 7] += std::min(pbu, pu - b * pbu) * mp;
+            big.xcd_rot[i] = best;
+            bdn.xcd_rot[i] = 0;   // the second half's panels cover every XCD (or K slices interleave them)
             wg_up += ef::ffn_gate_up_tiled_wgs(big.F[i], big.n_tiles[i]);
             wg_dn += ef::ffn_down_tiled_wgs(d, big.n_tiles[i]) * ksg;
         }
@@ -1066,15 +1082,15 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
     int tiled_stages_min = 1 << 30;   // fewest K stages (32 columns each) among the tiled groups
     if (T > 0 && (!c->q4 || c->q4_stage_slots > 0) && tune("EF_TUNE_TILED", 1) != 0) {
         long long wg_up = 0, wg_dn = 0;
-        auto add = [&](int F, int cnt) {
+        auto add = [&](int F, int cnt, bool routed) {
             const int nt = (cnt + ef::kTile - 1) / ef::kTile;
-            if (!ef::ffn_tiled_ok(d, F, nt) || nt < tune("EF_TUNE_TILED_MIN_TILES", 8)) return;
+            if (!ef::ffn_tiled_ok(d, F, nt) || (routed && nt < tiled_min_routed())) return;
             wg_up += ef::ffn_gate_up_tiled_wgs(F, nt);
             wg_dn += ef::ffn_down_tiled_wgs(d, nt);
             tiled_stages_min = std::min(tiled_stages_min, F / 32);
         };
-        for (int e = 0; e < E; ++e) add(c->cfg.d_ff, counts_host[e]);
-        if (has_shared) add(c->cfg.d_ff_shared, T);
+        for (int e = 0; e < E; ++e) add(c->cfg.d_ff, counts_host[e], true);
+        if (has_shared) add(c->cfg.d_ff_shared, T, false);
         use_tiled = wg_up >= tune("EF_TUNE_TILED_MIN_UP", 1) && wg_dn >= tune("EF_TUNE_TILED_MIN_DOWN", 1);
         tiled_dn_wgs = wg_dn;
     }
