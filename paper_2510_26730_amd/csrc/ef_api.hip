@@ -887,7 +887,19 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
     ef::DequantTable dq{};
     int n = 0, nb = 0, max_tiles = 1;
     const bool allow_tiled = use_tiled;
-    for (const PhaseGroup &pg : groups) {
+    // Workgroups start in index order; groups with the most work go first so that the launch's last round holds
+    // the short ones (the groups are independent: the order changes no result)
+    std::vector<PhaseGroup> ordered(groups);
+    if (tune("EF_TUNE_SORT_GROUPS", 1) != 0) {
+        auto work = [&](const PhaseGroup &pg) {
+            const long long cnt = pg.expert < 0 ? T : counts_host[pg.expert];
+            const long long F = pg.expert < 0 ? c->cfg.d_ff_shared : c->cfg.d_ff;
+            return ((cnt + ef::kTile - 1) / ef::kTile) * F;
+        };
+        std::stable_sort(ordered.begin(), ordered.end(),
+                         [&](const PhaseGroup &a, const PhaseGroup &b) { return work(a) > work(b); });
+    }
+    for (const PhaseGroup &pg : ordered) {
         int cnt, ts, F, ro;
         long long ao;
         const void *blob;
