@@ -96,8 +96,11 @@ __device__ __forceinline__ uint32_t tiled_pack2(float v0, float v1) {
 // the two operands, and the last token panel of a group is rarely full: the kernels are limited by power,
 // so matrix-core work on tiles that do not exist costs real throughput.  Loads and barriers are the same in
 // every variant (the waves of a workgroup run different ones side by side).
+// kSwapOperands (a constant of the kernel): the product is formed transposed, operand-B fragment first.  The two
+// operand layouts are mirror images (lane 32*g + i holds row / column i, k-group g), so the same fragments serve.
 #define EF_TILED_MF(ac, bc, r, j, NLA, NLB)                                                          \
-    if ((r) < (NLA) && (j) < (NLB)) acc[r][j] = tiled_mfma<HALF>(ac[r], bc[j], acc[r][j]);
+    if ((r) < (NLA) && (j) < (NLB))                                                                  \
+        acc[r][j] = kSwapOperands ? tiled_mfma<HALF>(bc[j], ac[r], acc[r][j]) : tiled_mfma<HALF>(ac[r], bc[j], acc[r][j]);
 #define EF_TILED_RA(an, buf, ks, r, NLA) if ((r) < (NLA)) an[r] = lds[buf][(ks) * 16 + AOFF + (r)][lane];
 #define EF_TILED_RB(bn, buf, ks, r, NLB) if ((r) < (NLB)) bn[r] = lds[buf][(ks) * 16 + 8 + BOFF + (r)][lane];
 #define EF_TILED_ROUND(ac, bc, r, x0, x1, x3, st, half, NLA, NLB)                                    \
@@ -176,6 +179,7 @@ __device__ __forceinline__ uint32_t tiled_pack2(float v0, float v1) {
 template <bool HALF>
 __global__ __launch_bounds__(256, 1) void ffn_gate_up_tiled_kernel(GroupTable gt, const uint4 *__restrict__ xp,
                                                                     uint4 *__restrict__ act, int d) {
+    constexpr bool kSwapOperands = false;
     __shared__ __attribute__((aligned(16))) u32x4_t lds[kTileStages][kStageFrags][64];
     const int wg = blockIdx.x;
     int grp = 0;
@@ -275,6 +279,10 @@ template <bool HALF>
 __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, const uint4 *__restrict__ act,
                                                                  float *__restrict__ Y, int d, int ksg,
                                                                  long long y_plane) {
+    // Y^T = W2 act^T: a lane then ends with one token (its index mod 32) and four consecutive output columns per
+    // accumulator quad, which is one 16-byte store; with the product the other way round a lane holds one
+    // column of four consecutive tokens and the tile leaves in 4-byte stores, four times as many instructions
+    constexpr bool kSwapOperands = true;
     __shared__ __attribute__((aligned(16))) u32x4_t lds[kTileStages][kStageFrags][64];
     const int wg = blockIdx.x;
     int grp = 0;
@@ -330,14 +338,16 @@ __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, c
     for (int i = 0; i < 4; ++i) {
         const int tile = t0 + wt * 4 + i;
         if (tile >= ntiles) continue;
+        const int tl = tile * kTile + (lane & 31);
+        if (tl >= gt.count[grp]) continue;
+        float *row = Yp + (size_t)(gt.row_offset[grp] + tl) * d;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int col = (cb0 + wc * 4 + j) * 32 + (lane & 31);
+            const int col = (cb0 + wc * 4 + j) * 32 + 4 * g;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int tl = tile * kTile + 8 * (v >> 2) + 4 * g + (v & 3);
-                if (tl < gt.count[grp]) Yp[(size_t)(gt.row_offset[grp] + tl) * d + col] = acc[i][j][v];
-            }
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<float4 *>(row + col + 8 * q) =
+                    make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
         }
     }
 }
