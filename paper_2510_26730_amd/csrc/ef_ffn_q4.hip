@@ -281,7 +281,7 @@ __global__ __launch_bounds__(256, 1) void ffn_down_q4_kernel(GroupTable gt, cons
             const int cw = idx >> 2, j = idx & 3;                                                         \
             u32x4_t n_ = w_;                                                                              \
             if (idx + 1 < CBW * 4) n_ = dequant_q4(qw[slot][(idx + 1) >> 2][(idx + 1) & 3], f_[(idx + 1) >> 2]); \
-            _Pragma("unroll") for (int tt = 0; tt < TT; ++tt) acc[cw][tt] = mfma32h(af_[tt][j], w_, acc[cw][tt]); \
+            _Pragma("unroll") for (int tt = 0; tt < TT; ++tt) acc[cw][tt] = mfma32h(w_, af_[tt][j], acc[cw][tt]); \
             if (idx + 1 < CBW * 4) {                                                                      \
                 _Pragma("unroll") for (int q_ = 0; q_ < TT; ++q_) {                                       \
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                    \
@@ -321,14 +321,18 @@ __global__ __launch_bounds__(256, 1) void ffn_down_q4_kernel(GroupTable gt, cons
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
         if (tt >= ntl) break;
+        // the product is formed transposed (W2 fragment first: the operand layouts are mirror images), so a lane
+        // holds token lane % 32 and four consecutive output columns per accumulator quad: 16-byte stores
+        const int tl = (pass * TT + tt) * kTile + (lane & 31);
+        if (tl >= gt.count[grp]) continue;
+        float *row = Yp + (size_t)(gt.row_offset[grp] + tl) * d;
 #pragma unroll
         for (int cw = 0; cw < CBW; ++cw) {
-            const int col = (cb0 + cw) * 32 + (lane & 31);
+            const int col = (cb0 + cw) * 32 + 4 * g;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int tl = (pass * TT + tt) * kTile + 8 * (v >> 2) + 4 * g + (v & 3);
-                if (tl < gt.count[grp]) Yp[(size_t)(gt.row_offset[grp] + tl) * d + col] = acc[cw][tt][v];
-            }
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<float4 *>(row + col + 8 * q) =
+                    make_float4(acc[cw][tt][4 * q], acc[cw][tt][4 * q + 1], acc[cw][tt][4 * q + 2], acc[cw][tt][4 * q + 3]);
         }
     }
 }

@@ -214,7 +214,7 @@ __global__ __launch_bounds__(256, OCC) void ffn_down_shared_kernel(GroupTable gt
             _Pragma("unroll") for (int tt = 0; tt < TT; ++tt) {                                          \
                 const u32x4_t af_ = as[(st) & (kShLds - 1)][tt * 4 + j][lane];                           \
                 _Pragma("unroll") for (int cw = 0; cw < CBW; ++cw)                                       \
-                    acc[cw][tt] = mfma32v(af_, wq[slot][cw][j], acc[cw][tt]);                            \
+                    acc[cw][tt] = mfma32v(wq[slot][cw][j], af_, acc[cw][tt]);                            \
             }                                                                                            \
         }                                                                                                \
     }
@@ -248,14 +248,18 @@ __global__ __launch_bounds__(256, OCC) void ffn_down_shared_kernel(GroupTable gt
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
         if (tt >= ntl) break;
+        // the product is formed transposed (W2 fragment first: the operand layouts are mirror images), so a lane
+        // holds token lane % 32 and four consecutive output columns per accumulator quad: 16-byte stores
+        const int tl = (pass * TT + tt) * kTile + (lane & 31);
+        if (tl >= gt.count[grp]) continue;
+        float *row = Yp + (size_t)(gt.row_offset[grp] + tl) * d;
 #pragma unroll
         for (int cw = 0; cw < CBW; ++cw) {
-            const int col = (cb0 + cw) * 32 + (lane & 31);
+            const int col = (cb0 + cw) * 32 + 4 * g;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int tl = (pass * TT + tt) * kTile + 8 * (v >> 2) + 4 * g + (v & 3);
-                if (tl < gt.count[grp]) Yp[(size_t)(gt.row_offset[grp] + tl) * d + col] = acc[cw][tt][v];
-            }
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<float4 *>(row + col + 8 * q) =
+                    make_float4(acc[cw][tt][4 * q], acc[cw][tt][4 * q + 1], acc[cw][tt][4 * q + 2], acc[cw][tt][4 * q + 3]);
         }
     }
 }
