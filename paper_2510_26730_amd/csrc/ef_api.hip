@@ -878,7 +878,7 @@ struct PhaseGroup {
 int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, const int32_t *counts_host,
                  const std::vector<int> &offs_host, const std::vector<int> &tile_start,
                  const std::vector<long long> &act_off, int shared_tile_start, long long shared_act_off, int T,
-                 int ksg, long long y_plane, bool use_tiled, hipStream_t s) {
+                 int ksg_stream, int ksg_tiled, ef::PlaneTable &planes, long long y_plane, bool use_tiled, hipStream_t s) {
     if (groups.empty()) return EF_OK;
     const int d = c->cfg.d_model, k = c->cfg.top_k;
     // groups with many tokens go to the tiled (matrix-core bound) kernels, the others to the
@@ -921,6 +921,7 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
             dq.F[nb] = F; dq.src[nb] = blob; dq.dst[nb] = copy;
             blob = copy;
         }
+        (pg.expert < 0 ? planes.shared : planes.routed[pg.expert]) = (uint8_t)(tiled ? ksg_tiled : ksg_stream);
         g.tile_start[i] = ts; g.n_tiles[i] = nt; g.row_offset[i] = ro;
         g.count[i] = cnt; g.F[i] = F; g.act_off[i] = ao; g.blob[i] = blob;
         if (!tiled) max_tiles = std::max(max_tiles, nt);
@@ -961,7 +962,7 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
             big.xcd_rot[i] = best;
             bdn.xcd_rot[i] = 0;   // the second half's panels cover every XCD (or K slices interleave them)
             wg_up += ef::ffn_gate_up_tiled_wgs(big.F[i], big.n_tiles[i]);
-            wg_dn += ef::ffn_down_tiled_wgs(d, big.n_tiles[i]) * ksg;
+            wg_dn += ef::ffn_down_tiled_wgs(d, big.n_tiles[i]) * ksg_tiled;
         }
         big.wg_start[nb] = wg_up;
         bdn.wg_start[nb] = wg_dn;
@@ -981,7 +982,7 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
         }
         {
             KernelTimer kt(c, s, EF_K_FFN_DOWN_TILED, b_dn, f_dn);
-            EF_HIP(c, ef::launch_ffn_down_tiled(bdn, wg_dn, ksg, c->act, c->y, y_plane, d, c->q4, s));
+            EF_HIP(c, ef::launch_ffn_down_tiled(bdn, wg_dn, ksg_tiled, c->act, c->y, y_plane, d, c->q4, s));
         }
     }
     if (n == 0) return EF_OK;
@@ -1007,12 +1008,13 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
         dn.wg_start[i] = wg_dn;
         if (shared) {
             wg_gu += ef::ffn_gate_up_shared_wgs(gu.F[i], gu.n_tiles[i], tpp);
-            wg_dn += ef::ffn_down_shared_wgs(d, gu.n_tiles[i], tpp, ksg);
+            wg_dn += ef::ffn_down_shared_wgs(d, gu.n_tiles[i], tpp, ksg_stream);
             continue;
         }
         wg_gu += c->q4 ? ef::ffn_gate_up_q4_wgs(gu.F[i], gu.n_tiles[i], tpp)
                        : ef::ffn_gate_up_wgs(gu.F[i], gu.n_tiles[i], tpp, ks);
-        wg_dn += c->q4 ? ef::ffn_down_q4_wgs(d, gu.n_tiles[i], tpp, ksg) : ef::ffn_down_wgs(d, gu.n_tiles[i], tpp, ksg);
+        wg_dn += c->q4 ? ef::ffn_down_q4_wgs(d, gu.n_tiles[i], tpp, ksg_stream)
+                       : ef::ffn_down_wgs(d, gu.n_tiles[i], tpp, ksg_stream);
     }
     gu.wg_start[n] = wg_gu;
     dn.wg_start[n] = wg_dn;
@@ -1029,9 +1031,9 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
     }
     {
         KernelTimer kt(c, s, EF_K_FFN_DOWN, b_dn);
-        if (shared) EF_HIP(c, ef::launch_ffn_down_shared(dn, wg_dn, tpp, occ, ksg, c->act, c->y, y_plane, d, s));
-        else if (c->q4) EF_HIP(c, ef::launch_ffn_down_q4(dn, wg_dn, tpp, ksg, c->act, c->y, y_plane, d, s));
-        else EF_HIP(c, ef::launch_ffn_down(dn, wg_dn, tpp, ksg, c->act, c->y, y_plane, d, s));
+        if (shared) EF_HIP(c, ef::launch_ffn_down_shared(dn, wg_dn, tpp, occ, ksg_stream, c->act, c->y, y_plane, d, s));
+        else if (c->q4) EF_HIP(c, ef::launch_ffn_down_q4(dn, wg_dn, tpp, ksg_stream, c->act, c->y, y_plane, d, s));
+        else EF_HIP(c, ef::launch_ffn_down(dn, wg_dn, tpp, ksg_stream, c->act, c->y, y_plane, d, s));
     }
     return EF_OK;
 }
@@ -1106,40 +1108,47 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         use_tiled = wg_up >= tune("EF_TUNE_TILED_MIN_UP", 1) && wg_dn >= tune("EF_TUNE_TILED_MIN_DOWN", 1);
         tiled_dn_wgs = wg_dn;
     }
-    int ksg = 1;
+    // K slices of the second half (one Y plane each, summed by the un-permute): the streamed launch and the tiled
+    // launch of the layer choose separately, each for its own workgroup count
+    int ksg = 1, ksg_tiled = 1;
     if (T > 0) {
         long long base_wgs = 0;
         int tmax = 1;
         for (int e = 0; e < E; ++e) tmax = std::max(tmax, (counts_host[e] + ef::kTile - 1) / ef::kTile);
         if (has_shared) tmax = std::max(tmax, (T + ef::kTile - 1) / ef::kTile);
         const int tpp = (tmax >= 3 && !c->q4) ? 4 : tmax >= 2 ? 2 : 1;
+        // workgroups of the streamed launch with one slice (groups that take the tiled kernels do not count)
         for (int e = 0; e < E; ++e)
             if (counts_host[e] > 0) {
                 const int nt = (counts_host[e] + ef::kTile - 1) / ef::kTile;
+                if (use_tiled && ef::ffn_tiled_ok(d, c->cfg.d_ff, nt) && nt >= tiled_min_routed()) continue;
                 base_wgs += c->q4 ? ef::ffn_down_q4_wgs(d, nt, tpp, 1)
                             : tpp == 4 ? ef::ffn_down_shared_wgs(d, nt, tpp, 1) : ef::ffn_down_wgs(d, nt, tpp, 1);
             }
-        if (has_shared)
+        if (has_shared && !(use_tiled && ef::ffn_tiled_ok(d, c->cfg.d_ff_shared, (T + ef::kTile - 1) / ef::kTile)))
             base_wgs += c->q4 ? ef::ffn_down_q4_wgs(d, (T + ef::kTile - 1) / ef::kTile, tpp, 1)
                         : tpp == 4 ? ef::ffn_down_shared_wgs(d, (T + ef::kTile - 1) / ef::kTile, tpp, 1)
                                    : ef::ffn_down_wgs(d, (T + ef::kTile - 1) / ef::kTile, tpp, 1);
-        const int want = tune("EF_TUNE_DOWN_WGS", 256);
+        // the LDS-shared kernels (passes of four tiles) run two workgroups per compute unit
+        const int want = tune("EF_TUNE_DOWN_WGS", (tpp == 4 && !c->q4) ? 512 : 256);
         const int nkb_min = std::min(c->cfg.d_ff, has_shared ? c->cfg.d_ff_shared : c->cfg.d_ff) / 16;
-        // a slice keeps >= 32 fragments per wave (bf16: four waves split it again) or >= 6 quads (4-bit)
-        const int units = c->q4 ? nkb_min / 4 / 6 : nkb_min / 4 / 32;
+        // a slice keeps >= 32 fragments per wave (bf16: four waves split it again), >= 6 quads (4-bit), or >= 8
+        // stages of four fragments (LDS-shared kernels: a wave walks the whole slice)
+        const int units = c->q4 ? nkb_min / 4 / 6 : tpp == 4 ? nkb_min / 4 / 8 : nkb_min / 4 / 32;
         while (ksg < 8 && base_wgs * ksg < want && units / (ksg * 2) >= 1 && y_plane * (ksg * 2) <= c->y_floats)
             ksg *= 2;
         if (use_tiled) {
-            // the tiled second half decides: slices until its 256 x 256 tiles fill the chip, each slice
-            // keeping at least 16 stages; the streamed groups of the layer write the same planes
-            ksg = 1;
-            while (ksg < 8 && tiled_dn_wgs * ksg < 256 && tiled_stages_min / (ksg * 2) >= 16 &&
-                   y_plane * (ksg * 2) <= c->y_floats)
-                ksg *= 2;
+            // the tiled second half: slices until its 256 x 256 tiles fill the chip, each slice keeping at least
+            // 16 stages
+            while (ksg_tiled < 8 && tiled_dn_wgs * ksg_tiled < 256 && tiled_stages_min / (ksg_tiled * 2) >= 16 &&
+                   y_plane * (ksg_tiled * 2) <= c->y_floats)
+                ksg_tiled *= 2;
+            if (tune("EF_TUNE_SPLIT_KSG", 1) == 0) ksg = ksg_tiled;   // one slice count for both launches
         }
-        int forced = tune("EF_TUNE_DOWN_KSG", ksg);
-        if (forced >= 1 && forced <= 8 && y_plane * forced <= c->y_floats) ksg = forced;
+        int forced = tune("EF_TUNE_DOWN_KSG", 0);
+        if (forced >= 1 && forced <= 8 && y_plane * forced <= c->y_floats) ksg = ksg_tiled = forced;
     }
+    ef::PlaneTable planes{};
 
     // classify the needed experts
     std::vector<PhaseGroup> ready, loading;
@@ -1253,7 +1262,7 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         if (with_shared && has_shared) g.push_back({-1, -1});
         if (!c->fake) {
             int r = launch_phase(c, layer, g, counts_host, offs_host, tile_start, act_off, shared_tile_start,
-                                 shared_act_off, T, ksg, y_plane, use_tiled, s);
+                                 shared_act_off, T, ksg, ksg_tiled, planes, y_plane, use_tiled, s);
             if (r) return r;
         }
         return mark_read(v);
@@ -1323,7 +1332,7 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
                 done = c->read_ring[c->read_next];
                 c->read_next = (c->read_next + 1) % c->read_ring.size();
             }
-            EF_HIP(c, ef::launch_combine(c->y, ksg, y_plane, topk_w, inv_perm, T, k, d,
+            EF_HIP(c, ef::launch_combine(c->y, planes, y_plane, topk_w, topk_ids, inv_perm, T, k, d,
                                          has_shared ? (long long)T * k : -1ll, out, done, s));
             if (done) {
                 for (int slot : read_slots) {

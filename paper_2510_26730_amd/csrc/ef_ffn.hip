@@ -489,11 +489,11 @@ hipError_t launch_ffn_down(const GroupTable &gt, int total_wgs, int tiles_per_pa
 }
 
 // ------------------------------------------------------------------------------------------
-// weighted un-permute: out[t] = sum_j w[t,j] * (sum over K-slice planes of Y[inv_perm[t*k+j]])
+// weighted un-permute: out[t] = sum_j w[t,j] * (sum over the K-slice planes of expert ids[t,j] of Y[inv_perm[t*k+j]])
 //                               (+ the dense shared FFN's row of token t)
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ Y, int ksg, long long y_plane,
-                                                      const float *__restrict__ w,
+__global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ Y, PlaneTable planes, long long y_plane,
+                                                      const float *__restrict__ w, const int32_t *__restrict__ ids,
                                                       const int32_t *__restrict__ inv_perm, int T, int k, int d,
                                                       long long shared_row0, float *__restrict__ out) {
     const int t = blockIdx.x;
@@ -503,9 +503,10 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
     for (int j = 0; j < k; ++j) {
         const int a = t * k + j;
         const float wj = w[a];
+        const int np = planes.routed[ids[a]];
         const float *row = Y + (size_t)inv_perm[a] * d + c;
         float4 y = *reinterpret_cast<const float4 *>(row);
-        for (int p = 1; p < ksg; ++p) {
+        for (int p = 1; p < np; ++p) {
             const float4 z = *reinterpret_cast<const float4 *>(row + (size_t)p * y_plane);
             y.x += z.x; y.y += z.y; y.z += z.z; y.w += z.w;
         }
@@ -514,7 +515,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
     if (shared_row0 >= 0) {
         const float *row = Y + (size_t)(shared_row0 + t) * d + c;
         float4 y = *reinterpret_cast<const float4 *>(row);
-        for (int p = 1; p < ksg; ++p) {
+        for (int p = 1; p < planes.shared; ++p) {
             const float4 z = *reinterpret_cast<const float4 *>(row + (size_t)p * y_plane);
             y.x += z.x; y.y += z.y; y.z += z.z; y.w += z.w;
         }
@@ -525,15 +526,16 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
 
 // `done` (may be null): an event that completes with this kernel.  It rides on the kernel's own completion
 // signal, which costs the stream nothing, where a separate event record behind the kernel costs 2-3 us.
-hipError_t launch_combine(const float *y, int ksg, long long y_plane, const float *w, const int32_t *inv_perm,
-                          int T, int k, int d, long long shared_row0, float *out, hipEvent_t done, hipStream_t s) {
+hipError_t launch_combine(const float *y, const PlaneTable &planes, long long y_plane, const float *w,
+                          const int32_t *ids, const int32_t *inv_perm, int T, int k, int d, long long shared_row0,
+                          float *out, hipEvent_t done, hipStream_t s) {
     if (T <= 0) return hipSuccess;
     if (done)
-        hipExtLaunchKernelGGL(combine_kernel, dim3(T, (d + 1023) / 1024), dim3(256), 0, s, nullptr, done, 0, y, ksg,
-                              y_plane, w, inv_perm, T, k, d, shared_row0, out);
+        hipExtLaunchKernelGGL(combine_kernel, dim3(T, (d + 1023) / 1024), dim3(256), 0, s, nullptr, done, 0, y, planes,
+                              y_plane, w, ids, inv_perm, T, k, d, shared_row0, out);
     else
-        hipLaunchKernelGGL(combine_kernel, dim3(T, (d + 1023) / 1024), dim3(256), 0, s, y, ksg, y_plane, w, inv_perm,
-                           T, k, d, shared_row0, out);
+        hipLaunchKernelGGL(combine_kernel, dim3(T, (d + 1023) / 1024), dim3(256), 0, s, y, planes, y_plane, w, ids,
+                           inv_perm, T, k, d, shared_row0, out);
     return hipGetLastError();
 }
 

@@ -97,8 +97,15 @@ hipError_t launch_ffn_gate_up(const GroupTable &gt, int total_wgs, int tiles_per
                               void *act, int d, hipStream_t s);
 hipError_t launch_ffn_down(const GroupTable &gt, int total_wgs, int tiles_per_pass, int ksg, const void *act,
                            float *y, long long y_plane, int d, hipStream_t s);
-hipError_t launch_combine(const float *y, int ksg, long long y_plane, const float *w, const int32_t *inv_perm,
-                          int T, int k, int d, long long shared_row0, float *out, hipEvent_t done, hipStream_t s);
+// K-slice planes of Y each expert's rows (and the shared FFN's) were written to: the streamed and the tiled launch
+// of a layer choose their slice counts separately
+struct PlaneTable {
+    uint8_t routed[kMaxE];
+    uint8_t shared;
+};
+hipError_t launch_combine(const float *y, const PlaneTable &planes, long long y_plane, const float *w,
+                          const int32_t *ids, const int32_t *inv_perm, int T, int k, int d, long long shared_row0,
+                          float *out, hipEvent_t done, hipStream_t s);
 
 // 4-bit expert weights (d and F multiples of 128): a workgroup of the first half takes four 32-row
 // blocks of F, one of the second half eight 32-column blocks of d and one of ksg K-slices
