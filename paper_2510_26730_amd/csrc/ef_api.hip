@@ -1094,6 +1094,7 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
     bool use_tiled = false;
     long long tiled_dn_wgs = 0;
     int tiled_stages_min = 1 << 30;   // fewest K stages (32 columns each) among the tiled groups
+    int tiled_stages_max = 0;         // ... and most
     if (T > 0 && (!c->q4 || c->q4_stage_slots > 0) && tune("EF_TUNE_TILED", 1) != 0) {
         long long wg_up = 0, wg_dn = 0;
         auto add = [&](int F, int cnt, bool routed) {
@@ -1102,6 +1103,7 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
             wg_up += ef::ffn_gate_up_tiled_wgs(F, nt);
             wg_dn += ef::ffn_down_tiled_wgs(d, nt);
             tiled_stages_min = std::min(tiled_stages_min, F / 32);
+            tiled_stages_max = std::max(tiled_stages_max, F / 32);
         };
         for (int e = 0; e < E; ++e) add(c->cfg.d_ff, counts_host[e], true);
         if (has_shared) add(c->cfg.d_ff_shared, T, false);
@@ -1140,7 +1142,7 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         if (use_tiled) {
             // the tiled second half: slices until its 256 x 256 tiles fill the chip, each slice keeping at least
             // 16 stages
-            while (ksg_tiled < 8 && tiled_dn_wgs * ksg_tiled < 256 && tiled_stages_min / (ksg_tiled * 2) >= 16 &&
+            while (ksg_tiled < 8 && tiled_dn_wgs * ksg_tiled < 256 && (tune("EF_TUNE_KSG_BY_MAX", 1) ? tiled_stages_max : tiled_stages_min) / (ksg_tiled * 2) >= 16 &&
                    y_plane * (ksg_tiled * 2) <= c->y_floats)
                 ksg_tiled *= 2;
             if (tune("EF_TUNE_SPLIT_KSG", 1) == 0) ksg = ksg_tiled;   // one slice count for both launches
