@@ -211,6 +211,34 @@ def test_drawn_shapes_full_layer(oracle_mod, cfg, T, beta):
         st.close()
 
 
+def test_shared_ffn_tiled_beside_streamed_routed_groups(oracle_mod):
+    """A batch whose shared FFN (10 token tiles, K = 1024) takes the tiled kernels with two K slices while the
+    routed experts (2-4 tiles, K = 128) stream with one: the un-permute sums a different number of planes per
+    expert.  Whole output against the oracle."""
+    cfg = shape("tiny", name="split_slices", d=256, F=128, F_shared=1024, T=300)
+    T = cfg.T
+    say(f"separate slice counts: d={cfg.d} F={cfg.F} Fs={cfg.F_shared} E={cfg.E} k={cfg.k} T={T}")
+    st = LayerStack(cfg, 1, slots_total=cfg.E, max_tokens=T, flags=ef.EF_FLAG_PROFILE)
+    try:
+        for e in range(cfg.E):
+            ef.ef_cache_swap_in(st.ctx, 0, e, 0, 0)
+        res = ef.ef_cache_query(st.ctx, 0, cfg.E)
+        h = synth.hidden(cfg, 2, T)
+        hd = dev_u16(h)
+        r = st.route(0, hd, T, 0.0)
+        got = to_np(r, T, cfg.k)
+        ora = oracle_mod.route(h, st.gates[0], st.biases[0], cfg.k, 0.0, res, renorm=cfg.renorm)
+        check_route(got, ora, cfg.E, cfg.k, cfg.renorm, oracle_mod=oracle_mod)
+        out = st.ffn(0, hd, T, r)
+        full = oracle_layer(oracle_mod, st, 0, h, 0.0, res, forced_ids=got["ids"])
+        e1, e2 = float_close(out, full["out"])
+        launches = dict(zip(ef.EF_KERNELS, ef.ef_get_stats(st.ctx)["kernel_launches"]))
+        say(f"  max abs {e1:.2e}, rel l2 {e2:.2e}, launches {launches}")
+        assert launches["ffn_down_tiled"] == 1 and launches["ffn_down"] == 1
+    finally:
+        st.close()
+
+
 def test_empty_batch(oracle_mod):
     cfg = synth.CONFIGS["tiny"]
     say("T=0")
