@@ -71,6 +71,10 @@ struct ef_ctx {
     float *st_w = nullptr;
     int32_t *meta_host = nullptr, *meta_dev = nullptr;
     int meta_seq = 0;
+    // side stream on which a phase's tiled launches run beside its streamed launches, and the fork / join events
+    hipStream_t side_stream = nullptr;
+    std::vector<hipEvent_t> fork_ring;
+    size_t fork_next = 0;
     // event rings
     std::vector<hipEvent_t> read_ring;
     size_t read_next = 0;
@@ -446,6 +450,8 @@ extern "C" int ef_destroy(ef_ctx *c) {
             if (s.ready) (void)hipEventDestroy(s.ready);
         }
         for (auto e : c->read_ring) (void)hipEventDestroy(e);
+        for (auto e : c->fork_ring) (void)hipEventDestroy(e);
+        if (c->side_stream) (void)hipStreamDestroy(c->side_stream);
         for (auto &p : c->stall_ring) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
         for (auto &p : c->layer_ring) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
         for (auto &p : c->prof_ring) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
@@ -591,6 +597,10 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
     }
     c->read_ring.resize(128);
     for (auto &ev : c->read_ring)
+        if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
+    if ((e = hipStreamCreateWithFlags(&c->side_stream, hipStreamNonBlocking)) != hipSuccess) return bail(e, "side stream");
+    c->fork_ring.resize(64);
+    for (auto &ev : c->fork_ring)
         if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
     c->stall_ring.resize(128);
     c->layer_ring.resize(128);
@@ -937,6 +947,7 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
             b_dn += wb * d * g.F[i] + 2.0 * g.count[i] * g.F[i] + 4.0 * g.count[i] * d;
         }
     };
+    hipEvent_t join = nullptr;   // set when this phase's tiled launches went to the side stream
     if (nb > 0) {
         ef::GroupTable bdn = big;
         int wg_up = 0, wg_dn = 0;
@@ -972,17 +983,35 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
             f_up += 4.0 * big.count[i] * d * big.F[i];   // two d x F products, 2 flops per multiply-add
             f_dn += 2.0 * big.count[i] * d * big.F[i];
         }
-        {
-            KernelTimer kt(c, s, EF_K_FFN_UP_TILED, b_up, f_up);   // 4-bit: the expansion is timed with the first half
-            if (c->q4) {
-                dq.n = nb;
-                EF_HIP(c, ef::launch_dequant_q4(dq, d, s));
-            }
-            EF_HIP(c, ef::launch_ffn_gate_up_tiled(big, wg_up, c->xp, c->act, d, c->q4, s));
+        // A phase with both kinds of groups runs its tiled launches on the side stream, beside the streamed ones:
+        // the two touch different groups (tiles of the packed tokens, activations, rows of Y), small tiled launches
+        // leave half of the compute units idle, and the streamed kernels are bound by HBM, not by compute units.
+        // Fork: the side stream waits for everything enqueued so far (the token packing, the previous layer's
+        // un-permute).  Join: the caller's stream waits for the side stream before anything after this phase.
+        hipStream_t ts = s;
+        if (n > 0 && c->side_stream && tune("EF_TUNE_OVERLAP", 1) != 0) {
+            hipEvent_t fork = c->fork_ring[c->fork_next];
+            c->fork_next = (c->fork_next + 1) % c->fork_ring.size();
+            EF_HIP(c, hipEventRecord(fork, s));
+            EF_HIP(c, hipStreamWaitEvent(c->side_stream, fork, 0));
+            ts = c->side_stream;
         }
         {
-            KernelTimer kt(c, s, EF_K_FFN_DOWN_TILED, b_dn, f_dn);
-            EF_HIP(c, ef::launch_ffn_down_tiled(bdn, wg_dn, ksg_tiled, c->act, c->y, y_plane, d, c->q4, s));
+            KernelTimer kt(c, ts, EF_K_FFN_UP_TILED, b_up, f_up);   // 4-bit: the expansion is timed with the first half
+            if (c->q4) {
+                dq.n = nb;
+                EF_HIP(c, ef::launch_dequant_q4(dq, d, ts));
+            }
+            EF_HIP(c, ef::launch_ffn_gate_up_tiled(big, wg_up, c->xp, c->act, d, c->q4, ts));
+        }
+        {
+            KernelTimer kt(c, ts, EF_K_FFN_DOWN_TILED, b_dn, f_dn);
+            EF_HIP(c, ef::launch_ffn_down_tiled(bdn, wg_dn, ksg_tiled, c->act, c->y, y_plane, d, c->q4, ts));
+        }
+        if (ts != s) {
+            join = c->fork_ring[c->fork_next];
+            c->fork_next = (c->fork_next + 1) % c->fork_ring.size();
+            EF_HIP(c, hipEventRecord(join, ts));
         }
     }
     if (n == 0) return EF_OK;
@@ -1035,6 +1064,7 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
         else if (c->q4) EF_HIP(c, ef::launch_ffn_down_q4(dn, wg_dn, tpp, ksg_stream, c->act, c->y, y_plane, d, s));
         else EF_HIP(c, ef::launch_ffn_down(dn, wg_dn, tpp, ksg_stream, c->act, c->y, y_plane, d, s));
     }
+    if (join) EF_HIP(c, hipStreamWaitEvent(s, join, 0));
     return EF_OK;
 }
 
