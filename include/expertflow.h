@@ -10,7 +10,9 @@
  * library owns the context, its HBM expert-slot pool, its copy stream, its
  * events and its scratch buffers.
  *
- * Asynchrony: ef_predict / ef_route / ef_moe_ffn only enqueue work on `stream`;
+ * Asynchrony: ef_predict / ef_route / ef_moe_ffn only enqueue work on `stream`
+ * (ef_moe_ffn may run part of a layer's kernels on a side stream of its own,
+ * forked from and joined back into `stream` by events inside the call);
  * outputs are valid once the caller has synchronised that stream.
  * ef_cache_swap_in enqueues a host-to-device copy on the library's own copy
  * stream and returns at once.
@@ -181,8 +183,8 @@ int ef_pack_expert(const uint16_t *W1, const uint16_t *W3, const uint16_t *W2,
 
 /* ---- context ---------------------------------------------------------------------------- */
 
-/* Allocates the slot pool (slots_total * ef_expert_bytes), scratch for max_tokens tokens, one copy
- * stream and the events.  With EF_FLAG_FAKE_COPY nothing touches the GPU. */
+/* Allocates the slot pool (slots_total * ef_expert_bytes), scratch for max_tokens tokens, the copy
+ * streams, one side stream for compute and the events.  With EF_FLAG_FAKE_COPY nothing touches the GPU. */
 int ef_create(const ef_config *cfg, ef_ctx **out);
 int ef_destroy(ef_ctx *ctx);
 const char *ef_last_error(ef_ctx *ctx);
