@@ -234,7 +234,7 @@ def test_shared_ffn_tiled_beside_streamed_routed_groups(oracle_mod):
         e1, e2 = float_close(out, full["out"])
         launches = dict(zip(ef.EF_KERNELS, ef.ef_get_stats(st.ctx)["kernel_launches"]))
         say(f"  max abs {e1:.2e}, rel l2 {e2:.2e}, launches {launches}")
-        assert launches["ffn_down_tiled"] == 1 and launches["ffn_down"] == 1
+        assert launches["ffn_down_tiled"] >= 1 and launches["ffn_down"] == 1   # shared FFN (+ routed groups of 10+ tiles)
     finally:
         st.close()
 
@@ -285,13 +285,17 @@ def test_outputs_do_not_depend_on_slots_or_phase_order(oracle_mod):
     assert np.array_equal(outs[0][1], outs[1][1]) and np.array_equal(outs[0][1], outs[2][1])
 
 
-@pytest.mark.parametrize("cfg_name,T,q4", [("tiny", 64, False), ("tiny", 7, False), ("tiny", 64, True), ("tiny", 300, True)])
+SHARED_TILED = shape("tiny", name="shared_tiled", d=256, F=128, F_shared=1024)   # shared FFN of 10 tiles at T = 300
+
+
+@pytest.mark.parametrize("cfg_name,T,q4", [("tiny", 64, False), ("tiny", 7, False), ("tiny", 64, True), ("tiny", 300, True),
+                                           (SHARED_TILED, 300, False), (SHARED_TILED, 40, False)])
 def test_layer_step_equals_separate_calls(cfg_name, T, q4):
     """The composite entry point (host-mapped hand-over, flag polling) gives bit-identical outputs,
     the same cache decisions and the same horizon as the separate entry points."""
     from paper_2510_26730_amd.runner import LayerLoop
-    cfg = synth.CONFIGS[cfg_name]
-    say(f"ef_layer_step vs separate calls, {cfg_name} T={T} 4-bit experts: {q4}")
+    cfg = synth.CONFIGS[cfg_name] if isinstance(cfg_name, str) else cfg_name
+    say(f"ef_layer_step vs separate calls, {cfg.name} T={T} 4-bit experts: {q4}")
     L = 3
     loops = [LayerLoop(cfg, L, T, cfg.slots_per_layer, beta=0.5, seed=1, fixed_estimates=True, q4=q4) for _ in range(2)]
     try:
