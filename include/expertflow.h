@@ -422,6 +422,50 @@ int ef_delta_drain(ef_delta_producer *p);
 int ef_delta_assemble(ef_delta_cache *c, const int32_t *token_ids, const int32_t *tok_off, int R, int layer,
                       int S, int H, int L, float gain, float *delta, int *n_hits);
 
+/*
+ * Inspection of the last ef_layer_step (tests, activation logging; cites no passage of the paper): synchronises
+ * `stream`, then copies the routing state that call left in library-owned device buffers into host arrays.
+ * Any pointer may be NULL.  topk_ids [T,k] i32, topk_w [T,k] f32, offsets [E+1] i32, perm / inv_perm [T*k] i32,
+ * pred_ids [H_eff,T,k] i32 and pred_hist [H_eff,E] i32 (the demand histograms as the host received them),
+ * with T and H_eff those of that call; *T_out / *H_eff_out (may be NULL) receive them.  EF_EINVAL before the
+ * first ef_layer_step.
+ */
+int ef_layer_step_fetch(ef_ctx *ctx, int32_t *topk_ids, float *topk_w, int32_t *offsets, int32_t *perm,
+                        int32_t *inv_perm, int32_t *pred_ids, int32_t *pred_hist, int *T_out, int *H_eff_out,
+                        void *stream);
+
+/*
+ * Launch-shape tuning: which kernel form a group takes and how launches are split.  For sweeps and for tests
+ * that force one kernel form; cites no passage of the paper.  No setting changes what is computed, only the
+ * order in which partial sums over K slices are added.  ef_create installs the defaults (the measured best);
+ * ef_set_tuning rejects values outside the ranges below with EF_EINVAL and changes nothing then.  "0 = auto"
+ * fields let the library choose per launch.  Nothing in the library reads environment variables.
+ */
+typedef struct ef_tuning {
+    int32_t tiled;                   /* 0/1: groups of many token tiles may take the matrix-core tiled kernels (1) */
+    int32_t tiled_min_tiles;         /* 8..4096: routed groups take them from this many 32-token tiles on (10) */
+    int32_t tiled_min_up_wgs;        /* >= 1: ... and only if the tiled first-half launch has this many workgroups (1) */
+    int32_t tiled_min_down_wgs;      /* >= 1: ... and the second-half launch this many (1) */
+    int32_t tiled_xcd_rotation;      /* 0/1: deal every group's weight-panel blocks from the least loaded XCD (1) */
+    int32_t overlap_tiled;           /* 0/1: a phase's tiled launches run on a side stream beside its streamed ones (1) */
+    int32_t sort_groups;             /* 0/1: groups with the most work first in a launch (1) */
+    int32_t passes_of_four;          /* 0/1: streamed groups of >= 3 token tiles take passes of four tiles (1) */
+    int32_t lds_shared;              /* 0/1: ... through the kernels whose waves share fragments in LDS (1) */
+    int32_t lds_shared_occupancy;    /* 1..2: workgroups per compute unit of those kernels (2) */
+    int32_t up_want_waves;           /* >= 1: the streamed first half splits K inside a workgroup below this many waves (768) */
+    int32_t up_k_slices;             /* 0 = auto, else 1, 2 or 4 */
+    int32_t down_want_wgs;           /* 0 = auto (256; 512 for the LDS-shared kernels), else >= 1: target of the K-slice split */
+    int32_t down_k_slices;           /* 0 = auto, else 1..8: K-slice planes of the second half (both launches) */
+    int32_t down_slices_by_longest_k; /* 0/1: the tiled second half sizes its slices by the group with the longest K (1) */
+    int32_t down_split_slice_counts; /* 0/1: the streamed and the tiled launch of a layer choose their slice counts separately (1) */
+    int32_t gate_k_split;            /* 0 = auto, else 1..16: workgroups sharing the K range of one (tile, gate group) */
+    int32_t gate_token_split;        /* 0/1: the gate's second step may split a tile's tokens over workgroups (1) */
+    int32_t gate_fused_finish;       /* 0/1: decode-sized batches fuse the gate's second step with the grouping (1) */
+    int32_t early_pack;              /* 0/1: ef_layer_step enqueues the token packing before the host has the counts (1) */
+} ef_tuning;
+int ef_get_tuning(ef_ctx *ctx, ef_tuning *out);
+int ef_set_tuning(ef_ctx *ctx, const ef_tuning *t);
+
 /* Statistics; synchronises outstanding timing events first (not for the hot loop). */
 int ef_get_stats(ef_ctx *ctx, ef_stats *out);
 int ef_reset_stats(ef_ctx *ctx);

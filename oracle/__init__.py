@@ -291,12 +291,12 @@ def route_from_ids(p, ids, E, renorm=True, routed_scale=1.0):
                 inv_perm=inv)
 
 
-def predict(h, gates, biases, k, beta=0.0, residents=None, delta=None, tok2req=None):
+def predict(h, gates, biases, k, beta=0.0, residents=None, delta=None, tok2req=None, return_scores=False):
     """Cross-layer prediction: the same h through the next H layers' gates.
 
     gates: list of H [E,d] arrays; biases: list of H [E] arrays (or None);
     residents: list of H [E] flags (or None); delta: [R,H,E] or None.
-    Returns ids [H,T,k], hist [H,E], gap [H,T].
+    Returns ids [H,T,k], hist [H,E], gap [H,T] (and the selection scores [H,T,E] on request).
     """
     H = len(gates)
     T = h.shape[0]
@@ -304,12 +304,16 @@ def predict(h, gates, biases, k, beta=0.0, residents=None, delta=None, tok2req=N
     ids = np.empty((H, T, k), dtype=np.int32)
     hist = np.empty((H, E), dtype=np.int32)
     gap = np.empty((H, T), dtype=np.float64)
+    sc = np.empty((H, T, E), dtype=np.float64)
     for j in range(H):
         z = gate_logits(h, gates[j], None if biases is None else biases[j])
         dj = None if delta is None else np.ascontiguousarray(delta[:, j, :])
         s = scores(z, beta, None if residents is None else residents[j], dj, tok2req)
         ids[j], gap[j] = topk(s, k)
         hist[j] = histogram(ids[j], E)
+        sc[j] = s
+    if return_scores:
+        return ids, hist, gap, sc
     return ids, hist, gap
 
 

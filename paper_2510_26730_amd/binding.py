@@ -30,7 +30,7 @@ EXPORTS = [
     "ef_strerror", "ef_expert_bytes", "ef_pack_expert", "ef_expert_bytes_q4", "ef_pack_expert_q4", "ef_create", "ef_destroy", "ef_last_error",
     "ef_register_layer", "ef_predict", "ef_route", "ef_route_predict", "ef_moe_ffn", "ef_layer_step", "ef_cache_swap_in", "ef_cache_query",
     "ef_choose_horizon", "ef_token_dist", "ef_get_stats", "ef_reset_stats", "ef_set_profile", "ef_set_profile_sampling",
-    "ef_fake_advance_time",
+    "ef_fake_advance_time", "ef_layer_step_fetch", "ef_get_tuning", "ef_set_tuning",
     "ef_forest_create", "ef_forest_destroy", "ef_delta_features", "ef_forest_fit", "ef_forest_predict",
     "ef_forest_tree_size", "ef_forest_tree_export", "ef_forest_bit_accuracy", "ef_delta_from_activation",
     "ef_delta_cache_create", "ef_delta_cache_destroy", "ef_delta_cache_put", "ef_delta_cache_get",
@@ -68,6 +68,14 @@ class ef_stats(C.Structure):
             v = getattr(self, n)
             out[n] = list(v) if hasattr(v, "__len__") else v
         return out
+
+
+class ef_tuning(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "tiled", "tiled_min_tiles", "tiled_min_up_wgs", "tiled_min_down_wgs", "tiled_xcd_rotation", "overlap_tiled",
+        "sort_groups", "passes_of_four", "lds_shared", "lds_shared_occupancy", "up_want_waves", "up_k_slices",
+        "down_want_wgs", "down_k_slices", "down_slices_by_longest_k", "down_split_slice_counts", "gate_k_split",
+        "gate_token_split", "gate_fused_finish", "early_pack")]
 
 
 class ef_forest_config(C.Structure):
@@ -120,6 +128,9 @@ def lib():
         L.ef_set_profile.argtypes = [vp, C.c_uint]
         L.ef_set_profile_sampling.argtypes = [vp, i32]
         L.ef_fake_advance_time.argtypes = [vp, C.c_double]
+        L.ef_layer_step_fetch.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.POINTER(i32), C.POINTER(i32), vp]
+        L.ef_get_tuning.argtypes = [vp, C.POINTER(ef_tuning)]
+        L.ef_set_tuning.argtypes = [vp, C.POINTER(ef_tuning)]
         ll = C.c_longlong
         L.ef_forest_create.argtypes = [C.POINTER(ef_forest_config), C.POINTER(vp)]
         L.ef_forest_destroy.argtypes = [vp]
@@ -284,6 +295,42 @@ def ef_layer_step(ctx, layer, hidden, T, beta, H, delta, tok2req, out, counts_ho
     _check(ctx, lib().ef_layer_step(ctx, layer, _ptr(hidden), T, beta, H, _ptr(delta), _ptr(tok2req), _ptr(out),
                                     C.byref(hn), _ptr(counts_host), _stream(stream)))
     return hn.value
+
+
+def ef_layer_step_fetch(ctx, T, k, E, H_max=EF_MAX_HORIZON, stream=None):
+    """Routing state the last ef_layer_step left in the library's buffers, as numpy arrays:
+    dict(ids [T,k], w [T,k], offsets [E+1], perm, inv_perm [T*k], pred_ids [H_eff,T,k], pred_hist [H_eff,E])."""
+    n = T * k
+    o = dict(ids=np.empty(n, np.int32), w=np.empty(n, np.float32), offsets=np.empty(E + 1, np.int32),
+             perm=np.empty(n, np.int32), inv_perm=np.empty(n, np.int32),
+             pred_ids=np.empty(H_max * n, np.int32), pred_hist=np.empty(H_max * E, np.int32))
+    t_out, he = C.c_int(0), C.c_int(0)
+    _check(ctx, lib().ef_layer_step_fetch(ctx, _ptr(o["ids"]), _ptr(o["w"]), _ptr(o["offsets"]), _ptr(o["perm"]),
+                                          _ptr(o["inv_perm"]), _ptr(o["pred_ids"]), _ptr(o["pred_hist"]),
+                                          C.byref(t_out), C.byref(he), _stream(stream)))
+    assert t_out.value == T, (t_out.value, T)
+    H = he.value
+    o["ids"], o["w"] = o["ids"].reshape(T, k), o["w"].reshape(T, k)
+    o["pred_ids"] = o["pred_ids"][:H * n].reshape(H, T, k)
+    o["pred_hist"] = o["pred_hist"][:H * E].reshape(H, E)
+    return o
+
+
+def ef_get_tuning(ctx):
+    t = ef_tuning()
+    _check(ctx, lib().ef_get_tuning(ctx, C.byref(t)))
+    return {n: getattr(t, n) for n, _ in t._fields_}
+
+
+def ef_set_tuning(ctx, **kw):
+    """Change the named fields of the context's launch tuning (the others keep their values)."""
+    t = ef_tuning()
+    _check(ctx, lib().ef_get_tuning(ctx, C.byref(t)))
+    for name, v in kw.items():
+        if name not in dict(t._fields_):
+            raise KeyError(name)
+        setattr(t, name, int(v))
+    return _check(ctx, lib().ef_set_tuning(ctx, C.byref(t)))
 
 
 def ef_token_dist(ctx, hidden, T, tok_dist, dist, stream=None):

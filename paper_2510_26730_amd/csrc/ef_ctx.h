@@ -1,0 +1,158 @@
+// The context behind the C ABI and the helpers its three translation units share:
+//   ef_api.hip      the ABI's utilities, context life cycle, statistics, tuning, the composite layer step
+//   ef_runtime.hip  expert cache runtime: slots, copy queue and streams, completion polling, estimators,
+//                   horizon controller
+//   ef_plan.hip     launch planner: gate / grouping launches, the phases of the grouped FFN
+// Declarations and argument contracts of the ABI itself are in include/expertflow.h.
+#pragma once
+#include "../../include/expertflow.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <deque>
+#include <string>
+#include <vector>
+
+#include "ef_cache.h"
+#include "ef_kernels.h"
+
+struct EfLayerReg {
+    const uint16_t *gate_w = nullptr;
+    const float *gate_b = nullptr;
+    const char *experts = nullptr;
+    const void *shared_blob = nullptr;
+    bool set = false;
+};
+
+struct EfSlotDev {
+    hipEvent_t copy_start = nullptr, ready = nullptr;
+    hipEvent_t last_read = nullptr;   // borrowed from the read-event ring (may be null)
+    bool copy_pending = false;        // a copy was enqueued and not yet seen complete
+    double fake_ready_at = 0.0;       // fake-copy contexts: completion time of the copy
+    size_t copy_bytes = 0;
+};
+
+struct EfEventPair {
+    hipEvent_t a, b;
+};
+
+struct ef_ctx {
+    ef_config cfg{};
+    ef_tuning tune{};
+    size_t expert_bytes = 0;
+    bool fake = false;
+    std::vector<EfLayerReg> layers;
+    ef::ExpertCache *cache = nullptr;
+    char *pool = nullptr;
+    std::vector<EfSlotDev> slots;
+    hipStream_t copy_stream[2] = {nullptr, nullptr};  // [0] prefetch, [1] miss
+    // scratch
+    int32_t *blockcounts = nullptr, *blockbase = nullptr;
+    void *xp = nullptr, *act = nullptr;
+    float *gate_part = nullptr;      // partial logits of K-split gate launches (small batches)
+    bool q4 = false;                 // routed experts are 4-bit blobs
+    char *q4_stage = nullptr;        // 16-bit copies of the 4-bit experts that go through the tiled kernels in a phase
+    int q4_stage_slots = 0;          // how many such copies fit (as many groups as can reach the tiled size at once)
+    size_t q4_stage_bytes = 0;       // bytes of one copy (the larger of routed and shared FFN)
+    bool prepacked = false;          // ef_layer_step already enqueued the token packing of the coming ef_moe_ffn
+    size_t gate_part_floats = 0;
+    float *y = nullptr;
+    long long y_floats = 0;          // capacity of y: several K-slice planes when the batch is small
+    int max_tiles = 0;
+    // buffers of ef_layer_step (library-owned routing state and the host-mapped hand-over area)
+    int32_t *st_ids = nullptr, *st_counts = nullptr, *st_offsets = nullptr, *st_perm = nullptr,
+            *st_inv = nullptr, *st_pred_ids = nullptr, *st_pred_hist = nullptr;
+    float *st_w = nullptr;
+    int32_t *meta_host = nullptr, *meta_dev = nullptr;
+    long long meta_seq = 0;
+    // what the last ef_layer_step saw (ef_layer_step_fetch)
+    int last_T = 0, last_He = 0;
+    int32_t last_hist[EF_MAX_HORIZON * EF_MAX_EXPERTS] = {};
+    // side stream on which a phase's tiled launches run beside its streamed launches, and the fork / join events
+    hipStream_t side_stream = nullptr;
+    std::vector<hipEvent_t> fork_ring;
+    size_t fork_next = 0;
+    // event rings
+    std::vector<hipEvent_t> read_ring;
+    size_t read_next = 0;
+    std::vector<EfEventPair> stall_ring, layer_ring;
+    size_t stall_next = 0, layer_next = 0;
+    std::deque<EfEventPair> stall_pending, layer_pending;
+    struct ProfItem { EfEventPair p; int kind; double bytes; double flops; };
+    std::vector<EfEventPair> prof_ring;
+    size_t prof_next = 0;
+    std::deque<ProfItem> prof_pending;
+    unsigned profile_mask = 0;       // bit per kernel kind that is bracketed with events
+    int profile_every = 1;           // bracket every n-th launch of a selected kernel kind
+    long long profile_seen[EF_K_COUNT] = {};
+    bool layer_open = false;
+    long long layer_calls = 0;       // layers started (every kLayerTimerEvery-th is timed)
+    EfEventPair layer_cur{nullptr, nullptr};
+    // estimators and feedback
+    double bw_Bps = 50e9, layer_s = 200e-6;
+    int horizon = 1, fb_adjust = 0;
+    int stall_counter = 0, overfetch_counter = 0;
+    ef_stats st{};
+    // fake clock
+    double fake_now = 0.0, fake_engine_free[2] = {0.0, 0.0};
+    std::string err;
+};
+
+namespace efi {
+
+// Every kLayerTimerEvery-th layer is bracketed with events for the T_l estimate: an event record between two
+// kernels costs the stream a bubble of 2-3 us, and the estimate is a moving average anyway.
+constexpr long long kLayerTimerEvery = 4;
+
+int fail(ef_ctx *ctx, int code, const char *fmt, ...) __attribute__((format(printf, 3, 4)));
+const char *thread_error();
+void set_thread_error(const std::string &s);
+
+#define EF_HIP(ctx, call)                                                                            \
+    do {                                                                                             \
+        hipError_t _e = (call);                                                                      \
+        if (_e != hipSuccess)                                                                        \
+            return efi::fail(ctx, EF_EHIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(_e),   \
+                             __FILE__, __LINE__);                                                    \
+    } while (0)
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+void tuning_defaults(ef_tuning *t);
+
+// ---- cache runtime (ef_runtime.hip) ---------------------------------------------------------------
+void poll_copy(ef_ctx *c, int slot);
+void poll_all_copies(ef_ctx *c);
+void poll_pairs(ef_ctx *c, bool wait);
+void poll_prof(ef_ctx *c, bool wait);
+EfEventPair next_pair(std::vector<EfEventPair> &ring, size_t &next, std::deque<EfEventPair> &pending);
+uint64_t resident_mask(ef_ctx *c, int layer);
+int check_ctx_layer(ef_ctx *c, int layer);
+// Make (layer, expert) resident; *loaded (may be null) tells whether a copy was started.
+int swap_in_impl(ef_ctx *c, int layer, int expert, int priority, int due_in, int *slot_out, bool *loaded);
+
+// Brackets one kernel launch with events on the launch stream when profiling is on.
+struct KernelTimer {
+    ef_ctx *c;
+    hipStream_t s;
+    int kind;
+    double bytes, flops;
+    EfEventPair p{nullptr, nullptr};
+    bool on;
+    KernelTimer(ef_ctx *ctx, hipStream_t st, int k, double b, double f = 0.0);
+    ~KernelTimer();
+};
+
+// ---- launch planner (ef_plan.hip) -----------------------------------------------------------------
+extern const ef::GroupExport kNoExport;
+// One pass over `hidden`: optionally the current layer's own gate (routing outputs and grouping)
+// and the gates of the next He layers (prediction outputs).  Wide launches are split over the gates.
+int run_gates(ef_ctx *c, int layer, const void *hidden, int T, float beta, bool do_route, int He, int H_stride,
+              const float *delta, const int32_t *tok2req, int32_t *topk_ids, float *topk_w, int32_t *counts,
+              int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *pred_ids, int32_t *pred_hist,
+              const ef::GroupExport &ex, hipStream_t s);
+int check_predict_args(ef_ctx *c, int layer, int T, int H, int *He_out, const char *who);
+int open_layer_timer(ef_ctx *c, hipStream_t s);
+
+}  // namespace efi

@@ -53,7 +53,8 @@ struct GroupTable {
 };
 
 // Optional hand-over of counts and predicted histograms to the host (host-mapped memory): every word is
-// (sequence tag << 24) | value, value < 2^24.
+// (tag << 24) | value, value < 2^24, tag = `seq` in 0..254 (the caller's sequence number modulo 255; the host
+// marks words it has consumed, and the fresh buffer, with tag 255, which no call carries).
 constexpr int kMetaHist = kMaxE;                          // hist starts after the E counts
 constexpr int kMetaInts = kMaxE + (kMaxGates - 1) * kMaxE;
 constexpr int kMetaValueBits = 24;

@@ -528,9 +528,9 @@ __device__ __forceinline__ void scatter_tile(const int32_t *__restrict__ ids, in
 }
 
 // Hand the per-expert counts and the predicted demand histograms to the host through host-mapped
-// memory.  Every word carries the call's sequence tag in its top 8 bits (values are below 2^24), and
-// the host polls until all the words it expects show the tag: no fence and no separate flag, which
-// would cost the kernel a system-scope fence of about 5 us.
+// memory.  Every word carries the call's tag (0..254) in its top 8 bits (values are below 2^24), and
+// the host polls until all the words it expects show the tag, then overwrites them with tag 255: no
+// fence and no separate flag, which would cost the kernel a system-scope fence of about 5 us.
 __device__ __forceinline__ void export_meta(const GroupExport &ex, const int *total, int E) {
     if (!ex.host_meta) return;  // uniform
     const int tag = (int)((unsigned)(ex.seq & 0xFF) << 24);

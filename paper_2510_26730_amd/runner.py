@@ -30,7 +30,7 @@ class LayerLoop:
     def __init__(self, cfg: synth.MoEShape, n_layers: int, T: int, slots_per_layer: int,
                  pool_slots: int | None = None, store_layers: int = 2, h_max: int = 4, beta: float = 0.0,
                  profile: bool = False, all_resident: bool = False, seed: int = 0,
-                 fixed_estimates: bool = False, q4: bool = False):
+                 fixed_estimates: bool = False, q4: bool = False, **create_kw):
         self.cfg, self.L, self.T, self.beta = cfg, n_layers, T, beta
         E, k, d = cfg.E, cfg.k, cfg.d
         dev = "cuda"
@@ -41,7 +41,7 @@ class LayerLoop:
                                 d_ff_shared=cfg.F_shared, slots_total=slots_total,
                                 slots_per_layer_max=0 if all_resident or pool_slots is not None else slots_per_layer,
                                 max_tokens=T, h_max=h_max, renorm_topk=int(cfg.renorm), flags=flags,
-                                weight_bits=4 if q4 else 0)
+                                weight_bits=4 if q4 else 0, **create_kw)
         self.q4 = q4
         self.es = ef.ef_expert_bytes_q4(d, cfg.F) if q4 else ef.ef_expert_bytes(d, cfg.F)
         g = torch.Generator(device=dev)

@@ -35,23 +35,34 @@ class LayerStack:
         self.es = ef.ef_expert_bytes_q4(cfg.d, cfg.F) if q4 else ef.ef_expert_bytes(cfg.d, cfg.F)
         pack = ef.ef_pack_expert_q4 if q4 else ef.ef_pack_expert
         self._keep = []
+        packed = {}    # layers without expert weights of their own register the packed store of the first layer that has
         for l in range(n_layers):
             gw, gb = dev_u16(self.gates[l]), torch.from_numpy(self.biases[l]).cuda()
             src = l if l in self.experts else self.expert_layers[0]
-            store = torch.empty(cfg.E * self.es, dtype=torch.uint8, pin_memory=True)
-            sv = store.numpy()
-            for e in range(cfg.E):
-                pack(*self.experts[src][e], blob=sv[e * self.es:(e + 1) * self.es])
-            sh = None
-            if cfg.F_shared:
-                if q4:
-                    sb = np.empty(ef.ef_expert_bytes_q4(cfg.d, cfg.F_shared), dtype=np.uint8)
-                    ef.ef_pack_expert_q4(*self.shared[src], blob=sb)
-                    sh = torch.from_numpy(sb).cuda()
-                else:
-                    sh = torch.from_numpy(ef.ef_pack_expert(*self.shared[src])).cuda()
+            if src not in packed:
+                store = torch.empty(cfg.E * self.es, dtype=torch.uint8, pin_memory=True)
+                sv = store.numpy()
+                for e in range(cfg.E):
+                    pack(*self.experts[src][e], blob=sv[e * self.es:(e + 1) * self.es])
+                sh = None
+                if cfg.F_shared:
+                    if q4:
+                        sb = np.empty(ef.ef_expert_bytes_q4(cfg.d, cfg.F_shared), dtype=np.uint8)
+                        ef.ef_pack_expert_q4(*self.shared[src], blob=sb)
+                        sh = torch.from_numpy(sb).cuda()
+                    else:
+                        sh = torch.from_numpy(ef.ef_pack_expert(*self.shared[src])).cuda()
+                packed[src] = (store, sh)
+            store, sh = packed[src]
             ef.ef_register_layer(self.ctx, l, gw, gb, store, sh)
             self._keep += [gw, gb, store, sh]
+
+    def experts_of(self, layer):
+        """Row-major expert weights the oracle uses for `layer` (its own, or those of the layer it shares a store with)."""
+        return self.experts[layer if layer in self.experts else self.expert_layers[0]]
+
+    def shared_of(self, layer):
+        return self.shared.get(layer if layer in self.experts else self.expert_layers[0]) if self.cfg.F_shared else None
 
     def close(self):
         torch.cuda.synchronize()
@@ -119,6 +130,16 @@ def check_route(got, ora, E, k, renorm, routed_scale=1.0, oracle_mod=None):
         assert np.array_equal(got[name], forced[name]), name
     assert np.max(np.abs(got["w"] - forced["w"])) < 1e-5
     return forced, int(tie.sum())
+
+
+def check_ids_valid(ids, s, gap, k):
+    """Expert ids [T,k] against oracle scores s [T,E] and gaps [T]: equal to the oracle's choice outside
+    near-ties (the caller checks that); inside a near-tie a valid choice: k distinct ids in ascending
+    order, each scoring within the tie gap of the k-th best score."""
+    for t in np.nonzero(gap < TIE_GAP)[0]:
+        kth = np.sort(s[t])[::-1][k - 1]
+        assert np.all(s[t][ids[t]] >= kth - TIE_GAP), t
+        assert len(set(ids[t].tolist())) == k and np.all(np.diff(ids[t]) > 0), t
 
 
 def float_close(got, ref, max_abs=2e-2, rel_l2=1e-2):

@@ -308,3 +308,28 @@ def test_pack_expert_q4_layout():
     assert np.array_equal(sa[:, :, 1, :].transpose(0, 2, 1).reshape(F, d // 128), s3)
     sb = blob[off + d * F // 32:].view(np.uint16).reshape(d // 32, F // 128, 32)
     assert np.array_equal(sb.transpose(0, 2, 1).reshape(d, F // 128), s2)
+
+
+def test_tuning_defaults_and_validation():
+    """The launch tuning lives in the context: defaults after ef_create, out-of-range values rejected
+    without changing anything, and no environment variable steers the library."""
+    ctx = fake_ctx()
+    try:
+        t = ef.ef_get_tuning(ctx)
+        assert t["tiled"] == 1 and t["tiled_min_tiles"] == 10 and t["lds_shared_occupancy"] == 2
+        assert t["up_want_waves"] == 768 and t["gate_k_split"] == 0 and t["early_pack"] == 1
+        ef.ef_set_tuning(ctx, tiled=0, down_k_slices=4, up_k_slices=2)
+        t2 = ef.ef_get_tuning(ctx)
+        assert (t2["tiled"], t2["down_k_slices"], t2["up_k_slices"]) == (0, 4, 2)
+        for bad in (dict(tiled=2), dict(tiled_min_tiles=7), dict(up_k_slices=3), dict(down_k_slices=9),
+                    dict(gate_k_split=17), dict(lds_shared_occupancy=3), dict(up_want_waves=0),
+                    dict(tiled_min_up_wgs=0), dict(early_pack=-1)):
+            with pytest.raises(ef.EfError) as ei:
+                ef.ef_set_tuning(ctx, **bad)
+            assert ei.value.code == ef.EF_EINVAL
+            assert ef.ef_get_tuning(ctx) == t2
+    finally:
+        ef.ef_destroy(ctx)
+    src_dir = os.path.join(ROOT, "paper_2510_26730_amd", "csrc")
+    for name in os.listdir(src_dir):
+        assert "getenv" not in open(os.path.join(src_dir, name)).read(), name

@@ -81,11 +81,12 @@ def test_tiny_predict_with_delta_and_residency(oracle_mod):
         for beta, dl, tr in [(0.0, None, None), (0.5, delta, t2r), (0.5, delta, None)]:
             he, ids, hist = st.predict(0, dev_u16(h), cfg.T, H, beta, dl, tr)
             assert he == H
-            oids, ohist, ogap = oracle_mod.predict(h, st.gates[1:3], st.biases[1:3], cfg.k, beta, residents,
-                                                   dl, tr)
+            oids, ohist, ogap, osc = oracle_mod.predict(h, st.gates[1:3], st.biases[1:3], cfg.k, beta, residents,
+                                                        dl, tr, return_scores=True)
             tie = ogap < helpers.TIE_GAP
             assert np.array_equal(ids[~tie], oids[~tie])
             for j in range(H):
+                helpers.check_ids_valid(ids[j], osc[j], ogap[j], cfg.k)    # inside a near-tie: a valid choice
                 assert np.array_equal(hist[j], oracle_mod.histogram(ids[j], cfg.E))
                 assert hist[j].sum() == cfg.T * cfg.k
             if not tie.any():
@@ -134,10 +135,13 @@ def test_fused_route_predict_equals_separate_calls(oracle_mod, cfg, T, H):
         assert np.array_equal(fhist.cpu().numpy().reshape(H, cfg.E), phist)
         # and the predictions themselves against the oracle
         residents = [ef.ef_cache_query(st.ctx, 1 + j, cfg.E) for j in range(H)]
-        oids, ohist, ogap = oracle_mod.predict(h, st.gates[1:1 + H], st.biases[1:1 + H], cfg.k, beta, residents,
-                                               delta, t2r)
+        oids, ohist, ogap, osc = oracle_mod.predict(h, st.gates[1:1 + H], st.biases[1:1 + H], cfg.k, beta, residents,
+                                                    delta, t2r, return_scores=True)
         tie = ogap < helpers.TIE_GAP
         assert np.array_equal(pids[~tie], oids[~tie])
+        for j in range(H):
+            helpers.check_ids_valid(pids[j], osc[j], ogap[j], cfg.k)
+            assert np.array_equal(phist[j], oracle_mod.histogram(pids[j], cfg.E))
     finally:
         st.close()
 
@@ -374,7 +378,7 @@ def test_full_size_mixtral_decode_layer(oracle_mod):
 
 
 @pytest.mark.parametrize("T,H", [(64, 3), (33, 1), (1, 2)])
-def test_decode_gate_second_step_fused_with_grouping_equals_separate_kernels(monkeypatch, T, H):
+def test_decode_gate_second_step_fused_with_grouping_equals_separate_kernels(T, H):
     """Decode-sized batches of the headline shape take the K-split gate followed by ONE workgroup that sums the
     partial logits, runs the per-token epilogue and groups the tokens; with the fusion switched off the same
     partial logits go through the separate second-step and grouping kernels.  Same arithmetic in the same
@@ -384,10 +388,10 @@ def test_decode_gate_second_step_fused_with_grouping_equals_separate_kernels(mon
     say(f"decode gate paths: T={T} H={H}")
     L = H + 1
     outs = []
-    for fused in ("1", "0"):
-        monkeypatch.setenv("EF_TUNE_FUSED_FINISH", fused)
+    for fused in (1, 0):
         st = LayerStack(cfg, L, slots_total=cfg.E, max_tokens=64, expert_layers=[0], h_max=H)
         try:
+            ef.ef_set_tuning(st.ctx, gate_fused_finish=fused)
             for l in range(L):
                 for e in np.nonzero(synth.residency(cfg, l, n_resident=2, most_popular=False))[0]:
                     ef.ef_cache_swap_in(st.ctx, l, int(e), 0, l)
@@ -412,16 +416,16 @@ def test_decode_gate_second_step_fused_with_grouping_equals_separate_kernels(mon
 
 
 @pytest.mark.parametrize("force_tiled", [True, False])
-def test_full_size_qwen_mixed_batch(oracle_mod, monkeypatch, force_tiled):
+def test_full_size_qwen_mixed_batch(oracle_mod, force_tiled):
     """T = 640 with a shared expert of 20 token tiles: through the matrix-core tiled kernels (the
     default for groups of at least 8 tiles) and, with the library's workgroup threshold raised,
     through the weight-streaming kernels in several passes."""
     cfg = synth.CONFIGS["qwen15_moe"]
-    if not force_tiled:
-        monkeypatch.setenv("EF_TUNE_TILED_MIN_UP", "1000000")
     say(f"full size: Qwen1.5-MoE-shaped layer, T=640, shared expert, tiled kernels forced: {force_tiled}")
     st = LayerStack(cfg, 1, slots_total=cfg.E, max_tokens=640)
     try:
+        if not force_tiled:
+            ef.ef_set_tuning(st.ctx, tiled_min_up_wgs=1000000)
         res = synth.residency(cfg, 0)
         for e in np.nonzero(res)[0]:
             ef.ef_cache_swap_in(st.ctx, 0, int(e), 0, 0)
@@ -431,19 +435,19 @@ def test_full_size_qwen_mixed_batch(oracle_mod, monkeypatch, force_tiled):
 
 
 @pytest.mark.parametrize("streamed_form", ["shared4", "plain4", "plain2"])
-def test_full_size_deepseek_prefill(oracle_mod, monkeypatch, streamed_form):
+def test_full_size_deepseek_prefill(oracle_mod, streamed_form):
     """DeepSeek-V2-Lite-shaped layer at its three batch shapes: 32 decode tokens, 1024 prefill tokens and
     the mixed 1056 (shared experts through the tiled kernels from 256 tokens on, routed experts
     streamed).  The routed experts of the larger batches hold 3-7 token tiles: by default they take passes of
     four tiles through the kernels that share fragments in LDS; the other two forms (plain kernels with
-    passes of four, or of two tiles) are forced through the library's tuning variables."""
-    if streamed_form != "shared4":
-        monkeypatch.setenv("EF_TUNE_SHARED", "0")
-    if streamed_form == "plain2":
-        monkeypatch.setenv("EF_TUNE_TPP4", "0")
+    passes of four, or of two tiles) are forced through ef_set_tuning."""
     cfg = synth.CONFIGS["deepseek_v2_lite"]
     st = LayerStack(cfg, 1, slots_total=cfg.E, max_tokens=1056)
     try:
+        if streamed_form != "shared4":
+            ef.ef_set_tuning(st.ctx, lds_shared=0)
+        if streamed_form == "plain2":
+            ef.ef_set_tuning(st.ctx, passes_of_four=0)
         res = synth.residency(cfg, 0)
         for e in np.nonzero(res)[0]:
             ef.ef_cache_swap_in(st.ctx, 0, int(e), 0, 0)

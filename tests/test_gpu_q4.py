@@ -112,15 +112,15 @@ def test_q4_full_size_mixtral_decode(oracle_mod):
     (dict(d=512, F=384), 900, False),            # the same batch with the tiled kernels switched off
     (dict(d=384, F=256), 1500, True),            # d not a multiple of 256: stays on the streaming kernels
 ])
-def test_q4_large_groups_through_tiled_kernels(oracle_mod, monkeypatch, kw, T, tiled):
+def test_q4_large_groups_through_tiled_kernels(oracle_mod, kw, T, tiled):
     """Groups of 8 token tiles or more: the 4-bit blobs are expanded to fp16 blobs and go through the
     matrix-core tiled kernels; smaller groups of the same layer keep the streaming kernels."""
     cfg = q4_shape("tiny", name="tiny_q4_prefill", **kw)
-    if not tiled:
-        monkeypatch.setenv("EF_TUNE_TILED", "0")
     say(f"q4 large groups d={cfg.d} F={cfg.F} E={cfg.E} k={cfg.k} T={T} tiled={tiled}")
     st = LayerStack(cfg, 1, slots_total=cfg.E, max_tokens=T, q4=True, flags=ef.EF_FLAG_PROFILE)
     try:
+        if not tiled:
+            ef.ef_set_tuning(st.ctx, tiled=0)
         for e in range(cfg.E):
             ef.ef_cache_swap_in(st.ctx, 0, e, 0, 0)
         res = ef.ef_cache_query(st.ctx, 0, cfg.E)
