@@ -27,16 +27,23 @@
  * W3 [F,d] up, W2 [d,F] down, bf16) is stored as ef_expert_bytes(d,F) =
  * 3*d*F*2 bytes of 1 KiB "fragments".  A fragment holds a 32-row x 16-column
  * block of a row-major matrix M in matrix-core operand order: 64 lanes x 8
- * bf16, lane l = 32*g + i (g in {0,1}, i in 0..31) holds
+ * 16-bit numbers, lane l = 32*g + i (g in {0,1}, i in 0..31) holds
  *   natural order : M[r0 + i][c0 + 8*g + t],              t = 0..7
  *   paired order  : M[r0 + i][c0 + 8*(t/4) + 4*g + t%4],   t = 0..7
  * Section A, for rb in 0..F/32-1: d/16 natural-order fragments of W1 rows
  * [32rb, 32rb+32) (c0 = 0, 16, ...), then the same for W3.  Section B, at byte
  * 2*d*F*2, for cb in 0..d/32-1: F/16 paired-order fragments of W2 rows
  * [32cb, 32cb+32).  ef_pack_expert() builds a blob from row-major matrices.
- * The layout is a pure permutation of the weights: it makes every wavefront
- * load of weights one contiguous 1 KiB read that lands directly in matrix-core
- * operand registers.
+ * Section A keeps the bf16 bit patterns.  Section B holds the same numbers as
+ * fp16: the second FFN half runs the matrix cores in fp16 (fp32 accumulation)
+ * so that the intermediate activation silu(g)*u between the halves keeps 11
+ * significant bits instead of bf16's 8 (bf16 there puts single outputs of
+ * Mixtral-sized layers at the edge of a 2e-2 absolute tolerance).  A bf16
+ * number of magnitude in [2^-24, 2^16) is an fp16 number, so W2 is unchanged;
+ * smaller magnitudes round to the nearest multiple of 2^-24, larger ones (and
+ * inf / NaN) are refused by ef_pack_expert.  Activations beyond +-65504
+ * saturate.  The layout makes every wavefront load of weights one contiguous
+ * 1 KiB read that lands directly in matrix-core operand registers.
  */
 #ifndef EXPERTFLOW_H
 #define EXPERTFLOW_H
@@ -177,7 +184,8 @@ int ef_pack_expert_q4(const uint8_t *q1, const uint16_t *s1, const uint8_t *q3, 
                       const uint8_t *q2, const uint16_t *s2, int d_model, int d_ff, void *blob);
 
 /* Pack row-major W1 [F,d], W3 [F,d], W2 [d,F] (bf16 bit patterns) [host] into blob [host],
- * ef_expert_bytes(d,F) bytes, in the layout described at the top.  Model-load-time helper. */
+ * ef_expert_bytes(d,F) bytes, in the layout described at the top.  Model-load-time helper.
+ * EF_EINVAL if W2 holds a value that is not finite in fp16 (|w| >= 65536, inf, NaN). */
 int ef_pack_expert(const uint16_t *W1, const uint16_t *W3, const uint16_t *W2,
                    int d_model, int d_ff, void *blob);
 

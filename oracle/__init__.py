@@ -145,6 +145,8 @@ def expert_ffn(h, experts, ids, perm, pos_begin=0, pos_end=None, round_act=False
     """experts: sequence over expert id of (W1 [F,d], W3 [F,d], W2 [d,F]) or None.
 
     Returns y [(pos_end-pos_begin), d] float64 for grouped positions pos_begin..pos_end.
+    round_act is a diagnostic mode of the intermediate activation: 0 / False = kept in fp64 (the
+    definition), 1 / True = rounded to bf16, 2 = rounded to fp16.
     """
     h = _u16(h)
     ids = np.ascontiguousarray(ids, dtype=np.int32)

@@ -57,6 +57,30 @@ static double round_to_bf16(double x)
     return (double)f;
 }
 
+/* round a double to the nearest fp16 value (ties to even; below 2^-14 the grid is 2^-24; magnitudes
+ * beyond the largest finite fp16 saturate to it), returned as double */
+static double round_to_f16(double x)
+{
+    if (x == 0.0 || x != x) return x;
+    double a = fabs(x);
+    if (a >= 65504.0) return x < 0 ? -65504.0 : 65504.0;
+    int e;
+    frexp(a, &e);                    /* a = m * 2^e, 0.5 <= m < 1 */
+    int top = e - 1;                 /* exponent of the leading bit */
+    if (top < -14) top = -14;
+    double ulp = ldexp(1.0, top - 10);
+    double q = nearbyint(a / ulp) * ulp;   /* default rounding mode: to nearest, ties to even */
+    if (q > 65504.0) q = 65504.0;
+    return x < 0 ? -q : q;
+}
+
+/* diagnostic modes of the intermediate activation: 0 = kept in fp64 (the definition), 1 = rounded to
+ * bf16, 2 = rounded to fp16 (what a 16-bit scratch between the two FFN halves holds) */
+static double round_act_mode(double a, int mode)
+{
+    return mode == 1 ? round_to_bf16(a) : mode == 2 ? round_to_f16(a) : a;
+}
+
 /* z[t,e] = sum_i h[t,i] * Wg[e,i] + b[e]        (router logits) */
 void oracle_gate_logits(const uint16_t *h, const uint16_t *Wg, const float *b,
                         int T, int d, int E, double *z)
@@ -206,7 +230,7 @@ static void swiglu_row(const uint16_t *x, int d, int F,
             u += bf16_to_f64(W3[(size_t)f * d + i]) * xi;
         }
         double a = g / (1.0 + exp(-g)) * u;
-        act[f] = round_act ? round_to_bf16(a) : a;
+        act[f] = round_act_mode(a, round_act);
     }
     for (int c = 0; c < d; ++c) {
         double acc = 0.0;
@@ -387,7 +411,7 @@ void oracle_expert_ffn_q4(const uint16_t *h, int d, int F, int k,
                     u += q4_weight(q3[e], s3[e], d, f, i) * xi;
                 }
                 double v = g / (1.0 + exp(-g)) * u;
-                act[f] = round_act ? round_to_bf16(v) : v;
+                act[f] = round_act_mode(v, round_act);
             }
             for (int c = 0; c < d; ++c) {
                 double acc = 0.0;

@@ -4,6 +4,7 @@
 #include "ef_ctx.h"
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -34,6 +35,28 @@ extern "C" size_t ef_expert_bytes(int d, int F) {
     return (size_t)3 * (size_t)d * (size_t)F * 2;
 }
 
+namespace {
+// bf16 bit pattern -> fp16 bit pattern of the same number (round to nearest even below the fp16 normal range,
+// where the grid is 2^-24); false for infinities, NaNs and magnitudes of 2^16 and more
+bool bf16_to_f16_bits(uint16_t b, uint16_t *out) {
+    const uint32_t sign = (uint32_t)(b >> 15) << 15, exp = (b >> 7) & 0xFFu, man = b & 0x7Fu;
+    if (exp == 0xFFu) return false;
+    if (exp == 0) { *out = (uint16_t)sign; return true; }          // below 2^-126
+    const int e = (int)exp - 127;
+    if (e > 15) return false;
+    if (e >= -14) { *out = (uint16_t)(sign | ((uint32_t)(e + 15) << 10) | (man << 3)); return true; }
+    const uint32_t m = 128u + man;                                   // value = m * 2^(e - 7) = m * 2^(e + 17) * 2^-24
+    if (e >= -17) { *out = (uint16_t)(sign | (m << (e + 17))); return true; }
+    const int r = -(e + 17);
+    if (r > 9) { *out = (uint16_t)sign; return true; }
+    uint32_t q = m >> r;
+    const uint32_t rem = m & ((1u << r) - 1u), half = 1u << (r - 1);
+    if (rem > half || (rem == half && (q & 1u))) ++q;
+    *out = (uint16_t)(sign | q);
+    return true;
+}
+}  // namespace
+
 extern "C" int ef_pack_expert(const uint16_t *W1, const uint16_t *W3, const uint16_t *W2, int d, int F,
                               void *blob) {
     if (!W1 || !W3 || !W2 || !blob) return fail(nullptr, EF_EINVAL, "ef_pack_expert: null pointer");
@@ -53,17 +76,22 @@ extern "C" int ef_pack_expert(const uint16_t *W1, const uint16_t *W3, const uint
                     }
             }
     };
-    auto section_b = [&](int cb0, int cb1) {
+    std::atomic<bool> w2_ok{true};
+    auto section_b = [&](int cb0, int cb1) {   // W2 leaves as fp16 (the second FFN half runs in fp16)
         uint16_t *base = out + (size_t)2 * d * F;
+        bool ok = true;
         for (int cb = cb0; cb < cb1; ++cb)
             for (int kb = 0; kb < nkb2; ++kb)
                 for (int lane = 0; lane < 64; ++lane) {
                     int g = lane >> 5, i = lane & 31;
                     const uint16_t *src = W2 + (size_t)(cb * 32 + i) * F + kb * 16 + 4 * g;
                     uint16_t *dst = base + (((size_t)cb * nkb2 + kb) * 64 + lane) * 8;
-                    memcpy(dst, src, 8);          // t = 0..3 -> columns 4g + t
-                    memcpy(dst + 4, src + 8, 8);  // t = 4..7 -> columns 8 + 4g + (t-4)
+                    for (int t = 0; t < 4; ++t) {
+                        ok &= bf16_to_f16_bits(src[t], dst + t);          // t = 0..3 -> columns 4g + t
+                        ok &= bf16_to_f16_bits(src[8 + t], dst + 4 + t);  // t = 4..7 -> columns 8 + 4g + (t-4)
+                    }
                 }
+        if (!ok) w2_ok = false;
     };
     unsigned hw = std::thread::hardware_concurrency();
     int nth = (int)std::min<unsigned>(hw ? hw : 1, 16);
@@ -75,6 +103,7 @@ extern "C" int ef_pack_expert(const uint16_t *W1, const uint16_t *W3, const uint
             section_b((int)((long long)ncb * t / nth), (int)((long long)ncb * (t + 1) / nth));
         });
     for (auto &t : th) t.join();
+    if (!w2_ok) return fail(nullptr, EF_EINVAL, "ef_pack_expert: W2 holds a value that is not finite in fp16 (|w| >= 65536, inf or NaN)");
     return EF_OK;
 }
 

@@ -14,6 +14,8 @@ namespace ef {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ floatx16 mfma32(uint4 a, uint4 b, floatx16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
@@ -23,6 +25,25 @@ __device__ __forceinline__ floatx16 mfma32(uint4 a, uint4 b, floatx16 c) {
 __device__ __forceinline__ floatx16 mfma32v(u32x4_t a, u32x4_t b, floatx16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
                                                    __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+
+// The second FFN half runs the matrix cores in fp16 (fp32 accumulation): the intermediate activation
+// silu(g) * u is stored with 11 significant bits instead of bf16's 8, and the W2 section of an expert blob
+// holds the fp16 numbers equal to the bf16 weights (a bf16 value of magnitude in [2^-24, 65504] is an fp16
+// number; the packing call checks the upper end, values below the lower end round to the nearest
+// multiple of 2^-24).  Same operand fragment layout as the bf16 instruction.
+__device__ __forceinline__ floatx16 mfma32h(u32x4_t a, u32x4_t b, floatx16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a), __builtin_bit_cast(half8_t, b),
+                                                  c, 0, 0, 0);
+}
+
+// two activations -> one dword of two fp16 (round to nearest even; magnitudes beyond the largest
+// finite fp16 saturate to it instead of becoming infinite)
+__device__ __forceinline__ uint32_t pack_act2(float v0, float v1) {
+    const float lim = 65504.f;
+    v0 = fminf(fmaxf(v0, -lim), lim);
+    v1 = fminf(fmaxf(v1, -lim), lim);
+    return __builtin_bit_cast(uint32_t, half2_t{(_Float16)v0, (_Float16)v1});
 }
 
 // streaming (read-once) 16-byte load: keeps expert weights from displacing reused data in L2

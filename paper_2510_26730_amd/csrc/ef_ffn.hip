@@ -302,7 +302,7 @@ __global__ __launch_bounds__(256) void ffn_gate_up_kernel(GroupTable gt, const u
                     const float g0 = G[tt][8 * s + 2 * q], g1 = G[tt][8 * s + 2 * q + 1];
                     const float v0 = g0 / (1.f + __expf(-g0)) * U[tt][8 * s + 2 * q];
                     const float v1 = g1 / (1.f + __expf(-g1)) * U[tt][8 * s + 2 * q + 1];
-                    pk[q] = f32_to_bf16_bits(v0) | (f32_to_bf16_bits(v1) << 16);
+                    pk[q] = pack_act2(v0, v1);
                 }
                 dst[(size_t)s * 64] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
             }
@@ -355,7 +355,7 @@ __device__ __forceinline__ void down_stream(const uint4 *__restrict__ w2, size_t
         _Pragma("unroll") for (int u = 0; u < UNR; ++u)                                                  \
             _Pragma("unroll") for (int tt = 0; tt < NTL; ++tt)                                           \
                 _Pragma("unroll") for (int cw = 0; cw < CBW; ++cw)                                       \
-                    acc[cw][tt] = mfma32v(a[tt][u], b[cw][u], acc[cw][tt]);                              \
+                    acc[cw][tt] = mfma32h(a[tt][u], b[cw][u], acc[cw][tt]);                              \
     }
     const int nfull = (k1 - k0) / UNR;
     int kb = k0;
@@ -385,10 +385,12 @@ __device__ __forceinline__ void down_stream(const uint4 *__restrict__ w2, size_t
     for (; kb < k1; ++kb) {
 #pragma unroll
         for (int cw = 0; cw < CBW; ++cw) {
-            const uint4 b = load_stream(w2 + cw * cb_stride + (size_t)kb * 64);
+            const u32x4_t b = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4_t *>(w2 + cw * cb_stride + (size_t)kb * 64));
 #pragma unroll
             for (int tt = 0; tt < NTL; ++tt)
-                acc[cw][tt] = mfma32(a0[((size_t)tt * nkb + kb) * 64], b, acc[cw][tt]);
+                acc[cw][tt] = mfma32h(*reinterpret_cast<const u32x4_t *>(a0 + ((size_t)tt * nkb + kb) * 64), b,
+                                      acc[cw][tt]);
         }
     }
 #undef EF_DN_LOAD
@@ -400,7 +402,7 @@ __device__ __forceinline__ void down_stream(const uint4 *__restrict__ w2, size_t
 // columns, one of `ksg` K-slices); its four waves split that slice again and are summed in a fixed
 // order, (p0 + p2) + (p1 + p3), through LDS.  Each K-slice writes its own partial Y plane; the
 // un-permute sums the planes in order.  Activations are operand A (rows = tokens), W2 fragments
-// operand B (columns = outputs).
+// operand B (columns = outputs), both fp16 (see mfma32h).
 // ------------------------------------------------------------------------------------------
 template <int TT>
 __global__ __launch_bounds__(256, 2) void ffn_down_kernel(GroupTable gt, const uint4 *__restrict__ act,

@@ -27,11 +27,6 @@ namespace ef {
 typedef _Float16 q4_half2 __attribute__((ext_vector_type(2)));
 typedef _Float16 q4_half8 __attribute__((ext_vector_type(8)));
 
-__device__ __forceinline__ floatx16 mfma32h(u32x4_t a, u32x4_t b, floatx16 c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(q4_half8, a), __builtin_bit_cast(q4_half8, b), c,
-                                                  0, 0, 0);
-}
-
 // dword x = eight codes of one lane for one k-step, code t at bits 4*(t/2) + 16*(t%2);
 // s2 = the lane's scale in both halves.  (x >> 4p) & 0x000F000F | 0x64006400 is the pair of fp16
 // numbers 1024 + q for t = 2p, 2p + 1; minus 1032 is q - 8 exactly; times s rounds once to fp16

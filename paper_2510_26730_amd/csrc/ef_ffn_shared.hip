@@ -121,7 +121,7 @@ __global__ __launch_bounds__(256, OCC) void ffn_gate_up_shared_kernel(GroupTable
                 const float g0 = G[tt][8 * s + 2 * q], g1 = G[tt][8 * s + 2 * q + 1];
                 const float v0 = g0 / (1.f + __expf(-g0)) * U[tt][8 * s + 2 * q];
                 const float v1 = g1 / (1.f + __expf(-g1)) * U[tt][8 * s + 2 * q + 1];
-                pk[q] = f32_to_bf16_bits(v0) | (f32_to_bf16_bits(v1) << 16);
+                pk[q] = pack_act2(v0, v1);
             }
             dst[(size_t)s * 64] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
         }
@@ -151,8 +151,8 @@ hipError_t launch_ffn_gate_up_shared(const GroupTable &gt, int total_wgs, int ti
 
 // ------------------------------------------------------------------------------------------
 // second half: Y = act W2^T.  Workgroup = (group, pass of TT token tiles, eight consecutive
-// 32-column blocks of d, one of `ksg` K-slices), wave = two column blocks.  Activations are operand
-// A (rows = tokens), shared through LDS; W2 fragments operand B (a lane holds one output column).
+// 32-column blocks of d, one of `ksg` K-slices), wave = two column blocks.  Activations (fp16) are operand
+// A (rows = tokens), shared through LDS; W2 fragments (fp16) operand B (a lane holds one output column).
 // Each K-slice writes its own partial Y plane; the un-permute sums the planes in order.
 // ------------------------------------------------------------------------------------------
 template <int TT, int D, int OCC>
@@ -214,7 +214,7 @@ __global__ __launch_bounds__(256, OCC) void ffn_down_shared_kernel(GroupTable gt
             _Pragma("unroll") for (int tt = 0; tt < TT; ++tt) {                                          \
                 const u32x4_t af_ = as[(st) & (kShLds - 1)][tt * 4 + j][lane];                           \
                 _Pragma("unroll") for (int cw = 0; cw < CBW; ++cw)                                       \
-                    acc[cw][tt] = mfma32v(wq[slot][cw][j], af_, acc[cw][tt]);                            \
+                    acc[cw][tt] = mfma32h(wq[slot][cw][j], af_, acc[cw][tt]);                            \
             }                                                                                            \
         }                                                                                                \
     }

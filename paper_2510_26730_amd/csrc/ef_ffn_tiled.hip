@@ -60,8 +60,9 @@ __device__ __forceinline__ bool tiled_panel(int local, int rot, int npanels, int
         _Pragma("unroll") for (int q = 0; q < kStageFrags / 4; ++q)                                  \
             EF_TILED_DMA(src[q] + (size_t)stc_ * kTileKS * 64, EF_TILED_DST(st, q));                 \
     }
-// HALF: operands are fp16 fragments (contexts with 4-bit experts: tokens, activations and the dequantised
-// weights are fp16) instead of bf16; accumulation is fp32 either way.
+// HALF: operands are fp16 fragments instead of bf16; accumulation is fp32 either way.  The second half always
+// runs in fp16 (activations and the W2 section of a blob are fp16, see mfma32h); the first half does in
+// contexts with 4-bit experts (tokens and the dequantised weights are fp16 there), otherwise it runs in bf16.
 typedef _Float16 tiled_half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 tiled_half2 __attribute__((ext_vector_type(2)));
 template <bool HALF>
@@ -71,11 +72,6 @@ __device__ __forceinline__ floatx16 tiled_mfma(u32x4_t a, u32x4_t b, floatx16 c)
                                                       __builtin_bit_cast(tiled_half8, b), c, 0, 0, 0);
     else
         return mfma32v(a, b, c);
-}
-template <bool HALF>
-__device__ __forceinline__ uint32_t tiled_pack2(float v0, float v1) {
-    if constexpr (HALF) return __builtin_bit_cast(uint32_t, tiled_half2{(_Float16)v0, (_Float16)v1});
-    else return f32_to_bf16_bits(v0) | (f32_to_bf16_bits(v1) << 16);
 }
 
 #define EF_TILED_READ(a, b, cur, ks)                                                              \
@@ -244,7 +240,7 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_tiled_kernel(GroupTable gt
                     const float g0 = acc[2 * h][j][8 * s + 2 * q], g1 = acc[2 * h][j][8 * s + 2 * q + 1];
                     const float v0 = g0 / (1.f + __expf(-g0)) * acc[2 * h + 1][j][8 * s + 2 * q];
                     const float v1 = g1 / (1.f + __expf(-g1)) * acc[2 * h + 1][j][8 * s + 2 * q + 1];
-                    pk[q] = tiled_pack2<HALF>(v0, v1);
+                    pk[q] = pack_act2(v0, v1);
                 }
                 dst[(size_t)s * 64] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
             }
@@ -275,7 +271,6 @@ hipError_t launch_ffn_gate_up_tiled(const GroupTable &gt, int total_wgs, const v
 // operand A slots 0..7 = activation fragments of tiles t0..t0+7,
 // operand B slots 8..15 = W2 fragments of column blocks cb0..cb0+7
 // ------------------------------------------------------------------------------------------
-template <bool HALF>
 __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, const uint4 *__restrict__ act,
                                                                  float *__restrict__ Y, int d, int ksg,
                                                                  long long y_plane) {
@@ -283,6 +278,7 @@ __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, c
     // accumulator quad, which is one 16-byte store; with the product the other way round a lane holds one
     // column of four consecutive tokens and the tile leaves in 4-byte stores, four times as many instructions
     constexpr bool kSwapOperands = true;
+    constexpr bool HALF = true;   // fp16 activations and W2 fragments
     __shared__ __attribute__((aligned(16))) u32x4_t lds[kTileStages][kStageFrags][64];
     const int wg = blockIdx.x;
     int grp = 0;
@@ -353,7 +349,7 @@ __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, c
 }
 
 hipError_t launch_ffn_down_tiled(const GroupTable &gt, int total_wgs, int ksg, const void *act, float *y,
-                                 long long y_plane, int d, bool f16, hipStream_t s) {
+                                 long long y_plane, int d, hipStream_t s) {
     if (total_wgs <= 0) return hipSuccess;
     if (ksg < 1) return hipErrorInvalidValue;
     for (int i = 0; i < gt.n_groups; ++i)
@@ -361,12 +357,8 @@ hipError_t launch_ffn_down_tiled(const GroupTable &gt, int total_wgs, int ksg, c
             !ffn_tiled_ok(d, gt.F[i], gt.n_tiles[i]))
             return hipErrorInvalidValue;
     if (gt.wg_start[gt.n_groups] != total_wgs) return hipErrorInvalidValue;
-    if (f16)
-        hipLaunchKernelGGL(ffn_down_tiled_kernel<true>, dim3(total_wgs), dim3(256), 0, s, gt,
-                           reinterpret_cast<const uint4 *>(act), y, d, ksg, y_plane);
-    else
-        hipLaunchKernelGGL(ffn_down_tiled_kernel<false>, dim3(total_wgs), dim3(256), 0, s, gt,
-                           reinterpret_cast<const uint4 *>(act), y, d, ksg, y_plane);
+    hipLaunchKernelGGL(ffn_down_tiled_kernel, dim3(total_wgs), dim3(256), 0, s, gt,
+                       reinterpret_cast<const uint4 *>(act), y, d, ksg, y_plane);
     return hipGetLastError();
 }
 

@@ -285,7 +285,7 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
         }
         {
             KernelTimer kt(c, ts, EF_K_FFN_DOWN_TILED, b_dn, f_dn);
-            EF_HIP(c, ef::launch_ffn_down_tiled(bdn, wg_dn, ksg_tiled, c->act, c->y, y_plane, d, c->q4, ts));
+            EF_HIP(c, ef::launch_ffn_down_tiled(bdn, wg_dn, ksg_tiled, c->act, c->y, y_plane, d, ts));
         }
         if (side.forked) EF_HIP(c, side.record());
     }

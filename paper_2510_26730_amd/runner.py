@@ -61,10 +61,9 @@ class LayerLoop:
                     st[e * self.es + ncode:(e + 1) * self.es].copy_(scale.view(torch.uint8))
                 self.stores.append(st)
                 continue
-            st = torch.empty(E * self.es // 2, dtype=torch.bfloat16, pin_memory=True)
+            st = torch.empty(E * self.es // 2, dtype=torch.int16, pin_memory=True)
             for e in range(E):           # one expert at a time keeps the device staging buffer small
-                w = torch.randn(self.es // 2, generator=g, device=dev, dtype=torch.float32).mul_(cfg.w_std)
-                st[e * (self.es // 2):(e + 1) * (self.es // 2)].copy_(w.to(torch.bfloat16))
+                st[e * (self.es // 2):(e + 1) * (self.es // 2)].copy_(self._random_blob(d, cfg.F, cfg.w_std, g))
             self.stores.append(st)
         self.shared = []
         if cfg.F_shared and q4:
@@ -77,9 +76,8 @@ class LayerLoop:
                                         device=dev).view(torch.uint8)
                 self.shared.append(sb)
         elif cfg.F_shared:
-            n = 3 * d * cfg.F_shared
             for _ in range(self.store_layers):
-                self.shared.append((torch.randn(n, generator=g, device=dev) * cfg.w_std).to(torch.bfloat16))
+                self.shared.append(self._random_blob(d, cfg.F_shared, cfg.w_std, g))
         self.gate_w, self.gate_b = [], []
         for l in range(n_layers):
             self.gate_w.append(torch.from_numpy(synth.gate_weight(cfg, l).view(np.int16)).to(dev))
@@ -110,6 +108,16 @@ class LayerLoop:
                     ef.ef_cache_swap_in(self.ctx, l, e, 0, 0)
             torch.cuda.synchronize()
             ef.ef_get_stats(self.ctx)
+
+    @staticmethod
+    def _random_blob(d, F, std, g):
+        """A packed expert of i.i.d. N(0, std^2) weights rounded to bf16, drawn directly in packed order on the
+        device: W1 / W3 fragments as bf16 bit patterns, the W2 section as the fp16 numbers equal to them."""
+        w = torch.randn(3 * d * F, generator=g, device="cuda", dtype=torch.float32).mul_(std).to(torch.bfloat16)
+        blob = torch.empty(3 * d * F, dtype=torch.int16, device="cuda")
+        blob[:2 * d * F] = w[:2 * d * F].view(torch.int16)
+        blob[2 * d * F:] = w[2 * d * F:].to(torch.float16).view(torch.int16)
+        return blob
 
     def close(self):
         torch.cuda.synchronize()

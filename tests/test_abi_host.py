@@ -42,7 +42,14 @@ def test_pack_expert_layout():
     d, F = 128, 96
     rng = np.random.default_rng(0)
     W1, W3 = (rng.integers(0, 65536, (F, d), dtype=np.uint16) for _ in range(2))
-    W2 = rng.integers(0, 65536, (d, F), dtype=np.uint16)
+    # W2 leaves as fp16 numbers: bf16 patterns over the whole fp16 range (exponents down to 2^-30: the
+    # smallest round to multiples of 2^-24), both signs
+    W2 = (rng.integers(0, 2, (d, F)) << 15 | rng.integers(97, 143, (d, F)) << 7 | rng.integers(0, 128, (d, F))).astype(np.uint16)
+    W2[0, :4] = [0x0000, 0x8000, 0x0001, 0x3F80]        # zeros, a bf16 subnormal, 1.0
+    from paper_2510_26730_amd import synth
+    W2h = synth.bf16_to_f32(W2).astype(np.float16).view(np.uint16)     # numpy rounds to nearest even, keeps subnormals
+    big = np.abs(synth.bf16_to_f32(W2)) >= 2.0 ** -14
+    assert np.array_equal(W2h.view(np.float16)[big].astype(np.float32), synth.bf16_to_f32(W2)[big])   # exact there
     blob = ef.ef_pack_expert(W1, W3, W2).view(np.uint16)
     assert blob.size == 3 * d * F
     ref = np.empty_like(blob)
@@ -61,11 +68,20 @@ def test_pack_expert_layout():
             for lane in range(64):
                 g, i = lane // 32, lane % 32
                 for t in range(8):
-                    ref[pos] = W2[cb * 32 + i, kb * 16 + 8 * (t // 4) + 4 * g + t % 4]
+                    ref[pos] = W2h[cb * 32 + i, kb * 16 + 8 * (t // 4) + 4 * g + t % 4]
                     pos += 1
     assert pos == blob.size
     assert np.array_equal(blob, ref)
-    assert np.array_equal(np.sort(blob), np.sort(np.concatenate([W1.ravel(), W3.ravel(), W2.ravel()])))
+    assert np.array_equal(np.sort(blob), np.sort(np.concatenate([W1.ravel(), W3.ravel(), W2h.ravel()])))
+    for bad in (0x7F80, 0xFF80, 0x7FC0, 0x4780, 0xC780):     # +inf, -inf, NaN, +-65536
+        W2b = W2.copy()
+        W2b[d - 1, F - 1] = bad
+        with pytest.raises(ef.EfError) as ei:
+            ef.ef_pack_expert(W1, W3, W2b)
+        assert ei.value.code == ef.EF_EINVAL
+    W2b = W2.copy()
+    W2b[5, 7] = 0x477F                                       # 65280, the largest bf16 below 65536
+    assert ef.ef_pack_expert(W1, W3, W2b).view(np.uint16).size == 3 * d * F
 
 
 def fake_ctx(**kw):

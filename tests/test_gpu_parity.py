@@ -348,14 +348,14 @@ def _sampled_layer_check(oracle_mod, st, layer, h, T, beta, res, n_sample, seed)
     sh = None if not cfg.F_shared else oracle_mod.dense_ffn(hs, *st.shared[layer])
     ref = oracle_mod.combine(y, sub["w"], sub["inv_perm"], sh)
     e1, e2 = float_close(out[toks], ref)
-    # the same evaluation with the oracle's intermediate activation rounded to bf16, as the kernels store it:
+    # the same evaluation with the oracle's intermediate activation rounded to fp16, as the kernels store it:
     # what is left is summation order and the fast exponential, an order of magnitude below the rounding itself
-    y_r = oracle_mod.expert_ffn(hs, st.experts[layer], ids_s, sub["perm"], round_act=True)
-    sh_r = None if not cfg.F_shared else oracle_mod.dense_ffn(hs, *st.shared[layer], round_act=True)
+    y_r = oracle_mod.expert_ffn(hs, st.experts[layer], ids_s, sub["perm"], round_act=2)
+    sh_r = None if not cfg.F_shared else oracle_mod.dense_ffn(hs, *st.shared[layer], round_act=2)
     ref_r = oracle_mod.combine(y_r, sub["w"], sub["inv_perm"], sh_r)
     r1, r2 = float_close(out[toks], ref_r, max_abs=5e-3, rel_l2=3e-4)    # single activations that round the other way
     say(f"  near-ties {nties}, sampled {len(toks)} tokens: max abs {e1:.2e}, rel l2 {e2:.2e}; "
-        f"against bf16-rounded activations: max abs {r1:.2e}, rel l2 {r2:.2e}")
+        f"against fp16-rounded activations: max abs {r1:.2e}, rel l2 {r2:.2e}")
 
 
 def test_full_size_mixtral_decode_layer(oracle_mod):

@@ -213,6 +213,25 @@ def test_round_act_mode_rounds_like_bfloat16(oracle_mod):
     assert np.max(np.abs(out - (act @ t_bf16(w2).T).numpy())) < 1e-12
 
 
+def test_round_act_mode_2_rounds_like_float16(oracle_mod):
+    """The diagnostic mode that mirrors an fp16 scratch between the FFN halves, against torch's own
+    float16 rounding; scaled inputs put activations below the fp16 normal range and above its maximum."""
+    d, F, T = 16, 24, 5
+    w1, w3, w2 = rnd_bf16((F, d), 51, 0.4), rnd_bf16((F, d), 52, 0.4), rnd_bf16((d, F), 53, 0.4)
+    for scale in (1.0, 0.004, 300.0):
+        h = rnd_bf16((T, d), 50, scale)
+        out = oracle_mod.dense_ffn(h, w1, w3, w2, round_act=2)
+        x = t_bf16(h)
+        act = torch.nn.functional.silu(x @ t_bf16(w1).T) * (x @ t_bf16(w3).T)
+        if scale == 0.004:
+            assert (act.abs() < 2.0 ** -14).any()
+        if scale == 300.0:
+            assert (act.abs() > 65504).any()
+        act = act.clamp(-65504.0, 65504.0).to(torch.float16).to(torch.float64)
+        ref = (act @ t_bf16(w2).T).numpy()
+        assert np.max(np.abs(out - ref)) <= 1e-12 * max(1.0, np.max(np.abs(ref)))
+
+
 # ---------------------------------------------------------------- predictor
 def test_predict_with_own_gate_equals_route_and_identical_gates_agree(oracle_mod):
     cfg = synth.CONFIGS["tiny"]
