@@ -237,6 +237,24 @@ int ef_route(ef_ctx *ctx, int layer, const void *hidden, int T, float beta,
              int32_t *perm, int32_t *inv_perm, void *stream);
 
 /*
+ * ef_route for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same kernels and bit-identical results, but the kernels'
+ * scratch (per-tile expert counts and their prefixes, partial logits of K-split gate launches) is a static
+ * device array of EF_ROUTE_STATIC_SCRATCH_BYTES inside the library instead of buffers of the context; every
+ * GPU the library runs on holds that array until the process ends.  The call allocates nothing, on the host
+ * side of HIP or on the device, and calls no allocating routine.  T above EF_ROUTE_STATIC_MAX_TOKENS is
+ * EF_EINVAL (T beyond the context's max_tokens is fine: this call does not use the context's scratch).
+ * All calls on one GPU, of any context, share the one array: calls that overlap in time on that GPU (different
+ * streams, different contexts) race; issue them on one stream or order them with events.  Nothing has to be
+ * cleared between calls.  Arguments as ef_route.
+ */
+#define EF_ROUTE_STATIC_MAX_TOKENS 8192
+#define EF_ROUTE_STATIC_SCRATCH_BYTES (4u << 20)
+int ef_route_static(ef_ctx *ctx, int layer, const void *hidden, int T, float beta,
+                    int32_t *topk_ids, float *topk_w, int32_t *counts, int32_t *offsets,
+                    int32_t *perm, int32_t *inv_perm, void *stream);
+
+/*
  * ef_route and ef_predict of the same layer on ONE pass over `hidden` (the look-ahead gates see the
  * same hidden states as the layer's own gate, paper Sec. 2.3.2, so the hidden states need to be read
  * from HBM only once).  Results are identical to calling ef_route(layer, ..., beta) and

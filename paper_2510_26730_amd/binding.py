@@ -30,7 +30,7 @@ EXPORTS = [
     "ef_strerror", "ef_expert_bytes", "ef_pack_expert", "ef_expert_bytes_q4", "ef_pack_expert_q4", "ef_create", "ef_destroy", "ef_last_error",
     "ef_register_layer", "ef_predict", "ef_route", "ef_route_predict", "ef_moe_ffn", "ef_layer_step", "ef_cache_swap_in", "ef_cache_query",
     "ef_choose_horizon", "ef_token_dist", "ef_get_stats", "ef_reset_stats", "ef_set_profile", "ef_set_profile_sampling",
-    "ef_fake_advance_time", "ef_layer_step_fetch", "ef_get_tuning", "ef_set_tuning",
+    "ef_fake_advance_time", "ef_layer_step_fetch", "ef_get_tuning", "ef_set_tuning", "ef_route_static",
     "ef_forest_create", "ef_forest_destroy", "ef_delta_features", "ef_forest_fit", "ef_forest_predict",
     "ef_forest_tree_size", "ef_forest_tree_export", "ef_forest_bit_accuracy", "ef_delta_from_activation",
     "ef_delta_cache_create", "ef_delta_cache_destroy", "ef_delta_cache_put", "ef_delta_cache_get",
@@ -115,6 +115,7 @@ def lib():
         L.ef_register_layer.argtypes = [vp, i32, vp, vp, vp, vp]
         L.ef_predict.argtypes = [vp, i32, vp, i32, i32, vp, vp, f32, vp, vp, C.POINTER(i32), vp]
         L.ef_route.argtypes = [vp, i32, vp, i32, f32, vp, vp, vp, vp, vp, vp, vp]
+        L.ef_route_static.argtypes = [vp, i32, vp, i32, f32, vp, vp, vp, vp, vp, vp, vp]
         L.ef_route_predict.argtypes = [vp, i32, vp, i32, f32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                        C.POINTER(i32), vp]
         L.ef_moe_ffn.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -268,6 +269,12 @@ def ef_route(ctx, layer, hidden, T, beta, topk_ids, topk_w, counts, offsets, per
     return _check(ctx, lib().ef_route(ctx, layer, _ptr(hidden), T, beta, _ptr(topk_ids), _ptr(topk_w),
                                       _ptr(counts), _ptr(offsets), _ptr(perm), _ptr(inv_perm),
                                       _stream(stream)))
+
+
+def ef_route_static(ctx, layer, hidden, T, beta, topk_ids, topk_w, counts, offsets, perm, inv_perm, stream=None):
+    return _check(ctx, lib().ef_route_static(ctx, layer, _ptr(hidden), T, beta, _ptr(topk_ids), _ptr(topk_w),
+                                             _ptr(counts), _ptr(offsets), _ptr(perm), _ptr(inv_perm),
+                                             _stream(stream)))
 
 
 def ef_route_predict(ctx, layer, hidden, T, beta, H, delta, tok2req, topk_ids, topk_w, counts, offsets, perm,

@@ -320,6 +320,15 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
     for (int q = 0; q < 2; ++q)
         if ((e = hipStreamCreateWithFlags(&c->copy_stream[q], hipStreamNonBlocking)) != hipSuccess)
             return bail(e, "copy stream");
+    {   // resolve the address of ef_route_static's scratch on this device now, so that the call itself never has to
+        EfRouteScratch rs{};
+        if (static_route_scratch(c, &rs) != EF_OK) {
+            std::string keep = thread_error();
+            ef_destroy(c);
+            set_thread_error(keep);
+            return EF_EHIP;
+        }
+    }
     for (auto &s : c->slots) {
         if ((e = hipEventCreate(&s.copy_start)) != hipSuccess) return bail(e, "event");
         if ((e = hipEventCreate(&s.ready)) != hipSuccess) return bail(e, "event");
@@ -386,7 +395,7 @@ extern "C" int ef_predict(ef_ctx *c, int layer, const void *hidden, int T, int H
     if (!hidden || !topk_ids) return fail(c, EF_EINVAL, "ef_predict: null pointer");
     if (!aligned16(hidden)) return fail(c, EF_EINVAL, "ef_predict: hidden must be 16-byte aligned");
     return run_gates(c, layer, hidden, T, beta, false, He, H, delta, tok2req, nullptr, nullptr, nullptr, nullptr,
-                     nullptr, nullptr, topk_ids, hist, kNoExport, s);
+                     nullptr, nullptr, topk_ids, hist, kNoExport, ctx_route_scratch(c), s);
 }
 
 extern "C" int ef_token_dist(ef_ctx *c, const void *hidden, int T, float *tok_dist, double *dist, void *stream) {
@@ -434,7 +443,7 @@ extern "C" int ef_route(ef_ctx *c, int layer, const void *hidden, int T, float b
     if (!aligned16(hidden)) return fail(c, EF_EINVAL, "ef_route: hidden must be 16-byte aligned");
     if ((rc = open_layer_timer(c, s))) return rc;
     return run_gates(c, layer, hidden, T, beta, true, 0, 0, nullptr, nullptr, topk_ids, topk_w, counts, offsets,
-                     perm, inv_perm, nullptr, nullptr, kNoExport, s);
+                     perm, inv_perm, nullptr, nullptr, kNoExport, ctx_route_scratch(c), s);
 }
 
 extern "C" int ef_route_predict(ef_ctx *c, int layer, const void *hidden, int T, float beta, int H,
@@ -460,7 +469,7 @@ extern "C" int ef_route_predict(ef_ctx *c, int layer, const void *hidden, int T,
     if (!aligned16(hidden)) return fail(c, EF_EINVAL, "ef_route_predict: hidden must be 16-byte aligned");
     if ((rc = open_layer_timer(c, s))) return rc;
     return run_gates(c, layer, hidden, T, beta, true, He, H, delta, tok2req, topk_ids, topk_w, counts, offsets,
-                     perm, inv_perm, pred_ids, pred_hist, kNoExport, s);
+                     perm, inv_perm, pred_ids, pred_hist, kNoExport, ctx_route_scratch(c), s);
 }
 
 extern "C" int ef_layer_step(ef_ctx *c, int layer, const void *hidden, int T, float beta, int H,
@@ -488,7 +497,7 @@ extern "C" int ef_layer_step(ef_ctx *c, int layer, const void *hidden, int T, fl
     const int seq = (int)(++c->meta_seq % 255);
     ef::GroupExport ex{c->meta_dev, c->st_pred_hist, He * E, EF_MAX_HORIZON * E, seq};
     rc = run_gates(c, layer, hidden, T, beta, true, He, H, delta, tok2req, c->st_ids, c->st_w, c->st_counts,
-                   c->st_offsets, c->st_perm, c->st_inv, c->st_pred_ids, c->st_pred_hist, ex, s);
+                   c->st_offsets, c->st_perm, c->st_inv, c->st_pred_ids, c->st_pred_hist, ex, ctx_route_scratch(c), s);
     if (rc) return rc;
     // the token packing only needs what the grouping kernel left on the device: enqueue it now, so it
     // runs while the host waits for and digests the counts

@@ -37,6 +37,14 @@ struct EfEventPair {
     hipEvent_t a, b;
 };
 
+// Device scratch of the routing launches: per-tile expert counts and their prefixes ([token tiles][E] each) and
+// the partial logits of K-split gate launches.
+struct EfRouteScratch {
+    int32_t *blockcounts, *blockbase;
+    float *gate_part;
+    size_t gate_part_floats;
+};
+
 struct ef_ctx {
     ef_config cfg{};
     ef_tuning tune{};
@@ -151,7 +159,12 @@ extern const ef::GroupExport kNoExport;
 int run_gates(ef_ctx *c, int layer, const void *hidden, int T, float beta, bool do_route, int He, int H_stride,
               const float *delta, const int32_t *tok2req, int32_t *topk_ids, float *topk_w, int32_t *counts,
               int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *pred_ids, int32_t *pred_hist,
-              const ef::GroupExport &ex, hipStream_t s);
+              const ef::GroupExport &ex, const EfRouteScratch &rs, hipStream_t s);
+// the static device scratch of ef_route_static on the current device (ef_static.hip)
+int static_route_scratch(ef_ctx *c, EfRouteScratch *out);
+inline EfRouteScratch ctx_route_scratch(const ef_ctx *c) {
+    return EfRouteScratch{c->blockcounts, c->blockbase, c->gate_part, c->gate_part_floats};
+}
 int check_predict_args(ef_ctx *c, int layer, int T, int H, int *He_out, const char *who);
 int open_layer_timer(ef_ctx *c, hipStream_t s);
 

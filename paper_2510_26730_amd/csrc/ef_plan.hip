@@ -16,7 +16,7 @@ const ef::GroupExport kNoExport{nullptr, nullptr, 0, 0, 0};
 int run_gates(ef_ctx *c, int layer, const void *hidden, int T, float beta, bool do_route, int He, int H_stride,
               const float *delta, const int32_t *tok2req, int32_t *topk_ids, float *topk_w, int32_t *counts,
               int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *pred_ids, int32_t *pred_hist,
-              const ef::GroupExport &ex, hipStream_t s) {
+              const ef::GroupExport &ex, const EfRouteScratch &rs, hipStream_t s) {
     const int E = c->cfg.n_experts, k = c->cfg.top_k, d = c->cfg.d_model;
     const int ntiles = (T + ef::kTile - 1) / ef::kTile;
     // the library's own histogram buffer is left zeroed by the hand-over step of the previous layer
@@ -48,7 +48,7 @@ int run_gates(ef_ctx *c, int layer, const void *hidden, int T, float beta, bool 
                 a.ids[gi] = topk_ids;
                 a.hist[gi] = nullptr;
                 a.w = topk_w;
-                a.blockcounts = c->blockcounts;
+                a.blockcounts = rs.blockcounts;
                 a.renorm = c->cfg.renorm_topk;
                 a.routed_scale = c->cfg.routed_scale;
             } else {
@@ -62,19 +62,19 @@ int run_gates(ef_ctx *c, int layer, const void *hidden, int T, float beta, bool 
             }
         }
         a.gpw = ef::gate_pick_gpw(T, a.G, E);
-        a.ksplit = ef::gate_pick_ksplit(T, d, a.G, E, a.gpw, c->gate_part_floats);
+        a.ksplit = ef::gate_pick_ksplit(T, d, a.G, E, a.gpw, rs.gate_part_floats);
         {
             const int forced = c->tune.gate_k_split;
             if (forced >= 1 && forced <= 16 &&
-                (size_t)ntiles * ((a.G + a.gpw - 1) / a.gpw) * forced * ef::kTile * 128 <= c->gate_part_floats)
+                (size_t)ntiles * ((a.G + a.gpw - 1) / a.gpw) * forced * ef::kTile * 128 <= rs.gate_part_floats)
                 a.ksplit = forced;
         }
-        a.part = c->gate_part;
+        a.part = rs.gate_part;
         a.tsplit = 1;
         {   // the two-kernel form also pays off without a K split when the per-token part dominates
             const int ts = ef::gate_pick_tsplit(T, a.G, E, a.gpw);
             const size_t need = (size_t)ntiles * ((a.G + a.gpw - 1) / a.gpw) * a.ksplit * ef::kTile * 128;
-            if (ts > 1 && need <= c->gate_part_floats && c->tune.gate_token_split != 0) a.tsplit = ts;
+            if (ts > 1 && need <= rs.gate_part_floats && c->tune.gate_token_split != 0) a.tsplit = ts;
         }
         a.two_step = (a.ksplit > 1 || a.tsplit > 1) ? 1 : 0;
         const bool has_route = do_route && g0 == 0;
@@ -99,7 +99,7 @@ int run_gates(ef_ctx *c, int layer, const void *hidden, int T, float beta, bool 
     }
     if (do_route && !grouped) {
         KernelTimer kt(c, s, EF_K_GROUP, (double)ntiles * E * 8 + (double)(2 * E + 1) * 4 + (double)T * k * 12);
-        EF_HIP(c, ef::launch_group(c->blockcounts, topk_ids, T, k, E, c->blockbase, counts, offsets, perm,
+        EF_HIP(c, ef::launch_group(rs.blockcounts, topk_ids, T, k, E, rs.blockbase, counts, offsets, perm,
                                    inv_perm, ex, s));
     }
     return EF_OK;
