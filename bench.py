@@ -310,6 +310,76 @@ def run_workload(name, spec, args, cpu_seconds):
     return result
 
 
+def route_sweep(args):
+    """Routing and grouping alone (gate, softmax, biased top-k, per-tile counts, prefix, stable scatter) over a
+    sweep of batch sizes at the Mixtral-shaped gate (d = 4096, E = 8, top-2; experts of the smallest legal size,
+    none of them run): the sizes at which these kernels are bound by reading the hidden states from HBM."""
+    import dataclasses
+    import torch
+    from paper_2510_26730_amd import binding as ef
+    from paper_2510_26730_amd import synth
+    cfg = dataclasses.replace(synth.CONFIGS["mixtral_prefill"], name="mixtral_gate", F=32)
+    sizes = [int(t) for t in args.route_sweep.split(",")]
+    Tm, E, k, d = max(sizes), cfg.E, cfg.k, cfg.d
+    L = 2
+    ctx = ef.ef_create(n_layers=L, d_model=d, n_experts=E, top_k=k, d_ff=cfg.F, slots_total=E, max_tokens=Tm,
+                       renorm_topk=1)
+    keep = []
+    store = torch.zeros(E * ef.ef_expert_bytes(d, cfg.F), dtype=torch.uint8).pin_memory()
+    for l in range(L):
+        gw = torch.from_numpy(synth.gate_weight(cfg, l).view("int16")).cuda()
+        gb = torch.from_numpy(synth.gate_bias(cfg, l)).cuda()
+        ef.ef_register_layer(ctx, l, gw, gb, store, None)
+        keep += [gw, gb]
+    for e in range(2):
+        ef.ef_cache_swap_in(ctx, 0, e, 0, 0)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(synth.BASE_SEED)
+    h_all = torch.randn(Tm, d, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    n = Tm * k
+    o = dict(ids=torch.empty(n, **i32), w=torch.empty(n, dtype=torch.float32, device="cuda"), counts=torch.empty(E, **i32),
+             offsets=torch.empty(E + 1, **i32), perm=torch.empty(n, **i32), inv=torch.empty(n, **i32),
+             pids=torch.empty(n, **i32), phist=torch.empty(E, **i32))
+    stream = torch.cuda.current_stream()
+    reps = args.steps or 20
+    rows = []
+    for form in (1, 0):
+        ef.ef_set_tuning(ctx, gate_stream=form)
+        for H in (0, 1):
+            for T in sizes:
+                def call():
+                    if H:
+                        ef.ef_route_predict(ctx, 0, h_all, T, 1.0, H, None, None, o["ids"], o["w"], o["counts"],
+                                            o["offsets"], o["perm"], o["inv"], o["pids"], o["phist"], stream)
+                    else:
+                        ef.ef_route(ctx, 0, h_all, T, 1.0, o["ids"], o["w"], o["counts"], o["offsets"], o["perm"],
+                                    o["inv"], stream)
+                for _ in range(3):
+                    call()
+                torch.cuda.synchronize()
+                ef.ef_set_profile(ctx, (1 << ef.EF_KERNELS.index("route")) | (1 << ef.EF_KERNELS.index("group")))
+                ef.ef_reset_stats(ctx)
+                t0 = time.perf_counter()
+                for _ in range(reps):
+                    call()
+                torch.cuda.synchronize()
+                wall = time.perf_counter() - t0
+                kt = kernel_table(ef, ef.ef_get_stats(ctx), wall)
+                ef.ef_set_profile(ctx, 0)
+                assert int(o["counts"].sum()) == T * k
+                rows.append({"T": T, "look_ahead": H, "streaming_form": bool(form), "us_per_call_wall": 1e6 * wall / reps,
+                             "gate": {"avg_us": kt["route"]["avg_us"], "alg_bytes": kt["route"]["alg_bytes_per_launch"],
+                                      "GBps": kt["route"]["GBps"], "frac_of_hbm_peak": kt["route"]["GBps"] / HBM_PEAK_GBPS},
+                             "group": {"avg_us": kt["group"]["avg_us"], "alg_bytes": kt["group"]["alg_bytes_per_launch"],
+                                       "GBps": kt["group"]["GBps"]}})
+                print(f"bench.py: route sweep T={T} H={H} streaming={form}: gate {kt['route']['avg_us']:.1f} us "
+                      f"{kt['route']['GBps']:.0f} GB/s, group {kt['group']['avg_us']:.1f} us", file=sys.stderr, flush=True)
+    ef.ef_destroy(ctx)
+    print(json.dumps({"metric": "routing kernels over batch size (gate + grouping), Mixtral-shaped gate", "unit": "GB/s",
+                      "hbm_peak_GBps": HBM_PEAK_GBPS, "route_sweep": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -340,6 +410,9 @@ def main():
     ap.add_argument("--prompts", type=int, default=256, help="--delta-forest: size of the pool of recurring prompts")
     ap.add_argument("--log-steps", type=int, default=24, help="--delta-forest: steps whose routing is logged for training")
     ap.add_argument("--eval-steps", type=int, default=6, help="--delta-forest: fresh steps the look-ahead is scored on")
+    ap.add_argument("--route-sweep", default=None, metavar="T1,T2,...",
+                    help="measure routing + grouping alone at these batch sizes (Mixtral-shaped gate, tiny experts), "
+                         "e.g. 8192,32768,131072, with both forms of the gate kernel, instead of the workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="target CPU time of the headline's oracle baseline")
     ap.add_argument("--calib-copy", type=int, default=0,
@@ -366,6 +439,10 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.route_sweep:
+        route_sweep(args)
+        return
 
     if args.delta_forest:
         from paper_2510_26730_amd import delta_bench

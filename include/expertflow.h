@@ -487,6 +487,7 @@ typedef struct ef_tuning {
     int32_t gate_k_split;            /* 0 = auto, else 1..16: workgroups sharing the K range of one (tile, gate group) */
     int32_t gate_token_split;        /* 0/1: the gate's second step may split a tile's tokens over workgroups (1) */
     int32_t gate_fused_finish;       /* 0/1: decode-sized batches fuse the gate's second step with the grouping (1) */
+    int32_t gate_stream;             /* 0/1: batches of many token tiles take the gate kernel that streams through LDS (1) */
     int32_t early_pack;              /* 0/1: ef_layer_step enqueues the token packing before the host has the counts (1) */
 } ef_tuning;
 int ef_get_tuning(ef_ctx *ctx, ef_tuning *out);

@@ -675,6 +675,7 @@ void efi::tuning_defaults(ef_tuning *t) {
     t->gate_k_split = 0;
     t->gate_token_split = 1;
     t->gate_fused_finish = 1;
+    t->gate_stream = 1;
     t->early_pack = 1;
 }
 
@@ -707,6 +708,7 @@ extern "C" int ef_set_tuning(ef_ctx *c, const ef_tuning *t) {
     else if (t->gate_k_split < 0 || t->gate_k_split > 16) bad = "gate_k_split";
     else if (!flag(t->gate_token_split)) bad = "gate_token_split";
     else if (!flag(t->gate_fused_finish)) bad = "gate_fused_finish";
+    else if (!flag(t->gate_stream)) bad = "gate_stream";
     else if (!flag(t->early_pack)) bad = "early_pack";
     if (bad) return fail(c, EF_EINVAL, "ef_set_tuning: %s out of range", bad);
     c->tune = *t;

@@ -36,6 +36,7 @@ struct GateArgs {
     int two_step;                  // 1: gate_kernel leaves partial logits, gate_finish_kernel does the per-token part
     int tsplit;                    // two_step: workgroups that share the 32 tokens of a tile in the finish (1, 2, 4)
     float *part;                   // two_step: [tiles][groups][ksplit][32][32 * column blocks] partial logits
+    int stream;                    // 1: launches that qualify (gate_stream_ok) take the streaming form of the kernel
 };
 
 // Grouped FFN launch: one group per active expert (+ one for the dense shared FFN).
@@ -79,6 +80,9 @@ int gate_pick_gpw(int T, int G, int E);
 int gate_pick_ksplit(int T, int d, int G, int E, int gpw, size_t part_floats);
 int gate_pick_tsplit(int T, int G, int E, int gpw);
 hipError_t launch_gate(const GateArgs &a, hipStream_t s);
+// batches of many token tiles: hidden states streamed through LDS by direct global -> LDS loads
+bool gate_stream_ok(const GateArgs &a);
+bool gate_stream_shape_ok(int T, int d, int G, int E, int gpw);
 // decode-sized batches: K-split gate, then its second step and the grouping fused in one workgroup
 constexpr int kFusedMaxTiles = 2;
 constexpr size_t kFusedMaxLds = 48 * 1024;   // dynamic LDS of the fused kernel (logits of all pairs)

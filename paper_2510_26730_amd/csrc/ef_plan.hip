@@ -71,7 +71,9 @@ int run_gates(ef_ctx *c, int layer, const void *hidden, int T, float beta, bool 
         }
         a.part = rs.gate_part;
         a.tsplit = 1;
-        {   // the two-kernel form also pays off without a K split when the per-token part dominates
+        // batches of many token tiles stream the hidden states through LDS in one kernel (no second step)
+        a.stream = (c->tune.gate_stream != 0 && a.ksplit == 1 && ef::gate_stream_shape_ok(T, d, a.G, E, a.gpw)) ? 1 : 0;
+        if (!a.stream) {   // the two-kernel form also pays off without a K split when the per-token part dominates
             const int ts = ef::gate_pick_tsplit(T, a.G, E, a.gpw);
             const size_t need = (size_t)ntiles * ((a.G + a.gpw - 1) / a.gpw) * a.ksplit * ef::kTile * 128;
             if (ts > 1 && need <= rs.gate_part_floats && c->tune.gate_token_split != 0) a.tsplit = ts;

@@ -52,7 +52,7 @@ __device__ __forceinline__ T pick(const T (&arr)[kMaxGates], int idx) {
     return v;
 }
 
-template <int NB>
+template <int NB, int NW = kGateWaves>
 __device__ __forceinline__ void gate_epilogue(const GateArgs &a, float (*logits)[NB * 32 + 1], int *cnt,
                                               const float *sbias, float (*s_sc)[64],
                                               int tile, int g0, int Gl, int tok_lo, int tok_n, bool shared_tile);
@@ -248,14 +248,14 @@ __global__ __launch_bounds__(64 * kGateWaves) void gate_kernel(GateArgs a) {
 
 // per-token part of the gate kernels: selection scores, biased top-k, combine weights, counts.
 // `logits` holds the tile's router logits without the gate bias (sbias), `cnt` is zeroed.
-template <int NB>
+template <int NB, int NW>
 __device__ __forceinline__ void gate_epilogue(const GateArgs &a, float (*logits)[NB * 32 + 1], int *cnt,
                                               const float *sbias, float (*s_sc)[64],
                                               int tile, int g0, int Gl, int tok_lo, int tok_n, bool shared_tile) {
     // tokens tok_lo .. tok_lo + tok_n - 1 of the tile (tok_n a multiple of the tokens per wave round);
     // shared_tile: other workgroups handle the tile's other tokens, so per-tile counts are added
-    // atomically to the (zeroed) table instead of stored
-    constexpr int NW = kGateWaves, NT = 64 * NW;
+    // atomically to the (zeroed) table instead of stored.  NW waves per workgroup.
+    constexpr int NT = 64 * NW;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int t0 = tile * kTile;
     const int N = Gl * a.E;
@@ -336,6 +336,212 @@ __device__ __forceinline__ void gate_epilogue(const GateArgs &a, float (*logits)
             else if (cnt[x] > 0) atomicAdd(&a.blockcounts[(size_t)tile * a.E + ee], cnt[x]);
         }
     }
+}
+
+// ------------------------------------------------------------------------------------------
+// gate for batches of many token tiles (every compute unit has at least one tile of its own, no K split):
+// bound by streaming the hidden states from HBM once.  A stage of KC columns of a 32-token tile is brought
+// into LDS by direct global -> LDS loads (no staging registers, no LDS store instructions), each wave
+// instruction copying 1 KiB (KC = 256: 512 contiguous bytes of two rows; KC = 512: one row), NS stages deep,
+// OCC workgroups per compute unit.
+// The gate rows of the stage come the same way (only the rows that exist; a workgroup re-reads them from
+// L2, a quarter or less of the bytes of its hidden states for E <= 8).  The k-steps of a stage are dealt to
+// the four waves, whose partial tiles meet in a fixed-order tree through LDS before the per-token epilogue
+// (the one of gate_kernel).  Every workgroup walks the stages in its own rotated order: with a common order
+// all workgroups would read the same column block of their 8 KiB-strided rows at the same time, and those
+// addresses share most of their channel-select bits.
+//
+// LDS layout: 1 KiB blocks as the loads deliver them, 1040 bytes apart, so that the 16-byte operand reads of
+// 16 consecutive rows cover all 64 banks.  With KC = 256 a block holds the stage's 512 bytes of rows j and
+// j + 16 of a 32-row block.  CB = gate-row loads per wave and stage (4 * CB blocks of gate rows per stage).
+// ------------------------------------------------------------------------------------------
+constexpr int kGsBlock = 1024 + 16;        // bytes between the 1 KiB blocks in LDS
+constexpr int kGsWaves = 4;
+constexpr int gs_waitcnt(int vm) { return (((vm >> 4) & 3) << 14) | (0x7 << 4) | (0xF << 8) | (vm & 15); }
+// as many stages as the LDS of a compute unit holds for OCC workgroups beside the epilogue's arrays, at most 4
+constexpr int gs_stages(int NB, int KC, int CB, int OCC) {
+    const int stage = (32 / (512 / KC) + 4 * CB) * kGsBlock;
+    const int budget = 160 * 1024 / OCC - (kTile * (NB * 32 + 1) * 4 + 2048);
+    return budget / stage >= 4 ? 4 : budget / stage;
+}
+
+template <int NB, int CB, int KC, int OCC>
+__global__ __launch_bounds__(64 * kGsWaves, OCC) void gate_stream_kernel(GateArgs a) {
+    constexpr int NW = kGsWaves, NT = 64 * NW;
+    constexpr int RPB = 512 / KC;                     // rows per block: 1 (KC = 512) or 2 (KC = 256)
+    constexpr int BLOCKS = 32 / RPB;                  // blocks of a 32-row tile
+    constexpr int LPR = 64 / RPB;                     // lanes per row in a load
+    constexpr int AL = BLOCKS / NW;                   // hidden-state loads per wave and stage
+    constexpr int BBLOCKS = 4 * CB;                   // gate-row blocks per stage
+    constexpr int A_BYTES = BLOCKS * kGsBlock, STAGE = A_BYTES + BBLOCKS * kGsBlock;
+    constexpr int NS = gs_stages(NB, KC, CB, OCC);
+    constexpr int LPS = AL + CB;                      // loads per wave and stage
+    constexpr int KSW = KC / 16 / NW;                 // k-steps per wave and stage
+    constexpr int RED_FLOATS = NB * 16 * 64;          // one wave's partial tile
+    static_assert(KC == 256 || KC == 512, "stage width");
+    static_assert(BBLOCKS <= NB * BLOCKS, "more gate-row blocks than columns");
+    static_assert(NS >= 2 && (NS - 2) * LPS <= 63, "stages / wait count out of range");
+    static_assert(2 * RED_FLOATS * 4 <= NS * STAGE, "the reduction reuses the stage buffers");
+    __shared__ __attribute__((aligned(16))) unsigned char stage[NS * STAGE];
+    __shared__ float logits[kTile][NB * 32 + 1];
+    __shared__ int cnt[4 * 32];
+    __shared__ float sbias[4 * 32];
+    __shared__ __attribute__((aligned(16))) float s_sc[NW][64];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS targets go through M0
+    const int g = lane >> 5, i = lane & 31;
+    const int tile = blockIdx.x;
+    const int g0 = blockIdx.y * a.gpw;
+    const int Gl = min(a.gpw, a.G - g0);
+    const int t0 = tile * kTile;
+    const int N = Gl * a.E;                            // logit columns of the group (<= NB*32)
+    const int nstage = a.d / KC;
+    const int rot0 = (tile * 5 + (int)blockIdx.y * 3) % nstage;
+
+    for (int x = tid; x < NB * 32; x += NT) cnt[x] = 0;
+    for (int x = tid; x < N; x += NT) {
+        const float *bp = pick(a.bias, g0 + x / a.E);
+        sbias[x] = bp ? bp[x % a.E] : 0.f;
+    }
+
+    // per-lane sources of this wave's loads of a stage (column offset of the stage added at issue)
+    const int sub = lane / LPR, c8 = (lane % LPR) * 8;
+    const uint16_t *srcA[AL];
+#pragma unroll
+    for (int q = 0; q < AL; ++q) {
+        const int row = wave * AL + q + BLOCKS * sub;  // rows past T re-read the last token (results dropped)
+        srcA[q] = a.h + (size_t)min(t0 + row, a.T - 1) * a.d + c8;
+    }
+    const uint16_t *srcB[CB];
+#pragma unroll
+    for (int q = 0; q < CB; ++q) {
+        const int b = wave * CB + q;                   // block b: rows n1 (+ BLOCKS) of 32-row block b / BLOCKS
+        const int n1 = (b / BLOCKS) * 32 + b % BLOCKS;
+        int n = n1 + BLOCKS * sub;
+        if (n >= N) n = n1 < N ? n1 : 0;               // rows that do not exist alias one that does (same cache lines)
+        srcB[q] = pick(a.Wg, g0 + n / a.E) + (size_t)(n % a.E) * a.d + c8;
+    }
+    const unsigned lds_base = (unsigned)(size_t)&stage[0];   // LDS byte offset: the low half of its flat address
+#define EF_GS_DMA(gptr, lds_off)                                                                     \
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_off) : "memory")
+    // every wave issues LPS loads per stage, unconditionally (past the end the last stage is re-read, in
+    // bounds, into a buffer nobody reads any more), so "my loads of stage st have landed" is a constant count
+#define EF_GS_ISSUE(st)                                                                              \
+    {                                                                                                \
+        int stc_ = min((st), nstage - 1) + rot0;                                                     \
+        if (stc_ >= nstage) stc_ -= nstage;                                                          \
+        const unsigned buf_ = lds_base + (unsigned)(((st) % NS) * STAGE);                            \
+        _Pragma("unroll") for (int q = 0; q < AL; ++q)                                               \
+            EF_GS_DMA(srcA[q] + stc_ * KC, buf_ + (unsigned)((wave * AL + q) * kGsBlock));           \
+        _Pragma("unroll") for (int q = 0; q < CB; ++q)                                               \
+            EF_GS_DMA(srcB[q] + stc_ * KC, buf_ + (unsigned)(A_BYTES + (wave * CB + q) * kGsBlock)); \
+    }
+
+    floatx16 acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) zero16(acc[nb]);
+
+#pragma unroll
+    for (int p = 0; p < NS - 1; ++p) EF_GS_ISSUE(p)
+    // operand reads of lane (g, i): row i of a 32-row block sits in block i % BLOCKS at (i / BLOCKS) * 2 KC bytes;
+    // columns 8g.. of a k-step.  Gate rows past the blocks that are loaded read block 0 (their columns are dropped).
+    const int a_off = (i % BLOCKS) * kGsBlock + (i / BLOCKS) * (2 * KC) + 16 * g;
+    int b_off[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int b = nb * BLOCKS + i % BLOCKS;
+        b_off[nb] = A_BYTES + (b < BBLOCKS ? b : 0) * kGsBlock + (i / BLOCKS) * (2 * KC) + 16 * g;
+    }
+    for (int st = 0; st < nstage; ++st) {
+        __builtin_amdgcn_s_waitcnt(gs_waitcnt((NS - 2) * LPS));   // my loads of stage st have landed
+        __syncthreads();   // ... and everybody else's; all reads of stage st - 1 are done: its buffer is free
+        EF_GS_ISSUE(st + NS - 1)
+        const unsigned char *sb = stage + (st % NS) * STAGE;
+#pragma unroll
+        for (int q = 0; q < KSW; ++q) {
+            const int kb = (wave * KSW + q) * 32;          // byte offset of the k-step inside a row
+            const u32x4_t af = *reinterpret_cast<const u32x4_t *>(sb + a_off + kb);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const u32x4_t bf = *reinterpret_cast<const u32x4_t *>(sb + b_off[nb] + kb);
+                acc[nb] = mfma32v(af, bf, acc[nb]);
+            }
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(gs_waitcnt(0));   // the re-read stages past the end have landed too
+    __syncthreads();
+#undef EF_GS_DMA
+#undef EF_GS_ISSUE
+
+    // fixed-order tree over the waves' partial tiles through LDS: (w, w+2), then (0, 1)
+    float *red = reinterpret_cast<float *>(stage);
+    auto put = [&](int region) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) red[region * RED_FLOATS + (nb * 16 + v) * 64 + lane] = acc[nb][v];
+    };
+    auto add = [&](int region) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[nb][v] += red[region * RED_FLOATS + (nb * 16 + v) * 64 + lane];
+    };
+    if (wave >= 2) put(wave - 2);
+    __syncthreads();
+    if (wave < 2) add(wave);
+    __syncthreads();
+    if (wave == 1) put(0);
+    __syncthreads();
+    if (wave == 0) {
+        add(0);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) logits[8 * (v >> 2) + 4 * g + (v & 3)][nb * 32 + i] = acc[nb][v];
+    }
+    __syncthreads();
+    gate_epilogue<NB, NW>(a, logits, cnt, sbias, s_sc, tile, g0, Gl, 0, kTile, false);
+}
+
+// whether a launch takes the streaming form: no K split or two-step form, whole stages, at most 64 logit
+// columns per workgroup, and enough (tile, gate group) pairs that every compute unit streams
+bool gate_stream_shape_ok(int T, int d, int G, int E, int gpw) {
+    const int ntiles = (T + kTile - 1) / kTile;
+    const int ngroups = (G + gpw - 1) / gpw;
+    const int nb = (std::min(gpw, G) * E + 31) / 32;
+    return d % 256 == 0 && nb <= 2 && (long long)ntiles * ngroups >= 192;
+}
+bool gate_stream_ok(const GateArgs &a) {
+    return !a.two_step && a.ksplit == 1 && a.tsplit == 1 && gate_stream_shape_ok(a.T, a.d, a.G, a.E, a.gpw);
+}
+
+static hipError_t launch_gate_stream(const GateArgs &a, hipStream_t s) {
+    const int ntiles = (a.T + kTile - 1) / kTile;
+    const int ngroups = (a.G + a.gpw - 1) / a.gpw;
+    const int n_max = std::min(a.gpw, a.G) * a.E;        // most logit columns of a gate group
+    const dim3 grid(ntiles, ngroups), block(64 * kGsWaves);
+    // stages of 512 columns (1 KiB per row and load) while the gate rows leave room for three of them in LDS
+    // Two workgroups per compute unit wherever two pipelines of at least two stages fit its LDS: one's fill,
+    // wave reduction and per-token epilogue then overlap the other's streaming (4.5 -> 6.2 TB/s of hidden states
+    // at 131072 tokens and 8 logit columns).  Stages of 256 columns: with 512 the same LDS holds fewer stages
+    // and the kernel is slower even at one workgroup per unit (4.5 against 5.0 TB/s).
+    // With fewer than two workgroups per compute unit in the launch there is nothing to overlap with, and the
+    // deeper pipeline of the single-workgroup form is worth more (8192 tokens with 16 columns: 21 against 23 us).
+    const bool two = (long long)ntiles * ngroups >= 512;
+    if (n_max > 32) hipLaunchKernelGGL((gate_stream_kernel<2, 8, 256, 1>), grid, block, 0, s, a);
+    else if (n_max > 8) {
+        if (two) hipLaunchKernelGGL((gate_stream_kernel<1, 4, 256, 2>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((gate_stream_kernel<1, 4, 256, 1>), grid, block, 0, s, a);
+    } else if (n_max > 4) {
+        if (two) hipLaunchKernelGGL((gate_stream_kernel<1, 2, 256, 2>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((gate_stream_kernel<1, 2, 256, 1>), grid, block, 0, s, a);
+    } else {
+        if (two) hipLaunchKernelGGL((gate_stream_kernel<1, 1, 256, 2>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((gate_stream_kernel<1, 1, 256, 1>), grid, block, 0, s, a);
+    }
+    return hipGetLastError();
 }
 
 // second step of the K-split form: adds the partial logits of the splits in ascending order
@@ -432,6 +638,7 @@ hipError_t launch_gate(const GateArgs &a, hipStream_t s) {
     if (a.ksplit < 1 || (a.ksplit > 1 && !a.two_step) || (a.two_step && !a.part)) return hipErrorInvalidValue;
     if (a.tsplit != 1 && a.tsplit != 2 && a.tsplit != 4) return hipErrorInvalidValue;
     if (a.tsplit > 1 && !a.two_step) return hipErrorInvalidValue;
+    if (a.stream && gate_stream_ok(a)) return launch_gate_stream(a, s);
     const int nb = (std::min(a.gpw, a.G) * a.E + 31) / 32;
     switch (nb) {
         case 1: return launch_gate_nb<1>(a, s);
@@ -445,24 +652,6 @@ hipError_t launch_gate(const GateArgs &a, hipStream_t s) {
 // ------------------------------------------------------------------------------------------
 // stable grouping by expert: per-tile counts (from the gate kernel) -> scan -> scatter
 // ------------------------------------------------------------------------------------------
-
-// one wave: exclusive prefix over the tiles of expert e, returns the total
-__device__ __forceinline__ int scan_expert(const int32_t *__restrict__ bc, int ntiles, int E, int e, int lane,
-                                           int32_t *__restrict__ base_out) {
-    int carry = 0;
-    for (int c0 = 0; c0 < ntiles; c0 += 64) {
-        int b = c0 + lane;
-        int v = b < ntiles ? bc[(size_t)b * E + e] : 0;
-        int incl = v;
-        for (int off = 1; off < 64; off <<= 1) {
-            int o = __shfl_up(incl, off);
-            if (lane >= off) incl += o;
-        }
-        if (b < ntiles) base_out[(size_t)b * E + e] = carry + incl - v;
-        carry += __shfl(incl, 63);
-    }
-    return carry;
-}
 
 // the same scan on counts already in LDS, in place: counts[b*E + e] becomes the exclusive prefix
 __device__ __forceinline__ int scan_expert_inplace(int *cnt, int ntiles, int E, int e, int lane) {
@@ -540,39 +729,77 @@ __device__ __forceinline__ void export_meta(const GroupExport &ex, const int *to
     for (int x = threadIdx.x; x < ex.n_clear; x += blockDim.x) ex.hist[x] = 0;   // ready for the next layer
 }
 
+// Batches of more than kGroupSmallTiles token tiles: one workgroup per expert forms the exclusive prefix of
+// that expert's per-tile counts over the tiles (16 waves, a contiguous range of tiles each: totals first,
+// then the scan with the bases of the waves before), and leaves the expert's total in counts[e].
 __global__ __launch_bounds__(1024) void group_scan_kernel(const int32_t *__restrict__ bc, int ntiles, int E,
                                                           int32_t *__restrict__ blockbase,
-                                                          int32_t *__restrict__ counts,
-                                                          int32_t *__restrict__ offsets, GroupExport ex) {
-    __shared__ int total[kMaxE];
+                                                          int32_t *__restrict__ counts) {
+    __shared__ int wtot[16];
+    const int e = blockIdx.x;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    for (int e = wave; e < E; e += 16) {
-        int tot = scan_expert(bc, ntiles, E, e, lane, blockbase);
-        if (lane == 0) total[e] = tot;
-    }
+    const int per = (((ntiles + 15) / 16 + 63) / 64) * 64;     // tiles per wave, whole chunks of 64
+    const int lo = min(ntiles, wave * per), hi = min(ntiles, lo + per);
+    int sum = 0;
+    for (int b = lo + lane; b < hi; b += 64) sum += bc[(size_t)b * E + e];
+    for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
+    if (lane == 0) wtot[wave] = sum;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        int run = 0;
-        for (int e = 0; e < E; ++e) {
-            counts[e] = total[e];
-            offsets[e] = run;
-            run += total[e];
-        }
-        offsets[E] = run;
+    int carry = 0, all = 0;
+    for (int w = 0; w < 16; ++w) {
+        if (w < wave) carry += wtot[w];
+        all += wtot[w];
     }
-    export_meta(ex, total, E);
+    for (int c0 = lo; c0 < hi; c0 += 64) {
+        const int b = c0 + lane;
+        const int v = b < hi ? bc[(size_t)b * E + e] : 0;
+        int incl = v;
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(incl, off);
+            if (lane >= off) incl += o;
+        }
+        if (b < hi) blockbase[(size_t)b * E + e] = carry + incl - v;
+        carry += __shfl(incl, 63);
+    }
+    if (threadIdx.x == 0) counts[e] = all;
 }
 
-__global__ __launch_bounds__(64) void group_scatter_kernel(const int32_t *__restrict__ ids, int T, int k, int E,
-                                                           const int32_t *__restrict__ blockbase,
-                                                           const int32_t *__restrict__ offsets,
-                                                           int32_t *__restrict__ perm,
-                                                           int32_t *__restrict__ inv_perm) {
-    __shared__ int nxt[64];
-    const int b = blockIdx.x, lane = threadIdx.x;
-    nxt[lane] = (lane < E) ? offsets[lane] + blockbase[(size_t)b * E + lane] : 0;
+// ... then one wave per token tile scatters: every wave forms the exclusive prefix of the experts' totals (E <= 64
+// lanes) itself; the first workgroup also writes `offsets` and hands counts and histograms to the host.
+constexpr int kScatterWaves = 4;
+__global__ __launch_bounds__(64 * kScatterWaves) void group_scatter_kernel(const int32_t *__restrict__ ids, int T, int k, int E,
+                                                                           int ntiles,
+                                                                           const int32_t *__restrict__ blockbase,
+                                                                           const int32_t *__restrict__ counts,
+                                                                           int32_t *__restrict__ offsets,
+                                                                           int32_t *__restrict__ perm,
+                                                                           int32_t *__restrict__ inv_perm, GroupExport ex) {
+    __shared__ int nxt[kScatterWaves][64];
+    __shared__ int total[kMaxE];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int t = lane < E ? counts[lane] : 0;
+    int incl = t;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(incl, off);
+        if (lane >= off) incl += o;
+    }
+    if (blockIdx.x == 0) {   // uniform over the workgroup
+        if (wave == 0) {
+            if (lane < E) {
+                offsets[lane] = incl - t;
+                total[lane] = t;
+            }
+            if (lane == 63) offsets[E] = incl;
+        }
+        __syncthreads();
+        export_meta(ex, total, E);
+    }
+    const int b = blockIdx.x * kScatterWaves + wave;
+    if (b >= ntiles) return;
+    nxt[wave][lane] = (lane < E) ? (incl - t) + blockbase[(size_t)b * E + lane] : 0;
     wave_lds_sync();
-    scatter_tile(ids, T, k, b, lane, nxt, perm, inv_perm);
+    scatter_tile(ids, T, k, b, lane, nxt[wave], perm, inv_perm);
 }
 
 // scan + scatter in one workgroup for up to kGroupSmallTiles token tiles (prefixes stay in LDS)
@@ -836,12 +1063,11 @@ hipError_t launch_group(const int32_t *blockcounts, const int32_t *ids, int T, i
                            counts, offsets, perm, inv_perm, ex);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(group_scan_kernel, dim3(1), dim3(1024), 0, s, blockcounts, ntiles, E, blockbase, counts,
-                       offsets, ex);
+    hipLaunchKernelGGL(group_scan_kernel, dim3(E), dim3(1024), 0, s, blockcounts, ntiles, E, blockbase, counts);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(group_scatter_kernel, dim3(ntiles), dim3(64), 0, s, ids, T, k, E, blockbase, offsets, perm,
-                       inv_perm);
+    hipLaunchKernelGGL(group_scatter_kernel, dim3((ntiles + kScatterWaves - 1) / kScatterWaves), dim3(64 * kScatterWaves),
+                       0, s, ids, T, k, E, ntiles, blockbase, counts, offsets, perm, inv_perm, ex);
     return hipGetLastError();
 }
 
