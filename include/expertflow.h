@@ -125,13 +125,12 @@ typedef struct ef_stats {
     int64_t prefetch_redundant; /* prefetch requests for experts already resident ("overfetch") */
     int64_t evictions;
     int64_t bytes_copied;       /* host-to-device expert bytes */
-    int64_t bytes_timed;        /* bytes of the copies that copy_seconds covers: a copy whose slot is handed to
-                                   the next copy before it was seen complete is counted above but not timed */
+    int64_t bytes_timed;        /* bytes of the copy chunks that copy_seconds covers (chunks that followed another
+                                   chunk on the link without a gap: their time is transfer time) */
     int64_t layers_run;         /* ef_moe_ffn calls */
     int64_t tokens_run;         /* sum of T over ef_moe_ffn calls */
-    double copy_seconds;        /* summed duration of the timed copies (copy-stream events around each copy; copies
-                                   on the two copy streams overlap and share the link, so bytes_timed /
-                                   copy_seconds is the mean rate of one copy, not the link's aggregate) */
+    double copy_seconds;        /* summed duration of the timed chunks (copy-stream events between consecutive
+                                   chunks): bytes_timed / copy_seconds is the rate the link sustains */
     double stall_seconds;       /* time the compute stream spent waiting for swap-ins */
     double layer_seconds;       /* summed ef_route..ef_moe_ffn layer time (compute-stream events) */
     double bandwidth_Bps;       /* current C_s estimate */
@@ -140,6 +139,17 @@ typedef struct ef_stats {
     int32_t horizon;            /* current look-ahead S */
     int32_t stall_counter, overfetch_counter;
     int32_t reserved_;
+    int64_t prefetch_used;      /* prefetched experts that a layer then used (counted at their first use) */
+    int64_t prefetch_wasted;    /* prefetched experts evicted before any layer used them (the overfetch the
+                                   feedback loop of paper Sec. 3.2.2 reacts to) */
+    int64_t miss_copies;        /* priority copies (misses, and prefetches a layer caught still in the queue) */
+    int64_t miss_copy_bytes;
+    double miss_copy_seconds;   /* summed time from a priority copy's request to its completion: miss_copy_bytes /
+                                   miss_copy_seconds is the rate a miss sees while prefetches are queued */
+    /* Prediction quality against look-ahead distance (the trend of paper Sec. 4.3): of the experts layer l really
+     * used, how many had the look-ahead made j layers earlier named (predicted demand > 0)?  Index j-1. */
+    int64_t pred_overlap_hits[EF_MAX_HORIZON];
+    int64_t pred_overlap_total[EF_MAX_HORIZON];
     /* EF_FLAG_PROFILE only: summed event time, launches, algorithmic bytes (minimal HBM traffic the
      * operation needs: operands read once, results written once) and, for the matrix-core kernels,
      * algorithmic flops (2 per multiply-add of the contraction, padding rows not counted) per kind */
@@ -283,10 +293,16 @@ int ef_moe_ffn(ef_ctx *ctx, int layer, const void *hidden, int T,
 
 /*
  * Make (layer, expert) resident in the HBM cache: pick a slot (free, else the two-level LRU's
- * victim: low tier first, paper Sec. 3.3.1), copy the blob from the pinned store on the copy
- * stream and record its ready event.  priority 0 = prefetch, due_in = layers until it is needed;
- * priority 1 = miss of the layer being run (due_in ignored).  An expert already resident is only
- * promoted.  *slot_out (may be NULL) receives the slot.  Returns EF_EBUSY if no slot can be evicted.
+ * victim: low tier first, paper Sec. 3.3.1) and queue the copy of the blob from the pinned store.
+ * priority 0 = prefetch, due_in = layers until it is needed; priority 1 = miss of the layer being
+ * run (due_in ignored).  An expert already resident is only promoted.  *slot_out (may be NULL)
+ * receives the slot.  Returns EF_EBUSY if no slot can be evicted.
+ *
+ * Copies go over one link, so the library keeps one queue (paper Sec. 3.4: miss resolution gets the
+ * highest priority in the memory queue): a worker thread of the context hands the copies to the copy
+ * stream in chunks of at most copy_chunk_mib, at most copy_depth chunks ahead, and always takes the
+ * oldest priority-1 copy before any prefetch; a prefetch a layer needs while it is still queued is
+ * promoted.  The call itself returns at once.
  */
 int ef_cache_swap_in(ef_ctx *ctx, int layer, int expert, int priority, int due_in, int *slot_out);
 
@@ -489,6 +505,9 @@ typedef struct ef_tuning {
     int32_t gate_fused_finish;       /* 0/1: decode-sized batches fuse the gate's second step with the grouping (1) */
     int32_t gate_stream;             /* 0/1: batches of many token tiles take the gate kernel that streams through LDS (1) */
     int32_t early_pack;              /* 0/1: ef_layer_step enqueues the token packing before the host has the counts (1) */
+    int32_t copy_chunk_mib;          /* 1..1024: expert copies go to the link in chunks of at most this many MiB; a miss
+                                        overtakes queued prefetches at the next chunk boundary (32) */
+    int32_t copy_depth;              /* 1..8: chunks handed to the copy stream ahead of the one in transfer (2) */
 } ef_tuning;
 int ef_get_tuning(ef_ctx *ctx, ef_tuning *out);
 int ef_set_tuning(ef_ctx *ctx, const ef_tuning *t);

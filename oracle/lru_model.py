@@ -15,14 +15,26 @@ are never evicted.  Inside ``high`` (only reached when ``low`` has no
 candidate) entries that no prediction is waiting for go first, least recently
 used first; if every candidate is still awaited, the one due furthest ahead
 goes (latest stamp among equals).
+
+One pool for all layers (no per-layer cap in force): a decode loop visits the
+layers cyclically, so plain recency order would evict what runs next (the
+premature eviction of the first layers' experts the section gives as the
+motivation of the two tiers).  Among the candidates of a tier the victim then
+comes from the layer holding the most entries, provided that is more than
+``top_k``; equal there, from the layer whose next turn in the cycle is furthest
+away; equal there, the least recently used.  ``advance(layer_run)`` tells the
+model which layer just ran.
 """
 from __future__ import annotations
 
 
 class TwoLevelLRU:
-    def __init__(self, slots_total: int, per_layer_cap: int = 0):
+    def __init__(self, slots_total: int, per_layer_cap: int = 0, n_layers: int = 1, top_k: int = 1):
         self.slots_total = slots_total
         self.cap = per_layer_cap
+        self.n_layers = n_layers
+        self.top_k = top_k
+        self.next_layer = 0
         self.entries = {}      # (layer, expert) -> dict(stamp, last_use, due, high, pinned)
         self.clock = 0
         self.S = 1
@@ -48,9 +60,11 @@ class TwoLevelLRU:
         for e in self.entries.values():
             e["high"] = self._is_high(e)
 
-    def advance(self, S=None):
-        """One layer executed; optionally a new look-ahead S.  Re-tiers everything."""
+    def advance(self, S=None, layer_run=None):
+        """One layer executed (layer_run: which one); optionally a new look-ahead S.  Re-tiers everything."""
         self.clock += 1
+        if layer_run is not None:
+            self.next_layer = (layer_run + 1) % self.n_layers
         if S is not None:
             self.S = S
         self.retier()
@@ -73,21 +87,33 @@ class TwoLevelLRU:
     def _victim(self, layer):
         keys = list(self.entries)
         in_layer = [k for k in keys if k[0] == layer]
+        pooled = False
         if self.cap and len(in_layer) >= self.cap:
             cand = in_layer
         elif len(keys) < self.slots_total:
             return None, True
         else:
             cand = keys
+            pooled = True
         cand = [k for k in cand if not self.entries[k]["pinned"]]
         if not cand:
             return None, False
+
+        def order(k):
+            """Smallest goes first."""
+            if not pooled:
+                return (0, 0, self.entries[k]["stamp"])
+            held = sum(1 for q in keys if q[0] == k[0])
+            crowd = held if held > self.top_k else 0
+            turn = (k[0] - self.next_layer) % self.n_layers
+            return (-crowd, -turn, self.entries[k]["stamp"])
+
         low = [k for k in cand if not self.entries[k]["high"]]
         if low:
-            return min(low, key=lambda k: self.entries[k]["stamp"]), True
+            return min(low, key=order), True
         idle = [k for k in cand if self.entries[k]["due"] < self.clock]
         if idle:
-            return min(idle, key=lambda k: self.entries[k]["stamp"]), True
+            return min(idle, key=order), True
         # every candidate is awaited by a prediction: give up the one needed last
         return max(cand, key=lambda k: (self.entries[k]["due"], self.entries[k]["stamp"])), True
 

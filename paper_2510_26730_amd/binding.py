@@ -58,6 +58,9 @@ class ef_stats(C.Structure):
         ("stall_seconds", C.c_double), ("layer_seconds", C.c_double), ("bandwidth_Bps", C.c_double),
         ("layer_seconds_est", C.c_double), ("miss_rate", C.c_double), ("horizon", C.c_int32),
         ("stall_counter", C.c_int32), ("overfetch_counter", C.c_int32), ("reserved_", C.c_int32),
+        ("prefetch_used", C.c_int64), ("prefetch_wasted", C.c_int64), ("miss_copies", C.c_int64),
+        ("miss_copy_bytes", C.c_int64), ("miss_copy_seconds", C.c_double),
+        ("pred_overlap_hits", C.c_int64 * 7), ("pred_overlap_total", C.c_int64 * 7),
         ("kernel_seconds", C.c_double * 10), ("kernel_bytes", C.c_double * 10),
         ("kernel_launches", C.c_int64 * 10), ("kernel_flops", C.c_double * 10),
     ]
@@ -75,7 +78,7 @@ class ef_tuning(C.Structure):
         "tiled", "tiled_min_tiles", "tiled_min_up_wgs", "tiled_min_down_wgs", "tiled_xcd_rotation", "overlap_tiled",
         "sort_groups", "passes_of_four", "lds_shared", "lds_shared_occupancy", "up_want_waves", "up_k_slices",
         "down_want_wgs", "down_k_slices", "down_slices_by_longest_k", "down_split_slice_counts", "gate_k_split",
-        "gate_token_split", "gate_fused_finish", "gate_stream", "early_pack")]
+        "gate_token_split", "gate_fused_finish", "gate_stream", "early_pack", "copy_chunk_mib", "copy_depth")]
 
 
 class ef_forest_config(C.Structure):

@@ -172,19 +172,17 @@ extern "C" int ef_pack_expert_q4(const uint8_t *q1, const uint16_t *s1, const ui
 extern "C" int ef_destroy(ef_ctx *c) {
     if (!c) return EF_OK;
     if (!c->fake) {
+        copy_engine_stop(c);      // the worker thread first: it uses the copy stream and the slot events
         (void)hipDeviceSynchronize();
-        for (auto &s : c->slots) {
-            if (s.copy_start) (void)hipEventDestroy(s.copy_start);
+        for (auto &s : c->slots)
             if (s.ready) (void)hipEventDestroy(s.ready);
-        }
         for (auto e : c->read_ring) (void)hipEventDestroy(e);
         for (auto e : c->fork_ring) (void)hipEventDestroy(e);
         if (c->side_stream) (void)hipStreamDestroy(c->side_stream);
         for (auto &p : c->stall_ring) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
         for (auto &p : c->layer_ring) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
         for (auto &p : c->prof_ring) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
-        for (int q = 0; q < 2; ++q)
-            if (c->copy_stream[q]) (void)hipStreamDestroy(c->copy_stream[q]);
+        if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
         if (c->pool) (void)hipFree(c->pool);
         if (c->blockcounts) (void)hipFree(c->blockcounts);
         if (c->blockbase) (void)hipFree(c->blockbase);
@@ -237,8 +235,12 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
     c->expert_bytes = c->q4 ? ef_expert_bytes_q4(g.d_model, g.d_ff) : ef_expert_bytes(g.d_model, g.d_ff);
     c->fake = (g.flags & EF_FLAG_FAKE_COPY) != 0;
     c->layers.resize((size_t)g.n_layers);
-    c->cache = new ef::ExpertCache(g.slots_total, g.slots_per_layer_max, g.n_layers, g.n_experts);
+    c->cache = new ef::ExpertCache(g.slots_total, g.slots_per_layer_max, g.n_layers, g.n_experts, g.top_k);
     c->slots.resize((size_t)g.slots_total);
+    c->pred_mask.assign((size_t)g.n_layers * EF_MAX_HORIZON, 0);
+    c->pred_valid.assign((size_t)g.n_layers * EF_MAX_HORIZON, 0);
+    c->eng.chunk_bytes = (size_t)c->tune.copy_chunk_mib << 20;
+    c->eng.depth = c->tune.copy_depth;
     if (g.init_bandwidth_gbps > 0.f) c->bw_Bps = (double)g.init_bandwidth_gbps * 1e9;
     if (g.init_layer_us > 0.f) c->layer_s = (double)g.init_layer_us * 1e-6;
     c->horizon = 1;
@@ -317,9 +319,8 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
         if ((e = hipHostGetDevicePointer(reinterpret_cast<void **>(&c->meta_dev), c->meta_host, 0)) != hipSuccess)
             return bail(e, "host-mapped hand-over buffer");
     }
-    for (int q = 0; q < 2; ++q)
-        if ((e = hipStreamCreateWithFlags(&c->copy_stream[q], hipStreamNonBlocking)) != hipSuccess)
-            return bail(e, "copy stream");
+    if ((e = hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking)) != hipSuccess)
+        return bail(e, "copy stream");
     {   // resolve the address of ef_route_static's scratch on this device now, so that the call itself never has to
         EfRouteScratch rs{};
         if (static_route_scratch(c, &rs) != EF_OK) {
@@ -329,10 +330,8 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
             return EF_EHIP;
         }
     }
-    for (auto &s : c->slots) {
-        if ((e = hipEventCreate(&s.copy_start)) != hipSuccess) return bail(e, "event");
-        if ((e = hipEventCreate(&s.ready)) != hipSuccess) return bail(e, "event");
-    }
+    for (auto &s : c->slots)
+        if ((e = hipEventCreateWithFlags(&s.ready, hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
     c->read_ring.resize(128);
     for (auto &ev : c->read_ring)
         if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
@@ -350,6 +349,12 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
             if ((e = hipEventCreate(&p.a)) != hipSuccess) return bail(e, "event");
             if ((e = hipEventCreate(&p.b)) != hipSuccess) return bail(e, "event");
         }
+    if (copy_engine_start(c) != EF_OK) {
+        std::string keep = thread_error();
+        ef_destroy(c);
+        set_thread_error(keep);
+        return EF_EHIP;
+    }
     *out = c;
     return EF_OK;
 }
@@ -578,7 +583,8 @@ extern "C" int ef_layer_step(ef_ctx *c, int layer, const void *hidden, int T, fl
 extern "C" int ef_get_stats(ef_ctx *c, ef_stats *out) {
     if (!c || !out) return fail(c, EF_EINVAL, "ef_get_stats: null pointer");
     if (!c->fake) {
-        for (int q = 0; q < 2; ++q) (void)hipStreamSynchronize(c->copy_stream[q]);
+        int rc = copy_engine_drain(c);
+        if (rc) return rc;
         poll_pairs(c, true);
         poll_prof(c, true);
     }
@@ -677,6 +683,8 @@ void efi::tuning_defaults(ef_tuning *t) {
     t->gate_fused_finish = 1;
     t->gate_stream = 1;
     t->early_pack = 1;
+    t->copy_chunk_mib = 32;
+    t->copy_depth = 2;
 }
 
 extern "C" int ef_get_tuning(ef_ctx *c, ef_tuning *out) {
@@ -710,7 +718,14 @@ extern "C" int ef_set_tuning(ef_ctx *c, const ef_tuning *t) {
     else if (!flag(t->gate_fused_finish)) bad = "gate_fused_finish";
     else if (!flag(t->gate_stream)) bad = "gate_stream";
     else if (!flag(t->early_pack)) bad = "early_pack";
+    else if (t->copy_chunk_mib < 1 || t->copy_chunk_mib > 1024) bad = "copy_chunk_mib";
+    else if (t->copy_depth < 1 || t->copy_depth > 8) bad = "copy_depth";
     if (bad) return fail(c, EF_EINVAL, "ef_set_tuning: %s out of range", bad);
     c->tune = *t;
+    {
+        std::lock_guard<std::mutex> lock(c->eng.mu);     // the copy worker reads these
+        c->eng.chunk_bytes = (size_t)t->copy_chunk_mib << 20;
+        c->eng.depth = t->copy_depth;
+    }
     return EF_OK;
 }

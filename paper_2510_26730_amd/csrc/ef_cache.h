@@ -6,6 +6,15 @@
 // changes.  Readings where the paper is silent: the window is S layers; a prediction keeps an
 // entry high until the tick it is due; inside `high`, entries no prediction waits for go first
 // (least recently used first), and if every candidate is awaited the one due furthest ahead goes.
+//
+// One pool shared by all layers (no per-layer cap): a decode loop runs the layers in a cycle, so the least
+// recently used entry of the pool belongs to the layer that runs next, and plain recency order evicts exactly
+// what is needed soonest (the premature eviction of the first layers' experts that Sec. 3.3.1 names as the
+// motivation of the two tiers).  Among the candidates of a tier the victim is therefore taken (1) from the
+// layer that holds the most entries, as long as that is more than top_k (a layer needs top_k resident experts
+// before the residency bias can keep its tokens on them), (2) then from the layer whose next turn in the
+// cycle is furthest away, (3) then least recently used.  With a per-layer cap in force all candidates belong
+// to one layer and (3) alone decides, as before.
 #pragma once
 #include <cstdint>
 #include <vector>
@@ -25,8 +34,8 @@ enum class SwapResult { Hit, Load, Busy };
 
 class ExpertCache {
 public:
-    ExpertCache(int slots_total, int per_layer_cap, int n_layers, int n_experts)
-        : cap_(per_layer_cap), n_layers_(n_layers), n_experts_(n_experts),
+    ExpertCache(int slots_total, int per_layer_cap, int n_layers, int n_experts, int top_k = 1)
+        : cap_(per_layer_cap), n_layers_(n_layers), n_experts_(n_experts), top_k_(top_k),
           slots_((size_t)slots_total), map_((size_t)n_layers * n_experts, -1),
           per_layer_((size_t)n_layers, 0) {}
 
@@ -40,7 +49,12 @@ public:
         for (auto &e : slots_)
             if (e.layer >= 0) e.high = is_high(e);
     }
-    void advance() { ++clock_; retier(); }
+    // one layer executed (`layer_run`: which one, -1 = unknown; the next turn is then layer_run + 1, cyclically)
+    void advance(int layer_run = -1) {
+        ++clock_;
+        if (layer_run >= 0) next_layer_ = (layer_run + 1) % n_layers_;
+        retier();
+    }
     void set_S(int S) { S_ = S; retier(); }
 
     void touch(int slot) {
@@ -106,14 +120,24 @@ private:
             for (size_t s = 0; s < slots_.size(); ++s)
                 if (slots_[s].layer < 0) return (int)s;
         int best_low = -1, best_idle = -1, best_due = -1;
+        // true if entry a goes before entry b
+        auto before = [&](const CacheEntry &a, const CacheEntry &b) {
+            if (!layer_full) {
+                const int ca = crowd(a.layer), cb = crowd(b.layer);
+                if (ca != cb) return ca > cb;
+                const int da = turn_distance(a.layer), db = turn_distance(b.layer);
+                if (da != db) return da > db;
+            }
+            return a.stamp < b.stamp;
+        };
         for (size_t s = 0; s < slots_.size(); ++s) {
             const CacheEntry &e = slots_[s];
             if (e.layer < 0 || e.pinned) continue;
             if (layer_full && e.layer != layer) continue;
             if (!e.high) {
-                if (best_low < 0 || e.stamp < slots_[(size_t)best_low].stamp) best_low = (int)s;
+                if (best_low < 0 || before(e, slots_[(size_t)best_low])) best_low = (int)s;
             } else if (e.due < clock_) {
-                if (best_idle < 0 || e.stamp < slots_[(size_t)best_idle].stamp) best_idle = (int)s;
+                if (best_idle < 0 || before(e, slots_[(size_t)best_idle])) best_idle = (int)s;
             } else {
                 if (best_due < 0) best_due = (int)s;
                 else {
@@ -127,7 +151,13 @@ private:
         return best_due;
     }
 
-    int cap_, n_layers_, n_experts_;
+    // entries the layer holds if that is more than top_k, else 0: layers at or below top_k are robbed last
+    int crowd(int layer) const { return per_layer_[(size_t)layer] > top_k_ ? per_layer_[(size_t)layer] : 0; }
+    // layers until `layer` runs again, counted from the layer that runs next
+    int turn_distance(int layer) const { return (layer - next_layer_ + n_layers_) % n_layers_; }
+
+    int cap_, n_layers_, n_experts_, top_k_;
+    int next_layer_ = 0;
     std::vector<CacheEntry> slots_;
     std::vector<int> map_;
     std::vector<int> per_layer_;

@@ -9,9 +9,13 @@
 
 #include <hip/hip_runtime.h>
 
+#include <chrono>
+#include <condition_variable>
 #include <cstdint>
 #include <deque>
+#include <mutex>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "ef_cache.h"
@@ -26,11 +30,54 @@ struct EfLayerReg {
 };
 
 struct EfSlotDev {
-    hipEvent_t copy_start = nullptr, ready = nullptr;
+    hipEvent_t ready = nullptr;       // recorded behind the last chunk of the slot's copy
     hipEvent_t last_read = nullptr;   // borrowed from the read-event ring (may be null)
-    bool copy_pending = false;        // a copy was enqueued and not yet seen complete
+    bool copy_pending = false;        // a copy was requested and not yet seen complete
+    bool copy_queued = false;         // ... and not all of its chunks have been handed to the link yet (guarded by
+                                      // the copy engine's mutex)
+    bool prefetched_unused = false;   // filled by a prefetch that no layer has used yet
     double fake_ready_at = 0.0;       // fake-copy contexts: completion time of the copy
     size_t copy_bytes = 0;
+};
+
+// One expert copy in the queue of the copy engine: the bytes not yet handed to the link.
+struct EfCopyJob {
+    int slot = -1, layer = -1, expert = -1;
+    bool miss = false;                // priority copy: taken before any prefetch
+    bool started = false;
+    size_t done = 0, total = 0;
+    hipEvent_t war = nullptr;         // the last kernels that read the slot's previous content
+    std::chrono::steady_clock::time_point t_request;
+    double fake_request = 0.0;
+};
+
+// The copy queue of a context (paper Sec. 3.4): one link, chunked copies, misses first.  On a device a worker
+// thread hands chunks to the copy stream; fake-copy contexts run the same policy on the fake clock.
+struct EfCopyEngine {
+    std::mutex mu;
+    std::condition_variable cv_work, cv_done;
+    std::deque<EfCopyJob> pending;    // arrival order
+    size_t chunk_bytes = (size_t)32 << 20;
+    int depth = 2;
+    // device
+    struct InFlight { hipEvent_t ev; size_t bytes; bool back_to_back; bool last_of_miss; size_t miss_bytes;
+                      std::chrono::steady_clock::time_point t_request; };
+    std::vector<hipEvent_t> chunk_ev;
+    size_t chunk_next = 0;
+    std::deque<InFlight> inflight;
+    hipEvent_t prev_done = nullptr;   // the chunk that completed last (start of the next chunk's transfer)
+    std::thread worker;
+    bool stop = false, failed = false;
+    int device = 0;
+    std::string error;
+    // results the worker leaves for the context's thread (applied in poll_all_copies)
+    std::vector<double> bw_samples;
+    double copy_seconds = 0.0, miss_seconds = 0.0;
+    long long bytes_timed = 0, miss_bytes = 0, miss_copies = 0;
+    // fake clock
+    struct FakeChunk { double finish; int slot; bool last; };
+    std::deque<FakeChunk> fake_committed;
+    double fake_t = 0.0, fake_link_free = 0.0;
 };
 
 struct EfEventPair {
@@ -54,7 +101,12 @@ struct ef_ctx {
     ef::ExpertCache *cache = nullptr;
     char *pool = nullptr;
     std::vector<EfSlotDev> slots;
-    hipStream_t copy_stream[2] = {nullptr, nullptr};  // [0] prefetch, [1] miss
+    hipStream_t copy_stream = nullptr;
+    EfCopyEngine eng;
+    // look-ahead bookkeeping for the overlap statistics: pred_mask[(layer, j-1)] = experts the look-ahead made j
+    // layers before `layer` named, pred_valid its "was made" flags
+    std::vector<uint64_t> pred_mask;
+    std::vector<uint8_t> pred_valid;
     // scratch
     int32_t *blockcounts = nullptr, *blockbase = nullptr;
     void *xp = nullptr, *act = nullptr;
@@ -103,7 +155,7 @@ struct ef_ctx {
     int stall_counter = 0, overfetch_counter = 0;
     ef_stats st{};
     // fake clock
-    double fake_now = 0.0, fake_engine_free[2] = {0.0, 0.0};
+    double fake_now = 0.0;
     std::string err;
 };
 
@@ -139,6 +191,16 @@ uint64_t resident_mask(ef_ctx *c, int layer);
 int check_ctx_layer(ef_ctx *c, int layer);
 // Make (layer, expert) resident; *loaded (may be null) tells whether a copy was started.
 int swap_in_impl(ef_ctx *c, int layer, int expert, int priority, int due_in, int *slot_out, bool *loaded);
+// copy engine
+int copy_engine_start(ef_ctx *c);        // device contexts: events and the worker thread
+void copy_engine_stop(ef_ctx *c);
+// The layer being run needs these slots: their copies become priority copies, and the call returns once every
+// chunk of them has been handed to the copy stream (their ready events can then be waited for by a stream).
+int copy_engine_flush(ef_ctx *c, const int *slots, int n);
+int copy_engine_drain(ef_ctx *c);        // until the queue is empty (statistics, destruction)
+// fake-copy contexts: run the queue up to the fake clock / until the copies into these slots are complete
+void fake_copy_advance(ef_ctx *c, double now);
+double fake_copy_wait(ef_ctx *c, const int *slots, int n);
 
 // Brackets one kernel launch with events on the launch stream when profiling is on.
 struct KernelTimer {

@@ -373,6 +373,18 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool strict = (c->cfg.flags & EF_FLAG_STRICT_RESIDENT) != 0;
     poll_all_copies(c);
+    if (T > 0) {   // how much of what this layer uses had the look-ahead of j layers ago named?
+        uint64_t used = 0;
+        for (int e = 0; e < E; ++e)
+            if (counts_host[e] > 0) used |= 1ull << e;
+        for (int j = 0; j < EF_MAX_HORIZON; ++j) {
+            const size_t at = (size_t)layer * EF_MAX_HORIZON + j;
+            if (!c->pred_valid[at]) continue;
+            c->pred_valid[at] = 0;
+            c->st.pred_overlap_hits[j] += __builtin_popcountll(used & c->pred_mask[at]);
+            c->st.pred_overlap_total[j] += __builtin_popcountll(used);
+        }
+    }
 
     // host copies of the group geometry
     std::vector<int> offs_host((size_t)E + 1, 0), tile_start((size_t)E, 0);
@@ -486,6 +498,10 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
             continue;
         }
         c->st.hits += 1;
+        if (c->slots[(size_t)slot].prefetched_unused) {
+            c->slots[(size_t)slot].prefetched_unused = false;
+            c->st.prefetch_used += 1;
+        }
         c->cache->touch(slot);
         c->cache->pin(slot, true);
         if (c->slots[(size_t)slot].copy_pending) { loading.push_back({e, slot}); any_not_ready = true; }
@@ -574,9 +590,10 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
     };
     auto wait_loaded = [&](const std::vector<PhaseGroup> &v) -> int {
         if (v.empty()) return EF_OK;
+        std::vector<int> slots;
+        for (const auto &g : v) slots.push_back(g.slot);
         if (c->fake) {
-            double need = c->fake_now;
-            for (const auto &g : v) need = std::max(need, c->slots[(size_t)g.slot].fake_ready_at);
+            const double need = fake_copy_wait(c, slots.data(), (int)slots.size());
             c->st.stall_seconds += need - c->fake_now;
             c->fake_now = need;
             for (const auto &g : v) poll_copy(c, g.slot);
@@ -584,6 +601,10 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         }
         EfEventPair p = next_pair(c->stall_ring, c->stall_next, c->stall_pending);
         EF_HIP(c, hipEventRecord(p.a, s));
+        // copies still (partly) in the queue become priority copies; once every chunk of them is on the copy
+        // stream their ready events exist and the compute stream can wait for them
+        int fr = copy_engine_flush(c, slots.data(), (int)slots.size());
+        if (fr) return fr;
         for (const auto &g : v) EF_HIP(c, hipStreamWaitEvent(s, c->slots[(size_t)g.slot].ready, 0));
         EF_HIP(c, hipEventRecord(p.b, s));
         c->stall_pending.push_back(p);
@@ -687,7 +708,7 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
     }
     c->st.layers_run += 1;
     c->st.tokens_run += T;
-    c->cache->advance();
+    c->cache->advance(layer);
     return EF_OK;
 }
 

@@ -153,7 +153,7 @@ def test_cache_runtime_follows_the_lru_model():
     rng = np.random.default_rng(5)
     for cap in (0, 2):
         ctx = fake_ctx(slots_total=6, slots_per_layer_max=cap, n_layers=6)
-        model = TwoLevelLRU(6, cap)
+        model = TwoLevelLRU(6, cap, n_layers=6, top_k=1)
         try:
             for step in range(40):
                 layer = step % 6
@@ -180,7 +180,7 @@ def test_cache_runtime_follows_the_lru_model():
                         model.pin(layer, e)
                 for e in need:
                     model.pin(layer, e, False)
-                model.advance()
+                model.advance(layer_run=layer)
                 run_layer(ctx, layer, need)
                 for l in range(6):
                     got = ef.ef_cache_query(ctx, l, 8)

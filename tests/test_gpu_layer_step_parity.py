@@ -41,7 +41,7 @@ class CacheMirror:
         from oracle.lru_model import TwoLevelLRU
         self.o, self.cfg, self.L, self.es, self.h_max = oracle_mod, cfg, L, expert_bytes, h_max
         self.tau = float(np.float32(tau))            # the configuration field is a C float
-        self.model = TwoLevelLRU(L * slots_per_layer, slots_per_layer)
+        self.model = TwoLevelLRU(L * slots_per_layer, slots_per_layer, n_layers=L, top_k=cfg.k)
         self.S = 1
 
     def resident(self, layer):
@@ -77,7 +77,7 @@ class CacheMirror:
             assert wave, "no slot can be freed"
             for e in wave:
                 m.pin(layer, e, False)
-        m.advance()
+        m.advance(layer_run=layer)
 
     def choose_horizon(self, layer, hist):
         """hist [He, E]: demand of layers layer+1.. as the library's host received it."""

@@ -92,3 +92,41 @@ def test_thrash_when_lookahead_working_set_exceeds_capacity():
         return loads
     assert run(1) == 3 * (12 + 1) and run(2) == 3 * (12 + 2)      # every expert moved exactly once
     assert run(4) > 3 * (12 + 4)
+
+
+def test_pool_victim_follows_the_layer_cycle_and_the_per_layer_share():
+    """One pool for 4 layers that run cyclically, top_k = 1, window S = 1.  Worked out by hand from the stated
+    order: most crowded layer (above top_k) first, then the layer whose next turn is furthest away, then least
+    recently used."""
+    c = TwoLevelLRU(6, n_layers=4, top_k=1)
+    c.S = 1
+    for layer in (0, 1, 2):                       # ticks 0, 1, 2: each layer loads and uses two experts
+        for e in (0, 1):
+            assert c.swap_in(layer, e) == "load"
+            c.touch(layer, e)
+        c.advance(layer_run=layer)
+    # tick 3, layer 3 runs next.  Layers 0 and 1 were last used 3 and 2 ticks ago: low.  Layer 2: 1 tick ago: high.
+    assert [c.tier(l, 0) for l in (0, 1, 2)] == ["low", "low", "high"]
+    # both low layers hold two entries.  After layer 3 the cycle continues with layer 0 (1 turn away), then layer 1
+    # (2 turns away): layer 1 is needed later, its least recently used entry goes.  Plain recency order would have
+    # taken (0, 0), the expert needed soonest.
+    assert c.swap_in(3, 5) == "load"
+    assert c.evictions == [(1, 0)]
+    # layer 1 is down to top_k entries and is robbed last now; layer 0 still holds two
+    assert c.swap_in(3, 6) == "load"
+    assert c.evictions == [(1, 0), (0, 0)]
+    # both down to one entry: the cycle decides again
+    assert c.swap_in(3, 7) == "load"
+    assert c.evictions == [(1, 0), (0, 0), (1, 1)]
+
+
+def test_pool_rule_needs_no_cycle_when_a_per_layer_cap_is_in_force():
+    """With a cap the candidates all belong to the layer being filled: least recently used, whatever the cycle."""
+    c = TwoLevelLRU(8, per_layer_cap=2, n_layers=4, top_k=1)
+    c.S = 1
+    assert c.swap_in(2, 0) == "load" and c.swap_in(2, 1) == "load"
+    c.touch(2, 1)
+    c.touch(2, 0)                                  # (2, 1) is the older use now
+    c.advance(layer_run=2)
+    assert c.swap_in(2, 5) == "load"
+    assert c.evictions == [(2, 1)]
