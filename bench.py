@@ -290,7 +290,17 @@ def run_workload(name, spec, args, cpu_seconds):
         "link_bound_bytes_per_layer": bw * us_per_layer * 1e-6,
         "expert_bytes": loop.es,
         "cache": {"hits": st["hits"], "misses": st["misses"], "miss_rate": st["miss_rate"],
-                  "prefetch_issued": st["prefetch_issued"], "bytes_copied": st["bytes_copied"],
+                  "prefetch_issued": st["prefetch_issued"], "prefetch_used": st["prefetch_used"],
+                  "prefetch_wasted": st["prefetch_wasted"], "prefetch_redundant": st["prefetch_redundant"],
+                  "evictions": st["evictions"], "bytes_copied": st["bytes_copied"],
+                  "bytes_copied_per_step": st["bytes_copied"] / steps,
+                  # priority copies (misses and prefetches a layer caught in the queue): request -> complete
+                  "miss_copies": st["miss_copies"],
+                  "miss_copy_ms": 1e3 * st["miss_copy_seconds"] / st["miss_copies"] if st["miss_copies"] else None,
+                  "miss_copy_GBps": st["miss_copy_bytes"] / st["miss_copy_seconds"] / 1e9 if st["miss_copy_seconds"] > 0 else None,
+                  # of the experts a layer used, the share the look-ahead of j layers earlier had named (j = 1, 2, ...)
+                  "prediction_overlap_by_distance": [st["pred_overlap_hits"][j] / st["pred_overlap_total"][j]
+                                                     for j in range(7) if st["pred_overlap_total"][j] > 0],
                   "bytes_copied_per_layer": st["bytes_copied"] / (L * steps),
                   "pcie_GBps": st["bytes_timed"] / st["copy_seconds"] / 1e9 if st["copy_seconds"] > 0 else None,
                   "horizon": st["horizon"], "bandwidth_est_GBps": bw / 1e9, "layer_est_us": st["layer_seconds_est"] * 1e6},

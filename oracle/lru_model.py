@@ -19,11 +19,13 @@ goes (latest stamp among equals).
 One pool for all layers (no per-layer cap in force): a decode loop visits the
 layers cyclically, so plain recency order would evict what runs next (the
 premature eviction of the first layers' experts the section gives as the
-motivation of the two tiers).  Among the candidates of a tier the victim then
-comes from the layer holding the most entries, provided that is more than
-``top_k``; equal there, from the layer whose next turn in the cycle is furthest
-away; equal there, the least recently used.  ``advance(layer_run)`` tells the
-model which layer just ran.
+motivation of the two tiers).  Once the pool is full, a layer that already
+holds its share of it (``slots_total // n_layers``, at least ``top_k``) replaces
+its own entries, as under a per-layer cap.  A layer below its share takes, among
+the candidates of a tier, the victim from the layer holding the most entries,
+provided that is more than ``top_k``; equal there, from the layer whose next
+turn in the cycle is furthest away; equal there, the least recently used.
+``advance(layer_run)`` tells the model which layer just ran.
 """
 from __future__ import annotations
 
@@ -92,6 +94,8 @@ class TwoLevelLRU:
             cand = in_layer
         elif len(keys) < self.slots_total:
             return None, True
+        elif len(in_layer) >= max(self.top_k, self.slots_total // self.n_layers):
+            cand = in_layer              # full pool and the layer has its share: it replaces its own
         else:
             cand = keys
             pooled = True

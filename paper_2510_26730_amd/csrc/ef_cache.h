@@ -10,12 +10,16 @@
 // One pool shared by all layers (no per-layer cap): a decode loop runs the layers in a cycle, so the least
 // recently used entry of the pool belongs to the layer that runs next, and plain recency order evicts exactly
 // what is needed soonest (the premature eviction of the first layers' experts that Sec. 3.3.1 names as the
-// motivation of the two tiers).  Among the candidates of a tier the victim is therefore taken (1) from the
-// layer that holds the most entries, as long as that is more than top_k (a layer needs top_k resident experts
-// before the residency bias can keep its tokens on them), (2) then from the layer whose next turn in the
-// cycle is furthest away, (3) then least recently used.  With a per-layer cap in force all candidates belong
-// to one layer and (3) alone decides, as before.
+// motivation of the two tiers).  Once the pool is full, a layer that already holds its share of it
+// (slots_total / n_layers, at least top_k) replaces entries of its own, like under a per-layer cap: with a pool
+// just large enough for top_k experts per layer, a layer that grew at the others' expense would leave them
+// below top_k and the misses would cascade from layer to layer.  A layer below its share takes its victim,
+// among the candidates of a tier, (1) from the layer that holds the most entries, as long as that is more
+// than top_k (a layer needs top_k resident experts before the residency bias can keep its tokens on them),
+// (2) then from the layer whose next turn in the cycle is furthest away, (3) then least recently used.
+// With a per-layer cap in force all candidates belong to one layer and (3) alone decides, as before.
 #pragma once
+#include <algorithm>
 #include <cstdint>
 #include <vector>
 
@@ -116,9 +120,13 @@ private:
 
     int victim(int layer) const {
         bool layer_full = cap_ > 0 && per_layer_[(size_t)layer] >= cap_;
-        if (!layer_full)
+        if (!layer_full) {
             for (size_t s = 0; s < slots_.size(); ++s)
                 if (slots_[s].layer < 0) return (int)s;
+            // the pool is full: a layer at its share of it replaces its own entries
+            const int share = std::max(top_k_, (int)slots_.size() / n_layers_);
+            if (per_layer_[(size_t)layer] >= share) layer_full = true;
+        }
         int best_low = -1, best_idle = -1, best_due = -1;
         // true if entry a goes before entry b
         auto before = [&](const CacheEntry &a, const CacheEntry &b) {

@@ -157,6 +157,21 @@ uint64_t resident_mask(ef_ctx *c, int layer) {
 
 // ---- swap-in ---------------------------------------------------------------------------------
 
+namespace {
+EfCopyJob *next_job(EfCopyEngine &g);
+void issue_chunk(ef_ctx *c, EfCopyJob *job);
+// A priority copy does not wait for the worker to wake up: while the link may take more chunks the caller hands
+// them over itself (mutex held); the worker carries on from there.
+void pump_from_caller(ef_ctx *c) {
+    EfCopyEngine &g = c->eng;
+    while (!g.failed && (int)g.inflight.size() < g.depth) {
+        EfCopyJob *j = next_job(g);
+        if (!j) break;
+        issue_chunk(c, j);
+    }
+}
+}  // namespace
+
 int swap_in_impl(ef_ctx *c, int layer, int expert, int priority, int due_in, int *slot_out, bool *loaded) {
     int slot = -1, evl = -1, eve = -1;
     if (loaded) *loaded = false;
@@ -200,6 +215,7 @@ int swap_in_impl(ef_ctx *c, int layer, int expert, int priority, int due_in, int
                 it = it->slot == slot ? g.pending.erase(it) : it + 1;
             g.pending.push_back(job);
             s.copy_queued = true;
+            if (job.miss) pump_from_caller(c);
         }
         g.cv_work.notify_one();
     }
@@ -354,7 +370,10 @@ int copy_engine_flush(ef_ctx *c, const int *slots, int n) {
                 j.t_request = std::chrono::steady_clock::now();
                 any = true;
             }
-    if (any) g.cv_work.notify_one();
+    if (any) {
+        pump_from_caller(c);
+        g.cv_work.notify_one();
+    }
     g.cv_done.wait(lk, [&] {
         if (g.failed) return true;
         for (int i = 0; i < n; ++i)

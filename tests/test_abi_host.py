@@ -150,6 +150,7 @@ def run_layer(ctx, layer, experts, T=8):
 def test_cache_runtime_follows_the_lru_model():
     """Drive ef_cache_swap_in / ef_moe_ffn and the Python model with the same scripted trace."""
     from oracle.lru_model import TwoLevelLRU
+    from cache_replay import replay_layer
     rng = np.random.default_rng(5)
     for cap in (0, 2):
         ctx = fake_ctx(slots_total=6, slots_per_layer_max=cap, n_layers=6)
@@ -169,18 +170,7 @@ def test_cache_runtime_follows_the_lru_model():
                                 ef.ef_cache_swap_in(ctx, layer + j, int(e), 0, j)
                 # the layer itself needs two experts: resident ones are touched, the others are misses
                 need = sorted(int(e) for e in rng.permutation(8)[:2])
-                for e in need:
-                    if model.resident(layer, e):
-                        model.touch(layer, e)
-                        model.pin(layer, e)
-                for e in need:
-                    if not model.resident(layer, e):
-                        assert model.swap_in(layer, e) == "load"
-                        model.touch(layer, e)
-                        model.pin(layer, e)
-                for e in need:
-                    model.pin(layer, e, False)
-                model.advance(layer_run=layer)
+                replay_layer(model, layer, need)
                 run_layer(ctx, layer, need)
                 for l in range(6):
                     got = ef.ef_cache_query(ctx, l, 8)

@@ -21,6 +21,7 @@ from paper_2510_26730_amd import binding as ef
 from paper_2510_26730_amd import synth
 
 import helpers
+from cache_replay import replay_layer
 from helpers import LayerStack, check_ids_valid, check_route, dev_u16, float_close
 
 pytestmark = pytest.mark.gpu
@@ -48,36 +49,7 @@ class CacheMirror:
         return np.array([self.model.resident(layer, e) for e in range(self.cfg.E)], np.uint8)
 
     def run_layer(self, layer, counts):
-        m = self.model
-        need = [e for e in range(self.cfg.E) if counts[e] > 0]
-        missing = [e for e in need if not m.resident(layer, e)]
-        held = []
-        for e in need:
-            if m.resident(layer, e):
-                m.touch(layer, e)
-                m.pin(layer, e)
-                held.append(e)
-        deferred = []
-        for e in missing:                       # misses that find a slot start at once
-            if m.swap_in(layer, e, 0) == "busy":
-                deferred.append(e)
-                continue
-            m.touch(layer, e)
-            m.pin(layer, e)
-            held.append(e)
-        for e in held:                          # their groups have run: the slots are released
-            m.pin(layer, e, False)
-        while deferred:                         # the others take the slots in waves
-            wave = []
-            while deferred and m.swap_in(layer, deferred[0], 0) != "busy":
-                e = deferred.pop(0)
-                m.touch(layer, e)
-                m.pin(layer, e)
-                wave.append(e)
-            assert wave, "no slot can be freed"
-            for e in wave:
-                m.pin(layer, e, False)
-        m.advance(layer_run=layer)
+        replay_layer(self.model, layer, [e for e in range(self.cfg.E) if counts[e] > 0])
 
     def choose_horizon(self, layer, hist):
         """hist [He, E]: demand of layers layer+1.. as the library's host received it."""

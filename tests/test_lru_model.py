@@ -95,29 +95,30 @@ def test_thrash_when_lookahead_working_set_exceeds_capacity():
 
 
 def test_pool_victim_follows_the_layer_cycle_and_the_per_layer_share():
-    """One pool for 4 layers that run cyclically, top_k = 1, window S = 1.  Worked out by hand from the stated
-    order: most crowded layer (above top_k) first, then the layer whose next turn is furthest away, then least
-    recently used."""
-    c = TwoLevelLRU(6, n_layers=4, top_k=1)
+    """One pool of 8 slots for 4 layers that run cyclically (share: 2 per layer), top_k = 1, window S = 1.
+    Worked out by hand from the stated order: a layer at its share replaces its own; otherwise most crowded
+    layer (above top_k) first, then the layer whose next turn is furthest away, then least recently used."""
+    c = TwoLevelLRU(8, n_layers=4, top_k=1)
     c.S = 1
-    for layer in (0, 1, 2):                       # ticks 0, 1, 2: each layer loads and uses two experts
-        for e in (0, 1):
+    for layer, experts in ((0, (0, 1, 2)), (1, (0, 1, 2)), (2, (0, 1))):     # ticks 0, 1, 2; the pool is full after them
+        for e in experts:
             assert c.swap_in(layer, e) == "load"
             c.touch(layer, e)
         c.advance(layer_run=layer)
     # tick 3, layer 3 runs next.  Layers 0 and 1 were last used 3 and 2 ticks ago: low.  Layer 2: 1 tick ago: high.
     assert [c.tier(l, 0) for l in (0, 1, 2)] == ["low", "low", "high"]
-    # both low layers hold two entries.  After layer 3 the cycle continues with layer 0 (1 turn away), then layer 1
-    # (2 turns away): layer 1 is needed later, its least recently used entry goes.  Plain recency order would have
-    # taken (0, 0), the expert needed soonest.
+    # layer 3 holds nothing.  Both low layers hold three entries.  After layer 3 the cycle continues with layer 0
+    # (1 turn away), then layer 1 (2 turns away): layer 1 is needed later, its least recently used entry goes.
+    # Plain recency order would have taken (0, 0), the expert needed soonest.
     assert c.swap_in(3, 5) == "load"
     assert c.evictions == [(1, 0)]
-    # layer 1 is down to top_k entries and is robbed last now; layer 0 still holds two
+    # layer 3 holds one, still below its share; layer 0 (three entries) is more crowded than layer 1 (two) now
     assert c.swap_in(3, 6) == "load"
     assert c.evictions == [(1, 0), (0, 0)]
-    # both down to one entry: the cycle decides again
+    # layer 3 has its share of the full pool: a third expert replaces one of its own.  Both are awaited now
+    # (due at this tick): the later one goes.
     assert c.swap_in(3, 7) == "load"
-    assert c.evictions == [(1, 0), (0, 0), (1, 1)]
+    assert c.evictions == [(1, 0), (0, 0), (3, 6)]
 
 
 def test_pool_rule_needs_no_cycle_when_a_per_layer_cap_is_in_force():
