@@ -256,7 +256,9 @@ __device__ __forceinline__ void gate_epilogue(const GateArgs &a, float (*logits)
     // shared_tile: other workgroups handle the tile's other tokens, so per-tile counts are added
     // atomically to the (zeroed) table instead of stored.  NW waves per workgroup.
     constexpr int NT = 64 * NW;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    // the wave index as a scalar: the gate a round works on is then known to be the same for the whole wave, and
+    // its kernel arguments are picked in scalar registers instead of by per-lane loads from the argument block
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int t0 = tile * kTile;
     const int N = Gl * a.E;
     // A sub-group of W lanes (W = power of two >= E) owns one token; a wave
@@ -720,12 +722,17 @@ __device__ __forceinline__ void scatter_tile(const int32_t *__restrict__ ids, in
 // memory.  Every word carries the call's tag (0..254) in its top 8 bits (values are below 2^24), and
 // the host polls until all the words it expects show the tag, then overwrites them with tag 255: no
 // fence and no separate flag, which would cost the kernel a system-scope fence of about 5 us.
+// A word goes to host memory with a system-scope store the wave does not wait for (a volatile store is followed
+// by a wait for its completion, about 1 us over the link, in the middle of the kernel's critical path).
+__device__ __forceinline__ void host_word(int32_t *p, int32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
 __device__ __forceinline__ void export_meta(const GroupExport &ex, const int *total, int E) {
     if (!ex.host_meta) return;  // uniform
     const int tag = (int)((unsigned)(ex.seq & 0xFF) << 24);
-    volatile int32_t *hm = ex.host_meta;
-    for (int x = threadIdx.x; x < E; x += blockDim.x) hm[x] = tag | total[x];
-    for (int x = threadIdx.x; x < ex.n_hist; x += blockDim.x) hm[kMetaHist + x] = tag | ex.hist[x];
+    int32_t *hm = ex.host_meta;
+    for (int x = threadIdx.x; x < E; x += blockDim.x) host_word(hm + x, tag | total[x]);
+    for (int x = threadIdx.x; x < ex.n_hist; x += blockDim.x) host_word(hm + kMetaHist + x, tag | ex.hist[x]);
     for (int x = threadIdx.x; x < ex.n_clear; x += blockDim.x) ex.hist[x] = 0;   // ready for the next layer
 }
 
@@ -875,7 +882,9 @@ __global__ __launch_bounds__(1024) void gate_finish_group_kernel(GateArgs a, int
     __shared__ int total[kMaxE];
     __shared__ int offs[kMaxE + 1];
     __shared__ int nxt[NW][64];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    __shared__ int32_t s_ids[kFusedMaxTiles * kTile * kMaxK];   // ids of the routed gate, for the scatter below
+    // the wave index as a scalar: what is derived from it (the gate a round works on) stays in scalar registers
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int E = a.E, G = a.G;
     const int ntiles = (a.T + kTile - 1) / kTile;
     const int ngroups = (G + a.gpw - 1) / a.gpw;
@@ -956,6 +965,7 @@ __global__ __launch_bounds__(1024) void gate_finish_group_kernel(GateArgs a, int
             const int slot = __popcll(submask & ((1ull << e) - 1ull));   // ascending expert id
             if (sel) {
                 pick(a.ids, gi)[(size_t)t * a.k + slot] = e;
+                if (gi == 0) s_ids[t * a.k + slot] = e;
                 if (want_w) a.w[(size_t)t * a.k + slot] = exv / den * a.routed_scale;
                 atomicAdd(&cnt[(tile * G + gi) * E + e], 1);
             }
@@ -975,7 +985,7 @@ __global__ __launch_bounds__(1024) void gate_finish_group_kernel(GateArgs a, int
         if (!hp) continue;
         if (ex.host_meta) {
             const int at = (int)(hp - ex.hist) + ee;           // position inside the exported histograms
-            if (at >= 0 && at < ex.n_hist) reinterpret_cast<volatile int32_t *>(ex.host_meta)[kMetaHist + at] = tag | sum;
+            if (at >= 0 && at < ex.n_hist) host_word(ex.host_meta + kMetaHist + at, tag | sum);
         } else if (sum > 0) {
             atomicAdd(&hp[ee], sum);
         }
@@ -1005,12 +1015,13 @@ __global__ __launch_bounds__(1024) void gate_finish_group_kernel(GateArgs a, int
     }
     __syncthreads();
     if (ex.host_meta)   // the host starts planning while the scatter below still runs
-        for (int x = tid; x < E; x += NT) reinterpret_cast<volatile int32_t *>(ex.host_meta)[x] = tag | total[x];
-    // the scatter reads the ids the epilogue above stored: same workgroup, ordered by the barriers
+        for (int x = tid; x < E; x += NT) host_word(ex.host_meta + x, tag | total[x]);
+    // the scatter reads the routed ids from the copy the epilogue above left in LDS (reading them back from
+    // global memory would be one more memory round trip); same workgroup, ordered by the barriers
     for (int b = wave; b < ntiles; b += NW) {
         nxt[wave][lane] = (lane < E) ? offs[lane] + base[b * E + lane] : 0;
         wave_lds_sync();
-        scatter_tile(pick(a.ids, 0), a.T, a.k, b, lane, nxt[wave], perm, inv_perm);
+        scatter_tile(s_ids, a.T, a.k, b, lane, nxt[wave], perm, inv_perm);
     }
 }
 
