@@ -355,7 +355,7 @@ __device__ __forceinline__ void down_stream(const uint4 *__restrict__ w2, size_t
         _Pragma("unroll") for (int u = 0; u < UNR; ++u)                                                  \
             _Pragma("unroll") for (int tt = 0; tt < NTL; ++tt)                                           \
                 _Pragma("unroll") for (int cw = 0; cw < CBW; ++cw)                                       \
-                    acc[cw][tt] = mfma32h(a[tt][u], b[cw][u], acc[cw][tt]);                              \
+                    acc[cw][tt] = mfma32h(b[cw][u], a[tt][u], acc[cw][tt]);                              \
     }
     const int nfull = (k1 - k0) / UNR;
     int kb = k0;
@@ -389,7 +389,7 @@ __device__ __forceinline__ void down_stream(const uint4 *__restrict__ w2, size_t
                 reinterpret_cast<const u32x4_t *>(w2 + cw * cb_stride + (size_t)kb * 64));
 #pragma unroll
             for (int tt = 0; tt < NTL; ++tt)
-                acc[cw][tt] = mfma32h(*reinterpret_cast<const u32x4_t *>(a0 + ((size_t)tt * nkb + kb) * 64), b,
+                acc[cw][tt] = mfma32h(b, *reinterpret_cast<const u32x4_t *>(a0 + ((size_t)tt * nkb + kb) * 64),
                                       acc[cw][tt]);
         }
     }
@@ -401,8 +401,9 @@ __device__ __forceinline__ void down_stream(const uint4 *__restrict__ w2, size_t
 // second half: Y = act W2^T.  A workgroup owns (group, pass of TT token tiles, CBW*32 output
 // columns, one of `ksg` K-slices); its four waves split that slice again and are summed in a fixed
 // order, (p0 + p2) + (p1 + p3), through LDS.  Each K-slice writes its own partial Y plane; the
-// un-permute sums the planes in order.  Activations are operand A (rows = tokens), W2 fragments
-// operand B (columns = outputs), both fp16 (see mfma32h).
+// un-permute sums the planes in order.  The product is formed transposed (W2 fragment first: the operand
+// layouts are mirror images), so a lane ends with one token and groups of four consecutive output columns:
+// 16-byte LDS accesses in the reduction and 16-byte stores to Y.  Both operands fp16 (see mfma32h).
 // ------------------------------------------------------------------------------------------
 template <int TT>
 __global__ __launch_bounds__(256, 2) void ffn_down_kernel(GroupTable gt, const uint4 *__restrict__ act,
@@ -411,8 +412,8 @@ __global__ __launch_bounds__(256, 2) void ffn_down_kernel(GroupTable gt, const u
     constexpr int CBW = kDownColBlocks;
     constexpr int UNR = TT > 2 ? 1 : 2;
     constexpr int TH = TT > 2 ? 2 : TT;          // token tiles per round of the epilogue (LDS budget)
-    constexpr int REGION = CBW * TH * 16 * 64;   // floats of one wave's partial of one round
-    __shared__ float red[4 * REGION];
+    constexpr int REGION = CBW * TH * 4 * 64;    // 16-byte units of one wave's partial of one round
+    __shared__ __attribute__((aligned(16))) float4 red[4 * REGION];
     const int wg = blockIdx.x;
     int grp = 0;
     while (grp + 1 < gt.n_groups && gt.wg_start[grp + 1] <= wg) ++grp;
@@ -447,9 +448,10 @@ __global__ __launch_bounds__(256, 2) void ffn_down_kernel(GroupTable gt, const u
     // order (p0 + p2) + (p1 + p3) and stores that quarter, so the adds and the stores of the epilogue run on
     // all four waves instead of a three-step tree that leaves one wave to store everything.  Passes of four
     // token tiles take two such rounds of two tiles (the partials of all four would not fit the LDS budget).
+    // A lane holds token lane % 32 and, per accumulator quad q, output columns 8q + 4 (lane / 32) .. + 3.
     const int g = lane >> 5;
     float *Yp = Y + (size_t)kslice * y_plane;
-    constexpr int UNITS = CBW * TH * 16;          // 64-lane slices of a round's tile; a quarter per wave
+    constexpr int UNITS = CBW * TH * 4;           // 64-lane slices of 16 bytes of a round's tile; a quarter per wave
     static_assert(UNITS % 4 == 0, "the tile is dealt to four waves");
 #pragma unroll
     for (int round = 0; round < TT / TH; ++round) {
@@ -459,19 +461,24 @@ __global__ __launch_bounds__(256, 2) void ffn_down_kernel(GroupTable gt, const u
 #pragma unroll
             for (int th = 0; th < TH; ++th)
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    red[wave * REGION + ((cw * TH + th) * 16 + v) * 64 + lane] = acc[cw][round * TH + th][v];
+                for (int q = 0; q < 4; ++q) {
+                    const floatx16 &v = acc[cw][round * TH + th];
+                    red[wave * REGION + ((cw * TH + th) * 4 + q) * 64 + lane] =
+                        make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+                }
         __syncthreads();
 #pragma unroll
-        for (int q = 0; q < UNITS / 4; ++q) {
-            const int u = wave * (UNITS / 4) + q;
-            const int cw = u / (TH * 16), tt = round * TH + (u / 16) % TH, v = u % 16;
-            const float *r = red + u * 64 + lane;
-            const float sum = (r[0] + r[2 * REGION]) + (r[REGION] + r[3 * REGION]);
+        for (int qq = 0; qq < UNITS / 4; ++qq) {
+            const int u = wave * (UNITS / 4) + qq;
+            const int cw = u / (TH * 4), tt = round * TH + (u / 4) % TH, q = u % 4;
+            const float4 *r = red + u * 64 + lane;
+            const float4 p0 = r[0], p1 = r[REGION], p2 = r[2 * REGION], p3 = r[3 * REGION];
+            const float4 sum = make_float4((p0.x + p2.x) + (p1.x + p3.x), (p0.y + p2.y) + (p1.y + p3.y),
+                                           (p0.z + p2.z) + (p1.z + p3.z), (p0.w + p2.w) + (p1.w + p3.w));
             if (tt >= ntl) continue;
-            const int col = (cb0 + cw) * 32 + (lane & 31);
-            const int tl = (pass * TT + tt) * kTile + 8 * (v >> 2) + 4 * g + (v & 3);
-            if (tl < gt.count[grp]) Yp[(size_t)(gt.row_offset[grp] + tl) * d + col] = sum;
+            const int col = (cb0 + cw) * 32 + 8 * q + 4 * g;
+            const int tl = (pass * TT + tt) * kTile + (lane & 31);
+            if (tl < gt.count[grp]) *reinterpret_cast<float4 *>(Yp + (size_t)(gt.row_offset[grp] + tl) * d + col) = sum;
         }
     }
 }
