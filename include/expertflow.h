@@ -508,6 +508,9 @@ typedef struct ef_tuning {
     int32_t copy_chunk_mib;          /* 1..1024: expert copies go to the link in chunks of at most this many MiB; a miss
                                         overtakes queued prefetches at the next chunk boundary (32) */
     int32_t copy_depth;              /* 1..8: chunks handed to the copy stream ahead of the one in transfer (2) */
+    int32_t tiled_tail_slices;       /* a tiled second half of more than 256 workgroups cuts its last group into K slices
+                                        that fill the launch's last, partly empty round: 0 = never, 1 = as many as a
+                                        model of the launch finds best, 2 / 4 / 8 = that many (1) */
 } ef_tuning;
 int ef_get_tuning(ef_ctx *ctx, ef_tuning *out);
 int ef_set_tuning(ef_ctx *ctx, const ef_tuning *t);

@@ -78,7 +78,8 @@ class ef_tuning(C.Structure):
         "tiled", "tiled_min_tiles", "tiled_min_up_wgs", "tiled_min_down_wgs", "tiled_xcd_rotation", "overlap_tiled",
         "sort_groups", "passes_of_four", "lds_shared", "lds_shared_occupancy", "up_want_waves", "up_k_slices",
         "down_want_wgs", "down_k_slices", "down_slices_by_longest_k", "down_split_slice_counts", "gate_k_split",
-        "gate_token_split", "gate_fused_finish", "gate_stream", "early_pack", "copy_chunk_mib", "copy_depth")]
+        "gate_token_split", "gate_fused_finish", "gate_stream", "early_pack", "copy_chunk_mib", "copy_depth",
+        "tiled_tail_slices")]
 
 
 class ef_forest_config(C.Structure):

@@ -260,9 +260,10 @@ extern "C" int ef_create(const ef_config *cfg, ef_ctx **out) {
     const size_t act_bytes = (size_t)routed_tiles * ef::kTile * g.d_ff * 2 +
                              (size_t)shared_tiles * ef::kTile * g.d_ff_shared * 2;
     // expert outputs: one plane of (T*k [+T]) x d floats, times up to 8 K-slice planes while that stays
-    // under 256 MiB (small batches split K of the second FFN half across workgroups)
+    // under 256 MiB (small batches split K of the second FFN half across workgroups), or up to 4 while it stays
+    // under 2 GiB (large batches cut the last group of a tiled second half into K slices)
     const long long y_plane_max = (Tm * k + (g.d_ff_shared > 0 ? Tm : 0)) * d;
-    long long planes = std::max(1ll, std::min(8ll, (64ll << 20) / y_plane_max));
+    long long planes = std::max({1ll, std::min(8ll, (64ll << 20) / y_plane_max), std::min(4ll, (512ll << 20) / y_plane_max)});
     c->y_floats = y_plane_max * planes;
     const size_t y_bytes = (size_t)c->y_floats * 4;
 
@@ -681,6 +682,7 @@ void efi::tuning_defaults(ef_tuning *t) {
     t->gate_k_split = 0;
     t->gate_token_split = 1;
     t->gate_fused_finish = 1;
+    t->tiled_tail_slices = 1;
     t->gate_stream = 1;
     t->early_pack = 1;
     t->copy_chunk_mib = 32;
@@ -716,6 +718,8 @@ extern "C" int ef_set_tuning(ef_ctx *c, const ef_tuning *t) {
     else if (t->gate_k_split < 0 || t->gate_k_split > 16) bad = "gate_k_split";
     else if (!flag(t->gate_token_split)) bad = "gate_token_split";
     else if (!flag(t->gate_fused_finish)) bad = "gate_fused_finish";
+    else if (t->tiled_tail_slices != 0 && t->tiled_tail_slices != 1 && t->tiled_tail_slices != 2 &&
+             t->tiled_tail_slices != 4 && t->tiled_tail_slices != 8) bad = "tiled_tail_slices";
     else if (!flag(t->gate_stream)) bad = "gate_stream";
     else if (!flag(t->early_pack)) bad = "early_pack";
     else if (t->copy_chunk_mib < 1 || t->copy_chunk_mib > 1024) bad = "copy_chunk_mib";

@@ -272,8 +272,8 @@ hipError_t launch_ffn_gate_up_tiled(const GroupTable &gt, int total_wgs, const v
 // operand B slots 8..15 = W2 fragments of column blocks cb0..cb0+7
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, const uint4 *__restrict__ act,
-                                                                 float *__restrict__ Y, int d, int ksg,
-                                                                 long long y_plane) {
+                                                                 float *__restrict__ Y, int d, int ksg_all,
+                                                                 int split_grp, int split_ksg, long long y_plane) {
     // Y^T = W2 act^T: a lane then ends with one token (its index mod 32) and four consecutive output columns per
     // accumulator quad, which is one 16-byte store; with the product the other way round a lane holds one
     // column of four consecutive tokens and the tile leaves in 4-byte stores, four times as many instructions
@@ -288,7 +288,10 @@ __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, c
     const int ntiles = gt.n_tiles[grp];
     const int mpanels = (ntiles + 7) >> 3;
     // K slices across workgroups (one Y plane each, summed by the un-permute) when the tiles alone
-    // would leave most of the chip idle; neighbouring workgroups take the slices of one tile
+    // would leave most of the chip idle; neighbouring workgroups take the slices of one tile.  One group of the
+    // launch (the last one) may have a slice count of its own: shorter workgroups that fill the launch's last,
+    // partly empty round over the compute units
+    const int ksg = grp == split_grp ? split_ksg : ksg_all;
     const int kslice = local % ksg;
     int np, mp;
     if (!tiled_panel(local / ksg, gt.xcd_rot[grp], d >> 8, mpanels, np, mp)) return;
@@ -348,17 +351,19 @@ __global__ __launch_bounds__(256, 1) void ffn_down_tiled_kernel(GroupTable gt, c
     }
 }
 
-hipError_t launch_ffn_down_tiled(const GroupTable &gt, int total_wgs, int ksg, const void *act, float *y,
-                                 long long y_plane, int d, hipStream_t s) {
+hipError_t launch_ffn_down_tiled(const GroupTable &gt, int total_wgs, int ksg, int split_grp, int split_ksg,
+                                 const void *act, float *y, long long y_plane, int d, hipStream_t s) {
     if (total_wgs <= 0) return hipSuccess;
-    if (ksg < 1) return hipErrorInvalidValue;
-    for (int i = 0; i < gt.n_groups; ++i)
-        if (gt.wg_start[i + 1] - gt.wg_start[i] != ffn_down_tiled_wgs(d, gt.n_tiles[i]) * ksg ||
-            !ffn_tiled_ok(d, gt.F[i], gt.n_tiles[i]))
+    if (ksg < 1 || (split_grp >= 0 && (split_grp >= gt.n_groups || split_ksg < 1))) return hipErrorInvalidValue;
+    for (int i = 0; i < gt.n_groups; ++i) {
+        const int ks = i == split_grp ? split_ksg : ksg;
+        if (gt.wg_start[i + 1] - gt.wg_start[i] != ffn_down_tiled_wgs(d, gt.n_tiles[i]) * ks ||
+            !ffn_tiled_ok(d, gt.F[i], gt.n_tiles[i]) || gt.F[i] / 32 < ks)
             return hipErrorInvalidValue;
+    }
     if (gt.wg_start[gt.n_groups] != total_wgs) return hipErrorInvalidValue;
     hipLaunchKernelGGL(ffn_down_tiled_kernel, dim3(total_wgs), dim3(256), 0, s, gt,
-                       reinterpret_cast<const uint4 *>(act), y, d, ksg, y_plane);
+                       reinterpret_cast<const uint4 *>(act), y, d, ksg, split_grp, split_ksg, y_plane);
     return hipGetLastError();
 }
 

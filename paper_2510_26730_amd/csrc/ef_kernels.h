@@ -144,8 +144,9 @@ hipError_t launch_token_dist(const uint16_t *h, int T, int d, const void *xp, fl
 // the staging copies launch_dequant_q4 wrote).  Activations and W2 fragments are fp16 in every context.
 hipError_t launch_ffn_gate_up_tiled(const GroupTable &gt, int total_wgs, const void *xp, void *act, int d,
                                     bool f16, hipStream_t s);
-hipError_t launch_ffn_down_tiled(const GroupTable &gt, int total_wgs, int ksg, const void *act, float *y,
-                                 long long y_plane, int d, hipStream_t s);
+// `split_grp` (or -1): the group of this launch whose slice count is `split_ksg` instead of `ksg`
+hipError_t launch_ffn_down_tiled(const GroupTable &gt, int total_wgs, int ksg, int split_grp, int split_ksg,
+                                 const void *act, float *y, long long y_plane, int d, hipStream_t s);
 
 // The tiled (matrix-core bound) kernels take groups of at least kTiledMinTiles token tiles whose shapes
 // fit their 256 x 256 workgroup tiles: F a multiple of 128 (4 row blocks), d a multiple of 256 (8 column

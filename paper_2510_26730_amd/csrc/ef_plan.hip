@@ -138,12 +138,27 @@ struct PhaseGroup {
     int expert;  // -1: dense shared FFN
     int slot;
 };
+constexpr int kNoSplit = -2;
+
+// The tiled second half of a layer is `before` workgroups of one time unit each, dealt in order to the 256 compute
+// units, then `units` more of the layer's last tiled group.  With that group cut into s K slices its workgroups
+// take 1/s of a unit each: the time, in units, until the last one ends.
+double tiled_tail_makespan(long long before, long long units, int s) {
+    const long long q = before / 256, r = before % 256;   // r compute units are busy until q + 1, the others until q
+    for (long long step = 1;; ++step) {
+        const long long cap = (256 - r) * step + r * std::max<long long>(0, step - s);
+        if (cap >= units * s) return (double)q + (double)step / s;
+    }
+}
 
 // Build the launch tables of one phase and enqueue both FFN halves.
 int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, const int32_t *counts_host,
                  const std::vector<int> &offs_host, const std::vector<int> &tile_start,
                  const std::vector<long long> &act_off, int shared_tile_start, long long shared_act_off, int T,
-                 int ksg_stream, int ksg_tiled, ef::PlaneTable &planes, long long y_plane, bool use_tiled, hipStream_t s) {
+                 int ksg_stream, int ksg_tiled, int split_expert, int split_ksg, ef::PlaneTable &planes, long long y_plane,
+                 bool use_tiled, hipStream_t s) {
+    // split_expert: the tiled group of the layer (expert id, -1 = shared FFN, kNoSplit = none) whose second half takes
+    // split_ksg K slices instead of ksg_tiled; it goes last among the tiled groups of its launch
     if (groups.empty()) return EF_OK;
     const int d = c->cfg.d_model, k = c->cfg.top_k;
     // groups with many tokens go to the tiled (matrix-core bound) kernels, the others to the
@@ -164,6 +179,11 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
         std::stable_sort(ordered.begin(), ordered.end(),
                          [&](const PhaseGroup &a, const PhaseGroup &b) { return work(a) > work(b); });
     }
+    if (split_expert != kNoSplit) {
+        auto it = std::find_if(ordered.begin(), ordered.end(), [&](const PhaseGroup &pg) { return pg.expert == split_expert; });
+        if (it != ordered.end()) std::rotate(it, it + 1, ordered.end());
+    }
+    int split_grp = -1;
     for (const PhaseGroup &pg : ordered) {
         int cnt, ts, F, ro;
         long long ao;
@@ -186,7 +206,10 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
             dq.F[nb] = F; dq.src[nb] = blob; dq.dst[nb] = copy;
             blob = copy;
         }
-        (pg.expert < 0 ? planes.shared : planes.routed[pg.expert]) = (uint8_t)(tiled ? ksg_tiled : ksg_stream);
+        const bool split = tiled && split_expert != kNoSplit && pg.expert == split_expert;
+        if (split) split_grp = nb;
+        (pg.expert < 0 ? planes.shared : planes.routed[pg.expert]) =
+            (uint8_t)(split ? split_ksg : tiled ? ksg_tiled : ksg_stream);
         g.tile_start[i] = ts; g.n_tiles[i] = nt; g.row_offset[i] = ro;
         g.count[i] = cnt; g.F[i] = F; g.act_off[i] = ao; g.blob[i] = blob;
         if (!tiled) max_tiles = std::max(max_tiles, nt);
@@ -254,7 +277,7 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
             big.xcd_rot[i] = best;
             bdn.xcd_rot[i] = 0;   // the second half's panels cover every XCD (or K slices interleave them)
             wg_up += ef::ffn_gate_up_tiled_wgs(big.F[i], big.n_tiles[i]);
-            wg_dn += ef::ffn_down_tiled_wgs(d, big.n_tiles[i]) * ksg_tiled;
+            wg_dn += ef::ffn_down_tiled_wgs(d, big.n_tiles[i]) * (i == split_grp ? split_ksg : ksg_tiled);
         }
         big.wg_start[nb] = wg_up;
         bdn.wg_start[nb] = wg_dn;
@@ -287,7 +310,7 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
         }
         {
             KernelTimer kt(c, ts, EF_K_FFN_DOWN_TILED, b_dn, f_dn);
-            EF_HIP(c, ef::launch_ffn_down_tiled(bdn, wg_dn, ksg_tiled, c->act, c->y, y_plane, d, ts));
+            EF_HIP(c, ef::launch_ffn_down_tiled(bdn, wg_dn, ksg_tiled, split_grp, split_ksg, c->act, c->y, y_plane, d, ts));
         }
         if (side.forked) EF_HIP(c, side.record());
     }
@@ -431,7 +454,7 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
     }
     // K slices of the second half (one Y plane each, summed by the un-permute): the streamed launch and the tiled
     // launch of the layer choose separately, each for its own workgroup count
-    int ksg = 1, ksg_tiled = 1;
+    int ksg = 1, ksg_tiled = 1, split_expert = kNoSplit, split_ksg = 1;
     if (T > 0) {
         long long base_wgs = 0;
         // token tiles per pass of the streamed launch: from the groups that stream (the tiled ones have kernels of
@@ -476,6 +499,39 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         }
         int forced = c->tune.down_k_slices;
         if (forced >= 1 && forced <= 8 && y_plane * forced <= c->y_floats) ksg = ksg_tiled = forced;
+        // A tiled second half of more than one round of workgroups over the compute units ends in a round that is
+        // partly empty (1056 workgroups: four rounds and an eighth; every compute unit holds one at a time).  The
+        // layer's last tiled group (the one with the least work; the highest expert among equals) is cut into K
+        // slices so that its shorter workgroups fill that round: the slice count with the least modelled time,
+        // a Y plane more costing what the second half and the un-permute take to write and read it.  The choice
+        // depends on the layer's token counts only, never on what is resident.
+        if (use_tiled && ksg_tiled == 1 && forced < 1 && tiled_dn_wgs > 256 && c->tune.tiled_tail_slices != 0) {
+            long long best_work = -1, units = 0, rows = 0;
+            int F_last = 0;
+            auto consider = [&](int expert, int F, int cnt, bool routed) {
+                const int nt = (cnt + ef::kTile - 1) / ef::kTile;
+                if (!ef::ffn_tiled_ok(d, F, nt) || (routed && nt < c->tune.tiled_min_tiles)) return;
+                const long long work = (long long)nt * F;
+                if (best_work < 0 || work <= best_work) {
+                    best_work = work; split_expert = expert; units = ef::ffn_down_tiled_wgs(d, nt); rows = cnt; F_last = F;
+                }
+            };
+            if (has_shared) consider(-1, c->cfg.d_ff_shared, T, false);
+            for (int e = 0; e < E; ++e) consider(e, c->cfg.d_ff, counts_host[e], true);
+            if (split_expert != kNoSplit) {
+                const double unit_s = (F_last / 32) * 0.77e-6;                        // one workgroup: its K stages
+                const double plane_units = (double)rows * d * 8.0 / 5e12 / unit_s;     // write + read of one more plane
+                double best = 0.0;
+                for (int sl = 1; sl <= 8; sl *= 2) {
+                    if (F_last / 32 / sl < 16 || y_plane * sl > c->y_floats) break;
+                    const double t = tiled_tail_makespan(tiled_dn_wgs - units, units, sl) + (sl - 1) * plane_units;
+                    if (sl == 1 || t < best - 1e-9) { best = t; split_ksg = sl; }
+                }
+                const int want = c->tune.tiled_tail_slices;   // 1: the modelled best; 2, 4, 8: that count if it fits
+                if (want > 1 && F_last / 32 / want >= 16 && y_plane * want <= c->y_floats) split_ksg = want;
+                if (split_ksg == 1) split_expert = kNoSplit;
+            }
+        }
     }
     ef::PlaneTable planes{};
 
@@ -615,7 +671,7 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         if (with_shared && has_shared) g.push_back({-1, -1});
         if (!c->fake) {
             int r = launch_phase(c, layer, g, counts_host, offs_host, tile_start, act_off, shared_tile_start,
-                                 shared_act_off, T, ksg, ksg_tiled, planes, y_plane, use_tiled, s);
+                                 shared_act_off, T, ksg, ksg_tiled, split_expert, split_ksg, planes, y_plane, use_tiled, s);
             if (r) {   // part of the phase may be enqueued: its slots still get their read marker
                 (void)mark_read(v);
                 v.clear();   // released: the caller's error path has nothing left to unpin

@@ -468,6 +468,20 @@ def test_full_size_mixtral_prefill_layer(oracle_mod):
         for e in range(cfg.E):
             ef.ef_cache_swap_in(st.ctx, 0, e, 0, 0)
         res = ef.ef_cache_query(st.ctx, 0, cfg.E)
-        _sampled_layer_check(oracle_mod, st, 0, synth.hidden(cfg, 0, 8192), 8192, 0.0, res, 64, 4)
+        h = synth.hidden(cfg, 0, 8192)
+        _sampled_layer_check(oracle_mod, st, 0, h, 8192, 0.0, res, 64, 4)
+        # The second half has more than one round of workgroups over the compute units, so the group with the
+        # least work is cut into K slices of its own (planes summed by the un-permute).  Without the cut, and
+        # with a cut in two, the same layer must agree to the rounding of a different summation order.
+        hd = dev_u16(h)
+        r = st.route(0, hd, 8192, 0.0)
+        outs = {}
+        for slices in (1, 0, 2):
+            ef.ef_set_tuning(st.ctx, tiled_tail_slices=slices)
+            outs[slices] = st.ffn(0, hd, 8192, r).copy()
+        for slices in (0, 2):
+            diff = float(np.max(np.abs(outs[slices] - outs[1])))
+            say(f"  tail slices {slices} against the default: max abs difference {diff:.2e}")
+            assert 0.0 < diff < 1e-4      # different planes were summed, nothing else changed
     finally:
         st.close()
