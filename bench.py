@@ -133,9 +133,9 @@ def kernel_table(ef, st, wall, every=1):
 def traffic_from_profile(kernel_tag, cfg_name, T, beta):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary of this very
     workload (FETCH_SIZE + WRITE_SIZE scaled by a copy kernel); counters cannot be read from inside this run."""
-    path = os.path.join(ROOT, "profiles", "ffn_kernels_mixtral_decode_T64_pmc_traffic.md")
+    import glob
     tag = f"TRAFFIC_BYTES_PER_LAUNCH {kernel_tag} {cfg_name} T={T} beta={beta} ="
-    if os.path.exists(path):
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
         for line in open(path):
             if line.startswith(tag):
                 return float(line.split("=")[-1]), os.path.relpath(path, ROOT)
@@ -254,8 +254,11 @@ def run_workload(name, spec, args, cpu_seconds):
         bound, kname = KIND_BOUND[dom_name]
         if bound == "mfma":
             a = dom["TFLOPps"]
+            traffic, src = (None, None)
+            if not (all_resident or pool_slots or int4 or args.layers):
+                traffic, src = traffic_from_profile(kname, cfg.name, T, beta)
             roof = {"bound": "mfma", "kernel": kname, "achieved": a, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": a / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "avg_launch_us": dom["avg_us"],
+                    "frac": a / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic, "traffic_source": src, "avg_launch_us": dom["avg_us"],
                     "alg_flops_per_launch": dom["alg_flops_per_launch"], "launches": dom["launches"],
                     "share_of_step_time": dom["share_of_step_time"]}
         else:
