@@ -529,6 +529,19 @@ int ef_set_profile(ef_ctx *ctx, unsigned kinds_mask);
  * ef_stats then cover the sampled launches only. */
 int ef_set_profile_sampling(ef_ctx *ctx, int every);
 
+/* Measured ceilings of the context's device, for the roofline figures of a benchmark (not a step of the method: the
+ * paper's Sec. 4 reports throughput only; a roofline needs to know what the part delivers to any kernel).
+ *   EF_PEAK_HBM_READ:   a plain streaming read of `bytes` bytes at `buf` (device memory, 16-byte aligned, a multiple of
+ *                       8 MiB; use more than the 256 MiB the caches hold), `reps` times after one untimed pass; GB/s.
+ *   EF_PEAK_MFMA_16BIT: a loop of 32x32x16 bf16 matrix-core instructions on registers, on every SIMD; TFLOP/s
+ *                       (`buf`, `bytes` ignored).
+ * Synchronous: enqueues on `stream`, times with events and waits.  Uses the routing scratch of the context: not to be
+ * called while a routing call of the same context is in flight.  EF_EINVAL on bad arguments, EF_ENOSYS in fake-copy
+ * contexts. */
+#define EF_PEAK_HBM_READ 0
+#define EF_PEAK_MFMA_16BIT 1
+int ef_measure_peak(ef_ctx *ctx, int what, const void *buf, size_t bytes, int reps, double *result, void *stream);
+
 /* Fake-copy contexts only: advance the fake clock; copies complete after bytes/bandwidth seconds. */
 int ef_fake_advance_time(ef_ctx *ctx, double seconds);
 

@@ -30,7 +30,7 @@ EXPORTS = [
     "ef_strerror", "ef_expert_bytes", "ef_pack_expert", "ef_expert_bytes_q4", "ef_pack_expert_q4", "ef_create", "ef_destroy", "ef_last_error",
     "ef_register_layer", "ef_predict", "ef_route", "ef_route_predict", "ef_moe_ffn", "ef_layer_step", "ef_cache_swap_in", "ef_cache_query",
     "ef_choose_horizon", "ef_token_dist", "ef_get_stats", "ef_reset_stats", "ef_set_profile", "ef_set_profile_sampling",
-    "ef_fake_advance_time", "ef_layer_step_fetch", "ef_get_tuning", "ef_set_tuning", "ef_route_static",
+    "ef_fake_advance_time", "ef_layer_step_fetch", "ef_get_tuning", "ef_set_tuning", "ef_route_static", "ef_measure_peak",
     "ef_forest_create", "ef_forest_destroy", "ef_delta_features", "ef_forest_fit", "ef_forest_predict",
     "ef_forest_tree_size", "ef_forest_tree_export", "ef_forest_bit_accuracy", "ef_delta_from_activation",
     "ef_delta_cache_create", "ef_delta_cache_destroy", "ef_delta_cache_put", "ef_delta_cache_get",
@@ -128,6 +128,7 @@ def lib():
         L.ef_cache_query.argtypes = [vp, i32, vp]
         L.ef_choose_horizon.argtypes = [vp, i32, vp, i32, i32, C.POINTER(i32), vp, C.POINTER(i32)]
         L.ef_token_dist.argtypes = [vp, vp, i32, vp, vp, vp]
+        L.ef_measure_peak.argtypes = [vp, i32, vp, C.c_size_t, i32, C.POINTER(C.c_double), vp]
         L.ef_get_stats.argtypes = [vp, C.POINTER(ef_stats)]
         L.ef_reset_stats.argtypes = [vp]
         L.ef_set_profile.argtypes = [vp, C.c_uint]
@@ -347,6 +348,17 @@ def ef_set_tuning(ctx, **kw):
 def ef_token_dist(ctx, hidden, T, tok_dist, dist, stream=None):
     """Dist(t) of the batch: tok_dist [T] f32 (or None) and dist [1] f64, both on the device."""
     return _check(ctx, lib().ef_token_dist(ctx, _ptr(hidden), T, _ptr(tok_dist), _ptr(dist), _stream(stream)))
+
+
+EF_PEAK_HBM_READ, EF_PEAK_MFMA_16BIT = 0, 1
+
+
+def ef_measure_peak(ctx, what, buf=None, nbytes=0, reps=4, stream=None):
+    """Measured ceiling of the device: GB/s of a plain streaming read of `buf` (EF_PEAK_HBM_READ) or TFLOP/s of a
+    register-resident matrix-core loop (EF_PEAK_MFMA_16BIT)."""
+    out = C.c_double(0.0)
+    _check(ctx, lib().ef_measure_peak(ctx, what, _ptr(buf), nbytes, reps, C.byref(out), _stream(stream)))
+    return out.value
 
 
 def ef_cache_swap_in(ctx, layer, expert, priority=0, due_in=0):
