@@ -494,7 +494,7 @@ typedef struct ef_tuning {
     int32_t passes_of_four;          /* 0/1: streamed groups of >= 3 token tiles take passes of four tiles (1) */
     int32_t lds_shared;              /* 0/1: ... through the kernels whose waves share fragments in LDS (1) */
     int32_t lds_shared_occupancy;    /* 1..2: workgroups per compute unit of those kernels (2) */
-    int32_t up_want_waves;           /* >= 1: the streamed first half splits K inside a workgroup below this many waves (768) */
+    int32_t up_want_waves;           /* >= 1: the streamed first half splits K inside a workgroup below this many waves (640) */
     int32_t up_k_slices;             /* 0 = auto, else 1, 2 or 4 */
     int32_t down_want_wgs;           /* 0 = auto (256; 512 for the LDS-shared kernels), else >= 1: target of the K-slice split */
     int32_t down_k_slices;           /* 0 = auto, else 1..8: K-slice planes of the second half (both launches) */
@@ -508,6 +508,8 @@ typedef struct ef_tuning {
     int32_t copy_chunk_mib;          /* 1..1024: expert copies go to the link in chunks of at most this many MiB; a miss
                                         overtakes queued prefetches at the next chunk boundary (32) */
     int32_t copy_depth;              /* 1..8: chunks handed to the copy stream ahead of the one in transfer (2) */
+    int32_t down_tail_split;         /* 0/1: a streamed second half of a little more than one round of workgroups over
+                                        the compute units takes twice the K slices (1) */
     int32_t tiled_tail_slices;       /* a tiled second half of more than 256 workgroups cuts its last group into K slices
                                         that fill the launch's last, partly empty round: 0 = never, 1 = as many as a
                                         model of the launch finds best, 2 / 4 / 8 = that many (1) */

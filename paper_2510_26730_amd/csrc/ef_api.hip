@@ -673,7 +673,7 @@ void efi::tuning_defaults(ef_tuning *t) {
     t->passes_of_four = 1;
     t->lds_shared = 1;
     t->lds_shared_occupancy = 2;
-    t->up_want_waves = 768;
+    t->up_want_waves = 640;
     t->up_k_slices = 0;
     t->down_want_wgs = 0;
     t->down_k_slices = 0;
@@ -682,6 +682,7 @@ void efi::tuning_defaults(ef_tuning *t) {
     t->gate_k_split = 0;
     t->gate_token_split = 1;
     t->gate_fused_finish = 1;
+    t->down_tail_split = 1;
     t->tiled_tail_slices = 1;
     t->gate_stream = 1;
     t->early_pack = 1;
@@ -718,6 +719,7 @@ extern "C" int ef_set_tuning(ef_ctx *c, const ef_tuning *t) {
     else if (t->gate_k_split < 0 || t->gate_k_split > 16) bad = "gate_k_split";
     else if (!flag(t->gate_token_split)) bad = "gate_token_split";
     else if (!flag(t->gate_fused_finish)) bad = "gate_fused_finish";
+    else if (!flag(t->down_tail_split)) bad = "down_tail_split";
     else if (t->tiled_tail_slices != 0 && t->tiled_tail_slices != 1 && t->tiled_tail_slices != 2 &&
              t->tiled_tail_slices != 4 && t->tiled_tail_slices != 8) bad = "tiled_tail_slices";
     else if (!flag(t->gate_stream)) bad = "gate_stream";

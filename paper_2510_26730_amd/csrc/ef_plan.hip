@@ -489,6 +489,17 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         const int units = c->q4 ? nkb_min / 4 / 6 : tpp == 4 ? nkb_min / 4 / 8 : nkb_min / 4 / 32;
         while (ksg < 8 && base_wgs * ksg < want && units / (ksg * 2) >= 1 && y_plane * (ksg * 2) <= c->y_floats)
             ksg *= 2;
+        // A streamed launch of a little more than one round of workgroups (two fit a compute unit: 512 at a time)
+        // ends in a round that is mostly empty: 544 workgroups took 28 us where 512 took 22.5.  Twice the slices make
+        // the rounds half as long; taken when that saves at least a tenth of a round and a wave keeps >= 8 fragments.
+        if (!c->q4 && tpp <= 2 && c->tune.down_tail_split != 0 && c->tune.down_k_slices == 0) {
+            const long long slots = 512, w = base_wgs * ksg;
+            if (w > slots && ksg < 8 && nkb_min / (ksg * 2 * 4) >= 8 && y_plane * (ksg * 2) <= c->y_floats) {
+                const double now = (double)((w + slots - 1) / slots);
+                const double halved = (double)((2 * w + slots - 1) / slots) / 2.0;
+                if (halved + 0.1 < now) ksg *= 2;
+            }
+        }
         if (use_tiled) {
             // the tiled second half: slices until its 256 x 256 tiles fill the chip, each slice keeping at least
             // 16 stages

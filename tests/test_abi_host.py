@@ -323,7 +323,7 @@ def test_tuning_defaults_and_validation():
     try:
         t = ef.ef_get_tuning(ctx)
         assert t["tiled"] == 1 and t["tiled_min_tiles"] == 10 and t["lds_shared_occupancy"] == 2
-        assert t["up_want_waves"] == 768 and t["gate_k_split"] == 0 and t["early_pack"] == 1
+        assert t["up_want_waves"] == 640 and t["gate_k_split"] == 0 and t["early_pack"] == 1
         ef.ef_set_tuning(ctx, tiled=0, down_k_slices=4, up_k_slices=2)
         t2 = ef.ef_get_tuning(ctx)
         assert (t2["tiled"], t2["down_k_slices"], t2["up_k_slices"]) == (0, 4, 2)
