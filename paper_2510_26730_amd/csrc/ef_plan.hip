@@ -434,7 +434,7 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
     // with a 2048 x 5632 shared expert, 1056 tokens over 64 experts) the tiled kernels were equal to or
     // 8 % faster than streaming the same groups in several passes, even at 150-200 workgroups.
     bool use_tiled = false;
-    long long tiled_dn_wgs = 0;
+    long long tiled_dn_wgs = 0, tiled_rows = 0;
     int tiled_stages_min = 1 << 30;   // fewest K stages (32 columns each) among the tiled groups
     int tiled_stages_max = 0;         // ... and most
     if (T > 0 && (!c->q4 || c->q4_stage_slots > 0) && c->tune.tiled != 0) {
@@ -444,6 +444,7 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
             if (!ef::ffn_tiled_ok(d, F, nt) || (routed && nt < c->tune.tiled_min_tiles)) return;
             wg_up += ef::ffn_gate_up_tiled_wgs(F, nt);
             wg_dn += ef::ffn_down_tiled_wgs(d, nt);
+            tiled_rows += cnt;
             tiled_stages_min = std::min(tiled_stages_min, F / 32);
             tiled_stages_max = std::max(tiled_stages_max, F / 32);
         };
@@ -503,9 +504,19 @@ extern "C" int ef_moe_ffn(ef_ctx *c, int layer, const void *hidden, int T, const
         if (use_tiled) {
             // the tiled second half: slices until its 256 x 256 tiles fill the chip, each slice keeping at least
             // 16 stages
-            while (ksg_tiled < 8 && tiled_dn_wgs * ksg_tiled < 256 && (c->tune.down_slices_by_longest_k ? tiled_stages_max : tiled_stages_min) / (ksg_tiled * 2) >= 16 &&
-                   y_plane * (ksg_tiled * 2) <= c->y_floats)
-                ksg_tiled *= 2;
+            // (any count from 1 to 8: 40 tiles in 6 slices are 240 workgroups, one round over the 256 compute units
+            // at a sixth of the length, where 8 slices are 320 workgroups, two rounds at an eighth; a plane more is
+            // priced at what it takes to write and read)
+            if (tiled_dn_wgs < 256) {
+                const int stages_ref = c->tune.down_slices_by_longest_k ? tiled_stages_max : tiled_stages_min;
+                const double plane_pen = (double)tiled_rows * d * 8.0 / 5e12 / (stages_ref * 0.77e-6);
+                double best = 0.0;
+                for (int ks = 1; ks <= 8; ++ks) {
+                    if (ks > 1 && (stages_ref / ks < 16 || y_plane * ks > c->y_floats)) break;
+                    const double t = (double)((tiled_dn_wgs * ks + 255) / 256) / ks + (ks - 1) * plane_pen;
+                    if (ks == 1 || t < best - 1e-9) { best = t; ksg_tiled = ks; }
+                }
+            }
             if (c->tune.down_split_slice_counts == 0) ksg = ksg_tiled;   // one slice count for both launches
         }
         int forced = c->tune.down_k_slices;
