@@ -1,5 +1,5 @@
 // Expert cache runtime: completion polling of copies and timing events, the estimators of link bandwidth and
-// layer time, swap-in of experts over the copy streams, residency queries and the horizon controller
+// layer time, swap-in of experts through the copy queue, residency queries and the horizon controller
 // (paper Sec. 3.2.1, 3.2.2, 3.3, 3.4).  Declarations and argument contracts are in include/expertflow.h.
 #include "ef_ctx.h"
 
