@@ -493,7 +493,8 @@ typedef struct ef_tuning {
     int32_t sort_groups;             /* 0/1: groups with the most work first in a launch (1) */
     int32_t passes_of_four;          /* 0/1: streamed groups of >= 3 token tiles take passes of four tiles (1) */
     int32_t lds_shared;              /* 0/1: ... through the kernels whose waves share fragments in LDS (1) */
-    int32_t lds_shared_occupancy;    /* 1..2: workgroups per compute unit of those kernels (2) */
+    int32_t lds_shared_occupancy;    /* workgroups per compute unit of those kernels: 1, 2, or 0 = two only beside a tiled
+                                        launch that covers every compute unit (0) */
     int32_t up_want_waves;           /* >= 1: the streamed first half splits K inside a workgroup below this many waves (640) */
     int32_t up_k_slices;             /* 0 = auto, else 1, 2 or 4 */
     int32_t down_want_wgs;           /* 0 = auto (256; 512 for the LDS-shared kernels), else >= 1: target of the K-slice split */

@@ -672,7 +672,7 @@ void efi::tuning_defaults(ef_tuning *t) {
     t->sort_groups = 1;
     t->passes_of_four = 1;
     t->lds_shared = 1;
-    t->lds_shared_occupancy = 2;
+    t->lds_shared_occupancy = 0;
     t->up_want_waves = 640;
     t->up_k_slices = 0;
     t->down_want_wgs = 0;
@@ -709,7 +709,7 @@ extern "C" int ef_set_tuning(ef_ctx *c, const ef_tuning *t) {
     else if (!flag(t->sort_groups)) bad = "sort_groups";
     else if (!flag(t->passes_of_four)) bad = "passes_of_four";
     else if (!flag(t->lds_shared)) bad = "lds_shared";
-    else if (t->lds_shared_occupancy < 1 || t->lds_shared_occupancy > 2) bad = "lds_shared_occupancy";
+    else if (t->lds_shared_occupancy < 0 || t->lds_shared_occupancy > 2) bad = "lds_shared_occupancy";
     else if (t->up_want_waves < 1) bad = "up_want_waves";
     else if (t->up_k_slices != 0 && t->up_k_slices != 1 && t->up_k_slices != 2 && t->up_k_slices != 4) bad = "up_k_slices";
     else if (t->down_want_wgs < 0) bad = "down_want_wgs";

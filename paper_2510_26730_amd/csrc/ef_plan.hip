@@ -252,6 +252,7 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
         }
         ~SideJoin() { (void)wait(); }
     } side{c, s};
+    int tiled_up_wgs = 0;
     if (nb > 0) {
         ef::GroupTable bdn = big;
         int wg_up = 0, wg_dn = 0;
@@ -281,6 +282,7 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
         }
         big.wg_start[nb] = wg_up;
         bdn.wg_start[nb] = wg_dn;
+        tiled_up_wgs = wg_up;
         double b_up = 0.0, b_dn = 0.0, f_up = 0.0, f_dn = 0.0;
         alg_bytes(big, nb, b_up, b_dn);
         for (int i = 0; i < nb; ++i) {
@@ -349,9 +351,11 @@ int launch_phase(ef_ctx *c, int layer, const std::vector<PhaseGroup> &groups, co
     dn.wg_start[n] = wg_dn;
     double b_up = 0.0, b_dn = 0.0;
     alg_bytes(gu, n, b_up, b_dn);
-    // workgroups per CU of the LDS-shared kernels: two (with a shorter register ring) measured 0-1.5 % faster
-    // than one on the mixed DeepSeek- and Qwen-shaped batches
-    const int occ = c->tune.lds_shared_occupancy;
+    // workgroups per CU of the LDS-shared kernels: one (register ring of three stages) unless the phase's tiled first
+    // half runs for well over one round of workgroups over the compute units, in which case two smaller ones (ring of
+    // two stages) share each unit as the tiled launch frees it: Qwen-shaped batch (240-290 tiled workgroups) 217 -> 202 us
+    // per layer with one, DeepSeek-shaped mixed batch (350-580 tiled workgroups) 304 against 309 us with two
+    const int occ = c->tune.lds_shared_occupancy != 0 ? c->tune.lds_shared_occupancy : (tiled_up_wgs > 320 ? 2 : 1);
     {
         KernelTimer kt(c, s, EF_K_FFN_UP, b_up);
         if (shared) EF_HIP(c, ef::launch_ffn_gate_up_shared(gu, wg_gu, tpp, occ, c->xp, c->act, d, s));

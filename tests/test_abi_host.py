@@ -322,7 +322,7 @@ def test_tuning_defaults_and_validation():
     ctx = fake_ctx()
     try:
         t = ef.ef_get_tuning(ctx)
-        assert t["tiled"] == 1 and t["tiled_min_tiles"] == 10 and t["lds_shared_occupancy"] == 2
+        assert t["tiled"] == 1 and t["tiled_min_tiles"] == 10 and t["lds_shared_occupancy"] == 0
         assert t["up_want_waves"] == 640 and t["gate_k_split"] == 0 and t["early_pack"] == 1
         assert t["copy_chunk_mib"] == 32 and t["copy_depth"] == 2 and t["tiled_tail_slices"] == 1 and t["down_tail_split"] == 1
         ef.ef_set_tuning(ctx, tiled=0, down_k_slices=4, up_k_slices=2)

@@ -434,17 +434,20 @@ def test_full_size_qwen_mixed_batch(oracle_mod, force_tiled):
         st.close()
 
 
-@pytest.mark.parametrize("streamed_form", ["shared4", "plain4", "plain2"])
+@pytest.mark.parametrize("streamed_form", ["shared4", "shared4_two_per_cu", "plain4", "plain2"])
 def test_full_size_deepseek_prefill(oracle_mod, streamed_form):
     """DeepSeek-V2-Lite-shaped layer at its three batch shapes: 32 decode tokens, 1024 prefill tokens and
     the mixed 1056 (shared experts through the tiled kernels from 256 tokens on, routed experts
     streamed).  The routed experts of the larger batches hold 3-7 token tiles: by default they take passes of
-    four tiles through the kernels that share fragments in LDS; the other two forms (plain kernels with
+    four tiles through the kernels that share fragments in LDS (one workgroup per compute unit, or two with a
+    shorter register ring: the form taken beside a large tiled launch); the other two forms (plain kernels with
     passes of four, or of two tiles) are forced through ef_set_tuning."""
     cfg = synth.CONFIGS["deepseek_v2_lite"]
     st = LayerStack(cfg, 1, slots_total=cfg.E, max_tokens=1056)
     try:
-        if streamed_form != "shared4":
+        if streamed_form == "shared4_two_per_cu":
+            ef.ef_set_tuning(st.ctx, lds_shared_occupancy=2)
+        elif streamed_form != "shared4":
             ef.ef_set_tuning(st.ctx, lds_shared=0)
         if streamed_form == "plain2":
             ef.ef_set_tuning(st.ctx, passes_of_four=0)
