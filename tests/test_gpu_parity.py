@@ -458,6 +458,16 @@ def test_full_size_deepseek_prefill(oracle_mod, streamed_form):
             say(f"full size: DeepSeek-V2-Lite-shaped layer, T={T}, shared experts")
             res_now = ef.ef_cache_query(st.ctx, 0, cfg.E)
             _sampled_layer_check(oracle_mod, st, 0, synth.hidden(cfg, 0, T), T, 0.5, res_now, n_sample, seed)
+        if streamed_form == "shared4":
+            # which of the two LDS-sharing forms a launch takes depends on what else is in the launch (how many
+            # tiled workgroups run beside it), so the two must agree bit for bit: same sums in the same order
+            hd = dev_u16(synth.hidden(cfg, 0, 1056))
+            r = st.route(0, hd, 1056, 0.5)
+            outs = []
+            for occ in (1, 2):
+                ef.ef_set_tuning(st.ctx, lds_shared_occupancy=occ)
+                outs.append(st.ffn(0, hd, 1056, r))
+            assert np.array_equal(outs[0], outs[1])
     finally:
         st.close()
 
