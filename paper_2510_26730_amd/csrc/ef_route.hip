@@ -529,9 +529,11 @@ static hipError_t launch_gate_stream(const GateArgs &a, hipStream_t s) {
     // wave reduction and per-token epilogue then overlap the other's streaming (4.5 -> 6.2 TB/s of hidden states
     // at 131072 tokens and 8 logit columns).  Stages of 256 columns: with 512 the same LDS holds fewer stages
     // and the kernel is slower even at one workgroup per unit (4.5 against 5.0 TB/s).
-    // With fewer than two workgroups per compute unit in the launch there is nothing to overlap with, and the
-    // deeper pipeline of the single-workgroup form is worth more (8192 tokens with 16 columns: 21 against 23 us).
-    const bool two = (long long)ntiles * ngroups >= 512;
+    // With about one workgroup per compute unit in the launch there is nothing to overlap with, and the deeper
+    // pipeline of the single-workgroup form is worth more (8192 tokens with 16 columns: 21 against 23 us); with more
+    // than one per unit the single-workgroup form needs a second, mostly empty round over the compute units (9216
+    // tokens took 24 us, 10240 tokens in the two-per-unit form 21 us), and two per unit fit the launch into one.
+    const bool two = (long long)ntiles * ngroups > 256;
     if (n_max > 32) hipLaunchKernelGGL((gate_stream_kernel<2, 8, 256, 1>), grid, block, 0, s, a);
     else if (n_max > 8) {
         if (two) hipLaunchKernelGGL((gate_stream_kernel<1, 4, 256, 2>), grid, block, 0, s, a);
