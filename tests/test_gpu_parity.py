@@ -472,6 +472,38 @@ def test_full_size_deepseek_prefill(oracle_mod, streamed_form):
         st.close()
 
 
+TAIL_SHARED = shape("tiny", name="tail_shared", d=1024, E=2, k=2, F=2048, F_shared=1024, slots_per_layer=2)
+
+
+def test_tail_cut_of_a_tiled_second_half_can_fall_on_the_shared_ffn(oracle_mod):
+    """Two routed experts that every token uses (top-2 of 2) and a shared FFN of half their hidden size at 6144
+    tokens: the tiled second half is 3 x 24 token panels x 4 column panels = 288 workgroups, more than one round over
+    the compute units, and the group with the least work, whose K range is cut into slices of its own, is the
+    shared FFN (its planes are summed by the un-permute's shared-row path).  Against the oracle, and against the
+    same layer without the cut."""
+    cfg = TAIL_SHARED
+    T = 6144
+    say(f"tail cut on the shared FFN: {cfg.name} T={T}")
+    st = LayerStack(cfg, 1, slots_total=2, max_tokens=T)
+    try:
+        for e in range(cfg.E):
+            ef.ef_cache_swap_in(st.ctx, 0, e, 0, 0)
+        res = ef.ef_cache_query(st.ctx, 0, cfg.E)
+        h = synth.hidden(cfg, 0, T)
+        _sampled_layer_check(oracle_mod, st, 0, h, T, 0.0, res, 48, 9)
+        hd = dev_u16(h)
+        r = st.route(0, hd, T, 0.0)
+        outs = {}
+        for slices in (1, 0):
+            ef.ef_set_tuning(st.ctx, tiled_tail_slices=slices)
+            outs[slices] = st.ffn(0, hd, T, r).copy()
+        diff = float(np.max(np.abs(outs[0] - outs[1])))
+        say(f"  with against without the cut: max abs difference {diff:.2e}")
+        assert 0.0 < diff < 1e-4
+    finally:
+        st.close()
+
+
 def test_full_size_mixtral_prefill_layer(oracle_mod):
     cfg = synth.CONFIGS["mixtral_prefill"]
     say("full size: Mixtral-shaped prefill layer, T=8192")
