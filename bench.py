@@ -38,7 +38,10 @@ WORKLOADS = {
     "deepseek_decode": dict(cfg="deepseek_v2_lite", baseline_config=4, T=32, beta=6.0, steps=12, warmup=4,
                             note="32 decode tokens, 16 of 64 slots per layer"),
     "deepseek_decode_beta4": dict(cfg="deepseek_v2_lite", baseline_config=4, T=32, beta=4.0, steps=12, warmup=6,
-                                  note="operating point with misses and prefetches (lower residency bias)"),
+                                  note="operating point with a few misses per step (lower residency bias)"),
+    "deepseek_decode_beta3": dict(cfg="deepseek_v2_lite", baseline_config=4, T=32, beta=3.0, steps=12, warmup=6,
+                                  note="hit rate 97-98 %: the band in which the look-ahead issues prefetches every few "
+                                       "layers and the link still has room (no-prediction and fixed horizons: DESIGN)"),
     "deepseek_mixed": dict(cfg="deepseek_v2_lite", baseline_config=4, T=1056, beta=8.0, steps=6, warmup=3,
                            note="1024 prefill + 32 decode tokens, 16 of 64 slots per layer"),
     "qwen_mixed": dict(cfg="qwen15_moe", baseline_config=5, T=640, beta=8.0, steps=8, warmup=4,
@@ -47,7 +50,8 @@ WORKLOADS = {
                              note="popularity ranks re-drawn every 256 tokens (every step): the resident set must be "
                                   "replaced each step, the link is saturated whatever the look-ahead"),
 }
-DEFAULT_SET = ["mixtral_decode", "tiny", "mixtral_prefill", "deepseek_decode", "deepseek_decode_beta4", "deepseek_mixed",
+DEFAULT_SET = ["mixtral_decode", "tiny", "mixtral_prefill", "deepseek_decode", "deepseek_decode_beta4", "deepseek_decode_beta3",
+               "deepseek_mixed",
                "qwen_mixed", "qwen_mixed_drift"]
 # kernel kind -> (what bounds it, name in the roofline object)
 KIND_BOUND = {"ffn_up": ("hbm", "ffn_gate_up_kernel (weight streaming)"), "ffn_down": ("hbm", "ffn_down_kernel (weight streaming)"),
