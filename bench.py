@@ -196,8 +196,9 @@ def run_workload(name, spec, args, cpu_seconds):
     pool_slots = spec.get("pool_slots")
     int4 = spec.get("int4", False)
     stream = torch.cuda.current_stream()
+    extra = {} if args.tau is None else {"cum_threshold": args.tau}
     loop = LayerLoop(cfg, L, T, slots, pool_slots=pool_slots, beta=beta, profile=False, all_resident=all_resident,
-                     q4=int4)
+                     q4=int4, **extra)
     loop.h_fixed = spec.get("horizon")
     if args.tune:
         ef.ef_set_tuning(loop.ctx, **dict((kv.split("=")[0], int(kv.split("=")[1])) for kv in args.tune))
@@ -449,6 +450,8 @@ def main():
     ap.add_argument("--pool-slots", type=int, default=None,
                     help="one global pool of this many cache slots shared by all layers instead of a per-layer quota")
     ap.add_argument("--horizon", type=int, default=None, help="fixed look-ahead H (default: the adaptive horizon)")
+    ap.add_argument("--tau", type=float, default=None,
+                    help="cumulative share of the predicted demand whose experts are prefetched (default: the library's 0.9)")
     ap.add_argument("--drift-tokens", type=int, default=None,
                     help="re-draw the expert popularity ranks (gate biases) whenever the running token count "
                          "crosses a multiple of this (0 = static popularity)")
