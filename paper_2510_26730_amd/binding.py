@@ -79,7 +79,7 @@ class ef_tuning(C.Structure):
         "sort_groups", "passes_of_four", "lds_shared", "lds_shared_occupancy", "up_want_waves", "up_k_slices",
         "down_want_wgs", "down_k_slices", "down_slices_by_longest_k", "down_split_slice_counts", "gate_k_split",
         "gate_token_split", "gate_fused_finish", "gate_stream", "early_pack", "copy_chunk_mib", "copy_depth",
-        "down_tail_split", "tiled_tail_slices")]
+        "down_tail_split", "tiled_tail_slices", "dist_form")]
 
 
 class ef_forest_config(C.Structure):

@@ -426,7 +426,8 @@ extern "C" int ef_token_dist(ef_ctx *c, const void *hidden, int T, float *tok_di
     const double bytes = 6.0 * T * d + 8.0 * T;
     KernelTimer kt(c, s, EF_K_DIST, bytes, flops);
     EF_HIP(c, ef::launch_pack_x(pt, ntiles, static_cast<const uint16_t *>(hidden), d, 1, nullptr, c->xp, false, s));
-    EF_HIP(c, ef::launch_token_dist(static_cast<const uint16_t *>(hidden), T, d, c->xp, c->y, tok_dist, dist, s));
+    EF_HIP(c, ef::launch_token_dist(static_cast<const uint16_t *>(hidden), T, d, c->xp, c->y, tok_dist, dist,
+                                    c->tune.dist_form, s));
     return EF_OK;
 }
 
@@ -684,6 +685,7 @@ void efi::tuning_defaults(ef_tuning *t) {
     t->gate_fused_finish = 1;
     t->down_tail_split = 1;
     t->tiled_tail_slices = 1;
+    t->dist_form = 0;
     t->gate_stream = 1;
     t->early_pack = 1;
     t->copy_chunk_mib = 32;
@@ -722,6 +724,7 @@ extern "C" int ef_set_tuning(ef_ctx *c, const ef_tuning *t) {
     else if (!flag(t->down_tail_split)) bad = "down_tail_split";
     else if (t->tiled_tail_slices != 0 && t->tiled_tail_slices != 1 && t->tiled_tail_slices != 2 &&
              t->tiled_tail_slices != 4 && t->tiled_tail_slices != 8) bad = "tiled_tail_slices";
+    else if (t->dist_form < 0 || t->dist_form > 2) bad = "dist_form";
     else if (!flag(t->gate_stream)) bad = "gate_stream";
     else if (!flag(t->early_pack)) bad = "early_pack";
     else if (t->copy_chunk_mib < 1 || t->copy_chunk_mib > 1024) bad = "copy_chunk_mib";

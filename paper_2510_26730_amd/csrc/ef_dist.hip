@@ -14,6 +14,7 @@
 //      sums) into Dist(t) in fp64: the result does not depend on scheduling.
 #include "ef_device.h"
 #include "ef_kernels.h"
+#include "ef_tiled_pipeline.h"
 
 namespace ef {
 
@@ -126,6 +127,114 @@ __global__ __launch_bounds__(256, 2) void dist_tile_kernel(const uint4 *__restri
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Gram tiles through the LDS operand pipeline (large batches): a workgroup owns 256 rows i x 256 columns
+// j, both operands are token fragments.  Same accumulation order over k, same epilogue sums and the same
+// partials as dist_tile_kernel: the two forms give the same bits.
+//
+// Only blocks with a pair i < j exist (block row IB <= block column JB).  They are numbered in strips of
+// four block rows, column by column within a strip, so that 32 consecutive blocks cover about 4 block
+// rows x 8 block columns; runs of 32 go to the XCDs in turn (workgroups with the same index mod 8 share an
+// XCD and run side by side on its 32 compute units), so the 64 operand panels of a run are 12 distinct ones
+// and an XCD's L2 serves the rest.
+// ------------------------------------------------------------------------------------------
+constexpr int kGramRun = 32;     // consecutive blocks that one XCD runs side by side
+constexpr int kGramStrip = 4;    // block rows per strip
+
+// blocks in the strips before strip R (nB block rows / columns)
+__host__ __device__ inline long long gram_blocks_before(int R, int nB) {
+    const long long r = kGramStrip * R < nB ? kGramStrip * R : nB;   // block rows before the strip
+    return r * nB - r * (r - 1) / 2;                           // row IB holds nB - IB blocks
+}
+inline long long gram_blocks(int nB) { return (long long)nB * (nB + 1) / 2; }
+constexpr long long kDistTiledMinBlocks = 64;
+
+__global__ __launch_bounds__(256, 1) void dist_gram_tiled_kernel(const uint4 *__restrict__ xp,
+                                                                  const float *__restrict__ norms, int T, int d,
+                                                                  float *__restrict__ part, int t_pad,
+                                                                  int n_rowblk, int nB, long long total) {
+    constexpr bool kSwapOperands = false;
+    constexpr bool HALF = false;   // bf16 token fragments
+    __shared__ __attribute__((aligned(16))) u32x4_t lds[kTileStages][kStageFrags][64];
+    const int w = blockIdx.x;
+    const long long t = ((long long)(w >> 3) / kGramRun * 8 + (w & 7)) * kGramRun + ((w >> 3) % kGramRun);
+    if (t >= total) return;
+    // strip R, then the block within the strip: its first h columns hold 1..h blocks (the diagonal), the
+    // columns after them h blocks each
+    int R = 0;
+    while (gram_blocks_before(R + 1, nB) <= t) ++R;
+    const int u = (int)(t - gram_blocks_before(R, nB));
+    const int h = min(kGramStrip, nB - kGramStrip * R);
+    int a, cidx;
+    if (u < h * (h + 1) / 2) {
+        cidx = 0;
+        while ((cidx + 1) * (cidx + 2) / 2 <= u) ++cidx;
+        a = u - cidx * (cidx + 1) / 2;
+    } else {
+        const int v = u - h * (h + 1) / 2;
+        cidx = h + v / h;
+        a = v % h;
+    }
+    const int IB = kGramStrip * R + a, JB = kGramStrip * R + cidx;
+
+    const int ntiles = (T + kTile - 1) / kTile;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS DMA targets go through M0
+    const int wi = wave & 1, wj = wave >> 1;
+    const int nkb = d >> 4;
+    const int nstage = nkb / kTileKS;
+    const int it0 = IB * 8, jt0 = JB * 8;
+
+    // operand A slots 0..7 = row tiles it0..it0+7, operand B slots 8..15 = column tiles jt0..jt0+7
+    const u32x4_t *src[kStageFrags / 4];
+#pragma unroll
+    for (int q = 0; q < kStageFrags / 4; ++q) {
+        const int fi = q * 4 + wave;
+        const int ks = fi >> 4, slot = fi & 15;
+        const int tile = min(slot < 8 ? it0 + slot : jt0 + slot - 8, ntiles - 1);
+        src[q] = reinterpret_cast<const u32x4_t *>(xp + ((size_t)tile * nkb + ks) * 64 + lane);
+    }
+
+    floatx16 acc[4][4];   // [row tile][column tile]
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) zero16(acc[i][j]);
+
+    const int AOFF = wi * 4, BOFF = wj * 4;
+    const unsigned lds_base = (unsigned)(size_t)&lds[0][0][0];   // LDS byte offset: the low half of its flat address
+    // column tiles of this wave that exist; none count when every row of the wave is past every column
+    // (the lower left quarter of a diagonal block)
+    const bool below = it0 + AOFF >= jt0 + BOFF + 4;
+    const int live = below ? 0 : max(0, min(4, ntiles - (jt0 + BOFF)));
+    EF_TILED_PIPELINE_TILES_B(0, nstage, live)
+
+    const int g = lane >> 5, c = lane & 31;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const int j = (jt0 + BOFF + b) * kTile + c;
+        const float nj = j < T ? norms[j] : 0.f;
+#pragma unroll
+        for (int rp = 0; rp < 2; ++rp) {   // the wave's two 64-row blocks of the partials
+            const int rowblk = IB * 4 + wi * 2 + rp;
+            float sum = 0.f;
+#pragma unroll
+            for (int aa = 0; aa < 2; ++aa) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int i = (it0 + AOFF + 2 * rp + aa) * kTile + 8 * (v >> 2) + 4 * g + (v & 3);
+                    if (i < j && j < T) {
+                        const float sq = norms[i] + nj - 2.f * acc[2 * rp + aa][b][v];
+                        sum += __builtin_sqrtf(fmaxf(sq, 0.f));
+                    }
+                }
+            }
+            sum += __shfl_xor(sum, 32);
+            if (g == 0 && j < t_pad && rowblk < n_rowblk) part[(size_t)rowblk * t_pad + j] = sum;
+        }
+    }
+}
+
 // s[j] = partials of row blocks 0 .. j/64 in ascending order; workgroup sum in fp64 by a fixed tree
 __global__ __launch_bounds__(256) void dist_reduce_kernel(const float *__restrict__ part, int T, int t_pad,
                                                           float *__restrict__ tok_dist,
@@ -134,7 +243,17 @@ __global__ __launch_bounds__(256) void dist_reduce_kernel(const float *__restric
     const int j = blockIdx.x * 256 + threadIdx.x;
     double s = 0.0;
     if (j < T) {
-        for (int rb = 0; rb <= (j >> 6); ++rb) s += (double)part[(size_t)rb * t_pad + j];
+        // eight loads in flight, added in ascending order of the row block
+        const int n = (j >> 6) + 1;
+        int rb = 0;
+        for (; rb + 8 <= n; rb += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = part[(size_t)(rb + u) * t_pad + j];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += (double)v[u];
+        }
+        for (; rb < n; ++rb) s += (double)part[(size_t)rb * t_pad + j];
         if (tok_dist) tok_dist[j] = (float)s;
     }
     red[threadIdx.x] = s;
@@ -162,8 +281,8 @@ size_t dist_scratch_floats(int T) {
 }
 
 hipError_t launch_token_dist(const uint16_t *h, int T, int d, const void *xp, float *scratch, float *tok_dist,
-                             double *dist, hipStream_t s) {
-    if (T <= 0 || d % 64 != 0) return hipErrorInvalidValue;
+                             double *dist, int form, hipStream_t s) {
+    if (T <= 0 || d % 64 != 0 || form < 0 || form > 2) return hipErrorInvalidValue;
     const int ntiles = (T + kTile - 1) / kTile;
     const int t_pad = ntiles * kTile;
     const int n_rowblk = (T + 63) / 64;
@@ -175,10 +294,22 @@ hipError_t launch_token_dist(const uint16_t *h, int T, int d, const void *xp, fl
     off += off & 1;
     double *wg_sums = reinterpret_cast<double *>(scratch + off);
     hipLaunchKernelGGL(dist_norm_kernel, dim3((t_pad + 3) / 4), dim3(256), 0, s, h, T, d, norms, t_pad);
-    const int nJB = (ntiles + kDistColTiles - 1) / kDistColTiles;
-    const int nIB = (ntiles + kDistRowTiles - 1) / kDistRowTiles;
-    hipLaunchKernelGGL(dist_tile_kernel, dim3(nJB, nIB), dim3(256), 0, s, reinterpret_cast<const uint4 *>(xp),
-                       norms, T, d, part, t_pad, n_rowblk);
+    // 256 x 256 blocks through LDS once they fill a quarter of the compute units; below that the
+    // 128 x 256 blocks of the register-fed kernel, two to a compute unit, spread the batch wider
+    const int nB = (ntiles + 7) / 8;
+    const long long total = gram_blocks(nB);
+    if (form == 2 || (form == 0 && total >= kDistTiledMinBlocks)) {
+        const long long runs = (total + kGramRun - 1) / kGramRun;
+        const long long grid = (runs + 7) / 8 * 8 * kGramRun;
+        if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(dist_gram_tiled_kernel, dim3((unsigned)grid), dim3(256), 0, s,
+                           reinterpret_cast<const uint4 *>(xp), norms, T, d, part, t_pad, n_rowblk, nB, total);
+    } else {
+        const int nJB = (ntiles + kDistColTiles - 1) / kDistColTiles;
+        const int nIB = (ntiles + kDistRowTiles - 1) / kDistRowTiles;
+        hipLaunchKernelGGL(dist_tile_kernel, dim3(nJB, nIB), dim3(256), 0, s, reinterpret_cast<const uint4 *>(xp),
+                           norms, T, d, part, t_pad, n_rowblk);
+    }
     hipLaunchKernelGGL(dist_reduce_kernel, dim3(n_wg), dim3(256), 0, s, part, T, t_pad, tok_dist, wg_sums);
     hipLaunchKernelGGL(dist_final_kernel, dim3(1), dim3(64), 0, s, wg_sums, n_wg, dist);
     return hipGetLastError();

@@ -137,8 +137,9 @@ hipError_t launch_dequant_q4(const DequantTable &t, int d, hipStream_t s);
 
 // Dist(t): scratch floats launch_token_dist needs for T tokens (norms, partials, workgroup sums)
 size_t dist_scratch_floats(int T);
+// `form`: 0 = by batch size, 1 = register-fed 128 x 256 Gram blocks, 2 = 256 x 256 blocks through LDS (same bits)
 hipError_t launch_token_dist(const uint16_t *h, int T, int d, const void *xp, float *scratch, float *tok_dist,
-                             double *dist, hipStream_t s);
+                             double *dist, int form, hipStream_t s);
 
 // f16: the W1 / W3 fragments and the packed tokens hold fp16 instead of bf16 (4-bit contexts: the blobs are
 // the staging copies launch_dequant_q4 wrote).  Activations and W2 fragments are fp16 in every context.

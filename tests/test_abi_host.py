@@ -324,13 +324,13 @@ def test_tuning_defaults_and_validation():
         t = ef.ef_get_tuning(ctx)
         assert t["tiled"] == 1 and t["tiled_min_tiles"] == 10 and t["lds_shared_occupancy"] == 0
         assert t["up_want_waves"] == 640 and t["gate_k_split"] == 0 and t["early_pack"] == 1
-        assert t["copy_chunk_mib"] == 32 and t["copy_depth"] == 2 and t["tiled_tail_slices"] == 1 and t["down_tail_split"] == 1
+        assert t["copy_chunk_mib"] == 32 and t["copy_depth"] == 2 and t["tiled_tail_slices"] == 1 and t["down_tail_split"] == 1 and t["dist_form"] == 0
         ef.ef_set_tuning(ctx, tiled=0, down_k_slices=4, up_k_slices=2)
         t2 = ef.ef_get_tuning(ctx)
         assert (t2["tiled"], t2["down_k_slices"], t2["up_k_slices"]) == (0, 4, 2)
         for bad in (dict(tiled=2), dict(tiled_min_tiles=7), dict(up_k_slices=3), dict(down_k_slices=9),
                     dict(gate_k_split=17), dict(lds_shared_occupancy=3), dict(up_want_waves=0),
-                    dict(tiled_min_up_wgs=0), dict(early_pack=-1), dict(tiled_tail_slices=3), dict(down_tail_split=2),
+                    dict(tiled_min_up_wgs=0), dict(early_pack=-1), dict(tiled_tail_slices=3), dict(down_tail_split=2), dict(dist_form=3),
                     dict(copy_chunk_mib=0), dict(copy_depth=9)):
             with pytest.raises(ef.EfError) as ei:
                 ef.ef_set_tuning(ctx, **bad)

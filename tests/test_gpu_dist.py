@@ -113,6 +113,27 @@ def test_full_size_prefill_batch_sampled(oracle_mod):
     assert np.all(np.isfinite(tok)) and np.all(tok[1:] > 0)
 
 
+@pytest.mark.parametrize("T,d", [(1, 64), (33, 64), (257, 128), (300, 192), (1025, 64), (1400, 256), (2304, 64)])
+def test_both_gram_forms_give_the_same_bits_and_match_oracle(oracle_mod, T, d):
+    """The Gram blocks staged through LDS (256 x 256, numbered in strips over the upper triangle) against the
+    register-fed blocks and the oracle, at sizes of 1 to 9 block columns with ragged last blocks."""
+    say(f"dist forms T={T} d={d}")
+    rng = np.random.default_rng(4000 + T)
+    h = synth.f32_to_bf16(rng.standard_normal((T, d)).astype(np.float32))
+    ctx = make_ctx(d, max(T, 64))
+    try:
+        out = {}
+        for form in (1, 2):
+            ef.ef_set_tuning(ctx, dist_form=form)
+            out[form] = run_dist(ctx, h, T)
+    finally:
+        ef.ef_destroy(ctx)
+    assert np.array_equal(out[1][0], out[2][0]) and out[1][1] == out[2][1]
+    ref = oracle_mod.token_dist(h)
+    np.testing.assert_allclose(out[2][0], ref, rtol=1e-5, atol=1e-5 * T)
+    assert abs(out[2][1] - ref.sum()) <= 1e-6 * max(ref.sum(), 1.0)
+
+
 def test_argument_errors():
     ctx = make_ctx(64, 64)
     try:
