@@ -11,8 +11,8 @@
 // register ring of kDepth stages filled that many stages ahead with unconditional loads (clamped
 // addresses), one barrier per stage.  Dequantisation happens on the operand fragment, where a lane
 // holds one matrix row (column) and therefore needs one scale per group, and in fp16: the codes
-// become the fp16 numbers 1024 + q by bit operations, a packed subtraction gives q - 8 exactly and a
-// packed multiplication (q - 8) * s: four vector instructions per pair of weights where an fp32
+// become the fp16 numbers 1024 + q (or 64 + q) by one bit operation, a packed subtraction gives q - 8 exactly and
+// a packed multiplication (q - 8) * s: three vector instructions per pair of weights where an fp32
 // route costs seven, which is what keeps these kernels on the memory side of the balance.  The
 // matrix cores therefore run in fp16 (fp32 accumulation): the packed tokens of a 4-bit context and
 // the intermediate activations are fp16 fragments (tokens convert exactly from bf16 for
@@ -28,16 +28,26 @@ typedef _Float16 q4_half2 __attribute__((ext_vector_type(2)));
 typedef _Float16 q4_half8 __attribute__((ext_vector_type(8)));
 
 // dword x = eight codes of one lane for one k-step, code t at bits 4*(t/2) + 16*(t%2);
-// s2 = the lane's scale in both halves.  (x >> 4p) & 0x000F000F | 0x64006400 is the pair of fp16
-// numbers 1024 + q for t = 2p, 2p + 1; minus 1032 is q - 8 exactly; times s rounds once to fp16
-// (11 significant bits for a 4-bit integer times an 8-bit mantissa: relative error <= 2^-12).
+// s2 = the lane's scale in both halves.  Codes in mantissa bits 0..3 under the exponent of 1024 (unit in the
+// last place 1) are the fp16 numbers 1024 + q, codes in mantissa bits 4..7 under the exponent of 64 (unit
+// 1/16) are 64 + q: x & 0x000F000F | 0x64006400 is the pair t = 0, 1, x & 0x00F000F0 | 0x54005400 the pair
+// t = 2, 3, and x >> 8 gives the other two pairs the same way (one shift per dword instead of three).  Minus
+// 1032 (72) is q - 8 exactly; times s rounds once to fp16 (11 significant bits for a 4-bit integer times an
+// 8-bit mantissa: relative error <= 2^-12).
 __device__ __forceinline__ u32x4_t dequant_q4(uint32_t x, q4_half2 s2) {
-    const q4_half2 off = {(_Float16)-1032.f, (_Float16)-1032.f};
+    const q4_half2 off_lo = {(_Float16)-1032.f, (_Float16)-1032.f}, off_hi = {(_Float16)-72.f, (_Float16)-72.f};
+    const uint32_t y = x >> 8;
+    // the masks live in vector registers the compiler cannot see through: "and" and "or" then fit one
+    // three-operand instruction (it takes a single literal, here the exponent pattern)
+    uint32_t m_lo = 0x000F000Fu, m_hi = 0x00F000F0u;
+    asm("" : "+v"(m_lo));
+    asm("" : "+v"(m_hi));
+    const uint32_t pr[4] = {(x & m_lo) | 0x64006400u, (x & m_hi) | 0x54005400u,
+                            (y & m_lo) | 0x64006400u, (y & m_hi) | 0x54005400u};
     u32x4_t out;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-        const uint32_t pr = ((x >> (4 * p)) & 0x000F000Fu) | 0x64006400u;
-        const q4_half2 w = (__builtin_bit_cast(q4_half2, pr) + off) * s2;
+        const q4_half2 w = (__builtin_bit_cast(q4_half2, pr[p]) + ((p & 1) ? off_hi : off_lo)) * s2;
         out[p] = __builtin_bit_cast(uint32_t, w);
     }
     return out;
