@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libexpertflow.so")
 SOURCES = ["ef_api.hip", "ef_runtime.hip", "ef_plan.hip", "ef_static.hip", "ef_route.hip", "ef_ffn.hip", "ef_ffn_tiled.hip", "ef_ffn_shared.hip", "ef_ffn_q4.hip", "ef_dist.hip", "ef_calib.hip", "ef_forest.cpp"]
-HEADERS = ["ef_ctx.h", "ef_kernels.h", "ef_device.h", "ef_cache.h", os.path.join("..", "..", "include", "expertflow.h")]
+HEADERS = ["ef_ctx.h", "ef_kernels.h", "ef_device.h", "ef_cache.h", "ef_tiled_pipeline.h", os.path.join("..", "..", "include", "expertflow.h")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

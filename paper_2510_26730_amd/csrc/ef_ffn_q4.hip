@@ -59,19 +59,27 @@ __device__ __forceinline__ q4_half2 q4_scale(uint16_t b) {
     return q4_half2{h, h};
 }
 
-// register ring: stages in flight per wave (four were measured slower than six with two token tiles per pass)
+// register ring: stages in flight per wave (four were measured slower than six with two token tiles per pass
+// and one wave per SIMD)
 template <int TT> constexpr int q4_depth() { return 6; }
 constexpr int kQ4Lds = 4;     // LDS ring of shared token / activation fragments (stages)
 
 // ------------------------------------------------------------------------------------------
 // first half: act = silu(X W1^T) * (X W3^T).  Workgroup = (group, pass of TT token tiles, four
-// consecutive 32-row blocks of F), wave = one row block, whole K range.
+// consecutive 32-row blocks of F), wave = one row block and one of KH halves of the K range.
+//
+// KH = 2: eight waves, two per SIMD.  A wave issues in order, so with one wave per SIMD its dequantising
+// vector instructions (about 40 % of its cycles), its waits for LDS and barriers (25 %) and its issue stalls
+// add up; a second wave on the SIMD fills them.  A launch rarely has enough row blocks for that (two Mixtral-
+// shaped experts: 896 for 1024 SIMDs), so the second wave comes from the K range: the four waves of a half
+// share their token fragments as before (a ring per half), and at the end the upper half hands its partial
+// sums to the lower one through LDS (the ring's space).
 // ------------------------------------------------------------------------------------------
-template <int TT>
-__global__ __launch_bounds__(256, 1) void ffn_gate_up_q4_kernel(GroupTable gt, const uint4 *__restrict__ xp,
-                                                                uint4 *__restrict__ act, int d) {
-    constexpr int D = q4_depth<TT>();
-    __shared__ __attribute__((aligned(16))) u32x4_t xs[kQ4Lds][TT * 4][64];
+template <int TT, int KH>
+__global__ __launch_bounds__(256 * KH, 1) void ffn_gate_up_q4_kernel(GroupTable gt, const uint4 *__restrict__ xp,
+                                                                     uint4 *__restrict__ act, int d) {
+    constexpr int D = KH == 2 ? 4 : q4_depth<TT>();   // 3 and 6 measured slower with two waves per SIMD
+    __shared__ __attribute__((aligned(16))) u32x4_t xs[KH][kQ4Lds][TT * 4][64];
     const int wg = blockIdx.x;
     int grp = 0;
     while (grp + 1 < gt.n_groups && gt.wg_start[grp + 1] <= wg) ++grp;
@@ -79,11 +87,14 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_q4_kernel(GroupTable gt, c
     const int F = gt.F[grp];
     const int rbw = (F >> 5) >> 2;               // workgroups per pass (F is a multiple of 128)
     const int pass = local / rbw;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = (threadIdx.x >> 6) & 3, kh = threadIdx.x >> 8, lane = threadIdx.x & 63;
     const int rb = (local % rbw) * 4 + wave;
     int ntl = gt.n_tiles[grp] - pass * TT;
     if (ntl > TT) ntl = TT;
     const int nkb = d >> 4, nq = d >> 6;
+    // stages [k0, k0 + nloc) of this wave's half (the launcher checks that the halves are equal: every wave
+    // passes the same barriers)
+    const int nloc = nq / KH, k0 = kh * nloc;
 
     const char *blob = reinterpret_cast<const char *>(gt.blob[grp]);
     const uint4 *w13 = reinterpret_cast<const uint4 *>(blob) + (size_t)rb * nq * 128 + lane;
@@ -104,7 +115,7 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_q4_kernel(GroupTable gt, c
     uint16_t sa[D], sb[D];
 #define EF_Q4U_LOAD(slot, kq)                                                                             \
     {                                                                                                     \
-        const int kc_ = min((kq), nq - 1);                                                                \
+        const int kc_ = k0 + min((kq), nloc - 1);                                                         \
         _Pragma("unroll") for (int u = 0; u < TT; ++u)                                                    \
             xr[slot][u] = *reinterpret_cast<const u32x4_t *>(xsrc[u] + (size_t)(4 * kc_ + wave) * 64);    \
         __builtin_amdgcn_sched_barrier(0);                                                                \
@@ -115,7 +126,7 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_q4_kernel(GroupTable gt, c
     }
 #define EF_Q4U_SHARE(slot, st)                                                                            \
     {                                                                                                     \
-        _Pragma("unroll") for (int u = 0; u < TT; ++u) xs[(st) & (kQ4Lds - 1)][u * 4 + wave][lane] = xr[slot][u]; \
+        _Pragma("unroll") for (int u = 0; u < TT; ++u) xs[kh][(st) & (kQ4Lds - 1)][u * 4 + wave][lane] = xr[slot][u]; \
     }
     // The MFMAs of a k-step are issued between the vector instructions that dequantise the next
     // k-step's fragments (one MFMA, then a share of the ~40 vector instructions), so the matrix
@@ -126,7 +137,7 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_q4_kernel(GroupTable gt, c
         const q4_half2 f1_ = q4_scale(sa[slot]), f3_ = q4_scale(sb[slot]);                                \
         u32x4_t xb_[TT][4];                                                                               \
         _Pragma("unroll") for (int tt = 0; tt < TT; ++tt)                                                 \
-            _Pragma("unroll") for (int j = 0; j < 4; ++j) xb_[tt][j] = xs[(st) & (kQ4Lds - 1)][tt * 4 + j][lane]; \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) xb_[tt][j] = xs[kh][(st) & (kQ4Lds - 1)][tt * 4 + j][lane]; \
         u32x4_t a1_ = dequant_q4(qa[slot][0], f1_), a3_ = dequant_q4(qb[slot][0], f3_);                   \
         _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                   \
             u32x4_t n1_ = a1_, n3_ = a3_;                                                                 \
@@ -159,18 +170,42 @@ __global__ __launch_bounds__(256, 1) void ffn_gate_up_q4_kernel(GroupTable gt, c
     EF_Q4U_SHARE(0, 0)
     __syncthreads();
     int st = 0;
-    for (; st + D <= nq; st += D) {
+    for (; st + D <= nloc; st += D) {
 #pragma unroll
         for (int ring_ = 0; ring_ < D; ++ring_) EF_Q4U_STAGE(ring_, (ring_ + 1) % D, st + ring_)
     }
 #pragma unroll
     for (int ring_ = 0; ring_ < D - 1; ++ring_)
-        if (st + ring_ < nq) EF_Q4U_STAGE(ring_, ring_ + 1, st + ring_)
+        if (st + ring_ < nloc) EF_Q4U_STAGE(ring_, ring_ + 1, st + ring_)
 #undef EF_Q4U_LOAD
 #undef EF_Q4U_SHARE
 #undef EF_Q4U_COMPUTE
 #undef EF_Q4U_STAGE
 
+    if constexpr (KH == 2) {
+        // every stage ends with a barrier: the ring is no longer read.  Lower half + upper half, in this order.
+        float4 *red = reinterpret_cast<float4 *>(&xs[0][0][0][0]) + (size_t)wave * (2 * TT * 4) * 64 + lane;
+        static_assert(sizeof(xs) >= (size_t)4 * (2 * TT * 4) * 64 * sizeof(float4), "partial sums fit the ring's space");
+        if (kh == 1) {
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    red[((tt * 2) * 4 + q) * 64] = make_float4(G[tt][4 * q], G[tt][4 * q + 1], G[tt][4 * q + 2], G[tt][4 * q + 3]);
+                    red[((tt * 2 + 1) * 4 + q) * 64] = make_float4(U[tt][4 * q], U[tt][4 * q + 1], U[tt][4 * q + 2], U[tt][4 * q + 3]);
+                }
+        }
+        __syncthreads();
+        if (kh == 1) return;
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 g = red[((tt * 2) * 4 + q) * 64], u = red[((tt * 2 + 1) * 4 + q) * 64];
+                G[tt][4 * q] += g.x; G[tt][4 * q + 1] += g.y; G[tt][4 * q + 2] += g.z; G[tt][4 * q + 3] += g.w;
+                U[tt][4 * q] += u.x; U[tt][4 * q + 1] += u.y; U[tt][4 * q + 2] += u.z; U[tt][4 * q + 3] += u.w;
+            }
+    }
     // a lane holds 16 F-values of one token: the two paired-order fragments (fp16) the second half consumes
     const int nkb2 = F >> 4;
 #pragma unroll
@@ -203,8 +238,12 @@ hipError_t launch_ffn_gate_up_q4(const GroupTable &gt, int total_wgs, int tiles_
     if (gt.wg_start[gt.n_groups] != total_wgs) return hipErrorInvalidValue;
     const uint4 *x = reinterpret_cast<const uint4 *>(xp);
     uint4 *a = reinterpret_cast<uint4 *>(act);
-    if (tiles_per_pass == 1) hipLaunchKernelGGL((ffn_gate_up_q4_kernel<1>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
-    else if (tiles_per_pass == 2) hipLaunchKernelGGL((ffn_gate_up_q4_kernel<2>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
+    // two K halves per workgroup when each half keeps a few stages (d / 64 stages in all, an even number)
+    const bool halves = (d >> 6) % 2 == 0 && (d >> 6) >= 8;
+    if (tiles_per_pass == 1 && halves) hipLaunchKernelGGL((ffn_gate_up_q4_kernel<1, 2>), dim3(total_wgs), dim3(512), 0, s, gt, x, a, d);
+    else if (tiles_per_pass == 1) hipLaunchKernelGGL((ffn_gate_up_q4_kernel<1, 1>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
+    else if (tiles_per_pass == 2 && halves) hipLaunchKernelGGL((ffn_gate_up_q4_kernel<2, 2>), dim3(total_wgs), dim3(512), 0, s, gt, x, a, d);
+    else if (tiles_per_pass == 2) hipLaunchKernelGGL((ffn_gate_up_q4_kernel<2, 1>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
