@@ -152,13 +152,23 @@ constexpr long long kDistTiledMinBlocks = 64;
 __global__ __launch_bounds__(256, 1) void dist_gram_tiled_kernel(const uint4 *__restrict__ xp,
                                                                   const float *__restrict__ norms, int T, int d,
                                                                   float *__restrict__ part, int t_pad,
-                                                                  int n_rowblk, int nB, long long total) {
+                                                                  int n_rowblk, int nB, long long total_whole,
+                                                                  int main_grid) {
     constexpr bool kSwapOperands = false;
     constexpr bool HALF = false;   // bf16 token fragments
     __shared__ __attribute__((aligned(16))) u32x4_t lds[kTileStages][kStageFrags][64];
     const int w = blockIdx.x;
-    const long long t = ((long long)(w >> 3) / kGramRun * 8 + (w & 7)) * kGramRun + ((w >> 3) % kGramRun);
-    if (t >= total) return;
+    // workgroups [0, main_grid): whole blocks [0, total_whole) in runs over the XCDs; the workgroups after them:
+    // the quarters (128 x 128) of the blocks from total_whole on
+    long long t;
+    int quarter = -1;
+    if (w < main_grid) {
+        t = ((long long)(w >> 3) / kGramRun * 8 + (w & 7)) * kGramRun + ((w >> 3) % kGramRun);
+        if (t >= total_whole) return;
+    } else {
+        t = total_whole + ((w - main_grid) >> 2);
+        quarter = (w - main_grid) & 3;
+    }
     // strip R, then the block within the strip: its first h columns hold 1..h blocks (the diagonal), the
     // columns after them h blocks each
     int R = 0;
@@ -183,48 +193,86 @@ __global__ __launch_bounds__(256, 1) void dist_gram_tiled_kernel(const uint4 *__
     const int wi = wave & 1, wj = wave >> 1;
     const int nkb = d >> 4;
     const int nstage = nkb / kTileKS;
-    const int it0 = IB * 8, jt0 = JB * 8;
-
-    // operand A slots 0..7 = row tiles it0..it0+7, operand B slots 8..15 = column tiles jt0..jt0+7
+    const int g = lane >> 5, c = lane & 31;
+    const unsigned lds_base = (unsigned)(size_t)&lds[0][0][0];   // LDS byte offset: the low half of its flat address
     const u32x4_t *src[kStageFrags / 4];
-#pragma unroll
-    for (int q = 0; q < kStageFrags / 4; ++q) {
-        const int fi = q * 4 + wave;
-        const int ks = fi >> 4, slot = fi & 15;
-        const int tile = min(slot < 8 ? it0 + slot : jt0 + slot - 8, ntiles - 1);
-        src[q] = reinterpret_cast<const u32x4_t *>(xp + ((size_t)tile * nkb + ks) * 64 + lane);
-    }
-
     floatx16 acc[4][4];   // [row tile][column tile]
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) zero16(acc[i][j]);
 
-    const int AOFF = wi * 4, BOFF = wj * 4;
-    const unsigned lds_base = (unsigned)(size_t)&lds[0][0][0];   // LDS byte offset: the low half of its flat address
-    // column tiles of this wave that exist; none count when every row of the wave is past every column
-    // (the lower left quarter of a diagonal block)
-    const bool below = it0 + AOFF >= jt0 + BOFF + 4;
-    const int live = below ? 0 : max(0, min(4, ntiles - (jt0 + BOFF)));
-    EF_TILED_PIPELINE_TILES_B(0, nstage, live)
+    if (quarter < 0) {
+        const int it0 = IB * 8, jt0 = JB * 8;
+        // operand A slots 0..7 = row tiles it0..it0+7, operand B slots 8..15 = column tiles jt0..jt0+7
+#pragma unroll
+        for (int q = 0; q < kStageFrags / 4; ++q) {
+            const int fi = q * 4 + wave;
+            const int ks = fi >> 4, slot = fi & 15;
+            const int tile = min(slot < 8 ? it0 + slot : jt0 + slot - 8, ntiles - 1);
+            src[q] = reinterpret_cast<const u32x4_t *>(xp + ((size_t)tile * nkb + ks) * 64 + lane);
+        }
+        const int AOFF = wi * 4, BOFF = wj * 4;
+        // column tiles of this wave that exist; none count when every row of the wave is past every column
+        // (the lower left quarter of a diagonal block)
+        const bool below = it0 + AOFF >= jt0 + BOFF + 4;
+        const int live = below ? 0 : max(0, min(4, ntiles - (jt0 + BOFF)));
+        EF_TILED_PIPELINE_TILES_B(0, nstage, live)
 
-    const int g = lane >> 5, c = lane & 31;
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-        const int j = (jt0 + BOFF + b) * kTile + c;
-        const float nj = j < T ? norms[j] : 0.f;
+        for (int b = 0; b < 4; ++b) {
+            const int j = (jt0 + BOFF + b) * kTile + c;
+            const float nj = j < T ? norms[j] : 0.f;
 #pragma unroll
-        for (int rp = 0; rp < 2; ++rp) {   // the wave's two 64-row blocks of the partials
-            const int rowblk = IB * 4 + wi * 2 + rp;
+            for (int rp = 0; rp < 2; ++rp) {   // the wave's two 64-row blocks of the partials
+                const int rowblk = IB * 4 + wi * 2 + rp;
+                float sum = 0.f;
+#pragma unroll
+                for (int aa = 0; aa < 2; ++aa) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int i = (it0 + AOFF + 2 * rp + aa) * kTile + 8 * (v >> 2) + 4 * g + (v & 3);
+                        if (i < j && j < T) {
+                            const float sq = norms[i] + nj - 2.f * acc[2 * rp + aa][b][v];
+                            sum += __builtin_sqrtf(fmaxf(sq, 0.f));
+                        }
+                    }
+                }
+                sum += __shfl_xor(sum, 32);
+                if (g == 0 && j < t_pad && rowblk < n_rowblk) part[(size_t)rowblk * t_pad + j] = sum;
+            }
+        }
+    } else {
+        // a quarter: 128 rows x 128 columns, a wave 64 x 64 (2 x 2 accumulators): the same loads and barriers
+        // per stage for a quarter of the matrix-core work, for the few blocks that would otherwise be a round
+        // of workgroups of their own over a mostly idle chip
+        const int it0 = IB * 8 + (quarter >> 1) * 4, jt0 = JB * 8 + (quarter & 1) * 4;
+        if (it0 >= jt0 + 4) return;   // every row past every column
+        // operand A slots 0..3 = row tiles it0..it0+3, operand B slots 8..11 = column tiles jt0..jt0+3; the other
+        // slots repeat them (never read from LDS)
+#pragma unroll
+        for (int q = 0; q < kStageFrags / 4; ++q) {
+            const int fi = q * 4 + wave;
+            const int ks = fi >> 4, slot = fi & 15;
+            const int tile = min(slot < 8 ? it0 + (slot & 3) : jt0 + (slot & 3), ntiles - 1);
+            src[q] = reinterpret_cast<const u32x4_t *>(xp + ((size_t)tile * nkb + ks) * 64 + lane);
+        }
+        const int AOFF = wi * 2, BOFF = wj * 2;
+        EF_TILED_PIPELINE_2X2(0, nstage)
+
+        const int rowblk = (it0 + AOFF) >> 1;
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int j = (jt0 + BOFF + b) * kTile + c;
+            const float nj = j < T ? norms[j] : 0.f;
             float sum = 0.f;
 #pragma unroll
             for (int aa = 0; aa < 2; ++aa) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int i = (it0 + AOFF + 2 * rp + aa) * kTile + 8 * (v >> 2) + 4 * g + (v & 3);
+                    const int i = (it0 + AOFF + aa) * kTile + 8 * (v >> 2) + 4 * g + (v & 3);
                     if (i < j && j < T) {
-                        const float sq = norms[i] + nj - 2.f * acc[2 * rp + aa][b][v];
+                        const float sq = norms[i] + nj - 2.f * acc[aa][b][v];
                         sum += __builtin_sqrtf(fmaxf(sq, 0.f));
                     }
                 }
@@ -299,11 +347,19 @@ hipError_t launch_token_dist(const uint16_t *h, int T, int d, const void *xp, fl
     const int nB = (ntiles + 7) / 8;
     const long long total = gram_blocks(nB);
     if (form == 2 || (form == 0 && total >= kDistTiledMinBlocks)) {
-        const long long runs = (total + kGramRun - 1) / kGramRun;
-        const long long grid = (runs + 7) / 8 * 8 * kGramRun;
+        // One block per compute unit at a time: the blocks left over after the last full round of 256 would be a
+        // round of their own.  Up to 64 of them run as quarters instead (at most 256 workgroups, each with a
+        // quarter of the matrix-core work per stage).
+        const long long rem = total % 256;
+        const long long n_split = total > 256 && rem <= 64 ? rem : 0;
+        const long long whole = total - n_split;
+        const long long runs = (whole + kGramRun - 1) / kGramRun;
+        const long long main_grid = (runs + 7) / 8 * 8 * kGramRun;
+        const long long grid = main_grid + 4 * n_split;
         if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
         hipLaunchKernelGGL(dist_gram_tiled_kernel, dim3((unsigned)grid), dim3(256), 0, s,
-                           reinterpret_cast<const uint4 *>(xp), norms, T, d, part, t_pad, n_rowblk, nB, total);
+                           reinterpret_cast<const uint4 *>(xp), norms, T, d, part, t_pad, n_rowblk, nB, whole,
+                           (int)main_grid);
     } else {
         const int nJB = (ntiles + kDistColTiles - 1) / kDistColTiles;
         const int nIB = (ntiles + kDistRowTiles - 1) / kDistRowTiles;

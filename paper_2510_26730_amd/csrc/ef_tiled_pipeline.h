@@ -146,4 +146,10 @@ __device__ __forceinline__ floatx16 tiled_mfma(u32x4_t a, u32x4_t b, floatx16 c)
     }                                                                                                \
     __builtin_amdgcn_s_waitcnt(0);
 
+// a wave with a 2 x 2 share of a 128 x 128 tile (operand-A slots AOFF, AOFF + 1, operand-B slots BOFF, BOFF + 1)
+#define EF_TILED_PIPELINE_2X2(first, last)                                                           \
+    EF_TILED_PROLOGUE(first)                                                                         \
+    EF_TILED_LOOP(first, last, 2, 2)                                                                 \
+    __builtin_amdgcn_s_waitcnt(0);
+
 }  // namespace ef

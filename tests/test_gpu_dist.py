@@ -113,10 +113,12 @@ def test_full_size_prefill_batch_sampled(oracle_mod):
     assert np.all(np.isfinite(tok)) and np.all(tok[1:] > 0)
 
 
-@pytest.mark.parametrize("T,d", [(1, 64), (33, 64), (257, 128), (300, 192), (1025, 64), (1400, 256), (2304, 64)])
+@pytest.mark.parametrize("T,d", [(1, 64), (33, 64), (257, 128), (300, 192), (1025, 64), (1400, 256), (2304, 64),
+                                 (5900, 64)])
 def test_both_gram_forms_give_the_same_bits_and_match_oracle(oracle_mod, T, d):
     """The Gram blocks staged through LDS (256 x 256, numbered in strips over the upper triangle) against the
-    register-fed blocks and the oracle, at sizes of 1 to 9 block columns with ragged last blocks."""
+    register-fed blocks and the oracle, at sizes of 1 to 9 block columns with ragged last blocks, and at 24 block
+    columns (300 blocks: the 44 past the first round of 256 run as quarters)."""
     say(f"dist forms T={T} d={d}")
     rng = np.random.default_rng(4000 + T)
     h = synth.f32_to_bf16(rng.standard_normal((T, d)).astype(np.float32))
