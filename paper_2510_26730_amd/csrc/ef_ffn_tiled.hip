@@ -5,7 +5,7 @@
 // wave (4 x 4 MFMA 32x32x16 accumulators), operands staged through LDS.  All three operands
 // (expert weights, packed tokens, activations) are already stored as 1 KiB operand fragments, so
 // the global -> LDS copy is a plain contiguous copy and an LDS operand read is 64 lanes x 16
-// consecutive bytes (no bank conflicts, no swizzle).  Four LDS stage buffers are filled by direct
+// consecutive bytes (no bank conflicts, no swizzle).  The LDS stage buffers (four) are filled by direct
 // global -> LDS loads three stages ahead of the one feeding the matrix cores, one barrier per stage.
 // Workgroups that share a weight panel (same rows, different token panels) have consecutive ids,
 // so the panel is fetched from HBM once and served to the others by L2 / MALL.

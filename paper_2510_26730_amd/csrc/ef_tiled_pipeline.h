@@ -1,7 +1,7 @@
 // The LDS operand pipeline of the matrix-core bound kernels (tiled expert FFN halves, Gram tiles of the
 // token distances): a workgroup of four waves owns a 256 x 256 output tile, a wave 128 x 128 (4 x 4 MFMA
 // 32x32x16 accumulators); both operands arrive as 1 KiB operand fragments (32 rows x 16 k), eight of each
-// per k-step, through four LDS stage buffers filled by direct global -> LDS loads three stages ahead of
+// per k-step, through kTileStages LDS stage buffers filled by direct global -> LDS loads kTileStages - 1 stages ahead of
 // the one that feeds the matrix cores, one barrier per stage.
 //
 // The macros below are written against names the using kernel defines: lds (the stage buffers), src (per
@@ -14,12 +14,17 @@ namespace ef {
 
 constexpr int kTileKS = 2;               // MFMA k-steps (16 columns each) per LDS stage
 constexpr int kStageFrags = 16 * kTileKS;  // fragments per stage: per k-step 8 of each operand
-constexpr int kTileStages = 4;           // LDS stage buffers (power of two)
-// s_waitcnt immediate "vmcnt <= 16, do not wait on expcnt / lgkmcnt" (gfx9 encoding: vmcnt[3:0] in bits
+constexpr int kTileStages = 4;           // LDS stage buffers (five, all of a compute unit's LDS, measured 1-3 % slower)
+// s_waitcnt immediate "vmcnt <= n, do not wait on expcnt / lgkmcnt" (gfx9 encoding: vmcnt[3:0] in bits
 // 3:0 and vmcnt[5:4] in bits 15:14, expcnt in 6:4, lgkmcnt in 11:8)
-constexpr int kWaitVm16 = (1 << 14) | (0x7 << 4) | (0xF << 8) | 0;
-constexpr int kWaitVm12 = (0 << 14) | (0x7 << 4) | (0xF << 8) | 12;
-static_assert(kStageFrags / 4 == 8, "the wait count assumes 8 loads per wave per stage");
+constexpr int tiled_wait_vm(int n) { return ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8) | (n & 15); }
+static_assert(kStageFrags / 4 == 8, "the wait counts assume 8 loads per wave per stage");
+// prologue: kTileStages - 1 stages are issued; the first has landed when at most the others' loads are outstanding
+constexpr int kWaitVmFirst = tiled_wait_vm(8 * (kTileStages - 2));
+// main loop, before the barrier of stage st: stage st+1 has landed when at most the loads of the stages issued
+// after it (st+2 .. st+kTileStages-2 and half of stage st+kTileStages-1) are outstanding
+constexpr int kWaitVmNext = tiled_wait_vm(8 * (kTileStages - 3) + 4);
+static_assert(8 * (kTileStages - 2) < 64, "vmcnt is a 6-bit counter");
 
 // ------------------------------------------------------------------------------------------
 // A direct global -> LDS load of 64 lanes x 16 bytes into LDS byte offset `lds_off` (wave-uniform,
@@ -28,8 +33,10 @@ static_assert(kStageFrags / 4 == 8, "the wait count assumes 8 loads per wave per
 // loads in this file is explicit.
 #define EF_TILED_DMA(gptr, lds_off)                                                                  \
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_off) : "memory")
+// ring buffer of stage st (the first stage of the wave's range sits in buffer 0)
+#define EF_TILED_BUF(st) ((int)((unsigned)((st) - ring0_) % (unsigned)kTileStages))
 // LDS byte offset of fragment slot q*4 + wave of the buffer of stage st
-#define EF_TILED_DST(st, q) (lds_base + ((((st) & (kTileStages - 1)) * kStageFrags + (q) * 4 + wave) << 10))
+#define EF_TILED_DST(st, q) (lds_base + ((EF_TILED_BUF(st) * kStageFrags + (q) * 4 + wave) << 10))
 // all of a wave's loads of one stage in a burst (prologue only).  Every wave issues kStageFrags/4 loads
 // per stage, unconditionally (past the end the last stage is re-read, in bounds), so "my loads of
 // stage st have landed" is a constant wait count.
@@ -100,29 +107,27 @@ __device__ __forceinline__ floatx16 tiled_mfma(u32x4_t a, u32x4_t b, floatx16 c)
         EF_TILED_ROUND(ac, bc, 3, , , , st, half, NLA, NLB)                                          \
     }
 // The main loop over stages [first, last): stage st feeds the matrix cores while the loads of stages
-// st+1 and st+2 are in flight and those of stage st+3 are being issued; one barrier per stage.
+// st+1 .. st+kTileStages-2 are in flight and those of stage st+kTileStages-1 are being issued; one barrier per stage.
 #define EF_TILED_LOOP(first, last, NLA, NLB)                                                         \
     for (int st = (first); st < (last); ++st) {                                                      \
-        const int cur = st & (kTileStages - 1), nxt = (st + 1) & (kTileStages - 1);                  \
-        /* the buffer of stage st+3 held stage st-1, whose last reads every wave finished before */  \
-        /* the barrier of the previous iteration */                                                  \
-        EF_TILED_STEP(a0, b0, a1, b1, cur, 1, st + 3, 0, NLA, NLB)                                   \
-        /* stage st+1 must have landed: of the loads issued after it (stage st+2 and half of */      \
-        /* stage st+3) all 12 may still be outstanding */                                            \
-        __builtin_amdgcn_s_waitcnt(kWaitVm12);                                                       \
+        const int cur = EF_TILED_BUF(st), nxt = EF_TILED_BUF(st + 1);                                \
+        /* the buffer of stage st+kTileStages-1 held stage st-1, whose last reads every wave */      \
+        /* finished before the barrier of the previous iteration */                                  \
+        EF_TILED_STEP(a0, b0, a1, b1, cur, 1, st + kTileStages - 1, 0, NLA, NLB)                     \
+        /* stage st+1 must have landed */                                                            \
+        __builtin_amdgcn_s_waitcnt(kWaitVmNext);                                                     \
         __syncthreads();                                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                           \
-        EF_TILED_STEP(a1, b1, a0, b0, nxt, 0, st + 3, 1, NLA, NLB)                                   \
+        EF_TILED_STEP(a1, b1, a0, b0, nxt, 0, st + kTileStages - 1, 1, NLA, NLB)                     \
     }
 #define EF_TILED_PROLOGUE(first)                                                                     \
     static_assert(kTileKS == 2, "the loop alternates two fragment register sets");                   \
     u32x4_t a0[4], b0[4], a1[4], b1[4];                                                              \
-    EF_TILED_ISSUE(first)                                                                            \
-    EF_TILED_ISSUE((first) + 1)                                                                      \
-    EF_TILED_ISSUE((first) + 2)                                                                      \
-    __builtin_amdgcn_s_waitcnt(kWaitVm16); /* my part of the first stage has landed */               \
-    __syncthreads();                       /* ... and everybody else's */                            \
-    EF_TILED_READ(a0, b0, (first) & (kTileStages - 1), 0)
+    const int ring0_ = (first);                                                                      \
+    _Pragma("unroll") for (int ps_ = 0; ps_ < kTileStages - 1; ++ps_) EF_TILED_ISSUE((first) + ps_)  \
+    __builtin_amdgcn_s_waitcnt(kWaitVmFirst); /* my part of the first stage has landed */            \
+    __syncthreads();                          /* ... and everybody else's */                         \
+    EF_TILED_READ(a0, b0, 0, 0)
 // `live` (wave-uniform, 0..4): live token tiles of the wave; they are operand B in the first half ...
 #define EF_TILED_PIPELINE_TILES_B(first, last, live)                                                 \
     EF_TILED_PROLOGUE(first)                                                                         \
