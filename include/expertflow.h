@@ -514,8 +514,9 @@ typedef struct ef_tuning {
     int32_t tiled_tail_slices;       /* a tiled second half of more than 256 workgroups cuts its last group into K slices
                                         that fill the launch's last, partly empty round: 0 = never, 1 = as many as a
                                         model of the launch finds best, 2 / 4 / 8 = that many (1) */
-    int32_t dist_form;               /* Gram blocks of ef_token_dist: 0 = by batch size, 1 = 128 x 256 blocks fed from
-                                        registers, 2 = 256 x 256 blocks staged through LDS; same bits either way (0) */
+    int32_t dist_form;               /* ef_token_dist: 0 = by batch size (up to 256 tokens: differences summed directly,
+                                        no Gram matrix), 1 = Gram blocks of 128 x 256 fed from registers, 2 = Gram blocks
+                                        of 256 x 256 staged through LDS; 1 and 2 give the same bits (0) */
 } ef_tuning;
 int ef_get_tuning(ef_ctx *ctx, ef_tuning *out);
 int ef_set_tuning(ef_ctx *ctx, const ef_tuning *t);

@@ -425,7 +425,8 @@ extern "C" int ef_token_dist(ef_ctx *c, const void *hidden, int T, float *tok_di
     const double flops = (double)T * (T - 1) * d;
     const double bytes = 6.0 * T * d + 8.0 * T;
     KernelTimer kt(c, s, EF_K_DIST, bytes, flops);
-    EF_HIP(c, ef::launch_pack_x(pt, ntiles, static_cast<const uint16_t *>(hidden), d, 1, nullptr, c->xp, false, s));
+    if (ef::dist_needs_packed(T, c->tune.dist_form))
+        EF_HIP(c, ef::launch_pack_x(pt, ntiles, static_cast<const uint16_t *>(hidden), d, 1, nullptr, c->xp, false, s));
     EF_HIP(c, ef::launch_token_dist(static_cast<const uint16_t *>(hidden), T, d, c->xp, c->y, tok_dist, dist,
                                     c->tune.dist_form, s));
     return EF_OK;

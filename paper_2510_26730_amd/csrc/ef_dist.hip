@@ -43,6 +43,62 @@ __global__ __launch_bounds__(256) void dist_norm_kernel(const uint16_t *__restri
     if (lane == 0) norms[t] = acc;   // rows of the padding up to whole tiles get 0
 }
 
+// Decode-sized batches (a few hundred tokens at most): the Gram route would be one or two workgroups walking all of
+// d in sequence behind five launches.  Here workgroup j owns token j: wave w of 16 takes the rows i = w, w + 16, ...
+// < j, two at a time (their loads are independent), the lanes stride the row pair in 16-byte pieces and add
+// (x_i - x_j)^2 in fp32 (no norms, no cancellation), a shuffle tree adds the lanes, the root is added to the wave's
+// sum in fp64 in ascending i; the waves' sums are added in order.  Everything in a fixed order: the result does not
+// depend on scheduling.
+constexpr int kDistSmallWaves = 16;
+__device__ __forceinline__ float dist_sq_piece(uint4 a, uint4 b) {
+    const uint32_t wa[4] = {a.x, a.y, a.z, a.w}, wb[4] = {b.x, b.y, b.z, b.w};
+    float acc = 0.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const float dl = __builtin_bit_cast(float, wa[q] << 16) - __builtin_bit_cast(float, wb[q] << 16);
+        const float dh = __builtin_bit_cast(float, wa[q] & 0xFFFF0000u) - __builtin_bit_cast(float, wb[q] & 0xFFFF0000u);
+        acc += dl * dl;
+        acc += dh * dh;
+    }
+    return acc;
+}
+__global__ __launch_bounds__(64 * kDistSmallWaves) void dist_small_kernel(const uint16_t *__restrict__ h, int T, int d,
+                                                                           float *__restrict__ tok_dist,
+                                                                           double *__restrict__ wg_sums) {
+    __shared__ double red[kDistSmallWaves];
+    const int j = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const uint4 *rj = reinterpret_cast<const uint4 *>(h + (size_t)j * d);
+    const int nc = d >> 3;
+    double s = 0.0;
+    for (int i = wave; i < j; i += 2 * kDistSmallWaves) {
+        const int i2 = i + kDistSmallWaves;
+        const bool two = i2 < j;
+        const uint4 *r0 = reinterpret_cast<const uint4 *>(h + (size_t)i * d);
+        const uint4 *r1 = reinterpret_cast<const uint4 *>(h + (size_t)(two ? i2 : i) * d);
+        float acc0 = 0.f, acc1 = 0.f;
+        for (int c = lane; c < nc; c += 64) {
+            const uint4 b = rj[c];
+            acc0 += dist_sq_piece(r0[c], b);
+            acc1 += dist_sq_piece(r1[c], b);
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            acc0 += __shfl_xor(acc0, off);
+            acc1 += __shfl_xor(acc1, off);
+        }
+        s += (double)__builtin_sqrtf(acc0);
+        if (two) s += (double)__builtin_sqrtf(acc1);
+    }
+    if (lane == 0) red[wave] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        for (int w = 0; w < kDistSmallWaves; ++w) t += red[w];
+        if (tok_dist) tok_dist[j] = (float)t;
+        wg_sums[j] = t;
+    }
+}
+
 constexpr int kDistRowTiles = 4;   // token tiles (32 rows) of operand A per workgroup: 128 rows i
 constexpr int kDistColTiles = 8;   // token tiles of operand B per workgroup: 256 columns j
 
@@ -335,6 +391,13 @@ hipError_t launch_token_dist(const uint16_t *h, int T, int d, const void *xp, fl
     const int t_pad = ntiles * kTile;
     const int n_rowblk = (T + 63) / 64;
     const int n_wg = (T + 255) / 256;
+    if (!dist_needs_packed(T, form)) {
+        // T doubles at the start of the scratch (8-byte aligned: the scratch is), then the usual final sum
+        double *sums = reinterpret_cast<double *>(scratch);
+        hipLaunchKernelGGL(dist_small_kernel, dim3(T), dim3(64 * kDistSmallWaves), 0, s, h, T, d, tok_dist, sums);
+        hipLaunchKernelGGL(dist_final_kernel, dim3(1), dim3(64), 0, s, sums, T, dist);
+        return hipGetLastError();
+    }
     float *norms = scratch;
     float *part = scratch + t_pad;
     // 8-byte aligned slot for the workgroup sums behind the partials

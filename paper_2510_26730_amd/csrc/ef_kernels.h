@@ -137,6 +137,10 @@ hipError_t launch_dequant_q4(const DequantTable &t, int d, hipStream_t s);
 
 // Dist(t): scratch floats launch_token_dist needs for T tokens (norms, partials, workgroup sums)
 size_t dist_scratch_floats(int T);
+// Batches of up to kDistSmallMaxTokens tokens take a kernel that reads the tokens as they are (form 0 only); the Gram
+// forms read the packed copy, which the caller writes first.
+constexpr int kDistSmallMaxTokens = 256;
+inline bool dist_needs_packed(int T, int form) { return !(form == 0 && T <= kDistSmallMaxTokens); }
 // `form`: 0 = by batch size, 1 = register-fed 128 x 256 Gram blocks, 2 = 256 x 256 blocks through LDS (same bits)
 hipError_t launch_token_dist(const uint16_t *h, int T, int d, const void *xp, float *scratch, float *tok_dist,
                              double *dist, int form, hipStream_t s);
