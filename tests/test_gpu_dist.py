@@ -5,7 +5,10 @@ norms are fp32 sums over d terms (relative error about 1e-6 of n_i + n_j), the d
 at typical separation sqrt(n_i + n_j) therefore carries a relative error of about 1e-6, and the
 per-token and total sums are taken in fp64.  Per-token values are compared to 1e-5 relative (plus
 1e-5 absolute per earlier token), the total to 1e-6 relative.  Integer-valued inputs make every
-fp32 sum exact; then only the correctly rounded fp32 square roots differ from fp64 (6e-8)."""
+fp32 sum exact; then only the correctly rounded fp32 square roots differ from fp64 (6e-8).
+Batches of up to 256 tokens take a kernel that sums the squared differences directly in fp32 (the same
+error model without the cancellation of n_i + n_j - 2 <v_i, v_j>); the tests below reach it through the
+default form and the Gram kernels through the forced forms."""
 import sys
 
 import numpy as np
