@@ -58,6 +58,8 @@ def layer_check(oracle_mod, st, h, T, beta, res, toks=None):
     ("tiny", dict(d=512, F=1024), 37),           # ragged tile
     ("tiny", dict(d=128, F=128), 5),             # one quad pair per row block, one scale group
     ("tiny", dict(d=384, F=640), 200),           # several passes of two tiles, odd quad counts per K slice
+    ("tiny", dict(d=640, F=256), 70),            # K halves of five stages: one full turn of the register ring and a tail
+    ("tiny", dict(d=896, F=128), 33),            # K halves of seven stages
     ("deepseek_v2_lite", dict(d=256, F=128), 130),   # 64 experts, mostly tiny groups
 ])
 def test_q4_layer_matches_oracle(oracle_mod, name, kw, T):
