@@ -68,6 +68,7 @@ constexpr int kQ4Lds = 4;     // LDS ring of shared token / activation fragments
 // first half: act = silu(X W1^T) * (X W3^T).  Workgroup = (group, pass of TT token tiles, four
 // consecutive 32-row blocks of F), wave = one row block and one of KH halves of the K range.
 //
+// OCC = 2: registers for two workgroups per compute unit (launches with more workgroups than compute units).
 // KH = 2: eight waves, two per SIMD.  A wave issues in order, so with one wave per SIMD its dequantising
 // vector instructions (about 40 % of its cycles), its waits for LDS and barriers (25 %) and its issue stalls
 // add up; a second wave on the SIMD fills them.  A launch rarely has enough row blocks for that (two Mixtral-
@@ -75,10 +76,10 @@ constexpr int kQ4Lds = 4;     // LDS ring of shared token / activation fragments
 // share their token fragments as before (a ring per half), and at the end the upper half hands its partial
 // sums to the lower one through LDS (the ring's space).
 // ------------------------------------------------------------------------------------------
-template <int TT, int KH>
-__global__ __launch_bounds__(256 * KH, 1) void ffn_gate_up_q4_kernel(GroupTable gt, const uint4 *__restrict__ xp,
-                                                                     uint4 *__restrict__ act, int d) {
-    constexpr int D = KH == 2 ? 4 : q4_depth<TT>();   // 3 and 6 measured slower with two waves per SIMD
+template <int TT, int KH, int OCC>
+__global__ __launch_bounds__(256 * KH, OCC) void ffn_gate_up_q4_kernel(GroupTable gt, const uint4 *__restrict__ xp,
+                                                                       uint4 *__restrict__ act, int d) {
+    constexpr int D = (KH == 2 || OCC == 2) ? 4 : q4_depth<TT>();   // 3 and 6 measured slower with two waves per SIMD
     __shared__ __attribute__((aligned(16))) u32x4_t xs[KH][kQ4Lds][TT * 4][64];
     const int wg = blockIdx.x;
     int grp = 0;
@@ -240,10 +241,16 @@ hipError_t launch_ffn_gate_up_q4(const GroupTable &gt, int total_wgs, int tiles_
     uint4 *a = reinterpret_cast<uint4 *>(act);
     // two K halves per workgroup when each half keeps a few stages (d / 64 stages in all, an even number)
     const bool halves = (d >> 6) % 2 == 0 && (d >> 6) >= 8;
-    if (tiles_per_pass == 1 && halves) hipLaunchKernelGGL((ffn_gate_up_q4_kernel<1, 2>), dim3(total_wgs), dim3(512), 0, s, gt, x, a, d);
-    else if (tiles_per_pass == 1) hipLaunchKernelGGL((ffn_gate_up_q4_kernel<1, 1>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
-    else if (tiles_per_pass == 2 && halves) hipLaunchKernelGGL((ffn_gate_up_q4_kernel<2, 2>), dim3(total_wgs), dim3(512), 0, s, gt, x, a, d);
-    else if (tiles_per_pass == 2) hipLaunchKernelGGL((ffn_gate_up_q4_kernel<2, 1>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
+    // more workgroups than compute units: two of them per unit instead (whole K range each, the short register ring);
+    // their waves stall at different times, where the halves of one workgroup meet at the same barriers
+    // (seven Mixtral-shaped experts: 127 against 135 us, Qwen-shaped batch 52 against 60 us)
+    const bool many = total_wgs > 256;
+    if (tiles_per_pass == 1 && many) hipLaunchKernelGGL((ffn_gate_up_q4_kernel<1, 1, 2>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
+    else if (tiles_per_pass == 2 && many) hipLaunchKernelGGL((ffn_gate_up_q4_kernel<2, 1, 2>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
+    else if (tiles_per_pass == 1 && halves) hipLaunchKernelGGL((ffn_gate_up_q4_kernel<1, 2, 1>), dim3(total_wgs), dim3(512), 0, s, gt, x, a, d);
+    else if (tiles_per_pass == 1) hipLaunchKernelGGL((ffn_gate_up_q4_kernel<1, 1, 1>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
+    else if (tiles_per_pass == 2 && halves) hipLaunchKernelGGL((ffn_gate_up_q4_kernel<2, 2, 1>), dim3(total_wgs), dim3(512), 0, s, gt, x, a, d);
+    else if (tiles_per_pass == 2) hipLaunchKernelGGL((ffn_gate_up_q4_kernel<2, 1, 1>), dim3(total_wgs), dim3(256), 0, s, gt, x, a, d);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
